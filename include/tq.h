@@ -1,0 +1,134 @@
+/* tq.h - C ABI of the MI355X (gfx950) int4 compressed-domain decode-attention library.
+ *
+ * The library computes single-query (decode) scaled-dot-product attention directly on a
+ * KV cache stored as packed int4 codes with one fp16 scale and one fp16 zero-point per
+ * group of 32 consecutive head_dim elements (Sec. 2.1, Eq. 2-3), dequantising in registers
+ * and never writing a dequantised K or V matrix (Sec. 3.1, Alg. 1), with the sequence split
+ * into chunks whose partial results are merged by an online-softmax correction
+ * (Sec. 3.2, Eq. 6).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates
+ *     nothing, frees nothing and never synchronises: work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and the call returns.
+ *   - Arguments are validated on the host before anything is launched.  A call that fails
+ *     validation launches nothing and touches no device memory.
+ *   - Return value: TQ_OK (0) or a negative TQ_ERR_* code.  Nothing is thrown across the ABI.
+ *   - Inputs must be finite; NaN/Inf are not scanned for and give unspecified output.
+ *   - fp16 is IEEE binary16.  Arrays are dense, row-major, no padding, in the shapes given,
+ *     and every data pointer is 16-byte aligned.
+ */
+#ifndef TQ_H_
+#define TQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  TQ_OK = 0,
+  TQ_ERR_NULL = -1,        /* a required pointer is NULL                                        */
+  TQ_ERR_SHAPE = -2,       /* head_dim not in {128,256}, group_size != 32, batch/heads < 1,
+                              n_q_heads not a multiple of n_kv_heads, unknown layout            */
+  TQ_ERR_EMPTY = -3,       /* seq_len < 1 or n_new < 1                                          */
+  TQ_ERR_CAPACITY = -4,    /* pos < 0, pos + n_new > capacity, or seq_len > capacity            */
+  TQ_ERR_WORKSPACE = -5,   /* workspace / dense scratch smaller than the *_bytes() query says   */
+  TQ_ERR_UNSUPPORTED = -6, /* a shape or option the kernels do not cover (e.g. GQA ratio > 16)  */
+  TQ_ERR_HIP = -7,         /* the HIP runtime reported an error at launch                       */
+  TQ_ERR_ALIGN = -8        /* a data pointer is not 16-byte aligned (workspace: 256-byte)        */
+};
+
+enum { TQ_LAYOUT_CANONICAL = 0 };
+
+/* One layer's caller-owned cache (Sec. 2.1).  Canonical layout:
+ *   k_codes, v_codes : uint8 [batch][n_kv_heads][capacity][head_dim/2]
+ *                      byte b of a token holds element 2b in its low nibble and element 2b+1
+ *                      in its high nibble (element j of a 16-bit word sits in bits 4j..4j+3,
+ *                      the order the masks of Eq. 5 assume)
+ *   k_scale, k_zero,
+ *   v_scale, v_zero  : fp16  [batch][n_kv_heads][capacity][head_dim/32]
+ * 5.0 bits per element in total.  Tokens [0, seq_len) are valid; the rest is never read. */
+typedef struct tq_kv_cache {
+  void* k_codes;
+  void* v_codes;
+  void* k_scale;
+  void* k_zero;
+  void* v_scale;
+  void* v_zero;
+  int32_t batch;
+  int32_t n_kv_heads;
+  int32_t head_dim;    /* 128 or 256 */
+  int32_t group_size;  /* 32 */
+  int32_t capacity;    /* tokens allocated per (batch, kv head) */
+  int32_t layout;      /* TQ_LAYOUT_CANONICAL */
+} tq_kv_cache;
+
+/* Optional tuning knobs for the decode entry points; NULL or zeros = library defaults. */
+typedef struct tq_decode_opts {
+  int32_t n_splits;  /* chunks the sequence is split into (Sec. 3.2); 0 = heuristic            */
+  int32_t variant;   /* 0 = default kernel, 1 = generic vector-ALU kernel, 2 = matrix-core kernel */
+} tq_decode_opts;
+
+/* Quantise and append (Sec. 2.1, Eq. 2-3; "quantize -> store" arm of Sec. 3.3).
+ * k_new, v_new: fp16 [batch][n_kv_heads][n_new][head_dim].  Tokens are written at positions
+ * pos .. pos+n_new-1 of every (batch, kv head).  Per token, per group of 32 elements, K and V
+ * independently:  s = fp16((max-min)/15) computed in fp32 (s := 1.0 if that rounds to 0),
+ * z = fp16(-min / s) from the stored s (saturated to +-65504, -0 stored as +0),
+ * code = clamp(rint_half_even(x/s + z), 0, 15) with fp32 divide then fp32 add.
+ * Errors: NULL, SHAPE, EMPTY (n_new < 1), CAPACITY, HIP. */
+int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_new, int32_t pos,
+                   int32_t n_new, void* stream);
+
+/* Fused compressed-domain decode attention (Sec. 3.1 Alg. 1 + Sec. 3.2 Eq. 6).
+ * q, out: fp16 [batch][n_q_heads][head_dim]; query head h reads KV head h / (n_q_heads /
+ * n_kv_heads) (GQA rule of Sec. 3.1).  out = softmax(attn_scale * q.K^) V^ over tokens
+ * [0, seq_len), fp32 accumulation, fp16 result.  workspace: at least tq_workspace_bytes()
+ * bytes, 256-byte aligned, holds the per-chunk partial results; contents undefined on return.
+ * Equivalent to tq_sdpa_int4_partial followed by tq_sdpa_int4_reduce on the same stream.
+ * Errors: NULL, SHAPE, EMPTY (seq_len < 1), CAPACITY (seq_len > capacity), WORKSPACE,
+ * UNSUPPORTED, HIP. */
+int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                        float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                        const tq_decode_opts* opts, void* stream);
+
+/* The two phases of Sec. 3.2, separately callable (used for per-kernel timing).
+ * partial: every chunk c writes (o_c, m_c, l_c) for each query head into workspace and
+ * *n_splits_out (host int, may be NULL) receives the chunk count used.  reduce: merges
+ * n_splits chunks from workspace by Eq. 6 and writes out.  Same errors as above. */
+int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                         float attn_scale, void* workspace, size_t workspace_bytes,
+                         const tq_decode_opts* opts, int32_t* n_splits_out, void* stream);
+int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits,
+                        const void* workspace, size_t workspace_bytes, void* out, void* stream);
+
+/* Unfused comparator (the "dequantize-then-attend" baseline of Sec. 3.1 / Table 2):
+ * phase 1 writes dense fp16 K^ and V^ [batch][n_kv_heads][seq_len][head_dim] (K^ first, then V^)
+ * into dense_scratch, phase 2 runs fp16 decode attention over them with the same split/merge.
+ * (The paper's baseline materialises FP32; fp16 is used here, which only favours the baseline.)
+ * dense_scratch: at least tq_dense_scratch_bytes() bytes.  Other arguments and errors as for
+ * tq_sdpa_int4_decode. */
+int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                           float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                           void* dense_scratch, size_t dense_scratch_bytes,
+                           const tq_decode_opts* opts, void* stream);
+
+/* Size queries (host only, no HIP calls).  Return 0 for invalid shapes.
+ * tq_kv_bytes: bytes of one layer's cache, K and V, codes + scales + zero-points
+ * (= 2 * batch * n_kv_heads * capacity * (head_dim/2 + 4*head_dim/32); Eq. 1 with 5 bits/element). */
+size_t tq_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim);
+size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim);
+size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim);
+
+/* Chunk count the heuristic would pick (host only). */
+int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len);
+
+/* Static, NUL-terminated description of a status code. */
+const char* tq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TQ_H_ */

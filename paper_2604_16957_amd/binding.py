@@ -1,0 +1,209 @@
+"""ctypes binding of include/tq.h: same names, argument marshalling only.
+
+There is no fallback: if the HIP library has not been built the import of any entry point
+fails loudly (build it with `python -m paper_2604_16957_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+_LIB_PATH = _PKG / "libtq_mi355x.so"
+
+TQ_OK = 0
+TQ_ERR_NULL, TQ_ERR_SHAPE, TQ_ERR_EMPTY, TQ_ERR_CAPACITY = -1, -2, -3, -4
+TQ_ERR_WORKSPACE, TQ_ERR_UNSUPPORTED, TQ_ERR_HIP, TQ_ERR_ALIGN = -5, -6, -7, -8
+
+
+class TqKvCacheStruct(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero")] + \
+               [(n, ctypes.c_int32) for n in ("batch", "n_kv_heads", "head_dim", "group_size", "capacity", "layout")]
+
+
+class TqDecodeOptsStruct(ctypes.Structure):
+    _fields_ = [("n_splits", ctypes.c_int32), ("variant", ctypes.c_int32)]
+
+
+class TqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tq_status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def library_path() -> Path:
+    return _LIB_PATH
+
+
+def raw():
+    """The loaded ctypes library with argtypes set (tests use it to pass deliberately bad arguments)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise RuntimeError(f"{_LIB_PATH} is missing: the HIP library is not built "
+                               "(run `python -m paper_2604_16957_amd.build`); there is no fallback path")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        P, I, F, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        CP = ctypes.POINTER(TqKvCacheStruct)
+        OP = ctypes.POINTER(TqDecodeOptsStruct)
+        L.tq_quantize_kv.argtypes = [CP, P, P, I, I, P]
+        L.tq_sdpa_int4_decode.argtypes = [CP, P, I, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_partial.argtypes = [CP, P, I, I, F, P, SZ, OP, ctypes.POINTER(ctypes.c_int32), P]
+        L.tq_sdpa_int4_reduce.argtypes = [I, I, I, I, P, SZ, P, P]
+        L.tq_dequant_then_attend.argtypes = [CP, P, I, I, F, P, P, SZ, P, SZ, OP, P]
+        for f in (L.tq_quantize_kv, L.tq_sdpa_int4_decode, L.tq_sdpa_int4_partial, L.tq_sdpa_int4_reduce,
+                  L.tq_dequant_then_attend):
+            f.restype = ctypes.c_int
+        L.tq_workspace_bytes.argtypes = [I, I, I]
+        L.tq_workspace_bytes.restype = SZ
+        L.tq_dense_scratch_bytes.argtypes = [I, I, I, I]
+        L.tq_dense_scratch_bytes.restype = SZ
+        L.tq_kv_bytes.argtypes = [I, I, I, I]
+        L.tq_kv_bytes.restype = SZ
+        L.tq_plan_splits.argtypes = [I, I, I]
+        L.tq_plan_splits.restype = I
+        L.tq_status_string.argtypes = [ctypes.c_int]
+        L.tq_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def tq_status_string(status: int) -> str:
+    return raw().tq_status_string(int(status)).decode()
+
+
+def tq_workspace_bytes(batch: int, n_q_heads: int, head_dim: int) -> int:
+    return int(raw().tq_workspace_bytes(batch, n_q_heads, head_dim))
+
+
+def tq_dense_scratch_bytes(batch: int, n_kv_heads: int, seq_len: int, head_dim: int) -> int:
+    return int(raw().tq_dense_scratch_bytes(batch, n_kv_heads, seq_len, head_dim))
+
+
+def tq_kv_bytes(batch: int, n_kv_heads: int, capacity: int, head_dim: int) -> int:
+    return int(raw().tq_kv_bytes(batch, n_kv_heads, capacity, head_dim))
+
+
+def tq_plan_splits(batch: int, n_kv_heads: int, seq_len: int) -> int:
+    return int(raw().tq_plan_splits(batch, n_kv_heads, seq_len))
+
+
+class KVCache:
+    """Caller-owned cache for one layer: six torch tensors in the canonical layout of tq.h."""
+
+    def __init__(self, batch: int, n_kv_heads: int, head_dim: int, capacity: int, device="cuda"):
+        ng = head_dim // 32
+        shape = (batch, n_kv_heads, capacity)
+        self.k_codes = torch.empty(shape + (head_dim // 2,), dtype=torch.uint8, device=device)
+        self.v_codes = torch.empty_like(self.k_codes)
+        self.k_scale = torch.empty(shape + (ng,), dtype=torch.float16, device=device)
+        self.k_zero = torch.empty_like(self.k_scale)
+        self.v_scale = torch.empty_like(self.k_scale)
+        self.v_zero = torch.empty_like(self.k_scale)
+        self.batch, self.n_kv_heads, self.head_dim, self.capacity = batch, n_kv_heads, head_dim, capacity
+        self.struct = TqKvCacheStruct(
+            self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(), self.k_zero.data_ptr(),
+            self.v_scale.data_ptr(), self.v_zero.data_ptr(), batch, n_kv_heads, head_dim, 32, capacity, 0)
+
+    def tensors(self):
+        return (self.k_codes, self.k_scale, self.k_zero, self.v_codes, self.v_scale, self.v_zero)
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in self.tensors())
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _opts(n_splits: int, variant: int):
+    if not n_splits and not variant:
+        return None
+    return ctypes.byref(TqDecodeOptsStruct(int(n_splits), int(variant)))
+
+
+def _check(rc: int, where: str):
+    if rc != TQ_OK:
+        raise TqError(rc, where)
+
+
+def _need(t: torch.Tensor, dtype, name: str):
+    if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of {dtype}")
+
+
+def tq_quantize_kv(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, pos: int, stream=None) -> None:
+    """k_new, v_new: fp16 [B, H_kv, n_new, d]; written at token positions pos .. pos+n_new-1."""
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    if k_new.shape != v_new.shape or k_new.dim() != 4 or \
+            tuple(k_new.shape[:2]) != (cache.batch, cache.n_kv_heads) or k_new.shape[3] != cache.head_dim:
+        raise ValueError("k_new/v_new must be [batch, n_kv_heads, n_new, head_dim]")
+    rc = raw().tq_quantize_kv(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(), int(pos),
+                              int(k_new.shape[2]), _stream_ptr(stream))
+    _check(rc, "tq_quantize_kv")
+
+
+def _workspace_for(cache: KVCache, n_q_heads: int, workspace):
+    need = tq_workspace_bytes(cache.batch, n_q_heads, cache.head_dim)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=cache.k_codes.device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,
+                        workspace=None, n_splits: int = 0, variant: int = 0, stream=None) -> torch.Tensor:
+    """q: fp16 [B, H_q, d] -> out fp16 [B, H_q, d]."""
+    _need(q, torch.float16, "q")
+    if out is None:
+        out = torch.empty_like(q)
+    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
+    rc = raw().tq_sdpa_int4_decode(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
+                                   float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
+                                   _opts(n_splits, variant), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_decode")
+    return out
+
+
+def tq_sdpa_int4_partial(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, workspace: torch.Tensor,
+                         n_splits: int = 0, variant: int = 0, stream=None) -> int:
+    """Phase 1 only; returns the number of chunks written into workspace."""
+    _need(q, torch.float16, "q")
+    n = ctypes.c_int32(0)
+    rc = raw().tq_sdpa_int4_partial(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
+                                    float(attn_scale), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _opts(n_splits, variant),
+                                    ctypes.byref(n), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_partial")
+    return n.value
+
+
+def tq_sdpa_int4_reduce(batch: int, n_q_heads: int, head_dim: int, n_splits: int, workspace: torch.Tensor,
+                        out: torch.Tensor, stream=None) -> torch.Tensor:
+    rc = raw().tq_sdpa_int4_reduce(batch, n_q_heads, head_dim, n_splits, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), out.data_ptr(), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_reduce")
+    return out
+
+
+def tq_dequant_then_attend(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,
+                           workspace=None, dense_scratch=None, n_splits: int = 0, stream=None) -> torch.Tensor:
+    _need(q, torch.float16, "q")
+    if out is None:
+        out = torch.empty_like(q)
+    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
+    if dense_scratch is None:
+        dense_scratch = torch.empty(tq_dense_scratch_bytes(cache.batch, cache.n_kv_heads, seq_len, cache.head_dim),
+                                    dtype=torch.uint8, device=q.device)
+    rc = raw().tq_dequant_then_attend(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
+                                      float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
+                                      dense_scratch.data_ptr(), dense_scratch.numel() * dense_scratch.element_size(),
+                                      _opts(n_splits, 0), _stream_ptr(stream))
+    _check(rc, "tq_dequant_then_attend")
+    return out

@@ -1,0 +1,213 @@
+// C ABI of the library: host-side validation, chunk planning and kernel dispatch.
+// Every argument check happens here, on the host, before any HIP call, so a rejected call
+// launches nothing (and the checks themselves can be exercised on a machine without a GPU).
+#include <algorithm>
+#include <cmath>
+
+#include "tq_internal.h"
+
+namespace {
+
+using tq::DecodeParams;
+using tq::half_t;
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_cache(const tq_kv_cache* c) {
+  if (!c) return TQ_ERR_NULL;
+  if (!c->k_codes || !c->v_codes || !c->k_scale || !c->k_zero || !c->v_scale || !c->v_zero) return TQ_ERR_NULL;
+  if (c->head_dim != 128 && c->head_dim != 256) return TQ_ERR_SHAPE;
+  if (c->group_size != tq::kGroup) return TQ_ERR_SHAPE;
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->capacity < 1) return TQ_ERR_SHAPE;
+  if (c->layout != TQ_LAYOUT_CANONICAL) return TQ_ERR_SHAPE;
+  const void* ptrs[] = {c->k_codes, c->v_codes, c->k_scale, c->k_zero, c->v_scale, c->v_zero};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return TQ_ERR_ALIGN;
+  return TQ_OK;
+}
+
+struct Plan { int n_splits, tokens_per_split; };
+
+// Chunks of whole 32-token tiles, about two blocks per compute unit, never an empty chunk.
+Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested) {
+  const int tiles = (seq_len + tq::kTile - 1) / tq::kTile;
+  int n = requested;
+  if (n <= 0) {
+    const int64_t rows = (int64_t)batch * n_kv_heads;
+    n = (int)std::max<int64_t>(1, (512 + rows - 1) / rows);
+  }
+  n = std::max(1, std::min({n, tiles, tq::kMaxSplits}));
+  const int tiles_per = (tiles + n - 1) / n;
+  Plan p;
+  p.tokens_per_split = tiles_per * tq::kTile;
+  p.n_splits = (seq_len + p.tokens_per_split - 1) / p.tokens_per_split;
+  return p;
+}
+
+int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len, const void* out,
+                 const void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, bool need_out) {
+  int rc = check_cache(c);
+  if (rc == TQ_ERR_NULL) return rc;
+  if (!q || (need_out && !out) || !workspace) return TQ_ERR_NULL;
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
+  if (n_q_heads < 1 || n_q_heads % c->n_kv_heads != 0) return TQ_ERR_SHAPE;
+  if (seq_len < 1) return TQ_ERR_EMPTY;
+  if (seq_len > c->capacity) return TQ_ERR_CAPACITY;
+  if (rc == TQ_ERR_ALIGN) return rc;
+  if (!aligned(q, 16) || (need_out && !aligned(out, 16)) || !aligned(workspace, 256)) return TQ_ERR_ALIGN;
+  if (workspace_bytes < tq_workspace_bytes(c->batch, n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
+  if (opts) {
+    if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0) return TQ_ERR_UNSUPPORTED;
+    if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, n_q_heads / c->n_kv_heads)) return TQ_ERR_UNSUPPORTED;
+  }
+  return TQ_OK;
+}
+
+DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len, float attn_scale,
+                         void* out, void* workspace, const Plan& plan) {
+  DecodeParams p{};
+  p.k_codes = static_cast<const uint8_t*>(c->k_codes);
+  p.v_codes = static_cast<const uint8_t*>(c->v_codes);
+  p.k_scale = static_cast<const half_t*>(c->k_scale);
+  p.k_zero = static_cast<const half_t*>(c->k_zero);
+  p.v_scale = static_cast<const half_t*>(c->v_scale);
+  p.v_zero = static_cast<const half_t*>(c->v_zero);
+  p.q = static_cast<const half_t*>(q);
+  p.out = static_cast<half_t*>(out);
+  p.part_o = static_cast<float*>(workspace);
+  p.part_ml = p.part_o + tq::workspace_o_floats(c->batch, n_q_heads, c->head_dim);
+  p.n_q_heads = n_q_heads;
+  p.n_kv_heads = c->n_kv_heads;
+  p.gqa = n_q_heads / c->n_kv_heads;
+  p.row_stride = c->capacity;
+  p.seq_len = seq_len;
+  p.n_splits = plan.n_splits;
+  p.tokens_per_split = plan.tokens_per_split;
+  p.scale_log2 = attn_scale * 1.4426950408889634f;
+  return p;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t tq_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim) {
+  if (batch < 1 || n_q_heads < 1 || (head_dim != 128 && head_dim != 256)) return 0;
+  return (tq::workspace_o_floats(batch, n_q_heads, head_dim) + tq::workspace_ml_floats(batch, n_q_heads)) *
+         sizeof(float);
+}
+
+size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim) {
+  if (batch < 1 || n_kv_heads < 1 || seq_len < 1 || (head_dim != 128 && head_dim != 256)) return 0;
+  return (size_t)2 * batch * n_kv_heads * seq_len * head_dim * sizeof(half_t);
+}
+
+size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim) {
+  if (batch < 1 || n_kv_heads < 1 || capacity < 1 || head_dim < 32 || head_dim % tq::kGroup != 0) return 0;
+  const size_t per_token = (size_t)head_dim / 2 + 2 * sizeof(half_t) * (head_dim / tq::kGroup);
+  return (size_t)2 * batch * n_kv_heads * capacity * per_token;
+}
+
+int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len) {
+  if (batch < 1 || n_kv_heads < 1 || seq_len < 1) return 0;
+  return plan_splits(batch, n_kv_heads, seq_len, 0).n_splits;
+}
+
+const char* tq_status_string(int status) {
+  switch (status) {
+    case TQ_OK: return "ok";
+    case TQ_ERR_NULL: return "a required pointer is NULL";
+    case TQ_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case TQ_ERR_EMPTY: return "empty request (seq_len < 1 or n_new < 1)";
+    case TQ_ERR_CAPACITY: return "position or sequence length exceeds the cache capacity";
+    case TQ_ERR_WORKSPACE: return "workspace or dense scratch too small";
+    case TQ_ERR_UNSUPPORTED: return "shape or option not covered by the kernels";
+    case TQ_ERR_HIP: return "HIP runtime error at launch";
+    case TQ_ERR_ALIGN: return "pointer not sufficiently aligned";
+    default: return "unknown status";
+  }
+}
+
+int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_new, int32_t pos, int32_t n_new,
+                   void* stream) {
+  int rc = check_cache(cache);
+  if (rc == TQ_ERR_NULL) return rc;
+  if (!k_new || !v_new) return TQ_ERR_NULL;
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
+  if (n_new < 1) return TQ_ERR_EMPTY;
+  if (pos < 0 || (int64_t)pos + n_new > cache->capacity) return TQ_ERR_CAPACITY;
+  if (rc == TQ_ERR_ALIGN || !aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
+  return hip_rc(tq::launch_quantize(*cache, k_new, v_new, pos, n_new, static_cast<hipStream_t>(stream)));
+}
+
+int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                         float attn_scale, void* workspace, size_t workspace_bytes, const tq_decode_opts* opts,
+                         int32_t* n_splits_out, void* stream) {
+  const int rc = check_decode(cache, q, n_q_heads, seq_len, nullptr, workspace, workspace_bytes, opts, false);
+  if (rc != TQ_OK) return rc;
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0);
+  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, plan);
+  if (n_splits_out) *n_splits_out = plan.n_splits;
+  const int variant = opts ? opts->variant : 0;
+  const bool use_mfma = variant == 2 || (variant == 0 && tq::mfma_supported(cache->head_dim, p.gqa));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, s));
+  return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
+}
+
+int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits, const void* workspace,
+                        size_t workspace_bytes, void* out, void* stream) {
+  if (!workspace || !out) return TQ_ERR_NULL;
+  if (batch < 1 || n_q_heads < 1 || (head_dim != 128 && head_dim != 256)) return TQ_ERR_SHAPE;
+  if (n_splits < 1) return TQ_ERR_EMPTY;
+  if (n_splits > tq::kMaxSplits) return TQ_ERR_UNSUPPORTED;
+  if (!aligned(workspace, 256) || !aligned(out, 16)) return TQ_ERR_ALIGN;
+  if (workspace_bytes < tq_workspace_bytes(batch, n_q_heads, head_dim)) return TQ_ERR_WORKSPACE;
+  DecodeParams p{};
+  p.part_o = const_cast<float*>(static_cast<const float*>(workspace));
+  p.part_ml = p.part_o + tq::workspace_o_floats(batch, n_q_heads, head_dim);
+  p.out = static_cast<half_t*>(out);
+  p.n_q_heads = n_q_heads;
+  p.n_splits = n_splits;
+  return hip_rc(tq::launch_reduce(p, batch, head_dim, static_cast<hipStream_t>(stream)));
+}
+
+int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len, float attn_scale,
+                        void* out, void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, void* stream) {
+  int rc = check_decode(cache, q, n_q_heads, seq_len, out, workspace, workspace_bytes, opts, true);
+  if (rc != TQ_OK) return rc;
+  int32_t n_splits = 0;
+  rc = tq_sdpa_int4_partial(cache, q, n_q_heads, seq_len, attn_scale, workspace, workspace_bytes, opts, &n_splits,
+                            stream);
+  if (rc != TQ_OK) return rc;
+  return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
+                             stream);
+}
+
+int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                           float attn_scale, void* out, void* workspace, size_t workspace_bytes, void* dense_scratch,
+                           size_t dense_scratch_bytes, const tq_decode_opts* opts, void* stream) {
+  int rc = check_decode(cache, q, n_q_heads, seq_len, out, workspace, workspace_bytes, opts, true);
+  if (rc != TQ_OK) return rc;
+  if (!dense_scratch) return TQ_ERR_NULL;
+  if (!aligned(dense_scratch, 16)) return TQ_ERR_ALIGN;
+  const size_t need = tq_dense_scratch_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
+  if (dense_scratch_bytes < need) return TQ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  half_t* k_dense = static_cast<half_t*>(dense_scratch);
+  half_t* v_dense = k_dense + need / sizeof(half_t) / 2;
+  rc = hip_rc(tq::launch_dequant_dense(*cache, seq_len, k_dense, v_dense, s));
+  if (rc != TQ_OK) return rc;
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0);
+  DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
+  p.k_dense = k_dense;
+  p.v_dense = v_dense;
+  p.row_stride = seq_len;                  // the dense buffers are packed to seq_len rows
+  rc = hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, true, s));
+  if (rc != TQ_OK) return rc;
+  return hip_rc(tq::launch_reduce(p, cache->batch, cache->head_dim, s));
+}
+
+}  // extern "C"

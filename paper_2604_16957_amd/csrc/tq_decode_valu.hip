@@ -1,0 +1,195 @@
+// Generic vector-ALU decode attention: the fused int4 kernel for any GQA ratio, and (same
+// template, fp16 loader) the attention phase of the dequantize-then-attend comparator.
+// Also the chunk merge of Sec. 3.2, Eq. 6.
+//
+// Work split: grid (n_splits, H_kv * head_tiles, B); a block of four 64-wide waves owns one
+// chunk of one KV head.  D/8 lanes cooperate on a token (each lane holds 8 consecutive
+// head_dim elements: one 32-bit word of codes, or 16 B of fp16), so a wave walks 64/(D/8)
+// tokens at a time and every token-slot keeps its own online-softmax state (m, l, o) for up to
+// 8 query heads of the GQA group in registers (Alg. 1, lines 3-11).  Slots are merged with
+// wave shuffles, waves through LDS, and the block writes ONE un-normalised partial
+// (o_c, m_c, l_c) per query head (Sec. 3.2).  Scores live in log2 units so exp is exp2.
+#include "tq_internal.h"
+
+namespace tq {
+namespace {
+
+constexpr int kHeadTile = 8;       // query heads per block pass
+constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite: no inf-inf)
+
+union Pack16 { uint4 v; half_t h[8]; };
+
+template <int D, bool DENSE>
+__global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p) {
+  constexpr int LPT = D / 8;           // lanes per token
+  constexpr int TPW = 64 / LPT;        // token slots per wave
+  constexpr int SPB = 4 * TPW;         // token slots per block
+  constexpr int NG = D / kGroup;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int sub = lane % LPT;          // which 8-element piece of the head vector
+  const int slot = wave * TPW + lane / LPT;
+  const int grp = sub / 4;             // quantisation group of that piece
+
+  const int split = blockIdx.x;
+  const int head_tiles = (p.gqa + kHeadTile - 1) / kHeadTile;
+  const int kv = blockIdx.y / head_tiles;
+  const int tile = blockIdx.y % head_tiles;
+  const int b = blockIdx.z;
+  const int h0 = kv * p.gqa + tile * kHeadTile;          // first query head of this pass
+  const int nh = min(kHeadTile, p.gqa - tile * kHeadTile);
+
+  // query piece for each head, pre-multiplied by attn_scale * log2(e) (Alg. 1, line 1)
+  float qf[kHeadTile][8];
+#pragma unroll
+  for (int h = 0; h < kHeadTile; ++h) {
+    if (h < nh) {
+      Pack16 u;
+      u.v = *reinterpret_cast<const uint4*>(p.q + ((int64_t)(b * p.n_q_heads + h0 + h) * D + sub * 8));
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qf[h][j] = (float)u.h[j] * p.scale_log2;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qf[h][j] = 0.0f;
+    }
+  }
+
+  float m[kHeadTile], l[kHeadTile], o[kHeadTile][8];
+#pragma unroll
+  for (int h = 0; h < kHeadTile; ++h) {
+    m[h] = kNegBig;
+    l[h] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[h][j] = 0.0f;
+  }
+
+  const int begin = split * p.tokens_per_split;
+  const int end = min(p.seq_len, begin + p.tokens_per_split);
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
+
+  for (int t0 = begin; t0 < end; t0 += SPB) {
+    const int t = t0 + slot;
+    const bool valid = t < end;
+    const int64_t row = row0 + (valid ? t : end - 1);    // clamped: always a written token
+
+    float kf[8], vf[8];
+    if constexpr (DENSE) {
+      Pack16 ku, vu;
+      ku.v = *reinterpret_cast<const uint4*>(p.k_dense + row * D + sub * 8);
+      vu.v = *reinterpret_cast<const uint4*>(p.v_dense + row * D + sub * 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { kf[j] = (float)ku.h[j]; vf[j] = (float)vu.h[j]; }
+    } else {
+      const uint32_t kw = *reinterpret_cast<const uint32_t*>(p.k_codes + row * (D / 2) + sub * 4);
+      const uint32_t vw = *reinterpret_cast<const uint32_t*>(p.v_codes + row * (D / 2) + sub * 4);
+      const float ks = (float)p.k_scale[row * NG + grp], kz = (float)p.k_zero[row * NG + grp];
+      const float vs = (float)p.v_scale[row * NG + grp], vz = (float)p.v_zero[row * NG + grp];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {                      // dequant4: nibble j, then (q - z) s
+        kf[j] = ((float)((kw >> (4 * j)) & 0xFu) - kz) * ks;
+        vf[j] = ((float)((vw >> (4 * j)) & 0xFu) - vz) * vs;
+      }
+    }
+
+#pragma unroll
+    for (int h = 0; h < kHeadTile; ++h) {
+      float a = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a = fmaf(qf[h][j], kf[j], a);
+#pragma unroll
+      for (int off = 1; off < LPT; off <<= 1) a += __shfl_xor(a, off);   // Alg. 1, line 5
+      const float m_new = valid ? fmaxf(m[h], a) : m[h];
+      const float corr = exp2f(m[h] - m_new);
+      const float pr = valid ? exp2f(a - m_new) : 0.0f;
+      l[h] = fmaf(l[h], corr, pr);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[h][j] = fmaf(o[h][j], corr, pr * vf[j]);
+      m[h] = m_new;
+    }
+  }
+
+  // merge the token slots of this wave (same head, same dims, different tokens)
+#pragma unroll
+  for (int off = LPT; off < 64; off <<= 1) {
+#pragma unroll
+    for (int h = 0; h < kHeadTile; ++h) {
+      const float m_o = __shfl_xor(m[h], off);
+      const float m_n = fmaxf(m[h], m_o);
+      const float wa = exp2f(m[h] - m_n), wb = exp2f(m_o - m_n);
+      l[h] = l[h] * wa + __shfl_xor(l[h], off) * wb;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[h][j] = o[h][j] * wa + __shfl_xor(o[h][j], off) * wb;
+      m[h] = m_n;
+    }
+  }
+
+  __shared__ float lds_o[4][kHeadTile][D];
+  __shared__ float lds_m[4][kHeadTile], lds_l[4][kHeadTile];
+  if (lane < LPT) {
+#pragma unroll
+    for (int h = 0; h < kHeadTile; ++h) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) lds_o[wave][h][sub * 8 + j] = o[h][j];
+      if (lane == 0) { lds_m[wave][h] = m[h]; lds_l[wave][h] = l[h]; }
+    }
+  }
+  __syncthreads();
+
+  for (int idx = threadIdx.x; idx < nh * D; idx += 256) {
+    const int h = idx / D, j = idx % D;
+    float mg = lds_m[0][h];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mg = fmaxf(mg, lds_m[w][h]);
+    float num = 0.0f, den = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float e = exp2f(lds_m[w][h] - mg);
+      num = fmaf(lds_o[w][h][j], e, num);
+      den = fmaf(lds_l[w][h], e, den);
+    }
+    const int64_t ph = ((int64_t)(b * p.n_q_heads + h0 + h) * p.n_splits + split);
+    p.part_o[ph * D + j] = num;
+    if (j == 0) { p.part_ml[ph * 2] = mg; p.part_ml[ph * 2 + 1] = den; }
+  }
+}
+
+// Eq. 6 with un-normalised chunk outputs: o = sum_c e^{m_c-m_g} o_c / sum_c e^{m_c-m_g} l_c.
+template <int D>
+__global__ __launch_bounds__(D) void reduce_kernel(DecodeParams p) {
+  const int h = blockIdx.x, b = blockIdx.y, j = threadIdx.x;
+  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * p.n_splits;
+  float mg = kNegBig;
+  for (int c = 0; c < p.n_splits; ++c) mg = fmaxf(mg, p.part_ml[(ph0 + c) * 2]);
+  float num = 0.0f, den = 0.0f;
+  for (int c = 0; c < p.n_splits; ++c) {
+    const float e = exp2f(p.part_ml[(ph0 + c) * 2] - mg);
+    num = fmaf(p.part_o[(ph0 + c) * D + j], e, num);
+    den = fmaf(p.part_ml[(ph0 + c) * 2 + 1], e, den);
+  }
+  p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
+}
+
+}  // namespace
+
+hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s) {
+  const int head_tiles = (p.gqa + kHeadTile - 1) / kHeadTile;
+  const dim3 grid(p.n_splits, p.n_kv_heads * head_tiles, batch), block(256);
+  if (head_dim == 128) {
+    if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<128, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_partial_valu_kernel<128, false>), grid, block, 0, s, p);
+  } else {
+    if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<256, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_partial_valu_kernel<256, false>), grid, block, 0, s, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
+  const dim3 grid(p.n_q_heads, batch);
+  if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(128), 0, s, p);
+  else hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace tq

@@ -1,0 +1,56 @@
+// Internal declarations shared by the library's translation units (host launchers and
+// the parameter blocks their kernels take).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tq.h"
+
+namespace tq {
+
+constexpr int kGroup = 32;        // elements per quantisation group (Sec. 2.1)
+constexpr int kMaxSplits = 128;   // upper bound on sequence chunks (Sec. 3.2); sizes the workspace
+constexpr int kTile = 32;         // chunk boundaries are multiples of this many tokens
+
+typedef _Float16 half_t;
+
+// Arguments of the decode kernels (fused int4, dense fp16 comparator, merge).
+struct DecodeParams {
+  const uint8_t* k_codes;   // [B][H_kv][row_stride][D/2]
+  const uint8_t* v_codes;
+  const half_t* k_scale;    // [B][H_kv][row_stride][D/32]
+  const half_t* k_zero;
+  const half_t* v_scale;
+  const half_t* v_zero;
+  const half_t* k_dense;    // comparator only: [B][H_kv][row_stride][D]
+  const half_t* v_dense;
+  const half_t* q;          // [B][H_q][D]
+  float* part_o;            // [B][H_q][n_splits][D]   un-normalised chunk outputs
+  float* part_ml;           // [B][H_q][n_splits][2]   (running max in log2 units, sum of exp)
+  half_t* out;              // [B][H_q][D]
+  int32_t n_q_heads, n_kv_heads, gqa;
+  int32_t row_stride;       // tokens between consecutive (b, kv head) rows
+  int32_t seq_len, n_splits, tokens_per_split;
+  float scale_log2;         // attn_scale * log2(e)
+};
+
+// Workspace carving: part_o first, then part_ml, both sized for kMaxSplits.
+inline size_t workspace_o_floats(int batch, int n_q_heads, int head_dim) {
+  return (size_t)batch * n_q_heads * kMaxSplits * head_dim;
+}
+inline size_t workspace_ml_floats(int batch, int n_q_heads) {
+  return (size_t)batch * n_q_heads * kMaxSplits * 2;
+}
+
+// Launchers (each returns a hipError_t from hipGetLastError after the launch).
+hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos, int n_new,
+                           hipStream_t s);
+hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_dense, half_t* v_dense,
+                                hipStream_t s);
+hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);
+bool mfma_supported(int head_dim, int gqa);
+hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
+hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
+
+}  // namespace tq

@@ -1,0 +1,164 @@
+// Quantise-and-append (Sec. 2.1, Eq. 2-3) and the comparator's dense dequantisation
+// (the materialising step of the dequantize-then-attend baseline, Sec. 3.1).
+//
+// One thread owns one group of 32 consecutive head_dim elements of one token: it reads 64 B of
+// fp16 (four 128-bit loads), finds min/max in registers, and writes 16 B of codes plus one fp16
+// scale and one fp16 zero-point.  No cross-lane traffic, no LDS.  The arithmetic must give the
+// same bits on every IEEE machine, so each fp32 step is a separately rounded operation:
+// contraction is off for this file and the correctly rounded divide is used.
+#include "tq_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace tq {
+namespace {
+
+struct QuantParams {
+  const half_t* src[2];   // k_new, v_new: [B*H_kv][n_new][D]
+  uint8_t* codes[2];      // [B*H_kv][capacity][D/2]
+  half_t* scale[2];       // [B*H_kv][capacity][D/32]
+  half_t* zero[2];
+  int32_t n_new, capacity, pos, head_dim;
+  int64_t groups_per_tensor;  // B*H_kv*n_new*(D/32)
+};
+
+union Pack16 { uint4 v; half_t h[8]; };
+
+__global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= p.groups_per_tensor) return;
+  const int which = blockIdx.y;                       // 0 = K, 1 = V
+  const int ng = p.head_dim / kGroup;
+  const int g = (int)(idx % ng);
+  const int64_t vec = idx / ng;                       // (b*H_kv + h) * n_new + t
+  const int64_t bh = vec / p.n_new;
+  const int t = (int)(vec % p.n_new);
+
+  const uint4* src = reinterpret_cast<const uint4*>(p.src[which] + (vec * p.head_dim + g * kGroup));
+  float x[kGroup];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    Pack16 u;
+    u.v = src[i];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[8 * i + j] = (float)u.h[j];
+  }
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+
+  // Eq. 2: s = (max - min) / 15, stored as fp16; a scale that rounds to zero becomes 1.0
+  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  half_t s16 = (half_t)s32;
+  if ((__builtin_bit_cast(uint16_t, s16) & 0x7FFFu) == 0) s16 = (half_t)1.0f;
+  const float sf = (float)s16;
+  // Eq. 2: z = -min / s from the STORED scale; saturate, and never store -0
+  const float z32 = __fdiv_rn(__fsub_rn(0.0f, mn), sf);
+  half_t z16 = (half_t)z32;
+  uint16_t zb = __builtin_bit_cast(uint16_t, z16);
+  if ((zb & 0x7FFFu) == 0x7C00u) zb = (uint16_t)((zb & 0x8000u) | 0x7BFFu);
+  if (zb == 0x8000u) zb = 0;
+  z16 = __builtin_bit_cast(half_t, zb);
+  const float zf = (float)z16;
+
+  // Eq. 3: q = clamp(round_half_even(x / s + z), 0, 15); element j of a word in bits 4j..4j+3
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float v = __fadd_rn(__fdiv_rn(x[8 * i + j], sf), zf);
+      const float r = fminf(fmaxf(rintf(v), 0.0f), 15.0f);
+      acc |= (uint32_t)r << (4 * j);
+    }
+    w[i] = acc;
+  }
+  const int64_t row = bh * p.capacity + p.pos + t;
+  *reinterpret_cast<uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2)) =
+      make_uint4(w[0], w[1], w[2], w[3]);
+  p.scale[which][row * ng + g] = s16;
+  p.zero[which][row * ng + g] = z16;
+}
+
+struct DequantParams {
+  const uint8_t* codes[2];
+  const half_t* scale[2];
+  const half_t* zero[2];
+  half_t* dense[2];           // [B*H_kv][seq_len][D]
+  int32_t seq_len, capacity, head_dim;
+  int64_t groups_per_tensor;  // B*H_kv*seq_len*(D/32)
+};
+
+// x^ = (q - z) * s (Eq. 3) rounded to fp16: what "dequantize, then attend" materialises.
+__global__ __launch_bounds__(256) void dequant_dense_kernel(DequantParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= p.groups_per_tensor) return;
+  const int which = blockIdx.y;
+  const int ng = p.head_dim / kGroup;
+  const int g = (int)(idx % ng);
+  const int64_t vec = idx / ng;                       // bh * seq_len + t
+  const int64_t bh = vec / p.seq_len;
+  const int t = (int)(vec % p.seq_len);
+  const int64_t row = bh * p.capacity + t;
+  const uint4 c = *reinterpret_cast<const uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2));
+  const float sf = (float)p.scale[which][row * ng + g];
+  const float zf = (float)p.zero[which][row * ng + g];
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  uint4* dst = reinterpret_cast<uint4*>(p.dense[which] + (vec * p.head_dim + g * kGroup));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    Pack16 u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float q = (float)((w[i] >> (4 * j)) & 0xFu);
+      u.h[j] = (half_t)((q - zf) * sf);
+    }
+    dst[i] = u.v;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos, int n_new,
+                           hipStream_t s) {
+  QuantParams p;
+  p.src[0] = static_cast<const half_t*>(k_new);
+  p.src[1] = static_cast<const half_t*>(v_new);
+  p.codes[0] = static_cast<uint8_t*>(c.k_codes);
+  p.codes[1] = static_cast<uint8_t*>(c.v_codes);
+  p.scale[0] = static_cast<half_t*>(c.k_scale);
+  p.scale[1] = static_cast<half_t*>(c.v_scale);
+  p.zero[0] = static_cast<half_t*>(c.k_zero);
+  p.zero[1] = static_cast<half_t*>(c.v_zero);
+  p.n_new = n_new;
+  p.capacity = c.capacity;
+  p.pos = pos;
+  p.head_dim = c.head_dim;
+  p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * n_new * (c.head_dim / kGroup);
+  const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);
+  hipLaunchKernelGGL(quantize_append_kernel, dim3(blocks, 2), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_dense, half_t* v_dense,
+                                hipStream_t s) {
+  DequantParams p;
+  p.codes[0] = static_cast<const uint8_t*>(c.k_codes);
+  p.codes[1] = static_cast<const uint8_t*>(c.v_codes);
+  p.scale[0] = static_cast<const half_t*>(c.k_scale);
+  p.scale[1] = static_cast<const half_t*>(c.v_scale);
+  p.zero[0] = static_cast<const half_t*>(c.k_zero);
+  p.zero[1] = static_cast<const half_t*>(c.v_zero);
+  p.dense[0] = k_dense;
+  p.dense[1] = v_dense;
+  p.seq_len = seq_len;
+  p.capacity = c.capacity;
+  p.head_dim = c.head_dim;
+  p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * seq_len * (c.head_dim / kGroup);
+  const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);
+  hipLaunchKernelGGL(dequant_dense_kernel, dim3(blocks, 2), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace tq

@@ -1,0 +1,131 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, answers the size queries, and rejects bad arguments before launching anything."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+import oracle
+import paper_2604_16957_amd as tq
+from paper_2604_16957_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def _declared_functions():
+    text = (ROOT / "include" / "tq.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"tq_quantize_kv", "tq_sdpa_int4_decode", "tq_dequant_then_attend", "tq_sdpa_int4_partial",
+            "tq_sdpa_int4_reduce", "tq_workspace_bytes", "tq_status_string"} <= set(names)
+    lib = ctypes.CDLL(str(tq.library_path()))
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_size_queries_follow_the_papers_format():
+    # 5 bits/element (Sec. 2.1): one 128K layer of the 70B shape is 160 MiB; 80 layers are 12.5 GiB
+    assert tq.tq_kv_bytes(1, 8, 131072, 128) == 167772160
+    assert tq.tq_kv_bytes(1, 8, 131072, 128) * 80 == oracle.kv_bytes_int4(80, 8, 131072, 128)
+    assert tq.tq_kv_bytes(1, 16, 32768, 256) == 167772160
+    assert tq.tq_dense_scratch_bytes(1, 8, 131072, 128) == 2 * 8 * 131072 * 128 * 2
+    assert tq.tq_workspace_bytes(1, 64, 128) % 256 == 0 and tq.tq_workspace_bytes(1, 64, 128) > 0
+    assert tq.tq_workspace_bytes(0, 64, 128) == 0 and tq.tq_kv_bytes(1, 8, 0, 128) == 0
+    for args in [(1, 8, 131072), (1, 1, 1024), (4, 8, 131072), (1, 16, 32768), (1, 1, 1), (1, 1, 33)]:
+        n = tq.tq_plan_splits(*args)
+        assert 1 <= n <= 128
+        assert n <= (args[2] + 31) // 32
+
+
+def test_status_strings():
+    seen = {tq.tq_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert tq.tq_status_string(-99) == "unknown status"
+
+
+FAKE = 0x10000  # 16- and 256-byte aligned, never dereferenced: validation fails first
+
+
+def _cache(**kw):
+    f = dict(k_codes=FAKE, v_codes=FAKE, k_scale=FAKE, k_zero=FAKE, v_scale=FAKE, v_zero=FAKE,
+             batch=1, n_kv_heads=8, head_dim=128, group_size=32, capacity=1024, layout=0)
+    f.update(kw)
+    return B.TqKvCacheStruct(*[f[n] for n, _ in B.TqKvCacheStruct._fields_])
+
+
+def _decode(cache, q=FAKE, hq=64, S=1024, out=FAKE, ws=FAKE, wsb=None, opts=None):
+    wsb = tq.tq_workspace_bytes(1, 64, 128) if wsb is None else wsb
+    return B.raw().tq_sdpa_int4_decode(ctypes.byref(cache) if cache is not None else None, q, hq, S, 0.1, out,
+                                       ws, wsb, opts, None)
+
+
+def test_decode_rejects_bad_arguments_without_a_gpu():
+    E = B
+    assert _decode(None) == E.TQ_ERR_NULL
+    assert _decode(_cache(k_scale=None)) == E.TQ_ERR_NULL
+    assert _decode(_cache(), q=None) == E.TQ_ERR_NULL
+    assert _decode(_cache(), out=None) == E.TQ_ERR_NULL
+    assert _decode(_cache(), ws=None) == E.TQ_ERR_NULL
+    assert _decode(_cache(head_dim=64)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(head_dim=192)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(group_size=64)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(batch=0)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(layout=7)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(), hq=63) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(), hq=0) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(), S=0) == E.TQ_ERR_EMPTY
+    assert _decode(_cache(), S=-5) == E.TQ_ERR_EMPTY
+    assert _decode(_cache(), S=1025) == E.TQ_ERR_CAPACITY
+    assert _decode(_cache(v_codes=FAKE + 4)) == E.TQ_ERR_ALIGN
+    assert _decode(_cache(), q=FAKE + 2) == E.TQ_ERR_ALIGN
+    assert _decode(_cache(), ws=FAKE + 16) == E.TQ_ERR_ALIGN
+    assert _decode(_cache(), wsb=1000) == E.TQ_ERR_WORKSPACE
+    bad = B.TqDecodeOptsStruct(0, 9)
+    assert _decode(_cache(), opts=ctypes.byref(bad)) == E.TQ_ERR_UNSUPPORTED
+    neg = B.TqDecodeOptsStruct(-1, 0)
+    assert _decode(_cache(), opts=ctypes.byref(neg)) == E.TQ_ERR_UNSUPPORTED
+
+
+def test_quantize_rejects_bad_arguments_without_a_gpu():
+    E = B
+    q = B.raw().tq_quantize_kv
+    c = _cache()
+    assert q(None, FAKE, FAKE, 0, 1, None) == E.TQ_ERR_NULL
+    assert q(ctypes.byref(c), None, FAKE, 0, 1, None) == E.TQ_ERR_NULL
+    assert q(ctypes.byref(c), FAKE, None, 0, 1, None) == E.TQ_ERR_NULL
+    assert q(ctypes.byref(c), FAKE, FAKE, 0, 0, None) == E.TQ_ERR_EMPTY
+    assert q(ctypes.byref(c), FAKE, FAKE, -1, 1, None) == E.TQ_ERR_CAPACITY
+    assert q(ctypes.byref(c), FAKE, FAKE, 1024, 1, None) == E.TQ_ERR_CAPACITY
+    assert q(ctypes.byref(c), FAKE, FAKE, 1000, 25, None) == E.TQ_ERR_CAPACITY
+    assert q(ctypes.byref(c), FAKE + 8, FAKE, 0, 1, None) == E.TQ_ERR_ALIGN
+    c2 = _cache(head_dim=96)
+    assert q(ctypes.byref(c2), FAKE, FAKE, 0, 1, None) == E.TQ_ERR_SHAPE
+
+
+def test_reduce_and_baseline_reject_bad_arguments_without_a_gpu():
+    E = B
+    r = B.raw().tq_sdpa_int4_reduce
+    wsb = tq.tq_workspace_bytes(1, 64, 128)
+    assert r(1, 64, 128, 4, None, wsb, FAKE, None) == E.TQ_ERR_NULL
+    assert r(1, 64, 100, 4, FAKE, wsb, FAKE, None) == E.TQ_ERR_SHAPE
+    assert r(1, 64, 128, 0, FAKE, wsb, FAKE, None) == E.TQ_ERR_EMPTY
+    assert r(1, 64, 128, 100000, FAKE, wsb, FAKE, None) == E.TQ_ERR_UNSUPPORTED
+    assert r(1, 64, 128, 4, FAKE, 10, FAKE, None) == E.TQ_ERR_WORKSPACE
+    d = B.raw().tq_dequant_then_attend
+    c = _cache()
+    need = tq.tq_dense_scratch_bytes(1, 8, 1024, 128)
+    assert d(ctypes.byref(c), FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, None, need, None, None) == E.TQ_ERR_NULL
+    assert d(ctypes.byref(c), FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, FAKE, need - 1, None, None) == E.TQ_ERR_WORKSPACE
+    assert d(ctypes.byref(c), FAKE, 64, 2000, 0.1, FAKE, FAKE, wsb, FAKE, need, None, None) == E.TQ_ERR_CAPACITY
+
+
+def test_binding_fails_loudly_when_library_is_missing(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "_LIB_PATH", tmp_path / "nope.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.raw()

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: int4 codes, scales and zero-points bit-exact; attention output max-abs <= 2e-3 and
+relative L2 <= 1e-3 against the fp64 oracle (fp32 accumulate, fp16 out)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_16957_amd as tq
+import tq_workloads as wl
+from gpu_common import (assert_cache_bit_exact, assert_close, errors, gpu_cache_from, make, np16, oracle_attend,
+                        oracle_cache_from)
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [1, 2]   # 1 = generic vector-ALU kernel, 2 = matrix-core kernel (skipped where unsupported)
+
+
+def _decode(cache, q, S, alpha, **kw):
+    try:
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, alpha, **kw)
+    except tq.TqError as e:
+        if e.status == -6 and kw.get("variant") == 2:
+            pytest.skip("matrix-core kernel does not cover this shape")
+        raise
+    torch.cuda.synchronize()
+    return out
+
+
+# ---------------------------------------------------------------- quantise-append (bit-exact)
+
+def _special_values(d=128):
+    rng = np.random.default_rng(77)
+    rows = []
+    rows.append(np.zeros(d))                                   # constant groups
+    rows.append(np.full(d, -0.0))
+    rows.append(np.full(d, 65504.0))
+    rows.append(np.full(d, -65504.0))
+    r = np.zeros(d); r[::2] = 65504.0; r[1::2] = -65504.0; rows.append(r)      # widest range
+    r = np.zeros(d); r[5] = 2.0 ** -24; rows.append(r)         # range underflows the fp16 scale
+    r = rng.integers(-3, 4, d) * 2.0 ** -24; rows.append(r)    # subnormal inputs
+    r = 1000.0 + rng.integers(0, 3, d) * 0.5; rows.append(r)   # large |zero-point|
+    r = -2000.0 + rng.integers(0, 2, d) * 1.0; rows.append(r)  # |z| > 1024: clamping can fire
+    r = rng.integers(0, 16, d) + 0.5; rows.append(r)           # ties everywhere
+    r = (rng.integers(0, 16, d) + 0.5) * 0.125 - 1.0; rows.append(r)
+    r = rng.standard_normal(d) * 1e-3; rows.append(r)
+    r = rng.standard_normal(d) * 300; rows.append(r)
+    x = np.stack(rows).astype(np.float16)
+    return torch.from_numpy(x).reshape(1, 1, len(rows), d)
+
+
+def test_quantize_special_values_bit_exact():
+    for d in (128, 256):
+        x = _special_values(d)
+        k, v = x, torch.flip(x, dims=(2,)).contiguous()
+        cache = gpu_cache_from(k, v)
+        torch.cuda.synchronize()
+        assert_cache_bit_exact(cache, oracle_cache_from(k, v), k.shape[2])
+
+
+@pytest.mark.parametrize("name", ["tiny", "gemma_small", "llama_small"])
+def test_quantize_random_bit_exact(name):
+    w = {"tiny": wl.WORKLOADS["tiny"],
+         "gemma_small": wl.custom(n_q_heads=4, n_kv_heads=2, head_dim=256, seq_len=777, qk_std=0.1, seed=21),
+         "llama_small": wl.custom(batch=2, n_q_heads=16, n_kv_heads=2, head_dim=128, seq_len=1500,
+                                  outlier_channels=4, seed=22)}[name]
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    torch.cuda.synchronize()
+    assert_cache_bit_exact(cache, oracle_cache_from(k, v), w.seq_len)
+
+
+def test_append_writes_only_its_positions():
+    w = wl.custom(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=40, seed=23)
+    q, k, v = make(w)
+    cap = 64
+    cache = gpu_cache_from(k[:, :, :33], v[:, :, :33], capacity=cap, fill=0xEE)      # bulk: tokens 0..32
+    for t in range(33, 40):                                                          # then one at a time
+        tq.tq_quantize_kv(cache, k[:, :, t:t + 1].contiguous().cuda(), v[:, :, t:t + 1].contiguous().cuda(), t)
+    torch.cuda.synchronize()
+    assert_cache_bit_exact(cache, oracle_cache_from(k, v), 40)
+    for t in cache.tensors():                                                        # the rest is untouched
+        assert bool((t.view(torch.uint8)[:, :, 40:] == 0xEE).all())
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_quantize_kv(cache, k[:, :, :30].contiguous().cuda(), v[:, :, :30].contiguous().cuda(), 40)
+    assert e.value.status == -4
+
+
+# ---------------------------------------------------------------- fused decode attention
+
+SHAPES = {
+    "g8_d128": dict(n_q_heads=8, n_kv_heads=1, head_dim=128),
+    "g8_d128_b2_kv3": dict(batch=2, n_q_heads=24, n_kv_heads=3, head_dim=128, outlier_channels=4),
+    "g2_d256": dict(n_q_heads=4, n_kv_heads=2, head_dim=256, attn_scale=1.0, qk_std=0.1),
+    "g1_d128": dict(n_q_heads=2, n_kv_heads=2, head_dim=128),
+    "g4_d256": dict(n_q_heads=4, n_kv_heads=1, head_dim=256),
+    "g3_d128": dict(n_q_heads=6, n_kv_heads=2, head_dim=128),
+    "g16_d128": dict(n_q_heads=16, n_kv_heads=1, head_dim=128),
+}
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 513, 1000, 4133])
+@pytest.mark.parametrize("shape", ["g8_d128", "g2_d256", "g8_d128_b2_kv3"])
+def test_decode_ragged_lengths(shape, S, variant):
+    w = wl.custom(seq_len=S, seed=100 + S, **SHAPES[shape])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v, capacity=S + (3 if S % 2 else 0))
+    ocache = oracle_cache_from(k, v)
+    assert_cache_bit_exact(cache, ocache, S)
+    out = _decode(cache, q, S, w.attn_scale, variant=variant)
+    assert_close(out, oracle_attend(q, ocache, S, w.attn_scale), f"{shape} S={S} variant={variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("shape", ["g1_d128", "g4_d256", "g3_d128", "g16_d128"])
+def test_decode_other_gqa_ratios(shape, variant):
+    w = wl.custom(seq_len=2100, seed=31, **SHAPES[shape])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    out = _decode(cache, q, w.seq_len, w.attn_scale, variant=variant)
+    assert_close(out, oracle_attend(q, ocache, w.seq_len, w.attn_scale), f"{shape} variant={variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_result_does_not_depend_on_the_chunking(variant):
+    w = wl.custom(seq_len=5000, seed=41, **SHAPES["g8_d128"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
+    outs = []
+    for n in (0, 1, 2, 7, 64, 128, 1000):
+        out = _decode(cache, q, w.seq_len, w.attn_scale, n_splits=n, variant=variant)
+        assert_close(out, ref, f"n_splits={n} variant={variant}")
+        outs.append(np16(out).astype(np.float64))
+    spread = max(np.abs(o - outs[0]).max() for o in outs)
+    assert spread <= 5e-4
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_attends_only_to_seq_len_tokens_of_a_larger_cache(variant):
+    w = wl.custom(seq_len=900, seed=42, **SHAPES["g8_d128"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v, capacity=1024)
+    ocache = oracle_cache_from(k[:, :, :517], v[:, :, :517])
+    out = _decode(cache, q, 517, w.attn_scale, variant=variant)
+    assert_close(out, oracle_attend(q, ocache, 517, w.attn_scale), "prefix of a larger cache")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_known_answers(variant):
+    # one token -> its dequantised value; identical keys -> mean of the values
+    w = wl.custom(seq_len=64, seed=43, **SHAPES["g8_d128"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    vh = oracle.dequantize(*oracle_cache_from(k, v)[3:])
+    out = _decode(cache, q, 1, w.attn_scale, variant=variant)
+    for h in range(8):
+        assert np.abs(np16(out)[0, h].astype(np.float64) - vh[0, 0, 0]).max() <= 2e-3
+    k2 = k.clone(); k2[:] = k[:, :, :1]
+    cache2 = gpu_cache_from(k2, v)
+    out2 = _decode(cache2, q, 64, w.attn_scale, variant=variant)
+    for h in range(8):
+        assert np.abs(np16(out2)[0, h].astype(np.float64) - vh[0, 0].mean(0)).max() <= 2e-3
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_sharp_softmax_large_scores(variant):
+    # large attn_scale: the softmax is close to one-hot and scores are far from zero
+    w = wl.custom(seq_len=700, seed=44, attn_scale=4.0, **SHAPES["g8_d128"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    out = _decode(cache, q, w.seq_len, w.attn_scale, variant=variant)
+    ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
+    max_abs, _ = errors(out, ref)
+    assert max_abs <= 2e-3 * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_bitwise_repeatable(variant):
+    w = wl.custom(seq_len=3000, seed=45, **SHAPES["g8_d128_b2_kv3"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    first = np16(_decode(cache, q, w.seq_len, w.attn_scale, variant=variant)).view(np.uint16)
+    for _ in range(5):
+        again = np16(_decode(cache, q, w.seq_len, w.attn_scale, variant=variant)).view(np.uint16)
+        assert np.array_equal(first, again)
+
+
+# ---------------------------------------------------------------- unfused comparator
+
+def test_dequant_then_attend_matches_oracle():
+    for shape, S in (("g8_d128_b2_kv3", 1999), ("g2_d256", 1030)):
+        w = wl.custom(seq_len=S, seed=51, **SHAPES[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k, v, capacity=S + 5)
+        ocache = oracle_cache_from(k, v)
+        nbytes = tq.tq_dense_scratch_bytes(w.batch, w.n_kv_heads, S, w.head_dim)
+        dense = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale, dense_scratch=dense)
+        torch.cuda.synchronize()
+        assert_close(out, oracle_attend(q, ocache, S, w.attn_scale), f"baseline {shape}")
+        # the dense buffers hold fp16((q - z) s) to within one fp16 ulp
+        got = np16(dense.view(torch.float16).view(2, w.batch, w.n_kv_heads, S, w.head_dim))
+        for i, part in enumerate((ocache[:3], ocache[3:])):
+            ref = oracle.dequantize_f16(*part)
+            a = got[i].view(np.int16).astype(np.int32)
+            b = ref.view(np.int16).astype(np.int32)
+            # compare in sign-magnitude order space
+            a = np.where(a < 0, -(a & 0x7FFF), a); b = np.where(b < 0, -(b & 0x7FFF), b)
+            assert np.abs(a - b).max() <= 1
+
+
+# ---------------------------------------------------------------- the named workloads, full size,
+# in the launch configuration the benchmark times (library defaults)
+
+@pytest.mark.parametrize("name", ["tiny", "llama8k", "gemma32k", "llama128k"])
+def test_named_workload_full_size(name):
+    w = wl.WORKLOADS[name]
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    assert_cache_bit_exact(cache, ocache, w.seq_len)
+    ref = oracle_attend(q, ocache, w.seq_len, w.attn_scale)
+    out = _decode(cache, q, w.seq_len, w.attn_scale)
+    max_abs, rel = assert_close(out, ref, name)
+    print(f"\n{name}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}")
+    if name in ("tiny", "llama8k"):
+        base = tq.tq_dequant_then_attend(cache, q.cuda(), w.seq_len, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(base, ref, name + " baseline")
+
+
+def test_decode_step_append_then_attend():
+    # one decode step of the sweep configuration, scaled down: append one token per sequence,
+    # then attend over seq_len+1 tokens, for a batch of 4
+    w = wl.custom(batch=4, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=2048, seed=61, outlier_channels=4)
+    q, k, v = make(w)
+    S = w.seq_len
+    cache = gpu_cache_from(k[:, :, :S - 1], v[:, :, :S - 1], capacity=S)
+    tq.tq_quantize_kv(cache, k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda(), S - 1)
+    ocache = oracle_cache_from(k, v)
+    assert_cache_bit_exact(cache, ocache, S)
+    out = _decode(cache, q, S, w.attn_scale)
+    assert_close(out, oracle_attend(q, ocache, S, w.attn_scale), "append+attend")
