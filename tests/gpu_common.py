@@ -11,6 +11,12 @@ import tq_workloads as wl
 
 MAX_ABS = 2e-3      # attention output: max |gpu - oracle|
 REL_L2 = 1e-3       # attention output: |gpu - oracle|_2 / |oracle|_2
+# The unfused comparator stores K^ and V^ as dense fp16: every element carries an extra relative
+# rounding error of up to 2^-11 (rms ~2.8e-4 of its magnitude).  Through q.k^ over d=128 elements
+# (outlier channels of magnitude ~8 included) that is ~5e-4 rms on a score, hence ~5e-4 relative on
+# each softmax weight, plus ~3e-4 from V^ itself: about 1e-3 relative L2 on the output.  Its bar is
+# therefore wider than the fused path's, which never rounds a dequantised value to fp16.
+BASELINE_REL_L2 = 3e-3
 
 
 def np16(t: torch.Tensor) -> np.ndarray:
@@ -50,9 +56,9 @@ def errors(out_gpu: torch.Tensor, ref: np.ndarray):
     return float(np.abs(diff).max()), float(np.linalg.norm(diff) / np.linalg.norm(ref))
 
 
-def assert_close(out_gpu, ref, what=""):
+def assert_close(out_gpu, ref, what="", rel_l2=REL_L2):
     max_abs, rel = errors(out_gpu, ref)
-    assert max_abs <= MAX_ABS and rel <= REL_L2, f"{what}: max-abs {max_abs:.3e}, rel-L2 {rel:.3e}"
+    assert max_abs <= MAX_ABS and rel <= rel_l2, f"{what}: max-abs {max_abs:.3e}, rel-L2 {rel:.3e}"
     return max_abs, rel
 
 
