@@ -155,19 +155,61 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 }
 
 // Eq. 6 with un-normalised chunk outputs: o = sum_c e^{m_c-m_g} o_c / sum_c e^{m_c-m_g} l_c.
+// One block per query head.  The chunk weights are computed once (one chunk per thread) and kept
+// in LDS; the weighted sum over chunks is split over 256/D thread groups with independent,
+// unrolled loads, so the kernel is a handful of memory round trips long.
 template <int D>
-__global__ __launch_bounds__(D) void reduce_kernel(DecodeParams p) {
-  const int h = blockIdx.x, b = blockIdx.y, j = threadIdx.x;
-  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * p.n_splits;
-  float mg = kNegBig;
-  for (int c = 0; c < p.n_splits; ++c) mg = fmaxf(mg, p.part_ml[(ph0 + c) * 2]);
-  float num = 0.0f, den = 0.0f;
-  for (int c = 0; c < p.n_splits; ++c) {
-    const float e = exp2f(p.part_ml[(ph0 + c) * 2] - mg);
-    num = fmaf(p.part_o[(ph0 + c) * D + j], e, num);
-    den = fmaf(p.part_ml[(ph0 + c) * 2 + 1], e, den);
+__global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
+  constexpr int PARTS = 256 / D;
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int n = p.n_splits;
+  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * n;
+  __shared__ float w_c[kMaxSplits];
+  __shared__ float red_m[4], red_l[4];
+  __shared__ float acc_part[PARTS][D];
+
+  float m = kNegBig, l = 0.0f;
+  if (tid < n) {
+    const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
+    m = ml.x;
+    l = ml.y;
   }
-  p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
+  float mw = m;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+  if ((tid & 63) == 0) red_m[tid >> 6] = mw;
+  __syncthreads();
+  const float mg = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  const float w = exp2f(m - mg);
+  if (tid < n) w_c[tid] = w;
+  float lw = l * w;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
+  if ((tid & 63) == 0) red_l[tid >> 6] = lw;
+  __syncthreads();
+  const float den = (red_l[0] + red_l[1]) + (red_l[2] + red_l[3]);
+
+  const int j = tid % D, part = tid / D;
+  const float* src = p.part_o + ph0 * D + j;
+  float num = 0.0f;
+  int c = part;
+  for (; c + 7 * PARTS < n; c += 8 * PARTS) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u * PARTS) * D];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) num = fmaf(v[u], w_c[c + u * PARTS], num);
+  }
+  for (; c < n; c += PARTS) num = fmaf(src[(int64_t)c * D], w_c[c], num);
+  if constexpr (PARTS > 1) {
+    acc_part[part][j] = num;
+    __syncthreads();
+    if (part == 0) {
+#pragma unroll
+      for (int q = 1; q < PARTS; ++q) num += acc_part[q][j];
+    }
+  }
+  if (part == 0) p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
 }
 
 }  // namespace
@@ -187,7 +229,7 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch);
-  if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(128), 0, s, p);
+  if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
