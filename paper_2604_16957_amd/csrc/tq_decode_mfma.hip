@@ -33,6 +33,8 @@
 // Work split: grid (n_splits, H_kv, B), 4 waves per block; the waves of a block interleave
 // 32-token supertiles of the chunk, keep private online-softmax state, and are merged through LDS
 // so that the block writes one partial (o_c, m_c, l_c) per query head.
+#include <type_traits>
+
 #include "tq_internal.h"
 
 namespace tq {
@@ -136,19 +138,90 @@ template <int D, int GP>
 __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParams p) {
   using C = Cfg<D, GP>;
   constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS;
-  constexpr int WB = D / 8;                       // 32-bit words per token row of codes
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int TB = D / 2;                       // bytes of codes per token
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, kq = lane >> 4;
   const int hl = c % GP, rep = c / GP;            // head and group replica of this lane's column / row
   const int split = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
   const int G = p.gqa;
 
-  // wave-private LDS: [K|V][scale|zero][tile][group][row] fp16, + rescale factors; block-shared merge area
-  __shared__ _Float16 lds_sz[4][2][2][2][NG][16];
+  // wave-private LDS: scales / zero-points of one supertile as [tile][group][row]; K as fp16,
+  // V as fp32 with the zero-point already shifted by -8.  Then the block-shared merge area.
+  __shared__ __attribute__((aligned(16))) _Float16 lds_ks[4][2][NG][16];
+  __shared__ __attribute__((aligned(16))) _Float16 lds_kz[4][2][NG][16];
+  __shared__ __attribute__((aligned(16))) float lds_vs[4][2][NG][16];
+  __shared__ __attribute__((aligned(16))) float lds_vz[4][2][NG][16];
   __shared__ float lds_f[4][16];
   __shared__ float lds_o[4][GP][D];
   __shared__ float lds_zc[4][GP][NG];
   __shared__ float lds_m[4][GP], lds_l[4][GP];
+
+  // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
+  const int begin = split * p.tokens_per_split;
+  const int end = min(p.seq_len, begin + p.tokens_per_split);
+  const int n_full = (end - begin) >> 5;          // whole 32-token supertiles of this chunk
+  const bool has_tail = ((end - begin) & 31) != 0;  // only the sequence's last supertile can be ragged
+  const int last_tok = p.seq_len - 1;
+  const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
+  const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
+  const uint32_t koff = tok_of_row(c) * TB + kq * (D / 8);
+  const uint32_t voff = kq * TB + c * 4 * NCS;
+  const int sz_tok = lane & 31;                   // token (within the supertile) whose scales this lane fetches
+  const int which = lane >> 5;                    // 0: this lane fetches scales, 1: zero-points
+  const char* ksz_row = reinterpret_cast<const char*>(which ? p.k_zero : p.k_scale) + row0 * (NG * 2);
+  const char* vsz_row = reinterpret_cast<const char*>(which ? p.v_zero : p.v_scale) + row0 * (NG * 2);
+
+  auto load_stage = [&](Stage<D>& st, int sidx, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int base = begin + sidx * 32;
+    if constexpr (!TAIL) {
+      const char* kb = kc_row + (int64_t)base * TB;
+      const char* vb = vc_row + (int64_t)base * TB;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ch = 0; ch < D / 128; ++ch)
+          st.k[t][ch] = *reinterpret_cast<const uint4v*>(kb + koff + t * 16 * TB + ch * 16);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int cs = 0; cs < NCS; ++cs)
+          st.v[cs][i] = *reinterpret_cast<const uint32_t*>(vb + voff + (16 * (i >> 2) + 4 * (i & 3)) * TB + cs * 4);
+      const int64_t so = (int64_t)(base + sz_tok) * (NG * 2);
+#pragma unroll
+      for (int i = 0; i < D / 64; ++i) {
+        st.ksz[i] = *reinterpret_cast<const uint32_t*>(ksz_row + so + i * 4);
+        st.vsz[i] = *reinterpret_cast<const uint32_t*>(vsz_row + so + i * 4);
+      }
+    } else {                                      // ragged tail: clamp every token to the last valid one
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
+#pragma unroll
+        for (int ch = 0; ch < D / 128; ++ch)
+          st.k[t][ch] = *reinterpret_cast<const uint4v*>(kc_row + (int64_t)tok * TB + kq * (D / 8) + ch * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int tok = min(base + 16 * (i >> 2) + 4 * (i & 3) + kq, last_tok);
+#pragma unroll
+        for (int cs = 0; cs < NCS; ++cs)
+          st.v[cs][i] = *reinterpret_cast<const uint32_t*>(vc_row + (int64_t)tok * TB + c * 4 * NCS + cs * 4);
+      }
+      const int64_t so = (int64_t)min(base + sz_tok, last_tok) * (NG * 2);
+#pragma unroll
+      for (int i = 0; i < D / 64; ++i) {
+        st.ksz[i] = *reinterpret_cast<const uint32_t*>(ksz_row + so + i * 4);
+        st.vsz[i] = *reinterpret_cast<const uint32_t*>(vsz_row + so + i * 4);
+      }
+    }
+  };
+
+  // first loads go out before the query set-up so that their latency overlaps it
+  Stage<D> stA, stB;
+  if (wave < n_full) load_stage(stA, wave, std::false_type{});
 
   // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
   const _Float16* qh = p.q + (int64_t)(b * p.n_q_heads + kv * G + (hl < G ? hl : 0)) * D;
@@ -168,49 +241,16 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
     float s = 0.0f;
-    const _Float16* qg = qh + (rep * NA + a) * kGroup;
+    const half8v* qg = reinterpret_cast<const half8v*>(qh + (rep * NA + a) * kGroup);
 #pragma unroll
-    for (int i = 0; i < kGroup; ++i) s += (float)qg[i];
+    for (int i = 0; i < 4; ++i) {
+      const half8v x = qg[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (float)x[e];
+    }
     qsum[a] = (hl < G) ? s * 0x1p-24f : 0.0f;
   }
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
-
-  // ---- addressing
-  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
-  const int begin = split * p.tokens_per_split;
-  const int end = min(p.seq_len, begin + p.tokens_per_split);
-  const int n_super = (end - begin + 31) >> 5;
-  const int last_tok = p.seq_len - 1;
-  const uint32_t* kc = reinterpret_cast<const uint32_t*>(p.k_codes);
-  const uint32_t* vc = reinterpret_cast<const uint32_t*>(p.v_codes);
-  const int sz_tok = lane & 31;                   // token (within the supertile) whose scales this lane fetches
-  const _Float16* ksz_base = (lane < 32) ? p.k_scale : p.k_zero;
-  const _Float16* vsz_base = (lane < 32) ? p.v_scale : p.v_zero;
-
-  auto load_stage = [&](Stage<D>& st, int sidx) {
-    const int base = begin + sidx * 32;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
-      const uint4v* src = reinterpret_cast<const uint4v*>(kc + (row0 + tok) * WB) + kq * (D / 128);
-#pragma unroll
-      for (int ch = 0; ch < D / 128; ++ch) st.k[t][ch] = src[ch];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tok = min(base + 16 * (i >> 2) + 4 * (i & 3) + kq, last_tok);
-      const uint32_t* src = vc + (row0 + tok) * WB + c * NCS;
-#pragma unroll
-      for (int cs = 0; cs < NCS; ++cs) st.v[cs][i] = src[cs];
-    }
-    {
-      const int tok = min(base + sz_tok, last_tok);
-      const uint32_t* ks = reinterpret_cast<const uint32_t*>(ksz_base + (row0 + tok) * NG);
-      const uint32_t* vs = reinterpret_cast<const uint32_t*>(vsz_base + (row0 + tok) * NG);
-#pragma unroll
-      for (int i = 0; i < D / 64; ++i) { st.ksz[i] = ks[i]; st.vsz[i] = vs[i]; }
-    }
-  };
 
   // ---- running state
   float m_run = kNegBig;                          // running max of this lane's head, raw units
@@ -229,27 +269,23 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   const half8v neg8_lo = as_half8(kNeg8Lo, kNeg8Lo, kNeg8Lo, kNeg8Lo);
   const half8v neg8_hi = as_half8(kNeg8Hi, kNeg8Hi, kNeg8Hi, kNeg8Hi);
 
-  Stage<D> cur, nxt;
-  int sidx = wave;
-  if (sidx < n_super) load_stage(cur, sidx);
+  // LDS destinations of this lane's scale / zero-point token (constant over the loop)
+  const int sz_slot = (sz_tok >> 4) * (NG * 16) + row_of_tok(sz_tok & 15);
+  _Float16* const k_dst = (which ? &lds_kz[wave][0][0][0] : &lds_ks[wave][0][0][0]) + sz_slot;
+  float* const v_dst = (which ? &lds_vz[wave][0][0][0] : &lds_vs[wave][0][0][0]) + sz_slot;
+  const float v_shift = which ? -8.0f : 0.0f;
 
-  for (; sidx < n_super; sidx += 4) {
-    const bool has_next = sidx + 4 < n_super;
-    if (has_next) load_stage(nxt, sidx + 4);
-    const int base = begin + sidx * 32;
-
+  auto process = [&](const Stage<D>& cur, int sidx, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
     // -- scales and zero-points: one token per lane -> LDS, transposed to [group][row]
-    {
-      const int t = sz_tok >> 4, r = row_of_tok(sz_tok & 15), which = lane >> 5;
 #pragma unroll
-      for (int i = 0; i < D / 64; ++i) {
-        const half2v ks = __builtin_bit_cast(half2v, cur.ksz[i]);
-        const half2v vs = __builtin_bit_cast(half2v, cur.vsz[i]);
-        lds_sz[wave][0][which][t][2 * i][r] = ks[0];
-        lds_sz[wave][0][which][t][2 * i + 1][r] = ks[1];
-        lds_sz[wave][1][which][t][2 * i][r] = vs[0];
-        lds_sz[wave][1][which][t][2 * i + 1][r] = vs[1];
-      }
+    for (int i = 0; i < D / 64; ++i) {
+      const half2v ks = __builtin_bit_cast(half2v, cur.ksz[i]);
+      const half2v vs = __builtin_bit_cast(half2v, cur.vsz[i]);
+      k_dst[(2 * i) * 16] = ks[0];
+      k_dst[(2 * i + 1) * 16] = ks[1];
+      v_dst[(2 * i) * 16] = (float)vs[0] + v_shift;
+      v_dst[(2 * i + 1) * 16] = (float)vs[1] + v_shift;
     }
     __builtin_amdgcn_wave_barrier();   // LDS is in order per wave; only the compiler must not reorder
 
@@ -275,8 +311,8 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
         const int g = rep * NA + a;
-        const half4v s4 = *reinterpret_cast<const half4v*>(&lds_sz[wave][0][0][t][g][4 * kq]);
-        const half4v z4 = *reinterpret_cast<const half4v*>(&lds_sz[wave][0][1][t][g][4 * kq]);
+        const half4v s4 = *reinterpret_cast<const half4v*>(&lds_ks[wave][t][g][4 * kq]);
+        const half4v z4 = *reinterpret_cast<const half4v*>(&lds_kz[wave][t][g][4 * kq]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float e = fmaf(-(float)z4[i], qsum[a], acc[a][i]);
@@ -289,8 +325,11 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
         if constexpr (C::GR >= 2) x = row_ror_add<8>(x);
         if constexpr (C::GR >= 4) x = row_ror_add<4>(x);
         if constexpr (C::GR >= 8) x = row_ror_add<2>(x);
-        const int tok = base + 16 * t + tok_of_row(4 * kq + i);
-        sc[t][i] = (tok < end) ? x : -INFINITY;
+        if constexpr (TAIL) {
+          const int tok = begin + sidx * 32 + 16 * t + tok_of_row(4 * kq + i);
+          x = (tok < end) ? x : -INFINITY;
+        }
+        sc[t][i] = x;
       }
     }
 
@@ -329,8 +368,29 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
         l_run += pr[t][i];
       }
 
-    // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages)
-    half8v vop[NCS][8];
+    // -- P V with rows (head, replica): A = fp16(p * s_v) for the lane's group of each pass
+    half8v pa[NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+      const int g = rep * NA + a;
+      const float4v s0 = *reinterpret_cast<const float4v*>(&lds_vs[wave][0][g][4 * kq]);
+      const float4v s1 = *reinterpret_cast<const float4v*>(&lds_vs[wave][1][g][4 * kq]);
+      const float4v z0 = *reinterpret_cast<const float4v*>(&lds_vz[wave][0][g][4 * kq]);
+      const float4v z1 = *reinterpret_cast<const float4v*>(&lds_vz[wave][1][g][4 * kq]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {             // fma(p, s, 0) rounded once to fp16 (v_fma_mixlo/hi_f16)
+        pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], s0[i], 0.0f);
+        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], s1[i], 0.0f);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {             // zero-point term from the SAME rounded operand
+        zacc[a] = fmaf((float)pa[a][2 * i], z0[i], zacc[a]);
+        zacc[a] = fmaf((float)pa[a][2 * i + 1], z1[i], zacc[a]);
+      }
+    }
+
+    // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
+    //    consumed two dims at a time so that few unpacked operands are live
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
       uint32_t x[8], y[8];
@@ -350,43 +410,37 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
 #pragma unroll
       for (int I = 0; I < 4; ++I) {
         const uint32_t r0 = y[2 * I], r1 = y[2 * I + 1], s0 = r0 >> 8, s1 = r1 >> 8;
-        vop[cs][2 * I] = as_half8(r0 & kMaskLo, r1 & kMaskLo, s0 & kMaskLo, s1 & kMaskLo);
-        vop[cs][2 * I + 1] = as_half8(r0 & kMaskHi, r1 & kMaskHi, s0 & kMaskHi, s1 & kMaskHi);
+        const half8v v_even = as_half8(r0 & kMaskLo, r1 & kMaskLo, s0 & kMaskLo, s1 & kMaskLo);
+        const half8v v_odd = as_half8(r0 & kMaskHi, r1 & kMaskHi, s0 & kMaskHi, s1 & kMaskHi);
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          oacc[cs][2 * I][a] = mfma16(pa[a], v_even, oacc[cs][2 * I][a]);
+          oacc[cs][2 * I + 1][a] = mfma16(pa[a], v_odd, oacc[cs][2 * I + 1][a]);
+        }
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          oacc[cs][2 * I][a] = mfma16(pa[a], neg8_lo, oacc[cs][2 * I][a]);
+          oacc[cs][2 * I + 1][a] = mfma16(pa[a], neg8_hi, oacc[cs][2 * I + 1][a]);
+        }
       }
     }
+  };
 
-    // -- P V with rows (head, replica): A = fp16(p * s_v) for the lane's group of this pass
-#pragma unroll
-    for (int a = 0; a < NA; ++a) {
-      const int g = rep * NA + a;
-      const half4v s0 = *reinterpret_cast<const half4v*>(&lds_sz[wave][1][0][0][g][4 * kq]);
-      const half4v s1 = *reinterpret_cast<const half4v*>(&lds_sz[wave][1][0][1][g][4 * kq]);
-      const half4v z0 = *reinterpret_cast<const half4v*>(&lds_sz[wave][1][1][0][g][4 * kq]);
-      const half4v z1 = *reinterpret_cast<const half4v*>(&lds_sz[wave][1][1][1][g][4 * kq]);
-      half8v pa;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const _Float16 a0 = (_Float16)(pr[0][i] * (float)s0[i]);
-        const _Float16 a1 = (_Float16)(pr[1][i] * (float)s1[i]);
-        pa[2 * i] = a0;
-        pa[2 * i + 1] = a1;
-        zacc[a] = fmaf((float)a0, (float)z0[i] - 8.0f, zacc[a]);
-        zacc[a] = fmaf((float)a1, (float)z1[i] - 8.0f, zacc[a]);
-      }
-#pragma unroll
-      for (int cs = 0; cs < NCS; ++cs) {
-#pragma unroll
-        for (int m = 0; m < 8; ++m) oacc[cs][m][a] = mfma16(pa, vop[cs][m], oacc[cs][m][a]);
-#pragma unroll
-        for (int m = 0; m < 8; ++m) oacc[cs][m][a] = mfma16(pa, (m & 1) ? neg8_hi : neg8_lo, oacc[cs][m][a]);
-      }
-    }
-
-    if (has_next) cur = nxt;
+  // ---- main loop over this wave's whole supertiles (wave, wave+4, ...), two register stages in ping-pong
+  for (int sidx = wave; sidx < n_full; sidx += 8) {
+    if (sidx + 4 < n_full) load_stage(stB, sidx + 4, std::false_type{});
+    process(stA, sidx, std::false_type{});
+    if (sidx + 4 >= n_full) break;
+    if (sidx + 8 < n_full) load_stage(stA, sidx + 8, std::false_type{});
+    process(stB, sidx + 4, std::false_type{});
+  }
+  if (has_tail && (n_full & 3) == wave) {                    // the ragged last supertile of the sequence
+    load_stage(stA, n_full, std::true_type{});
+    process(stA, n_full, std::true_type{});
   }
 
   // ---- wave result -> LDS
-  const bool active = wave < n_super;
+  const bool active = wave < n_full + (has_tail ? 1 : 0);
   const float l_tot = blocks_sum(l_run);
 #pragma unroll
   for (int a = 0; a < NA; ++a) zacc[a] = blocks_sum(zacc[a]);
