@@ -151,7 +151,10 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
   const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, plan);
   if (n_splits_out) *n_splits_out = plan.n_splits;
   const int variant = opts ? opts->variant : 0;
-  const bool use_mfma = variant == 2 || (variant == 0 && tq::mfma_supported(cache->head_dim, p.gqa));
+  // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
+  const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
+  if (variant == 2 && !scale_ok) return TQ_ERR_UNSUPPORTED;
+  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && tq::mfma_supported(cache->head_dim, p.gqa));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));

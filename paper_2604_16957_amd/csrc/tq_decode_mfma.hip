@@ -48,6 +48,7 @@ typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
 constexpr float kNegBig = -1.0e30f;
+constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
 constexpr uint32_t kMaskLo = 0x000F000Fu;   // nibbles 0 and 4 of a word -> fp16 subnormals c * 2^-24
 constexpr uint32_t kMaskHi = 0x00F000F0u;   // nibbles 1 and 5           -> c * 2^-20
 constexpr uint32_t kNeg8Lo = 0x80088008u;   // two fp16 of value -8 * 2^-24
@@ -251,6 +252,7 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
     qsum[a] = (hl < G) ? s * 0x1p-24f : 0.0f;
   }
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
+  const float slack = kSlack / kappa;             // the rescale slack in raw units
 
   // ---- running state
   float m_run = kNegBig;                          // running max of this lane's head, raw units
@@ -333,12 +335,15 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
       }
     }
 
-    // -- online softmax over the 32 tokens (Alg. 1 lines 6-7, 10), block-wise with an exact running max
-    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
-                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-    mx = blocks_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {      // some head's max moved: rescale (rare)
-      const float m_new = fmaxf(m_run, mx);
+    // -- online softmax over the 32 tokens (Alg. 1 lines 6-7, 10), block-wise.  m_run is a per-head
+    //    REFERENCE, not the exact running max: it only moves when some score exceeds it by more than
+    //    kSlack (log2 units), so exp2(score - m_run) <= 2^kSlack = 4 and p * s_v stays inside fp16 for
+    //    every representable scale, while the accumulator rescale (Alg. 1 lines 7, 9) becomes rare.
+    //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.
+    const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                           fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {   // wave-uniform, rare
+      const float m_new = fmaxf(m_run, blocks_max(mx));
       const float f = __builtin_amdgcn_exp2f((m_run - m_new) * kappa);
       m_run = m_new;
       l_run *= f;
