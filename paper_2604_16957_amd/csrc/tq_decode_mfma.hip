@@ -3,19 +3,25 @@
 // Why matrix cores: with a GQA group of G query heads every stored element is used by G heads;
 // at G=8 and d=128 that is 25.6 flop per HBM byte, above the vector-ALU ridge of the chip, so the
 // two contractions (Alg. 1 lines 5 and 9) run on v_mfma_f32_16x16x32_f16 and the vector ALU only
-// unpacks nibbles, applies the per-group scale/zero-point and does the softmax.
+// unpacks nibbles, applies the per-group scale/zero-point of K and does the softmax.
+//
+// Data path: the packed stream never passes through vector registers on its way in.  Each wave owns
+// a ring of LDS stages and fills them with direct global->LDS loads (global_load_lds_dwordx4: 64
+// lanes x 16 B = 1 KB per instruction, tracked by vmcnt), two to three 32-token supertiles ahead
+// of the one being consumed, so ~10 KB per wave are in flight with no register cost.
 //
 // Exactness: codes 0..15 enter the MFMA as fp16 SUBNORMALS (the nibble sits in the low mantissa
 // bits, value c*2^-24, or c*2^-20 for a nibble at bit 4) so unpacking is one AND per pair of
 // elements; products and sums are exact in the fp32 accumulator.  Scale and zero-point are applied
-// outside the contraction in fp32:  q.k^ = sum_g s_g (q_g.c_g - z_g sum(q_g))  and
+// outside the contraction:  q.k^ = sum_g s_g (q_g.c_g - z_g sum(q_g))  in fp32 on the vector ALU, and
 // sum_t p_t v^_t = sum_t (p_t s_t) c_t - sum_t (p_t s_t) z_t, where the product p_t s_t is rounded
-// to fp16 once and the SAME rounded value is used in both terms.
+// to fp16 once and the SAME rounded operand multiplies the codes and (in a small extra MFMA whose
+// B operand is the stored fp16 zero-point itself) the zero-points.
 // The matrix core truncates when it adds into the fp32 accumulator (measured: about -0.3 ulp per
-// step), and sum_t (p_t s_t) c_t is a sum of positive terms ~200x larger than the result, so the
-// codes are centred inside the accumulator: every P V step is followed by a second MFMA of the same
-// A operand against the constant -8 (the matrix pipe is otherwise ~15% busy), and the zero-point
-// term uses z - 8.  The running sum then stays at the size of the result.
+// step), and both sums are sums of positive terms ~200x larger than the result, so they are centred
+// inside the accumulator: every such MFMA is followed by one of the same A operand against the
+// constant -8 (the matrix pipe is otherwise mostly idle).  The running sums stay at the size of
+// the result.
 //
 // Mapping (one 64-lane wave; lane = 16*kq + c):
 //   QK^T is computed transposed, S^T = K Q^T: A = codes (row = token, 8 k-slots per lane = one packed
@@ -27,7 +33,7 @@
 //   the A-operand layout of P V when P V is computed as rows (h, r) x columns (dims): lane (h, r) of
 //   block kq already holds the probabilities of its 8 tokens, so they never move between lanes.
 //   For P V the contraction runs over tokens, so each lane needs 8 tokens of one dim in its k-slots:
-//   it loads the same packed word of 8 tokens and transposes 8x8 nibbles with two v_perm_b32 stages;
+//   it reads the same packed word of 8 tokens and transposes 8x8 nibbles with two v_perm_b32 stages;
 //   the nibble-level stage is free because the unpack masks already separate even and odd nibbles.
 //
 // Work split: grid (n_splits, H_kv, B), 4 waves per block; the waves of a block interleave
@@ -41,11 +47,9 @@ namespace tq {
 namespace {
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef _Float16 half4v __attribute__((ext_vector_type(4)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
-typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
 constexpr float kNegBig = -1.0e30f;
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
@@ -53,6 +57,7 @@ constexpr uint32_t kMaskLo = 0x000F000Fu;   // nibbles 0 and 4 of a word -> fp16
 constexpr uint32_t kMaskHi = 0x00F000F0u;   // nibbles 1 and 5           -> c * 2^-20
 constexpr uint32_t kNeg8Lo = 0x80088008u;   // two fp16 of value -8 * 2^-24
 constexpr uint32_t kNeg8Hi = 0x80808080u;   // two fp16 of value -8 * 2^-20
+constexpr uint32_t kNeg8 = 0xC800C800u;     // two fp16 of value -8
 
 template <int D, int GP>
 struct Cfg {
@@ -62,7 +67,7 @@ struct Cfg {
   static constexpr int NJ = NG;                  // K MFMAs per 16-token tile (= packed words per lane)
   static constexpr int NCS = D / 128;            // V column sets (16 packed words each)
   static constexpr bool SWAP = (D == 128 && GP == 8);
-  static_assert(NG % GR == 0 && NA >= 1, "unsupported (head_dim, padded GQA) pair");
+  static_assert(NG % GR == 0 && NA >= 1 && NA <= 2, "unsupported (head_dim, padded GQA) pair");
   // K MFMA j takes, from lane block kq, packed word a_word(j,kq) of group a_group(j,kq) and adds
   // into accumulator acc(j); column replica r of that accumulator stands for group r*NA + acc(j).
   static __device__ constexpr int a_group(int j, int kq) {
@@ -72,12 +77,25 @@ struct Cfg {
     return SWAP ? 2 * (j >> 1) + (kq & 1) : (D == 128 ? j : (j & 3));
   }
   static __device__ constexpr int acc(int j) { return SWAP ? (j & 1) : (D == 128 ? 0 : (NA == 2 ? (j >> 2) : 0)); }
+
+  // LDS stage of one 32-token supertile, in the order the stream is laid out in HBM
+  static constexpr int TB = D / 2;               // bytes of codes per token
+  static constexpr int KT = 16 * TB;             // one 16-token K tile
+  static constexpr int VB = 32 * TB;             // V codes of the supertile
+  static constexpr int SZ = 32 * NG * 2;         // one fp16 scale (or zero-point) array of the supertile
+  static constexpr int OFF_V = 2 * KT, OFF_KS = OFF_V + VB, OFF_KZ = OFF_KS + SZ, OFF_VS = OFF_KZ + SZ,
+                       OFF_VZ = OFF_VS + SZ, STAGE = OFF_VZ + SZ;
+  static constexpr int NS = (D == 128) ? 3 : 2;  // ring depth per wave
+  static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
+  static constexpr int RING = 4 * NS * STAGE;
+  static constexpr int MERGE = (4 * GP * D + 4 * GP * NG + 2 * 4 * GP) * 4;  // o, zero-point term, m, l
+  static constexpr int SMEM = RING > MERGE ? RING : MERGE;                   // the merge area reuses the rings
 };
 
-// token held by row r of a 16-token K tile (and by the matching k-slots of the P V contraction);
-// chosen so that one V load instruction of the wave covers 4 consecutive tokens
+// token held by row r of a 16-token K tile (and by the matching k-slots of the P V contraction):
+// lane block kq then owns tokens kq, kq+4, kq+8, kq+12 of each tile, which keeps the four blocks'
+// LDS reads of the V codes on different banks
 __device__ __forceinline__ constexpr int tok_of_row(int r) { return 4 * (r & 3) + (r >> 2); }
-__device__ __forceinline__ constexpr int row_of_tok(int t) { return 4 * (t & 3) + (t >> 2); }
 
 __device__ __forceinline__ half8v as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return __builtin_bit_cast(half8v, uint4v{a, b, c, d});
@@ -126,20 +144,36 @@ __device__ __forceinline__ float row_ror_add(float x) {      // x + (x rotated b
   return x + __builtin_bit_cast(float, y);
 }
 
-// one 32-token supertile of raw loads, kept in registers while in flight
-template <int D>
-struct Stage {
-  uint4v k[2][D / 128];        // K codes: tile, 16-byte chunk
-  uint32_t v[D / 128][8];      // V codes: column set, token slot
-  uint32_t ksz[D / 64];        // K scale (lanes 0-31) or zero-point (lanes 32-63) of one token
-  uint32_t vsz[D / 64];
-};
+// ---- direct global -> LDS loads.  Written as asm so that the compiler does not serialise them
+// against later LDS reads: each wave tracks its own ring with explicit vmcnt waits instead.
+// Lane l's bytes land at lds_base + l * (16 | 4).  M0 carries the LDS base of the instruction.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma16_lane(const void* addr, uint32_t lds_base) {   // per-lane 64-bit address
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(addr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma4_lane(const void* addr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(addr), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {               // until at most N loads are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
 
 template <int D, int GP>
 __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParams p) {
   using C = Cfg<D, GP>;
-  constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS;
-  constexpr int TB = D / 2;                       // bytes of codes per token
+  constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, kq = lane >> 4;
@@ -147,16 +181,9 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   const int split = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
   const int G = p.gqa;
 
-  // wave-private LDS: scales / zero-points of one supertile as [tile][group][row]; K as fp16,
-  // V as fp32 with the zero-point already shifted by -8.  Then the block-shared merge area.
-  __shared__ __attribute__((aligned(16))) _Float16 lds_ks[4][2][NG][16];
-  __shared__ __attribute__((aligned(16))) _Float16 lds_kz[4][2][NG][16];
-  __shared__ __attribute__((aligned(16))) float lds_vs[4][2][NG][16];
-  __shared__ __attribute__((aligned(16))) float lds_vz[4][2][NG][16];
-  __shared__ float lds_f[4][16];
-  __shared__ float lds_o[4][GP][D];
-  __shared__ float lds_zc[4][GP][NG];
-  __shared__ float lds_m[4][GP], lds_l[4][GP];
+  char* const ring = smem + wave * (NS * C::STAGE);
+  const uint32_t ring_lds =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * (NS * C::STAGE);
 
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
@@ -167,16 +194,17 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   const int last_tok = p.seq_len - 1;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
-  const uint32_t koff = tok_of_row(c) * TB + kq * (D / 8);
-  const uint32_t voff = kq * TB + c * 4 * NCS;
-  const int sz_tok = lane & 31;                   // token (within the supertile) whose scales this lane fetches
-  const int which = lane >> 5;                    // 0: this lane fetches scales, 1: zero-points
-  const char* ksz_row = reinterpret_cast<const char*>(which ? p.k_zero : p.k_scale) + row0 * (NG * 2);
-  const char* vsz_row = reinterpret_cast<const char*>(which ? p.v_zero : p.v_scale) + row0 * (NG * 2);
+  const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),
+                           reinterpret_cast<const char*>(p.k_zero) + row0 * (NG * 2),
+                           reinterpret_cast<const char*>(p.v_scale) + row0 * (NG * 2),
+                           reinterpret_cast<const char*>(p.v_zero) + row0 * (NG * 2)};
+  const uint32_t koff = tok_of_row(c) * TB + kq * (D / 8);   // this lane's 16 B (x D/128) of a K tile
 
-  auto load_stage = [&](Stage<D>& st, int sidx, auto tail_tag) {
+  // fills ring slot `slot` with supertile `sidx`: LPS load instructions, all 64 lanes each
+  auto issue = [&](int slot, int sidx, auto tail_tag) {
     constexpr bool TAIL = decltype(tail_tag)::value;
     const int base = begin + sidx * 32;
+    const uint32_t l = ring_lds + slot * C::STAGE;
     if constexpr (!TAIL) {
       const char* kb = kc_row + (int64_t)base * TB;
       const char* vb = vc_row + (int64_t)base * TB;
@@ -184,54 +212,66 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int ch = 0; ch < D / 128; ++ch)
-          st.k[t][ch] = *reinterpret_cast<const uint4v*>(kb + koff + t * 16 * TB + ch * 16);
+          dma16(kb + t * 16 * TB + ch * 16, koff, l + t * C::KT + ch * 1024);
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int u = 0; u < C::VB / 1024; ++u) dma16(vb + u * 1024, lane * 16, l + C::OFF_V + u * 1024);
 #pragma unroll
-        for (int cs = 0; cs < NCS; ++cs)
-          st.v[cs][i] = *reinterpret_cast<const uint32_t*>(vb + voff + (16 * (i >> 2) + 4 * (i & 3)) * TB + cs * 4);
-      const int64_t so = (int64_t)(base + sz_tok) * (NG * 2);
+      for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int i = 0; i < D / 64; ++i) {
-        st.ksz[i] = *reinterpret_cast<const uint32_t*>(ksz_row + so + i * 4);
-        st.vsz[i] = *reinterpret_cast<const uint32_t*>(vsz_row + so + i * 4);
-      }
+        for (int u = 0; u < C::SZ / 256; ++u)
+          dma4(sz_row[a] + (int64_t)base * (NG * 2) + u * 256, lane * 4, l + C::OFF_KS + a * C::SZ + u * 256);
     } else {                                      // ragged tail: clamp every token to the last valid one
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
 #pragma unroll
         for (int ch = 0; ch < D / 128; ++ch)
-          st.k[t][ch] = *reinterpret_cast<const uint4v*>(kc_row + (int64_t)tok * TB + kq * (D / 8) + ch * 16);
+          dma16_lane(kc_row + (int64_t)tok * TB + kq * (D / 8) + ch * 16, l + t * C::KT + ch * 1024);
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int tok = min(base + 16 * (i >> 2) + 4 * (i & 3) + kq, last_tok);
-#pragma unroll
-        for (int cs = 0; cs < NCS; ++cs)
-          st.v[cs][i] = *reinterpret_cast<const uint32_t*>(vc_row + (int64_t)tok * TB + c * 4 * NCS + cs * 4);
+      for (int u = 0; u < C::VB / 1024; ++u) {
+        const int chunk = u * 64 + lane;          // 16-byte chunk of the supertile's V codes
+        const int tok = min(base + chunk / (TB / 16), last_tok);
+        dma16_lane(vc_row + (int64_t)tok * TB + (chunk % (TB / 16)) * 16, l + C::OFF_V + u * 1024);
       }
-      const int64_t so = (int64_t)min(base + sz_tok, last_tok) * (NG * 2);
 #pragma unroll
-      for (int i = 0; i < D / 64; ++i) {
-        st.ksz[i] = *reinterpret_cast<const uint32_t*>(ksz_row + so + i * 4);
-        st.vsz[i] = *reinterpret_cast<const uint32_t*>(vsz_row + so + i * 4);
-      }
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int u = 0; u < C::SZ / 256; ++u) {
+          const int dw = u * 64 + lane;           // dword of the supertile's scale array
+          const int tok = min(base + dw / (NG / 2), last_tok);
+          dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + (dw % (NG / 2)) * 4,
+                    l + C::OFF_KS + a * C::SZ + u * 256);
+        }
     }
   };
 
-  // first loads go out before the query set-up so that their latency overlaps it
-  Stage<D> stA, stB;
-  if (wave < n_full) load_stage(stA, wave, std::false_type{});
+  // ---- this wave's supertiles: wave, wave+4, ... among the chunk's whole ones, then maybe the tail
+  const int n_mine = (n_full > wave) ? (n_full - wave + 3) >> 2 : 0;
+  const bool my_tail = has_tail && (n_full & 3) == wave;
 
-  // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
+  // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query);
+  //      their loads go out first, then the first ring stages, and only then are they consumed
   const _Float16* qh = p.q + (int64_t)(b * p.n_q_heads + kv * G + (hl < G ? hl : 0)) * D;
+  half8v qraw[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+    qraw[j] = *reinterpret_cast<const half8v*>(qh + C::a_group(j, kq) * kGroup + C::a_word(j, kq) * 8);
+  half8v qgrp[NA][4];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qgrp[a][i] = *reinterpret_cast<const half8v*>(qh + (rep * NA + a) * kGroup + i * 8);
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_mine) issue(s, wave + 4 * s, std::false_type{});
+
   half8v qb[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int g = C::a_group(j, kq), w = C::a_word(j, kq);
-    const bool mine = (g == rep * NA + C::acc(j)) && hl < G;
-    half8v x = *reinterpret_cast<const half8v*>(qh + g * kGroup + w * 8);
+    const bool mine = (C::a_group(j, kq) == rep * NA + C::acc(j)) && hl < G;
+    const half8v x = qraw[j];
     // k-slot order of unpack_word: nibbles 0,4,1,5,2,6,3,7; the "hi" slots carry c*2^-20, so pre-divide by 16
     half8v y = {x[0], x[4], x[1] * (_Float16)0.0625f, x[5] * (_Float16)0.0625f,
                 x[2], x[6], x[3] * (_Float16)0.0625f, x[7] * (_Float16)0.0625f};
@@ -242,25 +282,22 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
     float s = 0.0f;
-    const half8v* qg = reinterpret_cast<const half8v*>(qh + (rep * NA + a) * kGroup);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const half8v x = qg[i];
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += (float)x[e];
-    }
+      for (int e = 0; e < 8; ++e) s += (float)qgrp[a][i][e];
     qsum[a] = (hl < G) ? s * 0x1p-24f : 0.0f;
   }
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
 
   // ---- running state
-  float m_run = kNegBig;                          // running max of this lane's head, raw units
+  float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
   float l_run = 0.0f;                             // this lane's share of sum(exp)
-  float zacc[NA];
+  float4v zacc[NA];                               // sum_t (p s_v)(z_v - 8), rows (head, replica), col = group
+  float4v oacc[NCS][8][NA];                       // sum_t (p s_v)(c - 8), rows (head, replica), col = packed word
 #pragma unroll
-  for (int a = 0; a < NA; ++a) zacc[a] = 0.0f;
-  float4v oacc[NCS][8][NA];
+  for (int a = 0; a < NA; ++a) zacc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
   for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
@@ -270,26 +307,17 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
 
   const half8v neg8_lo = as_half8(kNeg8Lo, kNeg8Lo, kNeg8Lo, kNeg8Lo);
   const half8v neg8_hi = as_half8(kNeg8Hi, kNeg8Hi, kNeg8Hi, kNeg8Hi);
+  const half8v neg8 = as_half8(kNeg8, kNeg8, kNeg8, kNeg8);
 
-  // LDS destinations of this lane's scale / zero-point token (constant over the loop)
-  const int sz_slot = (sz_tok >> 4) * (NG * 16) + row_of_tok(sz_tok & 15);
-  _Float16* const k_dst = (which ? &lds_kz[wave][0][0][0] : &lds_ks[wave][0][0][0]) + sz_slot;
-  float* const v_dst = (which ? &lds_vz[wave][0][0][0] : &lds_vs[wave][0][0][0]) + sz_slot;
-  const float v_shift = which ? -8.0f : 0.0f;
+  // per-lane LDS byte offsets inside a stage
+  const uint32_t k_rd = lane * 16;                                  // the 16 B this lane asked for
+  const uint32_t v_rd = kq * TB + c * 4 * NCS;                      // packed word(s) c of token kq (+4i)
+  const uint32_t sz_rd = (kq * NG + rep * NA) * 2;                  // this lane's groups of token kq (+4i)
+  const uint32_t zb_rd = (kq * NG + (c % NG)) * 2;                  // zero-point of group c%NG, token kq (+4i)
 
-  auto process = [&](const Stage<D>& cur, int sidx, auto tail_tag) {
+  auto process = [&](int slot, int sidx, auto tail_tag) {
     constexpr bool TAIL = decltype(tail_tag)::value;
-    // -- scales and zero-points: one token per lane -> LDS, transposed to [group][row]
-#pragma unroll
-    for (int i = 0; i < D / 64; ++i) {
-      const half2v ks = __builtin_bit_cast(half2v, cur.ksz[i]);
-      const half2v vs = __builtin_bit_cast(half2v, cur.vsz[i]);
-      k_dst[(2 * i) * 16] = ks[0];
-      k_dst[(2 * i + 1) * 16] = ks[1];
-      v_dst[(2 * i) * 16] = (float)vs[0] + v_shift;
-      v_dst[(2 * i + 1) * 16] = (float)vs[1] + v_shift;
-    }
-    __builtin_amdgcn_wave_barrier();   // LDS is in order per wave; only the compiler must not reorder
+    const char* st = ring + slot * C::STAGE;
 
     // -- scores, S^T = K Q^T, per-group scale and zero-point applied in fp32 (raw units: 2^-24)
     float sc[2][4];
@@ -297,29 +325,40 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
     for (int t = 0; t < 2; ++t) {
       uint32_t w[NJ];
       if constexpr (C::SWAP) {
-        auto s01 = __builtin_amdgcn_permlane16_swap(cur.k[t][0][0], cur.k[t][0][1], false, false);
-        auto s23 = __builtin_amdgcn_permlane16_swap(cur.k[t][0][2], cur.k[t][0][3], false, false);
+        const uint4v kw = *reinterpret_cast<const uint4v*>(st + t * C::KT + k_rd);
+        auto s01 = __builtin_amdgcn_permlane16_swap(kw[0], kw[1], false, false);
+        auto s23 = __builtin_amdgcn_permlane16_swap(kw[2], kw[3], false, false);
         w[0] = s01[0]; w[1] = s01[1]; w[2] = s23[0]; w[3] = s23[1];
       } else {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) w[j] = cur.k[t][j >> 2][j & 3];
+        for (int ch = 0; ch < D / 128; ++ch) {
+          const uint4v kw = *reinterpret_cast<const uint4v*>(st + t * C::KT + ch * 1024 + k_rd);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) w[ch * 4 + i] = kw[i];
+        }
       }
       float4v acc[NA];
 #pragma unroll
       for (int a = 0; a < NA; ++a) acc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
       for (int j = 0; j < NJ; ++j) acc[C::acc(j)] = mfma16(unpack_word(w[j]), qb[j], acc[C::acc(j)]);
-      float part[4] = {0, 0, 0, 0};
+      float part[4];
 #pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        const int g = rep * NA + a;
-        const half4v s4 = *reinterpret_cast<const half4v*>(&lds_ks[wave][t][g][4 * kq]);
-        const half4v z4 = *reinterpret_cast<const half4v*>(&lds_kz[wave][t][g][4 * kq]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float e = fmaf(-(float)z4[i], qsum[a], acc[a][i]);
-          part[i] = fmaf((float)s4[i], e, part[i]);
+      for (int i = 0; i < 4; ++i) {               // token 16t + 4i + kq
+        const char* sp = st + C::OFF_KS + (t * 16 + i * 4) * NG * 2 + sz_rd;
+        const char* zp = st + C::OFF_KZ + (t * 16 + i * 4) * NG * 2 + sz_rd;
+        float x = 0.0f;
+        if constexpr (NA == 2) {
+          const half2v s2 = *reinterpret_cast<const half2v*>(sp);
+          const half2v z2 = *reinterpret_cast<const half2v*>(zp);
+          x = (float)s2[0] * fmaf(-(float)z2[0], qsum[0], acc[0][i]);
+          x = fmaf((float)s2[1], fmaf(-(float)z2[1], qsum[NA - 1], acc[NA - 1][i]), x);
+        } else {
+          const _Float16 s1 = *reinterpret_cast<const _Float16*>(sp);
+          const _Float16 z1 = *reinterpret_cast<const _Float16*>(zp);
+          x = (float)s1 * fmaf(-(float)z1, qsum[0], acc[0][i]);
         }
+        part[i] = x;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -347,13 +386,13 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
       const float f = __builtin_amdgcn_exp2f((m_run - m_new) * kappa);
       m_run = m_new;
       l_run *= f;
+      float fr[4];                                           // accumulator row 4kq+i belongs to head (4kq+i) % GP
 #pragma unroll
-      for (int a = 0; a < NA; ++a) zacc[a] *= f;
-      if (kq == 0) lds_f[wave][c] = f;                       // c = (head, replica): same f for all replicas
-      __builtin_amdgcn_wave_barrier();
-      float fr[4];
+      for (int i = 0; i < 4; ++i) fr[i] = __shfl(f, (4 * kq + i) % GP);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fr[i] = lds_f[wave][(4 * kq + i) % GP];
+      for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) zacc[a][i] *= fr[i];
 #pragma unroll
       for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
@@ -373,36 +412,45 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
         l_run += pr[t][i];
       }
 
-    // -- P V with rows (head, replica): A = fp16(p * s_v) for the lane's group of each pass
+    // -- A = fp16(p * s_v), rows (head, replica), one operand per group of the lane; the zero-point
+    //    term goes through the matrix core with the stored fp16 zero-points as B operand
     half8v pa[NA];
+    half8v zb;
 #pragma unroll
-    for (int a = 0; a < NA; ++a) {
-      const int g = rep * NA + a;
-      const float4v s0 = *reinterpret_cast<const float4v*>(&lds_vs[wave][0][g][4 * kq]);
-      const float4v s1 = *reinterpret_cast<const float4v*>(&lds_vs[wave][1][g][4 * kq]);
-      const float4v z0 = *reinterpret_cast<const float4v*>(&lds_vz[wave][0][g][4 * kq]);
-      const float4v z1 = *reinterpret_cast<const float4v*>(&lds_vz[wave][1][g][4 * kq]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {             // fma(p, s, 0) rounded once to fp16 (v_fma_mixlo/hi_f16)
-        pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], s0[i], 0.0f);
-        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], s1[i], 0.0f);
+    for (int i = 0; i < 4; ++i) {                 // tokens 4i + kq (tile 0) and 16 + 4i + kq (tile 1)
+      const char* s0 = st + C::OFF_VS + (i * 4) * NG * 2 + sz_rd;
+      const char* s1 = st + C::OFF_VS + (16 + i * 4) * NG * 2 + sz_rd;
+      if constexpr (NA == 2) {
+        const half2v a0 = *reinterpret_cast<const half2v*>(s0);
+        const half2v a1 = *reinterpret_cast<const half2v*>(s1);
+        pa[0][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)a0[0], 0.0f);
+        pa[0][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)a1[0], 0.0f);
+        pa[NA - 1][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)a0[1], 0.0f);
+        pa[NA - 1][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)a1[1], 0.0f);
+      } else {
+        pa[0][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)*reinterpret_cast<const _Float16*>(s0), 0.0f);
+        pa[0][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)*reinterpret_cast<const _Float16*>(s1), 0.0f);
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {             // zero-point term from the SAME rounded operand
-        zacc[a] = fmaf((float)pa[a][2 * i], z0[i], zacc[a]);
-        zacc[a] = fmaf((float)pa[a][2 * i + 1], z1[i], zacc[a]);
-      }
+      zb[2 * i] = *reinterpret_cast<const _Float16*>(st + C::OFF_VZ + (i * 4) * NG * 2 + zb_rd);
+      zb[2 * i + 1] = *reinterpret_cast<const _Float16*>(st + C::OFF_VZ + (16 + i * 4) * NG * 2 + zb_rd);
     }
+#pragma unroll
+    for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], zb, zacc[a]);
+#pragma unroll
+    for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], neg8, zacc[a]);
 
     // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
     //    consumed two dims at a time so that few unpacked operands are live
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
-      uint32_t x[8], y[8];
+      uint32_t v[8], x[8], y[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)               // token slot i: token 16*(i/4) + 4*(i%4) + kq
+        v[i] = *reinterpret_cast<const uint32_t*>(st + C::OFF_V + (16 * (i >> 2) + 4 * (i & 3)) * TB + v_rd + cs * 4);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        x[i] = __builtin_amdgcn_perm(cur.v[cs][i + 4], cur.v[cs][i], 0x05040100u);
-        x[i + 4] = __builtin_amdgcn_perm(cur.v[cs][i + 4], cur.v[cs][i], 0x07060302u);
+        x[i] = __builtin_amdgcn_perm(v[i + 4], v[i], 0x05040100u);
+        x[i + 4] = __builtin_amdgcn_perm(v[i + 4], v[i], 0x07060302u);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -431,45 +479,49 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
     }
   };
 
-  // ---- main loop over this wave's whole supertiles (wave, wave+4, ...), two register stages in ping-pong
-  for (int sidx = wave; sidx < n_full; sidx += 8) {
-    if (sidx + 4 < n_full) load_stage(stB, sidx + 4, std::false_type{});
-    process(stA, sidx, std::false_type{});
-    if (sidx + 4 >= n_full) break;
-    if (sidx + 8 < n_full) load_stage(stA, sidx + 8, std::false_type{});
-    process(stB, sidx + 4, std::false_type{});
+  // ---- main loop: keep NS-1 stages in flight ahead of the one being consumed
+  for (int k = 0; k < n_mine; ++k) {
+    if (k + NS - 1 < n_mine) issue((k + NS - 1) % NS, wave + 4 * (k + NS - 1), std::false_type{});
+    const int later = min(n_mine - 1 - k, NS - 1);           // stages issued after stage k
+    if (later == 2) wait_loads<2 * LPS>();
+    else if (later == 1) wait_loads<LPS>();
+    else wait_loads<0>();
+    process(k % NS, wave + 4 * k, std::false_type{});
   }
-  if (has_tail && (n_full & 3) == wave) {                    // the ragged last supertile of the sequence
-    load_stage(stA, n_full, std::true_type{});
-    process(stA, n_full, std::true_type{});
+  if (my_tail) {                                             // the ragged last supertile of the sequence
+    issue(0, n_full, std::true_type{});
+    wait_loads<0>();
+    process(0, n_full, std::true_type{});
   }
 
-  // ---- wave result -> LDS
-  const bool active = wave < n_full + (has_tail ? 1 : 0);
+  // ---- wave result -> LDS (the merge area reuses the rings, so everybody must be done reading)
+  float* const lds_o = reinterpret_cast<float*>(smem);                 // [4][GP][D]
+  float* const lds_zc = lds_o + 4 * GP * D;                            // [4][GP][NG]
+  float* const lds_m = lds_zc + 4 * GP * NG;                           // [4][GP]
+  float* const lds_l = lds_m + 4 * GP;                                 // [4][GP]
+  __syncthreads();
+  const bool active = n_mine > 0 || my_tail;
   const float l_tot = blocks_sum(l_run);
-#pragma unroll
-  for (int a = 0; a < NA; ++a) zacc[a] = blocks_sum(zacc[a]);
-  if (kq == 0 && hl < GP) {
-    if (rep == 0) {
-      lds_m[wave][hl] = active ? m_run * kappa : kNegBig;
-      lds_l[wave][hl] = active ? l_tot : 0.0f;
-    }
-#pragma unroll
-    for (int a = 0; a < NA; ++a) lds_zc[wave][hl][rep * NA + a] = zacc[a];
+  if (kq == 0 && rep == 0) {
+    lds_m[wave * GP + hl] = active ? m_run * kappa : kNegBig;
+    lds_l[wave * GP + hl] = active ? l_tot : 0.0f;
   }
 #pragma unroll
-  for (int cs = 0; cs < NCS; ++cs) {
-    const int word = c * NCS + cs;                // packed word (8 dims) this lane's column stands for
-    const int g = word >> 2;
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * kq + i, h = r % GP, rp = r / GP;       // accumulator row -> (head, replica)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = 4 * kq + i, h = r % GP, a_mine = g - (r / GP) * NA;
+    for (int a = 0; a < NA; ++a)
+      if (c == rp * NA + a) lds_zc[(wave * GP + h) * NG + c] = zacc[a][i];
+#pragma unroll
+    for (int cs = 0; cs < NCS; ++cs) {
+      const int word = c * NCS + cs;              // packed word (8 dims) this lane's column stands for
+      const int a_mine = (word >> 2) - rp * NA;
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
         if (a == a_mine) {
 #pragma unroll
           for (int m = 0; m < 8; ++m)
-            lds_o[wave][h][word * 8 + m] = oacc[cs][m][a][i] * ((m & 1) ? 0x1p20f : 0x1p24f);
+            lds_o[(wave * GP + h) * D + word * 8 + m] = oacc[cs][m][a][i] * ((m & 1) ? 0x1p20f : 0x1p24f);
         }
       }
     }
@@ -479,15 +531,15 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   // ---- merge the four waves, write one partial per query head (Sec. 3.2)
   for (int idx = threadIdx.x; idx < G * D; idx += 256) {
     const int h = idx / D, j = idx % D;
-    float mg = lds_m[0][h];
+    float mg = lds_m[h];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mg = fmaxf(mg, lds_m[w][h]);
+    for (int w = 1; w < 4; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
     float num = 0.0f, den = 0.0f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float e = __builtin_amdgcn_exp2f(lds_m[w][h] - mg);
-      num = fmaf(lds_o[w][h][j] - lds_zc[w][h][j >> 5], e, num);
-      den = fmaf(lds_l[w][h], e, den);
+      const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
+      num = fmaf(lds_o[(w * GP + h) * D + j] - lds_zc[(w * GP + h) * NG + (j >> 5)], e, num);
+      den = fmaf(lds_l[w * GP + h], e, den);
     }
     const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * p.n_splits + split;
     p.part_o[ph * D + j] = num;
@@ -500,6 +552,20 @@ int padded_gqa(int head_dim, int gqa) {
   return gqa <= 2 ? 2 : (gqa <= 4 ? 4 : 0);
 }
 
+template <int D, int GP>
+hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
+  constexpr int smem = Cfg<D, GP>::SMEM;
+  static bool configured = false;                 // dynamic LDS above 64 KB has to be opted into once
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP>), grid, dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool mfma_supported(int head_dim, int gqa) {
@@ -507,14 +573,13 @@ bool mfma_supported(int head_dim, int gqa) {
 }
 
 hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
-  const dim3 grid(p.n_splits, p.n_kv_heads, batch), block(256);
+  const dim3 grid(p.n_splits, p.n_kv_heads, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
-  if (head_dim == 128 && gp == 8) hipLaunchKernelGGL((decode_partial_mfma_kernel<128, 8>), grid, block, 0, s, p);
-  else if (head_dim == 128 && gp == 4) hipLaunchKernelGGL((decode_partial_mfma_kernel<128, 4>), grid, block, 0, s, p);
-  else if (head_dim == 256 && gp == 4) hipLaunchKernelGGL((decode_partial_mfma_kernel<256, 4>), grid, block, 0, s, p);
-  else if (head_dim == 256 && gp == 2) hipLaunchKernelGGL((decode_partial_mfma_kernel<256, 2>), grid, block, 0, s, p);
-  else return hipErrorNotSupported;
-  return hipGetLastError();
+  if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
+  if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);
+  if (head_dim == 256 && gp == 4) return launch<256, 4>(p, grid, s);
+  if (head_dim == 256 && gp == 2) return launch<256, 2>(p, grid, s);
+  return hipErrorNotSupported;
 }
 
 }  // namespace tq
