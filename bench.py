@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-baseline", action="store_true", help="skip the unfused GPU comparator")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled oracle check")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain device copy of packed_bytes (reference point for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -112,6 +114,22 @@ def main():
     k_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
     kernel_us = statistics.fmean(k_us)
     achieved = packed_bytes / (kernel_us * 1e-6) / 1e9
+    # the same kernel launched back to back (no other kernel or event in between), as a cross-check
+    e0.record()
+    for i in range(args.steps):
+        j = i % args.buffers
+        tq.tq_sdpa_int4_partial(caches[j], qs[j], S, w.attn_scale, ws, **kw)
+    e1.record()
+    torch.cuda.synchronize()
+    kernel_us_b2b = e0.elapsed_time(e1) * 1e3 / args.steps
+
+    if args.calibrate_copy:      # known traffic: reads packed_bytes, writes packed_bytes
+        src = torch.empty(packed_bytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(6):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- unfused comparator on the same inputs
     baseline = None
@@ -183,6 +201,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None, "kernel_us_mean": round(kernel_us, 3),
                      "kernel_us_median": round(statistics.median(k_us), 3),
+                     "kernel_us_back_to_back": round(kernel_us_b2b, 3),
                      "algorithmic_bytes_per_launch": packed_bytes},
         "cpu_baseline": cpu,
         "unfused_gpu_baseline": baseline,
@@ -192,8 +211,9 @@ def main():
     if prof.exists():
         try:
             t = json.loads(prof.read_text()).get(w.name)
-            if t:
-                line["roofline"]["traffic"] = t
+            if t:          # measured with rocprofv3 --pmc, see profiles/*_hbm_traffic.txt
+                line["roofline"]["traffic"] = t["total_bytes"]
+                line["roofline"]["traffic_detail"] = t
         except Exception:
             pass
     print(json.dumps(line), flush=True)

@@ -1,0 +1,85 @@
+#!/usr/bin/env python3
+"""Turns rocprofv3 CSV output of `bench.py` runs into the short text summaries kept under profiles/.
+
+  kernel trace : python bench_profile.py trace  <dir with *_kernel_stats.csv>
+  HBM traffic  : python bench_profile.py traffic <FETCH_SIZE run dir> <WRITE_SIZE run dir> [--json profiles/traffic.json]
+
+The traffic mode expects both runs to come from `bench.py --calibrate-copy`: the plain device copy of
+known size in that run gives the factor between the counter's reading and real bytes.
+"""
+from __future__ import annotations
+
+import csv
+import glob
+import json
+import statistics
+import sys
+
+PARTIAL = "decode_partial_mfma_kernel"
+COPY_KERNEL = "__amd_rocclr_copyBuffer"      # what torch's same-dtype device copy_ launches
+
+
+def _rows(d, suffix):
+    out = []
+    for f in sorted(glob.glob(f"{d}/**/*{suffix}", recursive=True)):
+        out += list(csv.DictReader(open(f)))
+    return out
+
+
+def trace(d):
+    rows = _rows(d, "kernel_stats.csv")
+    print(f"{'kernel':70s} {'calls':>6s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'pct':>7s}")
+    for r in rows:
+        name = r["Name"]
+        if "tq::" not in name and COPY_KERNEL not in name:
+            continue
+        name = name.replace("void tq::(anonymous namespace)::", "").replace("tq::(anonymous namespace)::", "")
+        name = name.split("(")[0][:70]
+        print(f"{name:70s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:10.2f} {float(r['MinNs']) / 1e3:10.2f} "
+              f"{float(r['MaxNs']) / 1e3:10.2f} {float(r['Percentage']):7.2f}")
+
+
+def _counter(d, counter):
+    vals = {}
+    for r in _rows(d, "counter_collection.csv"):
+        if r["Counter_Name"] == counter:
+            vals.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+    return vals
+
+
+def traffic(fetch_dir, write_dir, json_path=None, workload="llama128k", known_bytes=167772160):
+    out = {}
+    for label, d, counter in (("read", fetch_dir, "FETCH_SIZE"), ("write", write_dir, "WRITE_SIZE")):
+        vals = _counter(d, counter)
+        copy = [v for k, vs in vals.items() if COPY_KERNEL in k for v in vs if v * 1024 > 0.25 * known_bytes]
+        part = [v for k, vs in vals.items() if PARTIAL in k for v in vs]
+        part = part[len(part) // 4:]
+        copy_kib, part_kib = statistics.median(copy), statistics.fmean(part)
+        factor = known_bytes / (copy_kib * 1024)
+        out[label] = {"counter": counter, "copy_reading_KiB": copy_kib, "copy_true_bytes": known_bytes,
+                      "factor": factor, "partial_reading_KiB": part_kib, "partial_bytes": part_kib * 1024 * factor}
+        print(f"{counter}: plain copy of {known_bytes} B reads {copy_kib:.0f} KiB -> factor {factor:.3f}; "
+              f"partial kernel reads {part_kib:.0f} KiB per dispatch -> {part_kib * 1024 * factor / 1e6:.2f} MB")
+    total = out["read"]["partial_bytes"] + out["write"]["partial_bytes"]
+    print(f"HBM traffic of the partial kernel: {total / 1e6:.2f} MB per launch "
+          f"(algorithmic {known_bytes / 1e6:.2f} MB packed int4 + scales + zero-points)")
+    if json_path:
+        try:
+            cur = json.load(open(json_path))
+        except Exception:
+            cur = {}
+        cur[workload] = {"read_bytes": round(out["read"]["partial_bytes"]), "write_bytes": round(out["write"]["partial_bytes"]),
+                         "total_bytes": round(total), "read_factor": round(out["read"]["factor"], 4),
+                         "write_factor": round(out["write"]["factor"], 4), "unit": "bytes per launch of the partial kernel"}
+        json.dump(cur, open(json_path, "w"), indent=1)
+        print(f"wrote {json_path}")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "trace":
+        trace(sys.argv[2])
+    elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
+        jp = sys.argv[sys.argv.index("--json") + 1] if "--json" in sys.argv else None
+        traffic(sys.argv[2], sys.argv[3], jp)
+    else:
+        sys.exit(__doc__)
