@@ -28,13 +28,16 @@ int check_cache(const tq_kv_cache* c) {
 
 struct Plan { int n_splits, tokens_per_split; };
 
-// Chunks of whole 32-token tiles, about two blocks per compute unit, never an empty chunk.
-Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested) {
+constexpr int kBlocksMfma = 256;   // matrix-core kernel: 8-wave blocks, one per compute unit
+constexpr int kBlocksValu = 512;   // generic kernel: 4-wave blocks, two per compute unit
+
+// Chunks of whole 32-token tiles, `target_blocks` blocks in all, never an empty chunk.
+Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int target_blocks) {
   const int tiles = (seq_len + tq::kTile - 1) / tq::kTile;
   int n = requested;
   if (n <= 0) {
     const int64_t rows = (int64_t)batch * n_kv_heads;
-    n = (int)std::max<int64_t>(1, (512 + rows - 1) / rows);
+    n = (int)std::max<int64_t>(1, (target_blocks + rows - 1) / rows);
   }
   n = std::max(1, std::min({n, tiles, tq::kMaxSplits}));
   const int tiles_per = (tiles + n - 1) / n;
@@ -112,7 +115,7 @@ size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t 
 
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len) {
   if (batch < 1 || n_kv_heads < 1 || seq_len < 1) return 0;
-  return plan_splits(batch, n_kv_heads, seq_len, 0).n_splits;
+  return plan_splits(batch, n_kv_heads, seq_len, 0, kBlocksMfma).n_splits;
 }
 
 const char* tq_status_string(int status) {
@@ -147,14 +150,16 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
                          int32_t* n_splits_out, void* stream) {
   const int rc = check_decode(cache, q, n_q_heads, seq_len, nullptr, workspace, workspace_bytes, opts, false);
   if (rc != TQ_OK) return rc;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0);
-  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, plan);
-  if (n_splits_out) *n_splits_out = plan.n_splits;
   const int variant = opts ? opts->variant : 0;
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
   const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
   if (variant == 2 && !scale_ok) return TQ_ERR_UNSUPPORTED;
-  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && tq::mfma_supported(cache->head_dim, p.gqa));
+  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok &&
+                                         tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
+                                use_mfma ? kBlocksMfma : kBlocksValu);
+  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, plan);
+  if (n_splits_out) *n_splits_out = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
@@ -203,7 +208,7 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
   half_t* v_dense = k_dense + need / sizeof(half_t) / 2;
   rc = hip_rc(tq::launch_dequant_dense(*cache, seq_len, k_dense, v_dense, s));
   if (rc != TQ_OK) return rc;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0);
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, kBlocksValu);
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   p.k_dense = k_dense;
   p.v_dense = v_dense;

@@ -36,9 +36,10 @@
 //   it reads the same packed word of 8 tokens and transposes 8x8 nibbles with two v_perm_b32 stages;
 //   the nibble-level stage is free because the unpack masks already separate even and odd nibbles.
 //
-// Work split: grid (n_splits, H_kv, B), 4 waves per block; the waves of a block interleave
-// 32-token supertiles of the chunk, keep private online-softmax state, and are merged through LDS
-// so that the block writes one partial (o_c, m_c, l_c) per query head.
+// Work split: grid (n_splits, H_kv, B), 8 waves per block, one block per compute unit; the waves of
+// a block take 32-token supertiles of the chunk from a shared counter, keep private online-softmax
+// state, and are merged through LDS so that the block writes one partial (o_c, m_c, l_c) per query
+// head.
 #include <type_traits>
 
 #include "tq_internal.h"
@@ -59,7 +60,7 @@ constexpr uint32_t kNeg8Lo = 0x80088008u;   // two fp16 of value -8 * 2^-24
 constexpr uint32_t kNeg8Hi = 0x80808080u;   // two fp16 of value -8 * 2^-20
 constexpr uint32_t kNeg8 = 0xC800C800u;     // two fp16 of value -8
 
-template <int D, int GP>
+template <int D, int GP, int NW>
 struct Cfg {
   static constexpr int NG = D / kGroup;          // quantisation groups per token
   static constexpr int GR = 16 / GP;             // group replicas among the 16 columns / rows
@@ -85,11 +86,24 @@ struct Cfg {
   static constexpr int SZ = 32 * NG * 2;         // one fp16 scale (or zero-point) array of the supertile
   static constexpr int OFF_V = 2 * KT, OFF_KS = OFF_V + VB, OFF_KZ = OFF_KS + SZ, OFF_VS = OFF_KZ + SZ,
                        OFF_VZ = OFF_VS + SZ, STAGE = OFF_VZ + SZ;
-  static constexpr int NS = (D == 128) ? 3 : 2;  // ring depth per wave
+  static constexpr int NS = (D == 128) ? 3 : 2;  // ring depth per wave (LDS: 160 KB per CU)
   static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
-  static constexpr int RING = 4 * NS * STAGE;
-  static constexpr int MERGE = (4 * GP * D + 4 * GP * NG + 2 * 4 * GP) * 4;  // o, zero-point term, m, l
+  static constexpr int RING = NW * NS * STAGE;
+  static constexpr int MERGE = (NW * GP * D + NW * GP * NG + 2 * NW * GP) * 4;  // o, zero-point term, m, l
   static constexpr int SMEM = RING > MERGE ? RING : MERGE;                   // the merge area reuses the rings
+  // The fp16 scale and zero-point arrays are fetched dword by dword (two groups of one token), and the
+  // direct loads may gather: with NA == 2 a lane needs exactly one dword per token, so the dwords are
+  // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads.
+  static constexpr bool PERM = (NA == 2);
+  // Whether the K part of the next supertile is fetched into registers during the current one (it is
+  // not where the accumulators alone take half of the register file).
+  static constexpr bool PFK = !(D == 256 && NA == 2);
+  static __device__ constexpr int sz_token(int P) {       // token (0..31) whose dword sits at stage dword P
+    return PERM ? 16 * ((P >> 2) & 1) + 4 * (P & 3) + (P >> 3) / GR : P / (NG / 2);
+  }
+  static __device__ constexpr int sz_column(int P) {      // which dword of that token's NG/2
+    return PERM ? (P >> 3) % GR : P % (NG / 2);
+  }
 };
 
 // token held by row r of a 16-token K tile (and by the matching k-slots of the P V contraction):
@@ -168,10 +182,10 @@ __device__ __forceinline__ void wait_loads() {               // until at most N 
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int D, int GP>
-__global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParams p) {
-  using C = Cfg<D, GP>;
-  constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS;
+template <int D, int GP, int NW>
+__global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_kernel(DecodeParams p) {
+  using C = Cfg<D, GP, NW>;
+  constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS, GR = C::GR;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int lane = threadIdx.x & 63;
@@ -199,6 +213,13 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
                            reinterpret_cast<const char*>(p.v_scale) + row0 * (NG * 2),
                            reinterpret_cast<const char*>(p.v_zero) + row0 * (NG * 2)};
   const uint32_t koff = tok_of_row(c) * TB + kq * (D / 8);   // this lane's 16 B (x D/128) of a K tile
+  // scale / zero-point arrays: destination dword u*64+lane of the stage comes from (token, dword) of the supertile
+  uint32_t sz_tok[C::SZ / 256], sz_col[C::SZ / 256];
+#pragma unroll
+  for (int u = 0; u < C::SZ / 256; ++u) {
+    sz_tok[u] = C::sz_token(u * 64 + lane);
+    sz_col[u] = C::sz_column(u * 64 + lane);
+  }
 
   // fills ring slot `slot` with supertile `sidx`: LPS load instructions, all 64 lanes each
   auto issue = [&](int slot, int sidx, auto tail_tag) {
@@ -219,7 +240,8 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
       for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int u = 0; u < C::SZ / 256; ++u)
-          dma4(sz_row[a] + (int64_t)base * (NG * 2) + u * 256, lane * 4, l + C::OFF_KS + a * C::SZ + u * 256);
+          dma4(sz_row[a] + (int64_t)base * (NG * 2), (sz_tok[u] * (NG / 2) + sz_col[u]) * 4,
+               l + C::OFF_KS + a * C::SZ + u * 256);
     } else {                                      // ragged tail: clamp every token to the last valid one
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -238,21 +260,44 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
       for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int u = 0; u < C::SZ / 256; ++u) {
-          const int dw = u * 64 + lane;           // dword of the supertile's scale array
-          const int tok = min(base + dw / (NG / 2), last_tok);
-          dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + (dw % (NG / 2)) * 4,
-                    l + C::OFF_KS + a * C::SZ + u * 256);
+          const int tok = min(base + (int)sz_tok[u], last_tok);
+          dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + sz_col[u] * 4, l + C::OFF_KS + a * C::SZ + u * 256);
         }
     }
   };
+  auto wait_stages = [&](int k) {                 // until at most k whole stages are still in flight
+    if (k >= 2 && NS >= 3) wait_loads<2 * LPS>();
+    else if (k == 1) wait_loads<LPS>();
+    else wait_loads<0>();
+  };
 
-  // ---- this wave's supertiles: wave, wave+4, ... among the chunk's whole ones, then maybe the tail
-  const int n_mine = (n_full > wave) ? (n_full - wave + 3) >> 2 : 0;
-  const bool my_tail = has_tail && (n_full & 3) == wave;
+  // ---- work distribution: supertile i of this wave is supertile wave + i*NW of the chunk, so the waves
+  //      of a block walk the chunk side by side; the ragged last supertile, if any, goes to the wave
+  //      whose turn it would be and takes the clamped path.  The split is fixed, so the summation
+  //      order, and with it every output bit, is the same on every launch.
+  const int n_mine = n_full > wave ? (n_full - wave + NW - 1) / NW : 0;
+  const bool tail_mine = has_tail && (n_full % NW) == wave;
 
-  // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query);
-  //      their loads go out first, then the first ring stages, and only then are they consumed
-  const _Float16* qh = p.q + (int64_t)(b * p.n_q_heads + kv * G + (hl < G ? hl : 0)) * D;
+  // ---- prologue: the query rows of this KV head's group come in through the last ring slot (so that
+  //      every vector-memory operation of the kernel is one of the counted direct loads), then stages
+  //      0 .. NS-2 go out; the last slot is refilled once the query operands sit in registers.
+  {
+    const uint32_t l = ring_lds + (NS - 1) * C::STAGE + C::OFF_V;
+#pragma unroll
+    for (int u = 0; u < GP * D * 2 / 1024; ++u) {
+      const int chunk = u * 64 + lane;            // 16-byte chunk of the [GP][D] fp16 query block
+      const int h = min(chunk / (D / 8), G - 1);
+      dma16_lane(p.q + (int64_t)(b * p.n_q_heads + kv * G + h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
+    }
+  }
+  int issued = 0;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_mine) { issue(s, wave + s * NW, std::false_type{}); ++issued; }
+  wait_stages(issued);
+
+  // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
+  const _Float16* qh = reinterpret_cast<const _Float16*>(ring + (NS - 1) * C::STAGE + C::OFF_V) + hl * D;
   half8v qraw[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
@@ -262,10 +307,6 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int i = 0; i < 4; ++i) qgrp[a][i] = *reinterpret_cast<const half8v*>(qh + (rep * NA + a) * kGroup + i * 8);
-
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < n_mine) issue(s, wave + 4 * s, std::false_type{});
 
   half8v qb[NJ];
 #pragma unroll
@@ -290,6 +331,8 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   }
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
+  if (NS - 1 < n_mine) { issue(NS - 1, wave + (NS - 1) * NW, std::false_type{}); ++issued; }
 
   // ---- running state
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
@@ -312,60 +355,94 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   // per-lane LDS byte offsets inside a stage
   const uint32_t k_rd = lane * 16;                                  // the 16 B this lane asked for
   const uint32_t v_rd = kq * TB + c * 4 * NCS;                      // packed word(s) c of token kq (+4i)
-  const uint32_t sz_rd = (kq * NG + rep * NA) * 2;                  // this lane's groups of token kq (+4i)
-  const uint32_t zb_rd = (kq * NG + (c % NG)) * 2;                  // zero-point of group c%NG, token kq (+4i)
+  // scales of this lane's groups / zero-point of group c%NG, tokens kq (+4i): eight consecutive dwords
+  // in the permuted layout, else one halfword per token at the array's own stride
+  const uint32_t sz_rd = C::PERM ? (kq * GR + rep) * 32 : (kq * NG + rep * NA) * 2;
+  const uint32_t zb_rd = C::PERM ? (kq * GR + ((c % NG) >> 1)) * 32 : (kq * NG + (c % NG)) * 2;
+  const uint32_t zb_sel = ((c % NG) & 1) ? 0x07060302u : 0x05040100u;   // which half of a zero-point dword
 
-  auto process = [&](int slot, int sidx, auto tail_tag) {
-    constexpr bool TAIL = decltype(tail_tag)::value;
+  // Everything a supertile needs from LDS is fetched into registers well before it is used: the K part
+  // while the previous supertile is still in its P V phase, the V part at the start of the K phase.
+  struct KRegs { uint4v kw[2][D / 128]; uint32_t ks[2][4], kz[2][4]; };
+  struct VRegs { uint32_t v[NCS][8]; uint32_t vs[2][4]; uint32_t zb[8]; };
+  auto load_sz = [&](const char* arr, uint32_t rd, uint32_t (&dst)[2][4]) {
+    if constexpr (C::PERM) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint4v x = *reinterpret_cast<const uint4v*>(arr + rd + t * 16);
+        dst[t][0] = x[0]; dst[t][1] = x[1]; dst[t][2] = x[2]; dst[t][3] = x[3];
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          dst[t][i] = *reinterpret_cast<const uint16_t*>(arr + (t * 16 + i * 4) * NG * 2 + rd);
+    }
+  };
+  auto load_k = [&](int slot, KRegs& r) {
     const char* st = ring + slot * C::STAGE;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ch = 0; ch < D / 128; ++ch)
+        r.kw[t][ch] = *reinterpret_cast<const uint4v*>(st + t * C::KT + ch * 1024 + k_rd);
+    load_sz(st + C::OFF_KS, sz_rd, r.ks);
+    load_sz(st + C::OFF_KZ, sz_rd, r.kz);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto load_v = [&](int slot, VRegs& r) {
+    const char* st = ring + slot * C::STAGE;
+#pragma unroll
+    for (int cs = 0; cs < NCS; ++cs)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)                 // token slot i: token 16*(i/4) + 4*(i%4) + kq
+        r.v[cs][i] = *reinterpret_cast<const uint32_t*>(st + C::OFF_V + (16 * (i >> 2) + 4 * (i & 3)) * TB + v_rd + cs * 4);
+    load_sz(st + C::OFF_VS, sz_rd, r.vs);
+    uint32_t zr[2][4];
+    load_sz(st + C::OFF_VZ, zb_rd, zr);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r.zb[i] = zr[i >> 2][i & 3];
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // fp16 scale / zero-point number a (of this lane's NA) out of a fetched register
+  auto sz_half = [&](uint32_t w, int a) -> _Float16 {
+    const uint16_t h = (uint16_t)(a == 0 ? w : w >> 16);
+    return __builtin_bit_cast(_Float16, h);
+  };
 
-    // -- scores, S^T = K Q^T, per-group scale and zero-point applied in fp32 (raw units: 2^-24)
-    float sc[2][4];
+  // -- scores, S^T = K Q^T, per-group scale and zero-point applied in fp32 (raw units: 2^-24)
+  auto scores = [&](const KRegs& r, int sidx, auto tail_tag, float (&sc)[2][4]) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       uint32_t w[NJ];
       if constexpr (C::SWAP) {
-        const uint4v kw = *reinterpret_cast<const uint4v*>(st + t * C::KT + k_rd);
+        const uint4v kw = r.kw[t][0];
         auto s01 = __builtin_amdgcn_permlane16_swap(kw[0], kw[1], false, false);
         auto s23 = __builtin_amdgcn_permlane16_swap(kw[2], kw[3], false, false);
         w[0] = s01[0]; w[1] = s01[1]; w[2] = s23[0]; w[3] = s23[1];
       } else {
 #pragma unroll
-        for (int ch = 0; ch < D / 128; ++ch) {
-          const uint4v kw = *reinterpret_cast<const uint4v*>(st + t * C::KT + ch * 1024 + k_rd);
+        for (int ch = 0; ch < D / 128; ++ch)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) w[ch * 4 + i] = kw[i];
-        }
+          for (int i = 0; i < 4; ++i) w[ch * 4 + i] = r.kw[t][ch][i];
       }
       float4v acc[NA];
 #pragma unroll
       for (int a = 0; a < NA; ++a) acc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
       for (int j = 0; j < NJ; ++j) acc[C::acc(j)] = mfma16(unpack_word(w[j]), qb[j], acc[C::acc(j)]);
-      float part[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {               // token 16t + 4i + kq
-        const char* sp = st + C::OFF_KS + (t * 16 + i * 4) * NG * 2 + sz_rd;
-        const char* zp = st + C::OFF_KZ + (t * 16 + i * 4) * NG * 2 + sz_rd;
-        float x = 0.0f;
-        if constexpr (NA == 2) {
-          const half2v s2 = *reinterpret_cast<const half2v*>(sp);
-          const half2v z2 = *reinterpret_cast<const half2v*>(zp);
-          x = (float)s2[0] * fmaf(-(float)z2[0], qsum[0], acc[0][i]);
-          x = fmaf((float)s2[1], fmaf(-(float)z2[1], qsum[NA - 1], acc[NA - 1][i]), x);
-        } else {
-          const _Float16 s1 = *reinterpret_cast<const _Float16*>(sp);
-          const _Float16 z1 = *reinterpret_cast<const _Float16*>(zp);
-          x = (float)s1 * fmaf(-(float)z1, qsum[0], acc[0][i]);
-        }
-        part[i] = x;
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float x = part[i];
-        if constexpr (C::GR >= 2) x = row_ror_add<8>(x);
-        if constexpr (C::GR >= 4) x = row_ror_add<4>(x);
-        if constexpr (C::GR >= 8) x = row_ror_add<2>(x);
+        float x = __builtin_fmaf((float)sz_half(r.ks[t][i], 0),
+                                 __builtin_fmaf(-(float)sz_half(r.kz[t][i], 0), qsum[0], acc[0][i]), 0.0f);
+        if constexpr (NA == 2)
+          x = __builtin_fmaf((float)sz_half(r.ks[t][i], 1),
+                             __builtin_fmaf(-(float)sz_half(r.kz[t][i], 1), qsum[NA - 1], acc[NA - 1][i]), x);
+        if constexpr (GR >= 2) x = row_ror_add<8>(x);
+        if constexpr (GR >= 4) x = row_ror_add<4>(x);
+        if constexpr (GR >= 8) x = row_ror_add<2>(x);
         if constexpr (TAIL) {
           const int tok = begin + sidx * 32 + 16 * t + tok_of_row(4 * kq + i);
           x = (tok < end) ? x : -INFINITY;
@@ -373,12 +450,16 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
         sc[t][i] = x;
       }
     }
+  };
 
-    // -- online softmax over the 32 tokens (Alg. 1 lines 6-7, 10), block-wise.  m_run is a per-head
-    //    REFERENCE, not the exact running max: it only moves when some score exceeds it by more than
-    //    kSlack (log2 units), so exp2(score - m_run) <= 2^kSlack = 4 and p * s_v stays inside fp16 for
-    //    every representable scale, while the accumulator rescale (Alg. 1 lines 7, 9) becomes rare.
-    //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.
+  // -- online softmax over the 32 tokens (Alg. 1 lines 6-7, 10), block-wise.  m_run is a per-head
+  //    REFERENCE, not the exact running max: it only moves when some score exceeds it by more than
+  //    kSlack (log2 units), so exp2(score - m_run) <= 2^kSlack = 4 and p * s_v stays inside fp16 for
+  //    every representable scale, while the accumulator rescale (Alg. 1 lines 7, 9) becomes rare.
+  //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.
+  //    Then A = fp16(p * s_v), rows (head, replica), one operand per group of the lane; the zero-point
+  //    term goes through the matrix core with the stored fp16 zero-points as B operand.
+  auto softmax = [&](const float (&sc)[2][4], const VRegs& r, half8v (&pa)[NA]) {
     const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                            fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
     if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {   // wave-uniform, rare
@@ -411,46 +492,43 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
         pr[t][i] = __builtin_amdgcn_exp2f(fmaf(sc[t][i], kappa, -mk));
         l_run += pr[t][i];
       }
-
-    // -- A = fp16(p * s_v), rows (head, replica), one operand per group of the lane; the zero-point
-    //    term goes through the matrix core with the stored fp16 zero-points as B operand
-    half8v pa[NA];
     half8v zb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {                 // tokens 4i + kq (tile 0) and 16 + 4i + kq (tile 1)
-      const char* s0 = st + C::OFF_VS + (i * 4) * NG * 2 + sz_rd;
-      const char* s1 = st + C::OFF_VS + (16 + i * 4) * NG * 2 + sz_rd;
-      if constexpr (NA == 2) {
-        const half2v a0 = *reinterpret_cast<const half2v*>(s0);
-        const half2v a1 = *reinterpret_cast<const half2v*>(s1);
-        pa[0][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)a0[0], 0.0f);
-        pa[0][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)a1[0], 0.0f);
-        pa[NA - 1][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)a0[1], 0.0f);
-        pa[NA - 1][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)a1[1], 0.0f);
-      } else {
-        pa[0][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)*reinterpret_cast<const _Float16*>(s0), 0.0f);
-        pa[0][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)*reinterpret_cast<const _Float16*>(s1), 0.0f);
+    for (int i = 0; i < 4; ++i) {                 // k-slots 2i, 2i+1: tokens 4i + kq of tile 0 and of tile 1
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)sz_half(r.vs[0][i], a), 0.0f);
+        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)sz_half(r.vs[1][i], a), 0.0f);
       }
-      zb[2 * i] = *reinterpret_cast<const _Float16*>(st + C::OFF_VZ + (i * 4) * NG * 2 + zb_rd);
-      zb[2 * i + 1] = *reinterpret_cast<const _Float16*>(st + C::OFF_VZ + (16 + i * 4) * NG * 2 + zb_rd);
+    }
+    if constexpr (C::PERM) {
+      uint32_t zw[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) zw[i] = __builtin_amdgcn_perm(r.zb[4 + i], r.zb[i], zb_sel);
+      zb = as_half8(zw[0], zw[1], zw[2], zw[3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        zb[2 * i] = sz_half(r.zb[i], 0);
+        zb[2 * i + 1] = sz_half(r.zb[4 + i], 0);
+      }
     }
 #pragma unroll
     for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], zb, zacc[a]);
 #pragma unroll
     for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], neg8, zacc[a]);
+  };
 
-    // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
-    //    consumed two dims at a time so that few unpacked operands are live
+  // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
+  //    consumed two dims at a time so that few unpacked operands are live
+  auto pv = [&](const VRegs& r, const half8v (&pa)[NA]) {
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
-      uint32_t v[8], x[8], y[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i)               // token slot i: token 16*(i/4) + 4*(i%4) + kq
-        v[i] = *reinterpret_cast<const uint32_t*>(st + C::OFF_V + (16 * (i >> 2) + 4 * (i & 3)) * TB + v_rd + cs * 4);
+      uint32_t x[8], y[8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        x[i] = __builtin_amdgcn_perm(v[i + 4], v[i], 0x05040100u);
-        x[i + 4] = __builtin_amdgcn_perm(v[i + 4], v[i], 0x07060302u);
+        x[i] = __builtin_amdgcn_perm(r.v[cs][i + 4], r.v[cs][i], 0x05040100u);
+        x[i + 4] = __builtin_amdgcn_perm(r.v[cs][i + 4], r.v[cs][i], 0x07060302u);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -479,28 +557,58 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
     }
   };
 
-  // ---- main loop: keep NS-1 stages in flight ahead of the one being consumed
-  for (int k = 0; k < n_mine; ++k) {
-    if (k + NS - 1 < n_mine) issue((k + NS - 1) % NS, wave + 4 * (k + NS - 1), std::false_type{});
-    const int later = min(n_mine - 1 - k, NS - 1);           // stages issued after stage k
-    if (later == 2) wait_loads<2 * LPS>();
-    else if (later == 1) wait_loads<LPS>();
-    else wait_loads<0>();
-    process(k % NS, wave + 4 * k, std::false_type{});
+  // ---- main loop.  Supertile i: its K part already sits in registers; fetch its V part, compute the
+  //      scores, fetch the K part of supertile i+1 (whose stage has to have landed by then), softmax,
+  //      refill the ring slot of supertile i with supertile i+NS, P V.
+  KRegs kr;
+  VRegs vr;
+  if (C::PFK && n_mine > 0) {
+    wait_stages(issued - 1);
+    load_k(0, kr);
   }
-  if (my_tail) {                                             // the ragged last supertile of the sequence
+  int slot = 0;
+  for (int i = 0; i < n_mine; ++i) {
+    const int next = (slot + 1 == NS) ? 0 : slot + 1;
+    if constexpr (!C::PFK) {
+      wait_stages(min(NS - 1, n_mine - 1 - i));
+      load_k(slot, kr);
+    }
+    load_v(slot, vr);
+    float sc[2][4];
+    scores(kr, 0, std::false_type{}, sc);
+    if (C::PFK && i + 1 < n_mine) {
+      wait_stages(min(NS - 2, n_mine - 2 - i));
+      load_k(next, kr);
+    }
+    half8v pa[NA];
+    softmax(sc, vr, pa);
+    if (i + NS < n_mine) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // every LDS read of this slot has returned
+      issue(slot, wave + (i + NS) * NW, std::false_type{});
+    }
+    pv(vr, pa);
+    slot = next;
+  }
+  if (tail_mine) {                                           // the ragged last supertile of the sequence
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     issue(0, n_full, std::true_type{});
     wait_loads<0>();
-    process(0, n_full, std::true_type{});
+    load_k(0, kr);
+    load_v(0, vr);
+    float sc[2][4];
+    scores(kr, n_full, std::true_type{}, sc);
+    half8v pa[NA];
+    softmax(sc, vr, pa);
+    pv(vr, pa);
   }
 
   // ---- wave result -> LDS (the merge area reuses the rings, so everybody must be done reading)
-  float* const lds_o = reinterpret_cast<float*>(smem);                 // [4][GP][D]
-  float* const lds_zc = lds_o + 4 * GP * D;                            // [4][GP][NG]
-  float* const lds_m = lds_zc + 4 * GP * NG;                           // [4][GP]
-  float* const lds_l = lds_m + 4 * GP;                                 // [4][GP]
+  float* const lds_o = reinterpret_cast<float*>(smem);                 // [NW][GP][D]
+  float* const lds_zc = lds_o + NW * GP * D;                           // [NW][GP][NG]
+  float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
+  float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
   __syncthreads();
-  const bool active = n_mine > 0 || my_tail;
+  const bool active = n_mine > 0 || tail_mine;
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
     lds_m[wave * GP + hl] = active ? m_run * kappa : kNegBig;
@@ -528,15 +636,15 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(DecodeParam
   }
   __syncthreads();
 
-  // ---- merge the four waves, write one partial per query head (Sec. 3.2)
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+  // ---- merge the waves, write one partial per query head (Sec. 3.2)
+  for (int idx = threadIdx.x; idx < G * D; idx += NW * 64) {
     const int h = idx / D, j = idx % D;
     float mg = lds_m[h];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
+    for (int w = 1; w < NW; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
     float num = 0.0f, den = 0.0f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
       num = fmaf(lds_o[(w * GP + h) * D + j] - lds_zc[(w * GP + h) * NG + (j >> 5)], e, num);
       den = fmaf(lds_l[w * GP + h], e, den);
@@ -554,15 +662,18 @@ int padded_gqa(int head_dim, int gqa) {
 
 template <int D, int GP>
 hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
-  constexpr int smem = Cfg<D, GP>::SMEM;
+  // one block of 8 waves per compute unit: 8 rings of 3 x 5 KB (d=128) or 2 x 10 KB (d=256, all 160 KB of LDS)
+  constexpr int NW = 8;
+  constexpr int smem = Cfg<D, GP, NW>::SMEM;
+  static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
   static bool configured = false;                 // dynamic LDS above 64 KB has to be opted into once
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP>), grid, dim3(256), smem, s, p);
+  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW>), grid, dim3(NW * 64), smem, s, p);
   return hipGetLastError();
 }
 
