@@ -86,7 +86,7 @@ struct Cfg {
   static constexpr int SZ = 32 * NG * 2;         // one fp16 scale (or zero-point) array of the supertile
   static constexpr int OFF_V = 2 * KT, OFF_KS = OFF_V + VB, OFF_KZ = OFF_KS + SZ, OFF_VS = OFF_KZ + SZ,
                        OFF_VZ = OFF_VS + SZ, STAGE = OFF_VZ + SZ;
-  static constexpr int NS = (D == 128) ? 3 : 2;  // ring depth per wave (LDS: 160 KB per CU)
+  static constexpr int NS = 2;                  // ring depth per wave  // ring depth per wave (LDS: 160 KB per CU)
   static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
   static constexpr int RING = NW * NS * STAGE;
   static constexpr int MERGE = (NW * GP * D + NW * GP * NG + 2 * NW * GP) * 4;  // o, zero-point term, m, l
@@ -161,10 +161,6 @@ __device__ __forceinline__ float row_ror_add(float x) {      // x + (x rotated b
 // ---- direct global -> LDS loads.  Written as asm so that the compiler does not serialise them
 // against later LDS reads: each wave tracks its own ring with explicit vmcnt waits instead.
 // Lane l's bytes land at lds_base + l * (16 | 4).  M0 carries the LDS base of the instruction.
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
-}
 __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
@@ -176,6 +172,26 @@ __device__ __forceinline__ void dma16_lane(const void* addr, uint32_t lds_base) 
 __device__ __forceinline__ void dma4_lane(const void* addr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :: "v"(addr), "s"(lds_base) : "memory");
+}
+// Several loads of one array behind a single M0: the instruction's immediate offset moves the global
+// and the LDS address alike, so pieces that are equally far apart on both sides share the base.
+template <int O1>
+__device__ __forceinline__ void dma16_x2(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\t"
+               "global_load_lds_dwordx4 %0, %1 offset:%3"
+               :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(O1) : "memory");
+}
+template <int O0, int O1>
+__device__ __forceinline__ void dma16_x2o(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3\n\t"
+               "global_load_lds_dwordx4 %0, %1 offset:%4"
+               :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(O0), "n"(O1) : "memory");
+}
+__device__ __forceinline__ void dma16_x4(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\t"
+               "global_load_lds_dwordx4 %0, %1 offset:1024\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048\n\t"
+               "global_load_lds_dwordx4 %0, %1 offset:3072"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() {               // until at most N loads are outstanding
@@ -221,62 +237,77 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     sz_col[u] = C::sz_column(u * 64 + lane);
   }
 
-  // fills ring slot `slot` with supertile `sidx`: LPS load instructions, all 64 lanes each
-  auto issue = [&](int slot, int sidx, auto tail_tag) {
-    constexpr bool TAIL = decltype(tail_tag)::value;
+  // Fills the ring slot at LDS address l with the supertile whose codes start off_c bytes into the row:
+  // LPS load instructions, all 64 lanes each.  vk, vv, vs are the per-lane byte offsets inside the
+  // supertile (K tile, V block, scale array); passing zeros instead makes a PHANTOM stage, which reads
+  // one line per instruction and only keeps the count of outstanding loads uniform.
+  const uint32_t lane16 = lane * 16;
+  uint32_t szoff[C::SZ / 256];
+#pragma unroll
+  for (int u = 0; u < C::SZ / 256; ++u) szoff[u] = (sz_tok[u] * (NG / 2) + sz_col[u]) * 4;
+  auto issue_at = [&](uint32_t l, uint32_t off_c, uint32_t vk, uint32_t vv, const uint32_t (&vs)[C::SZ / 256]) {
+    const uint32_t off_s = off_c >> 3;            // (NG*2) / TB = 1/8: scale bytes per code byte
+    if constexpr (D == 128) {
+      dma16_x2<1024>(kc_row, vk + off_c, l);                           // two K tiles: 1 KB apart on both sides
+      dma16_x2<1024>(vc_row, vv + off_c, l + C::OFF_V);
+    } else {
+      dma16_x2<2048>(kc_row, vk + off_c, l);                           // first 16 B of each lane, tiles 0 and 1
+      dma16_x2o<16, 2064>(kc_row, vk + off_c, l + 1024 - 16);          // second 16 B: +16 in HBM, +1024 in LDS
+      dma16_x4(vc_row, vv + off_c, l + C::OFF_V);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int u = 0; u < C::SZ / 256; ++u) dma4(sz_row[a], vs[u] + off_s, l + C::OFF_KS + a * C::SZ + u * 256);
+  };
+  auto issue_tail = [&](int slot, int sidx) {     // ragged last supertile: clamp every token to the last valid one
     const int base = begin + sidx * 32;
     const uint32_t l = ring_lds + slot * C::STAGE;
-    if constexpr (!TAIL) {
-      const char* kb = kc_row + (int64_t)base * TB;
-      const char* vb = vc_row + (int64_t)base * TB;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) {
+      const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
 #pragma unroll
-        for (int ch = 0; ch < D / 128; ++ch)
-          dma16(kb + t * 16 * TB + ch * 16, koff, l + t * C::KT + ch * 1024);
-#pragma unroll
-      for (int u = 0; u < C::VB / 1024; ++u) dma16(vb + u * 1024, lane * 16, l + C::OFF_V + u * 1024);
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int u = 0; u < C::SZ / 256; ++u)
-          dma4(sz_row[a] + (int64_t)base * (NG * 2), (sz_tok[u] * (NG / 2) + sz_col[u]) * 4,
-               l + C::OFF_KS + a * C::SZ + u * 256);
-    } else {                                      // ragged tail: clamp every token to the last valid one
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
-#pragma unroll
-        for (int ch = 0; ch < D / 128; ++ch)
-          dma16_lane(kc_row + (int64_t)tok * TB + kq * (D / 8) + ch * 16, l + t * C::KT + ch * 1024);
-      }
-#pragma unroll
-      for (int u = 0; u < C::VB / 1024; ++u) {
-        const int chunk = u * 64 + lane;          // 16-byte chunk of the supertile's V codes
-        const int tok = min(base + chunk / (TB / 16), last_tok);
-        dma16_lane(vc_row + (int64_t)tok * TB + (chunk % (TB / 16)) * 16, l + C::OFF_V + u * 1024);
-      }
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int u = 0; u < C::SZ / 256; ++u) {
-          const int tok = min(base + (int)sz_tok[u], last_tok);
-          dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + sz_col[u] * 4, l + C::OFF_KS + a * C::SZ + u * 256);
-        }
+      for (int ch = 0; ch < D / 128; ++ch)
+        dma16_lane(kc_row + (int64_t)tok * TB + kq * (D / 8) + ch * 16, l + t * C::KT + ch * 1024);
     }
+#pragma unroll
+    for (int u = 0; u < C::VB / 1024; ++u) {
+      const int chunk = u * 64 + lane;            // 16-byte chunk of the supertile's V codes
+      const int tok = min(base + chunk / (TB / 16), last_tok);
+      dma16_lane(vc_row + (int64_t)tok * TB + (chunk % (TB / 16)) * 16, l + C::OFF_V + u * 1024);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int u = 0; u < C::SZ / 256; ++u) {
+        const int tok = min(base + (int)sz_tok[u], last_tok);
+        dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + sz_col[u] * 4, l + C::OFF_KS + a * C::SZ + u * 256);
+      }
   };
-  auto wait_stages = [&](int k) {                 // until at most k whole stages are still in flight
-    if (k >= 2 && NS >= 3) wait_loads<2 * LPS>();
-    else if (k == 1) wait_loads<LPS>();
-    else wait_loads<0>();
+  const uint32_t zero_vs[C::SZ / 256] = {};
+  auto off_of = [&](int sidx) { return (uint32_t)(begin + sidx * 32) * TB; };
+  auto issue = [&](int slot, int sidx) { issue_at(ring_lds + slot * C::STAGE, off_of(sidx), koff, lane16, szoff); };
+  auto issue_phantom = [&](int slot) { issue_at(ring_lds + slot * C::STAGE, off_of(0), 0u, 0u, zero_vs); };
+  // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
+  //      issues from its older wave first, so wave w gets through a supertile in about 7/9 of the time
+  //      wave w+4 needs.  The chunk's supertiles are therefore dealt round-robin to the four SIMDs, and
+  //      of every 16 that a SIMD gets, its older wave takes 9 and the younger 7, in a fixed pattern.
+  //      The split is static: the summation order, and with it every output bit, is the same on every
+  //      launch.  The ragged last supertile, if any, goes to the wave whose turn it would be and takes
+  //      the clamped path.
+  static_assert(NW == 8, "the work split assumes two waves per SIMD");
+  const int simd = wave & 3, young = wave >> 2;
+  auto sidx_of = [&](int i) {                     // i-th supertile of this wave -> supertile of the chunk
+    const int blk = young ? i / 7 : i / 9, j = i - blk * (young ? 7 : 9);
+    const int k = 16 * blk + (young ? 2 * j + 1 : (j < 8 ? 2 * j : 15));
+    return 4 * k + simd;
   };
-
-  // ---- work distribution: supertile i of this wave is supertile wave + i*NW of the chunk, so the waves
-  //      of a block walk the chunk side by side; the ragged last supertile, if any, goes to the wave
-  //      whose turn it would be and takes the clamped path.  The split is fixed, so the summation
-  //      order, and with it every output bit, is the same on every launch.
-  const int n_mine = n_full > wave ? (n_full - wave + NW - 1) / NW : 0;
-  const bool tail_mine = has_tail && (n_full % NW) == wave;
+  auto count_of = [&](int n) {                    // how many of the chunk's first n supertiles are this wave's
+    const int K = n > simd ? (n - simd + 3) >> 2 : 0, r = K & 15;
+    return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
+  };
+  const int n_mine = count_of(n_full);
+  const bool tail_mine = has_tail && count_of(n_full + 1) != n_mine;
 
   // ---- prologue: the query rows of this KV head's group come in through the last ring slot (so that
   //      every vector-memory operation of the kernel is one of the counted direct loads), then stages
@@ -290,11 +321,18 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       dma16_lane(p.q + (int64_t)(b * p.n_q_heads + kv * G + h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
     }
   }
-  int issued = 0;
+  // A wave with work always has exactly NS stages out before its loop and issues one per supertile,
+  // phantom ones standing in when its supertiles run out, so every wait in the loop is the same.
+  if (n_mine > 0) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < n_mine) { issue(s, wave + s * NW, std::false_type{}); ++issued; }
-  wait_stages(issued);
+    for (int s = 0; s < NS - 1; ++s) {
+      if (s < n_mine) issue(s, sidx_of(s));
+      else issue_phantom(s);
+    }
+    wait_loads<(NS - 1) * LPS>();
+  } else {
+    wait_loads<0>();
+  }
 
   // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
   const _Float16* qh = reinterpret_cast<const _Float16*>(ring + (NS - 1) * C::STAGE + C::OFF_V) + hl * D;
@@ -332,7 +370,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
-  if (NS - 1 < n_mine) { issue(NS - 1, wave + (NS - 1) * NW, std::false_type{}); ++issued; }
+  if (n_mine > 0) {
+    if (NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
+    else issue_phantom(NS - 1);
+  }
+  // supertile NS, the first one issued inside the loop, and how to step from one supertile to the next:
+  // position j in the wave's pattern of 9 (or 7) out of 16
+  int nx_j = young ? NS % 7 : NS % 9;
+  uint32_t nx_off = off_of(sidx_of(NS));
 
   // ---- running state
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
@@ -353,7 +398,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const half8v neg8 = as_half8(kNeg8, kNeg8, kNeg8, kNeg8);
 
   // per-lane LDS byte offsets inside a stage
-  const uint32_t k_rd = lane * 16;                                  // the 16 B this lane asked for
+  // K codes: the 16 B this lane asked for; where the query operand is block-diagonal over pairs of
+  // groups (SWAP), words w and w+2 of groups 2(kq/2) and 2(kq/2)+1 of token row c instead
+  const uint32_t k_rd = C::SWAP ? (32 * (kq >> 1) + c) * 16 + 4 * (kq & 1) : lane * 16;
   const uint32_t v_rd = kq * TB + c * 4 * NCS;                      // packed word(s) c of token kq (+4i)
   // scales of this lane's groups / zero-point of group c%NG, tokens kq (+4i): eight consecutive dwords
   // in the permuted layout, else one halfword per token at the array's own stride
@@ -363,7 +410,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 
   // Everything a supertile needs from LDS is fetched into registers well before it is used: the K part
   // while the previous supertile is still in its P V phase, the V part at the start of the K phase.
-  struct KRegs { uint4v kw[2][D / 128]; uint32_t ks[2][4], kz[2][4]; };
+  struct KRegs { uint32_t kw[2][NJ]; uint32_t ks[2][4], kz[2][4]; };   // kw[t][j]: A operand of K MFMA j, tile t
   struct VRegs { uint32_t v[NCS][8]; uint32_t vs[2][4]; uint32_t zb[8]; };
   auto load_sz = [&](const char* arr, uint32_t rd, uint32_t (&dst)[2][4]) {
     if constexpr (C::PERM) {
@@ -383,10 +430,19 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   auto load_k = [&](int slot, KRegs& r) {
     const char* st = ring + slot * C::STAGE;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) {
+      if constexpr (C::SWAP) {
+        // the lane wants words w, w+2 of two neighbouring groups, 256 B apart in the tile: two 2-dword reads
+        const uint32_t* g0 = reinterpret_cast<const uint32_t*>(st + t * C::KT + k_rd);
+        r.kw[t][0] = g0[0]; r.kw[t][2] = g0[2]; r.kw[t][1] = g0[64]; r.kw[t][3] = g0[66];
+      } else {
 #pragma unroll
-      for (int ch = 0; ch < D / 128; ++ch)
-        r.kw[t][ch] = *reinterpret_cast<const uint4v*>(st + t * C::KT + ch * 1024 + k_rd);
+        for (int ch = 0; ch < D / 128; ++ch) {
+          const uint4v x = *reinterpret_cast<const uint4v*>(st + t * C::KT + ch * 1024 + k_rd);
+          r.kw[t][ch * 4 + 0] = x[0]; r.kw[t][ch * 4 + 1] = x[1]; r.kw[t][ch * 4 + 2] = x[2]; r.kw[t][ch * 4 + 3] = x[3];
+        }
+      }
+    }
     load_sz(st + C::OFF_KS, sz_rd, r.ks);
     load_sz(st + C::OFF_KZ, sz_rd, r.kz);
     __builtin_amdgcn_sched_barrier(0);
@@ -416,23 +472,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      uint32_t w[NJ];
-      if constexpr (C::SWAP) {
-        const uint4v kw = r.kw[t][0];
-        auto s01 = __builtin_amdgcn_permlane16_swap(kw[0], kw[1], false, false);
-        auto s23 = __builtin_amdgcn_permlane16_swap(kw[2], kw[3], false, false);
-        w[0] = s01[0]; w[1] = s01[1]; w[2] = s23[0]; w[3] = s23[1];
-      } else {
-#pragma unroll
-        for (int ch = 0; ch < D / 128; ++ch)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) w[ch * 4 + i] = r.kw[t][ch][i];
-      }
       float4v acc[NA];
 #pragma unroll
       for (int a = 0; a < NA; ++a) acc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) acc[C::acc(j)] = mfma16(unpack_word(w[j]), qb[j], acc[C::acc(j)]);
+      for (int j = 0; j < NJ; ++j) acc[C::acc(j)] = mfma16(unpack_word(r.kw[t][j]), qb[j], acc[C::acc(j)]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {               // token 16t + 4i + kq
         float x = __builtin_fmaf((float)sz_half(r.ks[t][i], 0),
@@ -563,35 +607,42 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   KRegs kr;
   VRegs vr;
   if (C::PFK && n_mine > 0) {
-    wait_stages(issued - 1);
+    wait_loads<(NS - 1) * LPS>();
     load_k(0, kr);
   }
   int slot = 0;
   for (int i = 0; i < n_mine; ++i) {
     const int next = (slot + 1 == NS) ? 0 : slot + 1;
     if constexpr (!C::PFK) {
-      wait_stages(min(NS - 1, n_mine - 1 - i));
+      wait_loads<(NS - 1) * LPS>();
       load_k(slot, kr);
     }
     load_v(slot, vr);
     float sc[2][4];
     scores(kr, 0, std::false_type{}, sc);
-    if (C::PFK && i + 1 < n_mine) {
-      wait_stages(min(NS - 2, n_mine - 2 - i));
+    if constexpr (C::PFK) {                                  // past the last supertile this fetches unused bytes
+      wait_loads<(NS - 2) * LPS>();
       load_k(next, kr);
     }
     half8v pa[NA];
     softmax(sc, vr, pa);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // every LDS read of this slot has returned
     if (i + NS < n_mine) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // every LDS read of this slot has returned
-      issue(slot, wave + (i + NS) * NW, std::false_type{});
+      issue_at(ring_lds + slot * C::STAGE, nx_off, koff, lane16, szoff);
+      // next supertile of the pattern: the older wave holds k = 0,2,..,14,15 of every 16, the younger 1,3,..,13
+      const int step = young ? (nx_j < 6 ? 2 : 4) : (nx_j < 7 ? 2 : 1);
+      nx_j = (nx_j == (young ? 6 : 8)) ? 0 : nx_j + 1;
+      nx_off += (uint32_t)step * (4 * 32 * TB);
+    } else {
+      issue_phantom(slot);
     }
     pv(vr, pa);
     slot = next;
   }
+  wait_loads<0>();                                           // phantom stages included: the rings are quiet
   if (tail_mine) {                                           // the ragged last supertile of the sequence
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    issue(0, n_full, std::true_type{});
+    issue_tail(0, n_full);
     wait_loads<0>();
     load_k(0, kr);
     load_v(0, vr);
