@@ -3,13 +3,14 @@
 
 A step = one pass of the whole hot path for one layer of the workload:
   tq_quantize_kv (append one new token per sequence)  ->  tq_sdpa_int4_decode (fused int4 SDPA
-  over seq_len tokens: partial kernel + merge kernel).
+  over seq_len tokens: per-chunk partial results and their merge, one kernel where the matrix-core
+  kernel runs, else partial kernel + merge kernel).
 Inputs are resident in HBM before the timed region.  Steps rotate over several distinct KV
 caches so that the 256 MB Infinity Cache cannot serve the stream (one 128K layer is 168 MB).
 
 Prints ONE JSON line.  `value` is microseconds per decode step (lower is better); the same line
 carries effective GB/s (packed int4 + scales + zero-points actually needed, divided by time),
-the roofline block for the dominant kernel (the partial kernel, timed with stream events), the
+the roofline block for the dominant kernel (timed with stream events), the
 unfused GPU comparator and the CPU oracle timed on the host cores.
 """
 from __future__ import annotations
@@ -100,16 +101,27 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     us_per_step = ms_per_step * 1e3
 
-    # ---- dominant kernel (phase 1, the partial kernel): stream events around each launch
+    # ---- dominant kernel: stream events around each of its launches.  Where the decode call is ONE
+    #      launch (partials and chunk merge in the same kernel) that launch is timed; otherwise phase 1,
+    #      the partial kernel, which tq_sdpa_int4_partial launches on its own.
+    fused = tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, **kw) == 1
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    n_splits = 0
+    n_splits = tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
+
+    def dominant(j):
+        if fused:
+            tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
+        else:
+            tq.tq_sdpa_int4_partial(caches[j], qs[j], S, w.attn_scale, ws, **kw)
+
     for i in range(args.steps):
         j = i % args.buffers
         tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
         evs[i][0].record()
-        n_splits = tq.tq_sdpa_int4_partial(caches[j], qs[j], S, w.attn_scale, ws, **kw)
+        dominant(j)
         evs[i][1].record()
-        tq.tq_sdpa_int4_reduce(B, Hq, d, n_splits, ws, out)
+        if not fused:
+            tq.tq_sdpa_int4_reduce(B, Hq, d, n_splits, ws, out)
     torch.cuda.synchronize()
     k_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
     kernel_us = statistics.fmean(k_us)
@@ -117,8 +129,7 @@ def main():
     # the same kernel launched back to back (no other kernel or event in between), as a cross-check
     e0.record()
     for i in range(args.steps):
-        j = i % args.buffers
-        tq.tq_sdpa_int4_partial(caches[j], qs[j], S, w.attn_scale, ws, **kw)
+        dominant(i % args.buffers)
     e1.record()
     torch.cuda.synchronize()
     kernel_us_b2b = e0.elapsed_time(e1) * 1e3 / args.steps
@@ -192,12 +203,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
                    "seq_len": S, "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
-                   "n_splits": n_splits, "variant": args.variant},
+                   "n_splits": n_splits, "variant": args.variant, "decode_launches": 1 if fused else 2},
         "effective_GBps": round(packed_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100 * packed_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
         "packed_bytes_per_step": packed_bytes,
         "host_wall_ms_timed_region": round(wall_ms, 2),
-        "roofline": {"bound": "hbm", "kernel": "fused partial kernel (phase 1)", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm",
+                     "kernel": ("decode_partial_mfma_kernel: fused int4 attention over the chunks + in-kernel chunk merge "
+                                "(the whole tq_sdpa_int4_decode call)" if fused else "partial kernel (phase 1 of the decode)"),
+                     "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None, "kernel_us_mean": round(kernel_us, 3),
                      "kernel_us_median": round(statistics.median(k_us), 3),

@@ -87,7 +87,12 @@ int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_ne
  * n_kv_heads) (GQA rule of Sec. 3.1).  out = softmax(attn_scale * q.K^) V^ over tokens
  * [0, seq_len), fp32 accumulation, fp16 result.  workspace: at least tq_workspace_bytes()
  * bytes, 256-byte aligned, holds the per-chunk partial results; contents undefined on return.
- * Equivalent to tq_sdpa_int4_partial followed by tq_sdpa_int4_reduce on the same stream.
+ * Same result as tq_sdpa_int4_partial followed by tq_sdpa_int4_reduce on the same stream (up to the
+ * order of the fp32 sums of the merge).  For short sequences, where launch overhead outweighs the
+ * stream (see tq_decode_launches), the matrix-core kernel does both in ONE launch: the block that
+ * finishes a (batch, KV head) last merges its chunks in place.  That path keeps its arrival counters in device memory owned by the
+ * library (16 sets, taken in turn, left zero by every launch): at most 16 decode calls may be
+ * in flight on one device at the same time.
  * Errors: NULL, SHAPE, EMPTY (seq_len < 1), CAPACITY (seq_len > capacity), WORKSPACE,
  * UNSUPPORTED, HIP. */
 int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
@@ -124,6 +129,12 @@ size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t 
 
 /* Chunk count the heuristic would pick (host only). */
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len);
+
+/* Kernel launches one tq_sdpa_int4_decode call makes for this cache shape, query head count,
+ * seq_len, attn_scale and opts (host only): 1 = partial results and chunk merge in one kernel,
+ * 2 = partial kernel + merge kernel, 0 = invalid arguments. */
+int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t seq_len,
+                           float attn_scale, const tq_decode_opts* opts);
 
 /* Static, NUL-terminated description of a status code. */
 const char* tq_status_string(int status);

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     KVCache,
     TqError,
     library_path,
+    tq_decode_launches,
     tq_dense_scratch_bytes,
     tq_dequant_then_attend,
     tq_kv_bytes,

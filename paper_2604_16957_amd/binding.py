@@ -67,6 +67,8 @@ def raw():
         L.tq_kv_bytes.restype = SZ
         L.tq_plan_splits.argtypes = [I, I, I]
         L.tq_plan_splits.restype = I
+        L.tq_decode_launches.argtypes = [CP, I, I, F, OP]
+        L.tq_decode_launches.restype = I
         L.tq_status_string.argtypes = [ctypes.c_int]
         L.tq_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -91,6 +93,13 @@ def tq_kv_bytes(batch: int, n_kv_heads: int, capacity: int, head_dim: int) -> in
 
 def tq_plan_splits(batch: int, n_kv_heads: int, seq_len: int) -> int:
     return int(raw().tq_plan_splits(batch, n_kv_heads, seq_len))
+
+
+def tq_decode_launches(cache: "KVCache", n_q_heads: int, seq_len: int, attn_scale: float, n_splits: int = 0,
+                       variant: int = 0) -> int:
+    """Kernel launches one tq_sdpa_int4_decode call makes for this configuration (1 or 2; 0 = invalid)."""
+    return int(raw().tq_decode_launches(ctypes.byref(cache.struct), int(n_q_heads), int(seq_len), float(attn_scale),
+                                        _opts(n_splits, variant)))
 
 
 class KVCache:

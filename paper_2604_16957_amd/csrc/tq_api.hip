@@ -92,6 +92,45 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
+// Which kernel a decode call takes, and whether that kernel can also do the chunk merge.
+struct Route { bool ok, use_mfma, merge; };
+// The in-kernel merge ends the kernel with a chain of device-wide round trips (publish the partial,
+// count in, read all partials) that one block walks alone: about 5 us, against about 3.5 us for the
+// separate merge kernel plus its launch.  It pays where the call is bound by launch overhead, not by
+// the stream: below this many packed bytes per call.
+constexpr int64_t kMergeInKernelMaxBytes = 48ll << 20;
+
+Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts) {
+  const int variant = opts ? opts->variant : 0;
+  // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
+  const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
+  if (variant == 2 && !scale_ok) return {false, false, false};
+  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok &&
+                                         tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
+  const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
+  return {true, use_mfma,
+          use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, cache->n_kv_heads)};
+}
+
+// Phase 1 (and, with `out`, the whole decode where the matrix-core kernel can merge in place).
+// *merged tells whether `out` has been written.
+int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len, float attn_scale,
+                       void* out, void* workspace, const tq_decode_opts* opts, int32_t* n_splits_out, bool* merged,
+                       void* stream) {
+  const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+  if (!r.ok) return TQ_ERR_UNSUPPORTED;
+  const bool use_mfma = r.use_mfma;
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
+                                use_mfma ? kBlocksMfma : kBlocksValu);
+  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
+  if (n_splits_out) *n_splits_out = plan.n_splits;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool merge = out != nullptr && r.merge;
+  if (merged) *merged = merge;
+  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, merge, s));
+  return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
+}
+
 }  // namespace
 
 extern "C" {
@@ -116,6 +155,18 @@ size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t 
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len) {
   if (batch < 1 || n_kv_heads < 1 || seq_len < 1) return 0;
   return plan_splits(batch, n_kv_heads, seq_len, 0, kBlocksMfma).n_splits;
+}
+
+int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t seq_len, float attn_scale,
+                           const tq_decode_opts* opts) {
+  const int rc = check_cache(cache);
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return 0;
+  if (n_q_heads < 1 || n_q_heads % cache->n_kv_heads != 0 || seq_len < 1 || seq_len > cache->capacity) return 0;
+  if (opts && (opts->variant < 0 || opts->variant > 2)) return 0;
+  if (opts && opts->variant == 2 && !tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads)) return 0;
+  const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+  if (!r.ok) return 0;
+  return r.merge ? 1 : 2;
 }
 
 const char* tq_status_string(int status) {
@@ -150,19 +201,7 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
                          int32_t* n_splits_out, void* stream) {
   const int rc = check_decode(cache, q, n_q_heads, seq_len, nullptr, workspace, workspace_bytes, opts, false);
   if (rc != TQ_OK) return rc;
-  const int variant = opts ? opts->variant : 0;
-  // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
-  const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
-  if (variant == 2 && !scale_ok) return TQ_ERR_UNSUPPORTED;
-  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok &&
-                                         tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
-                                use_mfma ? kBlocksMfma : kBlocksValu);
-  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, plan);
-  if (n_splits_out) *n_splits_out = plan.n_splits;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, s));
-  return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
+  return run_partial(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, opts, n_splits_out, nullptr, stream);
 }
 
 int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits, const void* workspace,
@@ -187,9 +226,9 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
   int rc = check_decode(cache, q, n_q_heads, seq_len, out, workspace, workspace_bytes, opts, true);
   if (rc != TQ_OK) return rc;
   int32_t n_splits = 0;
-  rc = tq_sdpa_int4_partial(cache, q, n_q_heads, seq_len, attn_scale, workspace, workspace_bytes, opts, &n_splits,
-                            stream);
-  if (rc != TQ_OK) return rc;
+  bool merged = false;
+  rc = run_partial(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, opts, &n_splits, &merged, stream);
+  if (rc != TQ_OK || merged) return rc;
   return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
                              stream);
 }

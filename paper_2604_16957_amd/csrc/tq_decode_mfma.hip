@@ -40,6 +40,7 @@
 // a block take 32-token supertiles of the chunk from a shared counter, keep private online-softmax
 // state, and are merged through LDS so that the block writes one partial (o_c, m_c, l_c) per query
 // head.
+#include <atomic>
 #include <type_traits>
 
 #include "tq_internal.h"
@@ -53,6 +54,14 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr float kNegBig = -1.0e30f;
+
+// Arrival counters of the in-kernel chunk merge: one per (b, kv head), kCounterSlots independent sets so
+// that decode calls in flight at the same time (other streams) do not share one.  Zero when the module
+// is loaded; the block that arrives last wraps its counter back to zero, so every launch leaves them
+// zero again.
+constexpr int kCounterSlots = 16;
+constexpr int kCountersPerSlot = 2048;
+__device__ unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
 constexpr uint32_t kMaskLo = 0x000F000Fu;   // nibbles 0 and 4 of a word -> fp16 subnormals c * 2^-24
 constexpr uint32_t kMaskHi = 0x00F000F0u;   // nibbles 1 and 5           -> c * 2^-20
@@ -192,6 +201,13 @@ __device__ __forceinline__ void dma16_x4(const void* sbase, uint32_t voff, uint3
                "global_load_lds_dwordx4 %0, %1 offset:1024\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048\n\t"
                "global_load_lds_dwordx4 %0, %1 offset:3072"
                :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+// device-scope (all compute dies) store and load of one float, without any cache-wide maintenance
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() {               // until at most N loads are outstanding
@@ -701,8 +717,85 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       den = fmaf(lds_l[w * GP + h], e, den);
     }
     const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * p.n_splits + split;
-    p.part_o[ph * D + j] = num;
-    if (j == 0) { p.part_ml[ph * 2] = mg; p.part_ml[ph * 2 + 1] = den; }
+    // device-scope stores: they go through to where every compute die sees them (the L2 caches of
+    // different dies are not coherent with each other), so no cache-wide write-back is needed later
+    st_dev(p.part_o + ph * D + j, num);
+    if (j == 0) { st_dev(p.part_ml + ph * 2, mg); st_dev(p.part_ml + ph * 2 + 1, den); }
+  }
+  if (p.merge_slot < 0) return;
+
+  // ---- chunk merge (Eq. 6) by whichever block of this (b, kv head) finishes last.  A block publishes
+  //      its partial (device-scope stores, waited for), then counts itself in; the one that sees all
+  //      others counted re-reads all partials, with device-scope loads and in chunk order, so the
+  //      result does not depend on which block that is.
+  const int n = p.n_splits;
+  int* const is_last = reinterpret_cast<int*>(smem);
+  wait_loads<0>();                                // vmcnt counts stores too: this wave's partial has landed
+  __syncthreads();                                // every wave's has; and nobody reads the block-merge area any more
+  if (threadIdx.x == 0) {
+    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * p.n_kv_heads + kv];
+    *is_last = atomicInc(ctr, (unsigned int)(n - 1)) == (unsigned int)(n - 1);   // wraps to 0 on the last arrival
+  }
+  __syncthreads();
+  if (*is_last == 0) return;
+  float* const c_m = reinterpret_cast<float*>(smem) + 64;     // [G][n] chunk maxima, then chunk weights
+  float* const c_l = c_m + GP * kMaxSplits;                    // [G][n] chunk sums
+  float* const h_den = c_l + GP * kMaxSplits;                  // [G]
+  const int64_t head0 = (int64_t)b * p.n_q_heads + kv * G;
+  // Everything is asked for at once, so the merge is about one memory round trip long: the first 32
+  // chunks of this thread's output elements (which do not need the weights yet) and the chunk maxima
+  // and sums; the weights are worked out while the loads are in flight.
+  constexpr int PER = GP * D / (NW * 64);         // output elements per thread (padded group)
+  constexpr int FIRST = 32;
+  float pre[PER][FIRST];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int idx = threadIdx.x + e * NW * 64, h = idx / D, j = idx % D;
+    const float* src = p.part_o + (head0 + (h < G ? h : 0)) * n * D + j;
+#pragma unroll
+    for (int u = 0; u < FIRST; ++u) pre[e][u] = ld_dev(src + (int64_t)(u < n ? u : n - 1) * D);
+  }
+  for (int idx = threadIdx.x; idx < G * n; idx += NW * 64) {
+    const float* ml = p.part_ml + (head0 * n + idx) * 2;                 // [h][c] is contiguous
+    c_m[(idx / n) * kMaxSplits + idx % n] = ld_dev(ml);
+    c_l[(idx / n) * kMaxSplits + idx % n] = ld_dev(ml + 1);
+  }
+  __syncthreads();
+  if (wave < G) {                                 // wave h: weights and denominator of head h
+    float mx = kNegBig;
+    for (int cc = lane; cc < n; cc += 64) mx = fmaxf(mx, c_m[wave * kMaxSplits + cc]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    float dsum = 0.0f;
+    for (int cc = lane; cc < n; cc += 64) {
+      const float w = __builtin_amdgcn_exp2f(c_m[wave * kMaxSplits + cc] - mx);
+      c_m[wave * kMaxSplits + cc] = w;
+      dsum = fmaf(c_l[wave * kMaxSplits + cc], w, dsum);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dsum += __shfl_xor(dsum, off);
+    if (lane == 0) h_den[wave] = dsum;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int idx = threadIdx.x + e * NW * 64, h = idx / D, j = idx % D;
+    if (h >= G) continue;
+    const float* src = p.part_o + (head0 + h) * n * D + j;
+    const float* w = c_m + h * kMaxSplits;
+    float num = 0.0f;
+#pragma unroll
+    for (int u = 0; u < FIRST; ++u) num = fmaf(pre[e][u], u < n ? w[u] : 0.0f, num);
+    int cc = FIRST;
+    for (; cc + 8 <= n; cc += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = ld_dev(src + (int64_t)(cc + u) * D);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) num = fmaf(v[u], w[cc + u], num);
+    }
+    for (; cc < n; ++cc) num = fmaf(ld_dev(src + (int64_t)cc * D), w[cc], num);
+    p.out[(head0 + h) * D + j] = (half_t)(num / h_den[h]);
   }
 }
 
@@ -713,6 +806,7 @@ int padded_gqa(int head_dim, int gqa) {
 
 template <int D, int GP>
 hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
+  static_assert((64 + (2 * GP * kMaxSplits + GP) ) * 4 <= Cfg<D, GP, 8>::SMEM, "the chunk merge reuses the block's LDS");
   // one block of 8 waves per compute unit: 8 rings of 3 x 5 KB (d=128) or 2 x 10 KB (d=256, all 160 KB of LDS)
   constexpr int NW = 8;
   constexpr int smem = Cfg<D, GP, NW>::SMEM;
@@ -734,7 +828,17 @@ bool mfma_supported(int head_dim, int gqa) {
   return (head_dim == 128 || head_dim == 256) && gqa >= 1 && padded_gqa(head_dim, gqa) != 0;
 }
 
-hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
+bool mfma_can_merge(int batch, int n_kv_heads) { return (int64_t)batch * n_kv_heads <= kCountersPerSlot; }
+
+hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim, bool merge_in_kernel,
+                               hipStream_t s) {
+  static std::atomic<unsigned int> next_slot{0};
+  DecodeParams p = p_in;
+  p.merge_slot = -1;
+  if (merge_in_kernel) {
+    if (!mfma_can_merge(batch, p.n_kv_heads) || p.out == nullptr) return hipErrorInvalidValue;
+    p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
+  }
   const dim3 grid(p.n_splits, p.n_kv_heads, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);

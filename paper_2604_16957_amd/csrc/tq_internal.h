@@ -33,6 +33,8 @@ struct DecodeParams {
   int32_t row_stride;       // tokens between consecutive (b, kv head) rows
   int32_t seq_len, n_splits, tokens_per_split;
   float scale_log2;         // attn_scale * log2(e)
+  int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
+                            // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };
 
 // Workspace carving: part_o first, then part_ml, both sized for kMaxSplits.
@@ -50,7 +52,9 @@ hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_den
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);
 bool mfma_supported(int head_dim, int gqa);
-hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
+// With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
+bool mfma_can_merge(int batch, int n_kv_heads);
+hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 
 }  // namespace tq

@@ -124,6 +124,27 @@ def test_reduce_and_baseline_reject_bad_arguments_without_a_gpu():
     assert d(ctypes.byref(c), FAKE, 64, 2000, 0.1, FAKE, FAKE, wsb, FAKE, need, None, None) == E.TQ_ERR_CAPACITY
 
 
+def test_decode_launch_count_query():
+    f = B.raw().tq_decode_launches
+    short = _cache()                                                  # 1024 tokens: launch-bound
+    assert f(ctypes.byref(short), 64, 1024, 0.1, None) == 1           # matrix-core kernel merges in place
+    generic = B.TqDecodeOptsStruct(0, 1)
+    assert f(ctypes.byref(short), 64, 1024, 0.1, ctypes.byref(generic)) == 2
+    assert f(ctypes.byref(short), 64, 1024, -0.1, None) == 2          # non-positive scale: generic kernel
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, None) == 2       # GQA ratio 16: no matrix-core tiling
+    forced = B.TqDecodeOptsStruct(0, 2)
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, ctypes.byref(forced)) == 0
+    assert f(ctypes.byref(short), 64, 1024, -0.1, ctypes.byref(forced)) == 0
+    assert f(ctypes.byref(short), 63, 1024, 0.1, None) == 0
+    assert f(ctypes.byref(short), 64, 0, 0.1, None) == 0 and f(ctypes.byref(short), 64, 1025, 0.1, None) == 0
+    assert f(None, 64, 1024, 0.1, None) == 0
+    long = _cache(capacity=131072)                                    # stream-bound: separate merge kernel
+    assert f(ctypes.byref(long), 64, 131072, 0.1, None) == 2
+    assert f(ctypes.byref(long), 64, 8192, 0.1, None) == 1
+    big = _cache(batch=512)                                           # more (batch, KV head) rows than counters
+    assert f(ctypes.byref(big), 64, 16, 0.1, None) == 2
+
+
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "_LIB_PATH", tmp_path / "nope.so")

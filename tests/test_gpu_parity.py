@@ -189,6 +189,26 @@ def test_bitwise_repeatable(variant):
         assert np.array_equal(first, again)
 
 
+def test_in_kernel_merge_agrees_with_the_two_phase_path():
+    """Where decode is one launch (the last block of a KV head merges its chunks in place), the
+    result matches partial + reduce: same partials, and the merge differs only in summation order.
+    Repeated calls and several chunk counts also check that the arrival counters are left clean."""
+    for shape, S in (("g8_d128_b2_kv3", 3000), ("g2_d256", 2100), ("g8_d128", 40)):
+        w = wl.custom(seq_len=S, seed=46, **SHAPES[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k, v)
+        ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
+        assert tq.tq_decode_launches(cache, q.shape[1], S, w.attn_scale) == 1
+        ws = torch.empty(tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
+        for n_splits in (0, 1, 3, 0, 17, 0):
+            fused = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, workspace=ws, n_splits=n_splits)
+            assert_close(fused, ref, f"{shape} in-kernel merge n_splits={n_splits}")
+            n = tq.tq_sdpa_int4_partial(cache, q.cuda(), S, w.attn_scale, ws, n_splits=n_splits)
+            two = tq.tq_sdpa_int4_reduce(w.batch, w.n_q_heads, w.head_dim, n, ws, torch.empty_like(fused))
+            a, b = np16(fused).astype(np.float64), np16(two).astype(np.float64)
+            assert np.abs(a - b).max() <= 2.0 ** -10 * max(1.0, np.abs(b).max())    # an fp16 ulp or two
+
+
 # ---------------------------------------------------------------- unfused comparator
 
 def test_dequant_then_attend_matches_oracle():
