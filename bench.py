@@ -35,7 +35,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="llama128k")
+    ap.add_argument("--workload", default="llama128k",
+                    help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | sweep80 "
+                         "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
+    ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--n-splits", type=int, default=0)
@@ -47,10 +50,143 @@ def parse():
     return ap.parse_args()
 
 
+def sweep(args):
+    """Full decode-step attention sweep: the Llama-70B shape x `layers` layers x batch 4 at 128K, every
+    (layer, batch element) with its own seed; a step appends one token per sequence per layer
+    (tq_quantize_kv) and attends (tq_sdpa_int4_decode), layer after layer on one stream."""
+    import numpy as np
+    import torch
+
+    import paper_2604_16957_amd as tq
+    import tq_workloads as wl
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    L, B = args.layers, 4
+    base = wl.WORKLOADS["llama128k"]
+    S, Hq, Hkv, d = base.seq_len, base.n_q_heads, base.n_kv_heads, base.head_dim
+    steps = args.steps if args.steps != 400 else 5
+    warmup = args.warmup if args.warmup != 40 else 1
+    samples = {(0, 0), (L - 1, B - 1)}           # (layer, batch element) pairs checked against the oracle
+    kept = {}
+    caches, qs, news = [], [], []
+    kb = torch.empty((B, Hkv, S, d), dtype=torch.float16, device=dev)
+    vb = torch.empty_like(kb)
+    for l in range(L):
+        q4 = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
+        for b in range(B):
+            q, k, v = wl.make_inputs(wl.layer_workload(l, b), device=dev)
+            q4[b], kb[b], vb[b] = q[0], k[0], v[0]
+            if (l, b) in samples:
+                kept[(l, b)] = (q.cpu(), k.cpu(), v.cpu())
+            del q, k, v
+        c = tq.KVCache(B, Hkv, d, S)
+        tq.tq_quantize_kv(c, kb[:, :, :S - 1].contiguous(), vb[:, :, :S - 1].contiguous(), 0)
+        news.append((kb[:, :, S - 1:].contiguous(), vb[:, :, S - 1:].contiguous()))
+        caches.append(c)
+        qs.append(q4)
+        if l % 10 == 9:
+            torch.cuda.synchronize()
+            print(f"# sweep: {l + 1}/{L} layers resident", file=sys.stderr, flush=True)
+    del kb, vb
+    torch.cuda.synchronize()
+    ws = torch.empty(tq.tq_workspace_bytes(B, Hq, d), dtype=torch.uint8, device=dev)
+    outs = torch.empty((L, B, Hq, d), dtype=torch.float16, device=dev)
+    alpha = base.attn_scale
+    packed = L * B * base.packed_bytes
+
+    def step():
+        for l in range(L):
+            tq.tq_quantize_kv(caches[l], news[l][0], news[l][1], S - 1)
+            tq.tq_sdpa_int4_decode(caches[l], qs[l], S, alpha, out=outs[l], workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / steps
+    # the dominant kernel: events around the first launch of each layer's decode, one more step
+    fused = tq.tq_decode_launches(caches[0], Hq, S, alpha) == 1
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+    n_splits = 0
+    for l in range(L):
+        tq.tq_quantize_kv(caches[l], news[l][0], news[l][1], S - 1)
+        evs[l][0].record()
+        if fused:
+            tq.tq_sdpa_int4_decode(caches[l], qs[l], S, alpha, out=outs[l], workspace=ws)
+        else:
+            n_splits = tq.tq_sdpa_int4_partial(caches[l], qs[l], S, alpha, ws)
+        evs[l][1].record()
+        if not fused:
+            tq.tq_sdpa_int4_reduce(B, Hq, d, n_splits, ws, outs[l])
+    torch.cuda.synchronize()
+    k_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
+    kernel_us = statistics.fmean(k_us)
+    per_launch = B * base.packed_bytes
+    achieved = per_launch / (kernel_us * 1e-6) / 1e9
+
+    cpu = check = None
+    if not args.no_cpu or not args.no_check:
+        import oracle
+        worst_abs = worst_rel = 0.0
+        exact = True
+        t_cpu = []
+        for (l, b), (q0, k0, v0) in sorted(kept.items()):
+            kc, ks, kz = oracle.quantize(k0.numpy())
+            vc, vs, vz = oracle.quantize(v0.numpy())
+            t = time.perf_counter()
+            ref = oracle.attend_packed(q0.numpy(), kc, ks, kz, vc, vs, vz, seq_len=S, alpha=alpha,
+                                       nthreads=oracle.default_threads())
+            t_cpu.append(time.perf_counter() - t)
+            got = outs[l, b].cpu().numpy().astype(np.float64)
+            diff = got - ref[0]
+            worst_abs = max(worst_abs, float(np.abs(diff).max()))
+            worst_rel = max(worst_rel, float(np.linalg.norm(diff) / np.linalg.norm(ref)))
+            exact = exact and bool(np.array_equal(caches[l].k_codes[b].cpu().numpy(), kc[0])
+                                   and np.array_equal(caches[l].v_codes[b].cpu().numpy(), vc[0]))
+        check = {"sampled_layer_batch": sorted(kept), "max_abs": worst_abs, "rel_l2": worst_rel,
+                 "codes_bit_exact": exact, "ok": worst_abs <= 2e-3 and worst_rel <= 1e-3 and exact}
+        if not args.no_cpu:
+            cpu = {"value": round(statistics.fmean(t_cpu) * 1e6 * L * B, 1), "unit": "us/decode-step",
+                   "cores": oracle.default_threads(), "kind": "oracle",
+                   "sample": f"{len(t_cpu)} of the {L * B} (layer, batch element) attention calls timed whole "
+                             f"(fp64 naive softmax over the packed cache), mean x {L * B}; appends not included"}
+    line = {
+        "metric": "us_per_decode_step (int4 SDPA, all layers, append + fused attention)",
+        "value": round(ms_per_step * 1e3, 1), "unit": "us/decode-step", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 codes + fp16 scale/zero in HBM; fp16 MFMA/VALU inputs, fp32 accumulate, fp16 out",
+        "data": "synthetic",
+        "config": {"workload": f"sweep{L}: llama128k shape x {L} layers x batch {B}, one token appended per sequence per layer",
+                   "batch": B, "layers": L, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "seq_len": S,
+                   "attn_scale": alpha, "group_size": 32, "n_splits": n_splits, "decode_launches": 1 if fused else 2},
+        "effective_GBps": round(packed / (ms_per_step * 1e-3) / 1e9, 1),
+        "pct_of_hbm_peak": round(100 * packed / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "packed_bytes_per_step": packed,
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_mfma_kernel, one launch per layer (batch 4)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel_us_mean": round(kernel_us, 2), "kernel_us_median": round(statistics.median(k_us), 2),
+                     "algorithmic_bytes_per_launch": per_launch},
+        "cpu_baseline": cpu, "oracle_check": check,
+    }
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists).")
+    if args.workload == "sweep80":
+        import torch
+        if not torch.cuda.is_available():
+            sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+        return sweep(args)
     import numpy as np
     import torch
 
