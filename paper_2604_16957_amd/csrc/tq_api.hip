@@ -31,13 +31,20 @@ struct Plan { int n_splits, tokens_per_split; };
 constexpr int kBlocksMfma = 256;   // matrix-core kernel: 8-wave blocks, one per compute unit
 constexpr int kBlocksValu = 512;   // generic kernel: 4-wave blocks, two per compute unit
 
-// Chunks of whole 32-token tiles, `target_blocks` blocks in all, never an empty chunk.
-Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int target_blocks) {
+// A chunk is never longer than this many tokens under the heuristic: the fp32 accumulators of one wave
+// then take in at most 64 tiles, which bounds the rounding they pick up however long the sequence is.
+constexpr int kMaxChunkTokens = 16384;
+
+// Chunks of whole 32-token tiles, `target_blocks` blocks in all, never an empty chunk; with
+// `tiles_per_block_min` > 1 short sequences get fewer, fuller blocks (one tile per wave at least).
+Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int target_blocks, int tiles_per_block_min) {
   const int tiles = (seq_len + tq::kTile - 1) / tq::kTile;
   int n = requested;
   if (n <= 0) {
     const int64_t rows = (int64_t)batch * n_kv_heads;
     n = (int)std::max<int64_t>(1, (target_blocks + rows - 1) / rows);
+    n = std::min(n, std::max(1, tiles / tiles_per_block_min));
+    n = std::max(n, (seq_len + kMaxChunkTokens - 1) / kMaxChunkTokens);
   }
   n = std::max(1, std::min({n, tiles, tq::kMaxSplits}));
   const int tiles_per = (tiles + n - 1) / n;
@@ -121,7 +128,7 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
   const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
-                                use_mfma ? kBlocksMfma : kBlocksValu);
+                                use_mfma ? kBlocksMfma : kBlocksValu, use_mfma ? 8 : 1);
   const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   if (n_splits_out) *n_splits_out = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -154,7 +161,7 @@ size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t 
 
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len) {
   if (batch < 1 || n_kv_heads < 1 || seq_len < 1) return 0;
-  return plan_splits(batch, n_kv_heads, seq_len, 0, kBlocksMfma).n_splits;
+  return plan_splits(batch, n_kv_heads, seq_len, 0, kBlocksMfma, 8).n_splits;
 }
 
 int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t seq_len, float attn_scale,
@@ -247,7 +254,7 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
   half_t* v_dense = k_dense + need / sizeof(half_t) / 2;
   rc = hip_rc(tq::launch_dequant_dense(*cache, seq_len, k_dense, v_dense, s));
   if (rc != TQ_OK) return rc;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, kBlocksValu);
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, kBlocksValu, 1);
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   p.k_dense = k_dense;
   p.v_dense = v_dense;

@@ -516,6 +516,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //    REFERENCE, not the exact running max: it only moves when some score exceeds it by more than
   //    kSlack (log2 units), so exp2(score - m_run) <= 2^kSlack = 4 and p * s_v stays inside fp16 for
   //    every representable scale, while the accumulator rescale (Alg. 1 lines 7, 9) becomes rare.
+  //    When it moves it is set kSlack ABOVE the new maximum, so the next move needs a score 2*kSlack
+  //    higher than any seen so far; the weights then start at 2^-kSlack, far inside fp16's normal range.
   //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.
   //    Then A = fp16(p * s_v), rows (head, replica), one operand per group of the lane; the zero-point
   //    term goes through the matrix core with the stored fp16 zero-points as B operand.
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                            fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
     if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {   // wave-uniform, rare
-      const float m_new = fmaxf(m_run, blocks_max(mx));
+      const float m_new = fmaxf(m_run, blocks_max(mx)) + slack;   // headroom: the next move is 2*kSlack away
       const float f = __builtin_amdgcn_exp2f((m_run - m_new) * kappa);
       m_run = m_new;
       l_run *= f;
