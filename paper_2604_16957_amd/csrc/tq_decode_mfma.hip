@@ -99,7 +99,10 @@ struct Cfg {
   static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
   static constexpr int RING = NW * NS * STAGE;
   static constexpr int MERGE = (NW * GP * D + NW * GP * NG + 2 * NW * GP) * 4;  // o, zero-point term, m, l
-  static constexpr int SMEM = RING > MERGE ? RING : MERGE;                   // the merge area reuses the rings
+  // the block-merge area sits behind the rings where both fit into the 160 KB of a compute unit, else on top of them
+  static constexpr bool ALIAS = RING + MERGE > 160 * 1024;
+  static constexpr int OFF_MERGE = ALIAS ? 0 : RING;
+  static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE) : RING + MERGE;
   // The fp16 scale and zero-point arrays are fetched dword by dword (two groups of one token), and the
   // direct loads may gather: with NA == 2 a lane needs exactly one dword per token, so the dwords are
   // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads.
@@ -671,12 +674,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     pv(vr, pa);
   }
 
-  // ---- wave result -> LDS (the merge area reuses the rings, so everybody must be done reading)
-  float* const lds_o = reinterpret_cast<float*>(smem);                 // [NW][GP][D]
+  // ---- wave result -> LDS.  Raw accumulators go out (the 2^24 / 2^20 of the two nibble positions is
+  //      applied once per output element below); of a lane's NA accumulators per row only the one
+  //      whose group the lane's packed word belongs to is meaningful, so it is selected first and
+  //      the eight dims of the word leave as two 16-byte writes.
+  float* const lds_o = reinterpret_cast<float*>(smem + C::OFF_MERGE);  // [NW][GP][D]
   float* const lds_zc = lds_o + NW * GP * D;                           // [NW][GP][NG]
   float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
   float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
-  __syncthreads();
+  if constexpr (C::ALIAS) __syncthreads();                   // everybody is done reading the rings
   const bool active = n_mine > 0 || tail_mine;
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
@@ -693,13 +699,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     for (int cs = 0; cs < NCS; ++cs) {
       const int word = c * NCS + cs;              // packed word (8 dims) this lane's column stands for
       const int a_mine = (word >> 2) - rp * NA;
+      float4v lo, hi;
 #pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        if (a == a_mine) {
-#pragma unroll
-          for (int m = 0; m < 8; ++m)
-            lds_o[(wave * GP + h) * D + word * 8 + m] = oacc[cs][m][a][i] * ((m & 1) ? 0x1p20f : 0x1p24f);
-        }
+      for (int m = 0; m < 4; ++m) {
+        lo[m] = (NA == 2 && a_mine == 1) ? oacc[cs][m][NA - 1][i] : oacc[cs][m][0][i];
+        hi[m] = (NA == 2 && a_mine == 1) ? oacc[cs][m + 4][NA - 1][i] : oacc[cs][m + 4][0][i];
+      }
+      if (a_mine >= 0 && a_mine < NA) {
+        float4v* dst = reinterpret_cast<float4v*>(lds_o + (wave * GP + h) * D + word * 8);
+        dst[0] = lo;
+        dst[1] = hi;
       }
     }
   }
@@ -708,6 +717,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- merge the waves, write one partial per query head (Sec. 3.2)
   for (int idx = threadIdx.x; idx < G * D; idx += NW * 64) {
     const int h = idx / D, j = idx % D;
+    const float unit = (j & 1) ? 0x1p20f : 0x1p24f;          // odd dims were read from the high nibble position
     float mg = lds_m[h];
 #pragma unroll
     for (int w = 1; w < NW; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
@@ -715,7 +725,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
-      num = fmaf(lds_o[(w * GP + h) * D + j] - lds_zc[(w * GP + h) * NG + (j >> 5)], e, num);
+      num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
       den = fmaf(lds_l[w * GP + h], e, den);
     }
     const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * p.n_splits + split;
