@@ -168,6 +168,18 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   __shared__ float red_m[4], red_l[4];
   __shared__ float acc_part[PARTS][D];
 
+  // the first chunks of this thread's output element are asked for before anything else: they do not
+  // depend on the weights, so the kernel is about one memory round trip long
+  constexpr int FIRST = 16;
+  const int j = tid % D, part = tid / D;
+  const float* src = p.part_o + ph0 * D + j;
+  float pre[FIRST];
+#pragma unroll
+  for (int u = 0; u < FIRST; ++u) {
+    const int c = part + u * PARTS;
+    pre[u] = src[(int64_t)(c < n ? c : n - 1) * D];
+  }
+
   float m = kNegBig, l = 0.0f;
   if (tid < n) {
     const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
@@ -189,10 +201,13 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   __syncthreads();
   const float den = (red_l[0] + red_l[1]) + (red_l[2] + red_l[3]);
 
-  const int j = tid % D, part = tid / D;
-  const float* src = p.part_o + ph0 * D + j;
   float num = 0.0f;
-  int c = part;
+#pragma unroll
+  for (int u = 0; u < FIRST; ++u) {
+    const int c = part + u * PARTS;
+    num = fmaf(pre[u], c < n ? w_c[c] : 0.0f, num);
+  }
+  int c = part + FIRST * PARTS;
   for (; c + 7 * PARTS < n; c += 8 * PARTS) {
     float v[8];
 #pragma unroll
