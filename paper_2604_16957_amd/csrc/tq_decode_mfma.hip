@@ -17,11 +17,18 @@
 // sum_t p_t v^_t = sum_t (p_t s_t) c_t - sum_t (p_t s_t) z_t, where the product p_t s_t is rounded
 // to fp16 once and the SAME rounded operand multiplies the codes and (in a small extra MFMA whose
 // B operand is the stored fp16 zero-point itself) the zero-points.
-// The matrix core truncates when it adds into the fp32 accumulator (measured: about -0.3 ulp per
-// step), and both sums are sums of positive terms ~200x larger than the result, so they are centred
-// inside the accumulator: every such MFMA is followed by one of the same A operand against the
-// constant -8 (the matrix pipe is otherwise mostly idle).  The running sums stay at the size of
-// the result.
+// The matrix core aligns the 32 products of an MFMA to its fp32 accumulator and TRUNCATES each of
+// them, so an accumulator that grows (a sum of positive terms, ~200x larger than the result it is
+// later differenced into) costs accuracy in proportion to the tokens it has taken in.  Both sums are
+// therefore kept balanced around zero, at no cost in matrix instructions: a supertile is two 16-token
+// tiles, and the weights of the SECOND tile enter the A operand negated.  For the codes the second
+// tile's nibbles are complemented (15 - c, one NOT per packed word):
+//   sum_t0 w c - sum_t1 w (15 - c)  =  sum_t w c  - 15 sum_t1 w ,
+// for the zero-points the second tile's B entries get their sign flipped and a constant B operand
+// (0 on first-tile slots, 15 on second-tile slots) follows:
+//   sum_t w z - 15 sum_t1 w .
+// The two 15 sum_t1 w terms cancel in the difference, exactly (same A operand), and each running sum
+// stays at the size of the result.
 //
 // Mapping (one 64-lane wave; lane = 16*kq + c):
 //   QK^T is computed transposed, S^T = K Q^T: A = codes (row = token, 8 k-slots per lane = one packed
@@ -65,9 +72,7 @@ __device__ unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
 constexpr uint32_t kMaskLo = 0x000F000Fu;   // nibbles 0 and 4 of a word -> fp16 subnormals c * 2^-24
 constexpr uint32_t kMaskHi = 0x00F000F0u;   // nibbles 1 and 5           -> c * 2^-20
-constexpr uint32_t kNeg8Lo = 0x80088008u;   // two fp16 of value -8 * 2^-24
-constexpr uint32_t kNeg8Hi = 0x80808080u;   // two fp16 of value -8 * 2^-20
-constexpr uint32_t kNeg8 = 0xC800C800u;     // two fp16 of value -8
+constexpr uint32_t kPos15Odd = 0x4B800000u; // fp16 pair (0, 15): k-slots alternate first tile, second tile
 
 template <int D, int GP, int NW>
 struct Cfg {
@@ -401,8 +406,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- running state
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
   float l_run = 0.0f;                             // this lane's share of sum(exp)
-  float4v zacc[NA];                               // sum_t (p s_v)(z_v - 8), rows (head, replica), col = group
-  float4v oacc[NCS][8][NA];                       // sum_t (p s_v)(c - 8), rows (head, replica), col = packed word
+  float4v zacc[NA];                               // sum_t w z - 15 sum_t1 w (w = p s_v), rows (head, replica), col = group
+  float4v oacc[NCS][8][NA];                       // sum_t w c - 15 sum_t1 w, rows (head, replica), col = packed word
 #pragma unroll
   for (int a = 0; a < NA; ++a) zacc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
@@ -412,9 +417,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
       for (int a = 0; a < NA; ++a) oacc[cs][m][a] = float4v{0, 0, 0, 0};
 
-  const half8v neg8_lo = as_half8(kNeg8Lo, kNeg8Lo, kNeg8Lo, kNeg8Lo);
-  const half8v neg8_hi = as_half8(kNeg8Hi, kNeg8Hi, kNeg8Hi, kNeg8Hi);
-  const half8v neg8 = as_half8(kNeg8, kNeg8, kNeg8, kNeg8);
+  const half8v pos15_odd = as_half8(kPos15Odd, kPos15Odd, kPos15Odd, kPos15Odd);
 
   // per-lane LDS byte offsets inside a stage
   // K codes: the 16 B this lane asked for; where the query operand is block-diagonal over pairs of
@@ -522,8 +525,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //    When it moves it is set kSlack ABOVE the new maximum, so the next move needs a score 2*kSlack
   //    higher than any seen so far; the weights then start at 2^-kSlack, far inside fp16's normal range.
   //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.
-  //    Then A = fp16(p * s_v), rows (head, replica), one operand per group of the lane; the zero-point
-  //    term goes through the matrix core with the stored fp16 zero-points as B operand.
+  //    Then A = fp16(+-p * s_v) (minus on the second tile's k-slots), rows (head, replica), one operand
+  //    per group of the lane; the zero-point term goes through the matrix core with the stored fp16
+  //    zero-points (sign flipped on the second tile's k-slots) as B operand.
   auto softmax = [&](const float (&sc)[2][4], const VRegs& r, half8v (&pa)[NA]) {
     const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                            fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
@@ -563,25 +567,25 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
         pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)sz_half(r.vs[0][i], a), 0.0f);
-        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(pr[1][i], (float)sz_half(r.vs[1][i], a), 0.0f);
+        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(-pr[1][i], (float)sz_half(r.vs[1][i], a), 0.0f);
       }
     }
     if constexpr (C::PERM) {
       uint32_t zw[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) zw[i] = __builtin_amdgcn_perm(r.zb[4 + i], r.zb[i], zb_sel);
+      for (int i = 0; i < 4; ++i) zw[i] = __builtin_amdgcn_perm(r.zb[4 + i], r.zb[i], zb_sel) ^ 0x80000000u;
       zb = as_half8(zw[0], zw[1], zw[2], zw[3]);
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         zb[2 * i] = sz_half(r.zb[i], 0);
-        zb[2 * i + 1] = sz_half(r.zb[4 + i], 0);
+        zb[2 * i + 1] = -sz_half(r.zb[4 + i], 0);
       }
     }
 #pragma unroll
     for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], zb, zacc[a]);
 #pragma unroll
-    for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], neg8, zacc[a]);
+    for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], pos15_odd, zacc[a]);
   };
 
   // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
@@ -592,8 +596,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       uint32_t x[8], y[8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        x[i] = __builtin_amdgcn_perm(r.v[cs][i + 4], r.v[cs][i], 0x05040100u);
-        x[i + 4] = __builtin_amdgcn_perm(r.v[cs][i + 4], r.v[cs][i], 0x07060302u);
+        const uint32_t v1 = ~r.v[cs][i + 4];      // second tile: 15 - code in every nibble
+        x[i] = __builtin_amdgcn_perm(v1, r.v[cs][i], 0x05040100u);
+        x[i + 4] = __builtin_amdgcn_perm(v1, r.v[cs][i], 0x07060302u);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -612,11 +617,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         for (int a = 0; a < NA; ++a) {
           oacc[cs][2 * I][a] = mfma16(pa[a], v_even, oacc[cs][2 * I][a]);
           oacc[cs][2 * I + 1][a] = mfma16(pa[a], v_odd, oacc[cs][2 * I + 1][a]);
-        }
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-          oacc[cs][2 * I][a] = mfma16(pa[a], neg8_lo, oacc[cs][2 * I][a]);
-          oacc[cs][2 * I + 1][a] = mfma16(pa[a], neg8_hi, oacc[cs][2 * I + 1][a]);
         }
       }
     }
