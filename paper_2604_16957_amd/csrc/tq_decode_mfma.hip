@@ -1,4 +1,5 @@
-// Matrix-core fused int4 decode attention for gfx950 (phase 1 of Sec. 3.2: per-chunk partials).
+// Matrix-core fused int4 decode attention for gfx950 (phase 1 of Sec. 3.2: per-chunk partials; for
+// short sequences also phase 2, the chunk merge of Eq. 6, done by the block that finishes last).
 //
 // Why matrix cores: with a GQA group of G query heads every stored element is used by G heads;
 // at G=8 and d=128 that is 25.6 flop per HBM byte, above the vector-ALU ridge of the chip, so the
@@ -7,8 +8,13 @@
 //
 // Data path: the packed stream never passes through vector registers on its way in.  Each wave owns
 // a ring of LDS stages and fills them with direct global->LDS loads (global_load_lds_dwordx4: 64
-// lanes x 16 B = 1 KB per instruction, tracked by vmcnt), two to three 32-token supertiles ahead
-// of the one being consumed, so ~10 KB per wave are in flight with no register cost.
+// lanes x 16 B = 1 KB per instruction, tracked by vmcnt), one 32-token supertile ahead of the one
+// being consumed, with no register cost; the per-lane source address of such a load is free, so K
+// codes and the fp16 scale / zero-point arrays are gathered into the order the lanes read them back
+// in.  What a supertile needs from LDS is copied into registers ahead of use (its V part at the start
+// of its K phase, the next supertile's K part during the current softmax / P V phase).  The ring is
+// only two stages deep on purpose: once the last byte has landed every wave still has `ring depth`
+// supertiles to compute, and at 16 supertiles per wave that drain outweighs a deeper prefetch.
 //
 // Exactness: codes 0..15 enter the MFMA as fp16 SUBNORMALS (the nibble sits in the low mantissa
 // bits, value c*2^-24, or c*2^-20 for a nibble at bit 4) so unpacking is one AND per pair of
@@ -44,9 +50,9 @@
 //   the nibble-level stage is free because the unpack masks already separate even and odd nibbles.
 //
 // Work split: grid (n_splits, H_kv, B), 8 waves per block, one block per compute unit; the waves of
-// a block take 32-token supertiles of the chunk from a shared counter, keep private online-softmax
-// state, and are merged through LDS so that the block writes one partial (o_c, m_c, l_c) per query
-// head.
+// a block share the chunk's 32-token supertiles in a fixed pattern (9:7 between the older and the
+// younger wave of a SIMD, see the kernel), keep private online-softmax state, and are merged through
+// LDS so that the block writes one partial (o_c, m_c, l_c) per query head.
 #include <atomic>
 #include <type_traits>
 
