@@ -36,7 +36,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="llama128k",
-                    help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | sweep80 "
+                    help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | varlen8 (8 sequences of "
+                         "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | sweep80 "
                          "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
@@ -197,8 +198,19 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    w = wl.WORKLOADS[args.workload]
+    varlen = args.workload == "varlen8"
+    if varlen:     # continuous batching: 8 sequences of the llama shape, lengths drawn in [4096, 32768]
+        w = wl.custom("varlen8", batch=8, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=32768, seed=1100,
+                      outlier_channels=4)
+    else:
+        w = wl.WORKLOADS[args.workload]
     S, B, Hq, Hkv, d = w.seq_len, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    lens = None
+    if varlen:
+        g = torch.Generator().manual_seed(w.seed + 5)
+        lens = torch.randint(4096, S + 1, (B,), generator=g, dtype=torch.int32)
+        lens[0] = S                               # the bound is attained
+        lens_dev, pos_dev = lens.to(dev), (lens - 1).to(dev)
 
     # ---- resident inputs: `buffers` caches, each pre-filled with S-1 tokens; the step appends token S-1
     caches, qs, news = [], [], []
@@ -214,13 +226,25 @@ def main():
     torch.cuda.synchronize()
     ws = torch.empty(tq.tq_workspace_bytes(B, Hq, d), dtype=torch.uint8, device=dev)
     out = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
-    packed_bytes = w.packed_bytes
+    packed_bytes = w.packed_bytes if lens is None else int(lens.sum()) * Hkv * (w.packed_bytes // (B * Hkv * S))
     kw = dict(n_splits=args.n_splits, variant=args.variant)
+
+    def append(j):                                # the step's new token goes to the end of every sequence
+        if lens is None:
+            tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
+        else:
+            tq.tq_quantize_kv_varlen(caches[j], news[j][0], news[j][1], pos_dev)
+
+    def decode(j):
+        if lens is None:
+            tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
+        else:
+            tq.tq_sdpa_int4_decode_varlen(caches[j], qs[j], lens_dev, S, w.attn_scale, out=out, workspace=ws, **kw)
 
     def step(i):
         j = i % args.buffers
-        tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
-        tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
+        append(j)
+        decode(j)
 
     # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
     for i in range(args.warmup):
@@ -245,18 +269,18 @@ def main():
     n_splits = tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
 
     def dominant(j):
-        if fused:
-            tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
+        if fused or lens is not None:             # (no separate phase-1 entry point takes per-sequence lengths)
+            decode(j)
         else:
             tq.tq_sdpa_int4_partial(caches[j], qs[j], S, w.attn_scale, ws, **kw)
 
     for i in range(args.steps):
         j = i % args.buffers
-        tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
+        append(j)
         evs[i][0].record()
         dominant(j)
         evs[i][1].record()
-        if not fused:
+        if not fused and lens is None:
             tq.tq_sdpa_int4_reduce(B, Hq, d, n_splits, ws, out)
     torch.cuda.synchronize()
     k_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
@@ -283,7 +307,7 @@ def main():
 
     # ---- unfused comparator on the same inputs
     baseline = None
-    if not args.no_baseline:
+    if not args.no_baseline and lens is None:
         dense = torch.empty(tq.tq_dense_scratch_bytes(B, Hkv, S, d), dtype=torch.uint8, device=dev)
         nb = max(3, min(20, args.steps // 10))
         for i in range(2):
@@ -320,10 +344,17 @@ def main():
         threads = oracle.default_threads()
         reps, times = 3, []
         ref = None
+        def oracle_attend():
+            if lens is None:
+                return oracle.attend_packed(q0.numpy(), kc, ks, kz, vc, vs, vz, seq_len=S, alpha=w.attn_scale,
+                                            nthreads=threads)
+            return np.concatenate([oracle.attend_packed(q0.numpy()[b:b + 1], *[a[b:b + 1] for a in (kc, ks, kz, vc, vs, vz)],
+                                                        seq_len=int(lens[b]), alpha=w.attn_scale, nthreads=threads)
+                                   for b in range(B)], axis=0)
+
         for _ in range(reps if not args.no_cpu else 1):
             t = time.perf_counter()
-            ref = oracle.attend_packed(q0.numpy(), kc, ks, kz, vc, vs, vz, seq_len=S, alpha=w.attn_scale,
-                                       nthreads=threads)
+            ref = oracle_attend()
             times.append(time.perf_counter() - t)
         if not args.no_cpu:
             cpu = {"value": round(statistics.median(times) * 1e6, 1), "unit": "us/decode-step", "cores": threads,
@@ -333,7 +364,10 @@ def main():
         if not args.no_check:
             c = tq.KVCache(B, Hkv, d, S)
             tq.tq_quantize_kv(c, k0.to(dev), v0.to(dev), 0)
-            o = tq.tq_sdpa_int4_decode(c, q0.to(dev), S, w.attn_scale, workspace=ws, **kw)
+            if lens is None:
+                o = tq.tq_sdpa_int4_decode(c, q0.to(dev), S, w.attn_scale, workspace=ws, **kw)
+            else:
+                o = tq.tq_sdpa_int4_decode_varlen(c, q0.to(dev), lens_dev, S, w.attn_scale, workspace=ws, **kw)
             torch.cuda.synchronize()
             diff = o.cpu().numpy().astype(np.float64) - ref
             check = {"max_abs": float(np.abs(diff).max()), "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(ref)),
@@ -349,7 +383,7 @@ def main():
         "vs_baseline": None, "dtype": "int4 codes + fp16 scale/zero in HBM; fp16 MFMA/VALU inputs, fp32 accumulate, fp16 out",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
-                   "seq_len": S, "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
+                   "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "decode_launches": 1 if fused else 2},
         "effective_GBps": round(packed_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100 * packed_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
@@ -357,7 +391,9 @@ def main():
         "host_wall_ms_timed_region": round(wall_ms, 2),
         "roofline": {"bound": "hbm",
                      "kernel": ("decode_partial_mfma_kernel: fused int4 attention over the chunks + in-kernel chunk merge "
-                                "(the whole tq_sdpa_int4_decode call)" if fused else "partial kernel (phase 1 of the decode)"),
+                                "(the whole tq_sdpa_int4_decode call)" if fused else
+                                "partial kernel (phase 1 of the decode)" if lens is None else
+                                "the whole tq_sdpa_int4_decode_varlen call (partial kernel + merge kernel)"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None, "kernel_us_mean": round(kernel_us, 3),

@@ -82,6 +82,13 @@ typedef struct tq_decode_opts {
 int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_new, int32_t pos,
                    int32_t n_new, void* stream);
 
+/* The same with one position per sequence, as a decode server appends: sequence b is written at
+ * positions[b] .. positions[b]+n_new-1.  positions: DEVICE int32 [batch], read by the kernel (the
+ * host never sees the values): a sequence whose tokens would not fit into [0, capacity) is skipped,
+ * nothing of it is written.  Errors: NULL, SHAPE, EMPTY, CAPACITY (n_new > capacity), ALIGN, HIP. */
+int tq_quantize_kv_varlen(const tq_kv_cache* cache, const void* k_new, const void* v_new,
+                          const int32_t* positions, int32_t n_new, void* stream);
+
 /* Fused compressed-domain decode attention (Sec. 3.1 Alg. 1 + Sec. 3.2 Eq. 6).
  * q, out: fp16 [batch][n_q_heads][head_dim]; query head h reads KV head h / (n_q_heads /
  * n_kv_heads) (GQA rule of Sec. 3.1).  out = softmax(attn_scale * q.K^) V^ over tokens
@@ -98,6 +105,17 @@ int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_ne
 int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
                         float attn_scale, void* out, void* workspace, size_t workspace_bytes,
                         const tq_decode_opts* opts, void* stream);
+
+/* The same with one length per sequence (continuous batching; the paper's kernel takes one
+ * common N, Alg. 1): sequence b attends tokens [0, seq_lens[b]).  seq_lens: DEVICE int32 [batch],
+ * read by the kernels; each value is clamped to [1, max_seq_len].  max_seq_len (host, <= capacity)
+ * bounds them and sizes the chunking: chunks past a sequence's end do no work, so the call costs
+ * what the longest sequence costs per (batch, KV head) row it occupies.  Other arguments, routes
+ * and errors as for tq_sdpa_int4_decode (EMPTY / CAPACITY refer to max_seq_len). */
+int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads,
+                               const int32_t* seq_lens, int32_t max_seq_len, float attn_scale,
+                               void* out, void* workspace, size_t workspace_bytes,
+                               const tq_decode_opts* opts, void* stream);
 
 /* The two phases of Sec. 3.2, separately callable (used for per-kernel timing).
  * partial: every chunk c writes (o_c, m_c, l_c) for each query head into workspace and

@@ -53,6 +53,8 @@ def raw():
         OP = ctypes.POINTER(TqDecodeOptsStruct)
         L.tq_quantize_kv.argtypes = [CP, P, P, I, I, P]
         L.tq_sdpa_int4_decode.argtypes = [CP, P, I, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_decode_varlen.argtypes = [CP, P, I, P, I, F, P, P, SZ, OP, P]
+        L.tq_quantize_kv_varlen.argtypes = [CP, P, P, P, I, P]
         L.tq_sdpa_int4_partial.argtypes = [CP, P, I, I, F, P, SZ, OP, ctypes.POINTER(ctypes.c_int32), P]
         L.tq_sdpa_int4_reduce.argtypes = [I, I, I, I, P, SZ, P, P]
         L.tq_dequant_then_attend.argtypes = [CP, P, I, I, F, P, P, SZ, P, SZ, OP, P]
@@ -178,6 +180,33 @@ def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scal
                                    _opts(n_splits, variant), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode")
     return out
+
+
+def tq_sdpa_int4_decode_varlen(cache: KVCache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                               attn_scale: float, out=None, workspace=None, n_splits: int = 0, variant: int = 0,
+                               stream=None) -> torch.Tensor:
+    """q: fp16 [B, H_q, d]; seq_lens: int32 device tensor [B] -> out fp16 [B, H_q, d]."""
+    _need(q, torch.float16, "q")
+    _need(seq_lens, torch.int32, "seq_lens")
+    if out is None:
+        out = torch.empty_like(q)
+    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
+    rc = raw().tq_sdpa_int4_decode_varlen(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]),
+                                          seq_lens.data_ptr(), int(max_seq_len), float(attn_scale), out.data_ptr(),
+                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_decode_varlen")
+    return out
+
+
+def tq_quantize_kv_varlen(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, positions: torch.Tensor,
+                          stream=None) -> None:
+    """k_new, v_new: fp16 [B, H_kv, n_new, d]; positions: int32 device tensor [B]."""
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    _need(positions, torch.int32, "positions")
+    rc = raw().tq_quantize_kv_varlen(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(),
+                                     positions.data_ptr(), int(k_new.shape[2]), _stream_ptr(stream))
+    _check(rc, "tq_quantize_kv_varlen")
 
 
 def tq_sdpa_int4_partial(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, workspace: torch.Tensor,

@@ -121,15 +121,18 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
 
 // Phase 1 (and, with `out`, the whole decode where the matrix-core kernel can merge in place).
 // *merged tells whether `out` has been written.
-int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len, float attn_scale,
-                       void* out, void* workspace, const tq_decode_opts* opts, int32_t* n_splits_out, bool* merged,
-                       void* stream) {
+int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                const int32_t* seq_lens, float attn_scale, void* out, void* workspace, const tq_decode_opts* opts,
+                int32_t* n_splits_out, bool* merged, void* stream, int32_t* tokens_per_split_out = nullptr) {
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
-                                use_mfma ? kBlocksMfma : kBlocksValu, use_mfma ? 8 : 1);
-  const DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
+  const int target = use_mfma ? kBlocksMfma : kBlocksValu;
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, target,
+                                use_mfma ? 8 : 1);
+  if (tokens_per_split_out) *tokens_per_split_out = plan.tokens_per_split;
+  DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
+  p.seq_lens = seq_lens;
   if (n_splits_out) *n_splits_out = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool merge = out != nullptr && r.merge;
@@ -200,7 +203,19 @@ int tq_quantize_kv(const tq_kv_cache* cache, const void* k_new, const void* v_ne
   if (n_new < 1) return TQ_ERR_EMPTY;
   if (pos < 0 || (int64_t)pos + n_new > cache->capacity) return TQ_ERR_CAPACITY;
   if (rc == TQ_ERR_ALIGN || !aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
-  return hip_rc(tq::launch_quantize(*cache, k_new, v_new, pos, n_new, static_cast<hipStream_t>(stream)));
+  return hip_rc(tq::launch_quantize(*cache, k_new, v_new, pos, nullptr, n_new, static_cast<hipStream_t>(stream)));
+}
+
+int tq_quantize_kv_varlen(const tq_kv_cache* cache, const void* k_new, const void* v_new, const int32_t* positions,
+                          int32_t n_new, void* stream) {
+  int rc = check_cache(cache);
+  if (rc == TQ_ERR_NULL) return rc;
+  if (!k_new || !v_new || !positions) return TQ_ERR_NULL;
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
+  if (n_new < 1) return TQ_ERR_EMPTY;
+  if (n_new > cache->capacity) return TQ_ERR_CAPACITY;
+  if (rc == TQ_ERR_ALIGN || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(positions, 4)) return TQ_ERR_ALIGN;
+  return hip_rc(tq::launch_quantize(*cache, k_new, v_new, 0, positions, n_new, static_cast<hipStream_t>(stream)));
 }
 
 int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
@@ -208,7 +223,8 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
                          int32_t* n_splits_out, void* stream) {
   const int rc = check_decode(cache, q, n_q_heads, seq_len, nullptr, workspace, workspace_bytes, opts, false);
   if (rc != TQ_OK) return rc;
-  return run_partial(cache, q, n_q_heads, seq_len, attn_scale, nullptr, workspace, opts, n_splits_out, nullptr, stream);
+  return run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, nullptr, workspace, opts, n_splits_out, nullptr,
+                     stream);
 }
 
 int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits, const void* workspace,
@@ -234,10 +250,34 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
   if (rc != TQ_OK) return rc;
   int32_t n_splits = 0;
   bool merged = false;
-  rc = run_partial(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, opts, &n_splits, &merged, stream);
+  rc = run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, out, workspace, opts, &n_splits, &merged, stream);
   if (rc != TQ_OK || merged) return rc;
   return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
                              stream);
+}
+
+int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, const int32_t* seq_lens,
+                               int32_t max_seq_len, float attn_scale, void* out, void* workspace,
+                               size_t workspace_bytes, const tq_decode_opts* opts, void* stream) {
+  int rc = check_decode(cache, q, n_q_heads, max_seq_len, out, workspace, workspace_bytes, opts, true);
+  if (rc != TQ_OK) return rc;
+  if (!seq_lens) return TQ_ERR_NULL;
+  if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
+  int32_t n_splits = 0, tokens_per_split = 0;
+  bool merged = false;
+  rc = run_partial(cache, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, &n_splits, &merged,
+                   stream, &tokens_per_split);
+  if (rc != TQ_OK || merged) return rc;
+  DecodeParams p{};                               // the merge skips the chunks past each sequence's end
+  p.part_o = static_cast<float*>(workspace);
+  p.part_ml = p.part_o + tq::workspace_o_floats(cache->batch, n_q_heads, cache->head_dim);
+  p.out = static_cast<half_t*>(out);
+  p.n_q_heads = n_q_heads;
+  p.n_splits = n_splits;
+  p.seq_lens = seq_lens;
+  p.seq_len = max_seq_len;
+  p.tokens_per_split = tokens_per_split;
+  return hip_rc(tq::launch_reduce(p, cache->batch, cache->head_dim, static_cast<hipStream_t>(stream)));
 }
 
 int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,

@@ -248,10 +248,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
   const int begin = split * p.tokens_per_split;
-  const int end = min(p.seq_len, begin + p.tokens_per_split);
+  // tokens this sequence attends: the common length, or its own (a chunk past its end is empty)
+  const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
+  // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
+  // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
+  // goes through and publishes an empty partial.)
+  if (begin >= seq && p.merge_slot < 0) return;
+  const int end = max(begin, min(seq, begin + p.tokens_per_split));
   const int n_full = (end - begin) >> 5;          // whole 32-token supertiles of this chunk
   const bool has_tail = ((end - begin) & 31) != 0;  // only the sequence's last supertile can be ragged
-  const int last_tok = p.seq_len - 1;
+  const int last_tok = seq - 1;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
   const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),

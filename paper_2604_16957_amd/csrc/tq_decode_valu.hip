@@ -65,7 +65,9 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   }
 
   const int begin = split * p.tokens_per_split;
-  const int end = min(p.seq_len, begin + p.tokens_per_split);
+  const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
+  if (begin >= seq) return;                              // chunk past the end of its sequence: nothing to emit
+  const int end = min(seq, begin + p.tokens_per_split);
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
 
   for (int t0 = begin; t0 < end; t0 += SPB) {
@@ -162,8 +164,13 @@ template <int D>
 __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   constexpr int PARTS = 256 / D;
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const int n = p.n_splits;
-  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * n;
+  // chunks that exist for this sequence: all of them, or those that start before its own end
+  int n = p.n_splits;
+  if (p.seq_lens) {
+    const int seq = max(1, min(p.seq_lens[b], p.seq_len));
+    n = min(n, (seq + p.tokens_per_split - 1) / p.tokens_per_split);
+  }
+  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * p.n_splits;
   __shared__ float w_c[kMaxSplits];
   __shared__ float red_m[4], red_l[4];
   __shared__ float acc_part[PARTS][D];

@@ -26,12 +26,13 @@ struct DecodeParams {
   const half_t* k_dense;    // comparator only: [B][H_kv][row_stride][D]
   const half_t* v_dense;
   const half_t* q;          // [B][H_q][D]
+  const int32_t* seq_lens;  // device, [B], or null: tokens each sequence attends (clamped to [1, seq_len])
   float* part_o;            // [B][H_q][n_splits][D]   un-normalised chunk outputs
   float* part_ml;           // [B][H_q][n_splits][2]   (running max in log2 units, sum of exp)
   half_t* out;              // [B][H_q][D]
   int32_t n_q_heads, n_kv_heads, gqa;
   int32_t row_stride;       // tokens between consecutive (b, kv head) rows
-  int32_t seq_len, n_splits, tokens_per_split;
+  int32_t seq_len, n_splits, tokens_per_split;   // seq_len: every sequence's length, or the bound of seq_lens
   float scale_log2;         // attn_scale * log2(e)
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
@@ -46,8 +47,10 @@ inline size_t workspace_ml_floats(int batch, int n_q_heads) {
 }
 
 // Launchers (each returns a hipError_t from hipGetLastError after the launch).
-hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos, int n_new,
-                           hipStream_t s);
+// pos_dev (device, [B]) non-null: sequence b is written at pos_dev[b]; a sequence whose tokens would not
+// fit into [0, capacity) is skipped
+hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos,
+                           const int32_t* pos_dev, int n_new, hipStream_t s);
 hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_dense, half_t* v_dense,
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);

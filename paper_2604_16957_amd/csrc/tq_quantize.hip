@@ -18,7 +18,8 @@ struct QuantParams {
   uint8_t* codes[2];      // [B*H_kv][capacity][D/2]
   half_t* scale[2];       // [B*H_kv][capacity][D/32]
   half_t* zero[2];
-  int32_t n_new, capacity, pos, head_dim;
+  int32_t n_new, capacity, pos, head_dim, n_kv_heads;
+  const int32_t* pos_dev;     // per-sequence positions (device, [B]) or null
   int64_t groups_per_tensor;  // B*H_kv*n_new*(D/32)
 };
 
@@ -33,6 +34,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   const int64_t vec = idx / ng;                       // (b*H_kv + h) * n_new + t
   const int64_t bh = vec / p.n_new;
   const int t = (int)(vec % p.n_new);
+  int pos = p.pos;
+  if (p.pos_dev) {
+    pos = p.pos_dev[bh / p.n_kv_heads];
+    if (pos < 0 || pos > p.capacity - p.n_new) return;    // this sequence's tokens do not fit: nothing is written
+  }
 
   const uint4* src = reinterpret_cast<const uint4*>(p.src[which] + (vec * p.head_dim + g * kGroup));
   float x[kGroup];
@@ -74,7 +80,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
     }
     w[i] = acc;
   }
-  const int64_t row = bh * p.capacity + p.pos + t;
+  const int64_t row = bh * p.capacity + pos + t;
   *reinterpret_cast<uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2)) =
       make_uint4(w[0], w[1], w[2], w[3]);
   p.scale[which][row * ng + g] = s16;
@@ -120,8 +126,8 @@ __global__ __launch_bounds__(256) void dequant_dense_kernel(DequantParams p) {
 
 }  // namespace
 
-hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos, int n_new,
-                           hipStream_t s) {
+hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos,
+                           const int32_t* pos_dev, int n_new, hipStream_t s) {
   QuantParams p;
   p.src[0] = static_cast<const half_t*>(k_new);
   p.src[1] = static_cast<const half_t*>(v_new);
@@ -134,6 +140,8 @@ hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* 
   p.n_new = n_new;
   p.capacity = c.capacity;
   p.pos = pos;
+  p.pos_dev = pos_dev;
+  p.n_kv_heads = c.n_kv_heads;
   p.head_dim = c.head_dim;
   p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * n_new * (c.head_dim / kGroup);
   const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);

@@ -124,6 +124,25 @@ def test_reduce_and_baseline_reject_bad_arguments_without_a_gpu():
     assert d(ctypes.byref(c), FAKE, 64, 2000, 0.1, FAKE, FAKE, wsb, FAKE, need, None, None) == E.TQ_ERR_CAPACITY
 
 
+def test_varlen_entry_points_reject_bad_arguments_without_a_gpu():
+    E = B
+    c = _cache()
+    wsb = tq.tq_workspace_bytes(1, 64, 128)
+    d = B.raw().tq_sdpa_int4_decode_varlen
+    assert d(ctypes.byref(c), FAKE, 64, None, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_NULL
+    assert d(ctypes.byref(c), FAKE, 64, FAKE + 2, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_ALIGN
+    assert d(ctypes.byref(c), FAKE, 64, FAKE, 0, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_EMPTY
+    assert d(ctypes.byref(c), FAKE, 64, FAKE, 1025, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_CAPACITY
+    assert d(ctypes.byref(c), FAKE, 63, FAKE, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_SHAPE
+    assert d(ctypes.byref(c), FAKE, 64, FAKE, 1024, 0.1, FAKE, FAKE, 8, None, None) == E.TQ_ERR_WORKSPACE
+    q = B.raw().tq_quantize_kv_varlen
+    assert q(ctypes.byref(c), FAKE, FAKE, None, 1, None) == E.TQ_ERR_NULL
+    assert q(ctypes.byref(c), None, FAKE, FAKE, 1, None) == E.TQ_ERR_NULL
+    assert q(ctypes.byref(c), FAKE, FAKE, FAKE, 0, None) == E.TQ_ERR_EMPTY
+    assert q(ctypes.byref(c), FAKE, FAKE, FAKE, 1025, None) == E.TQ_ERR_CAPACITY
+    assert q(ctypes.byref(c), FAKE, FAKE, FAKE + 1, 1, None) == E.TQ_ERR_ALIGN
+
+
 def test_decode_launch_count_query():
     f = B.raw().tq_decode_launches
     short = _cache()                                                  # 1024 tokens: launch-bound

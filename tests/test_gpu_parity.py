@@ -265,3 +265,74 @@ def test_decode_step_append_then_attend():
     assert_cache_bit_exact(cache, ocache, S)
     out = _decode(cache, q, S, w.attn_scale)
     assert_close(out, oracle_attend(q, ocache, S, w.attn_scale), "append+attend")
+
+
+# ---------------------------------------------------------------- per-sequence lengths and positions
+
+def _oracle_varlen(q, ocache, lens, alpha):
+    """The oracle knows one common length: call it once per sequence with that sequence's own."""
+    rows = []
+    for b, n in enumerate(lens):
+        one = [a[b:b + 1] for a in ocache]
+        rows.append(oracle.attend_packed(np16(q[b:b + 1]), *one, seq_len=int(n), alpha=alpha))
+    return np.concatenate(rows, axis=0)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("shape", ["g8_d128_kv2", "g2_d256"])
+def test_decode_with_per_sequence_lengths(shape, variant):
+    shapes = dict(SHAPES, g8_d128_kv2=dict(n_q_heads=16, n_kv_heads=2, head_dim=128, outlier_channels=4))
+    lens = [1, 33, 1000, 4133, 2048, 31]
+    w = wl.custom(batch=len(lens), seq_len=max(lens), seed=71, **shapes[shape])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v, capacity=max(lens) + 11)
+    ocache = oracle_cache_from(k, v)
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    for n_splits in (0, 3):
+        try:
+            out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, max(lens), w.attn_scale,
+                                                n_splits=n_splits, variant=variant)
+        except tq.TqError as e:
+            if e.status == -6 and variant == 2:
+                pytest.skip("matrix-core kernel does not cover this shape")
+            raise
+        torch.cuda.synchronize()
+        assert_close(out, ref, f"{shape} varlen variant={variant} n_splits={n_splits}")
+    # lengths outside [1, max_seq_len] are clamped to it; a common length gives the plain call's bits
+    odd = torch.tensor([0, -5, 10 ** 6, 4133, 2048, 31], dtype=torch.int32, device="cuda")
+    clamped = [1, 1, max(lens), 4133, 2048, 31]
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), odd, max(lens), w.attn_scale, variant=variant)
+    assert_close(out, _oracle_varlen(q, ocache, clamped, w.attn_scale), "clamped lengths")
+    same = torch.full((len(lens),), 1000, dtype=torch.int32, device="cuda")
+    a = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant)
+    b = tq.tq_sdpa_int4_decode(cache, q.cuda(), 1000, w.attn_scale, variant=variant)
+    assert torch.equal(a, b)
+
+
+def test_append_at_per_sequence_positions():
+    w = wl.custom(batch=5, n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=3, seed=72)
+    _, k, v = make(w)
+    cap = 40
+    cache = tq.KVCache(5, 2, 128, cap)
+    for t in cache.tensors():
+        t.view(torch.uint8).fill_(0xEE)
+    pos = [0, 17, cap - 3, cap - 2, -1]          # the last two do not fit: skipped
+    tq.tq_quantize_kv_varlen(cache, k.cuda(), v.cuda(), torch.tensor(pos, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    ocache = oracle_cache_from(k, v)
+    names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero")
+    for name, g, o in zip(names, cache.tensors(), ocache):
+        g = np16(g)
+        raw_g = g.view(np.uint8).reshape(5, 2, cap, -1)
+        for b, p0 in enumerate(pos):
+            fits = 0 <= p0 <= cap - 3
+            if fits:
+                got, want = g[b, :, p0:p0 + 3], o[b]
+                if got.dtype == np.float16:
+                    got, want = got.view(np.uint16), want.view(np.uint16)
+                assert np.array_equal(got, want), f"{name} sequence {b}"
+            keep = np.ones(cap, dtype=bool)
+            if fits:
+                keep[p0:p0 + 3] = False
+            assert (raw_g[b][:, keep] == 0xEE).all(), f"{name} sequence {b}: wrote outside its positions"
