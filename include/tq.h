@@ -108,10 +108,13 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
 
 /* The same with one length per sequence (continuous batching; the paper's kernel takes one
  * common N, Alg. 1): sequence b attends tokens [0, seq_lens[b]).  seq_lens: DEVICE int32 [batch],
- * read by the kernels; each value is clamped to [1, max_seq_len].  max_seq_len (host, <= capacity)
- * bounds them and sizes the chunking: chunks past a sequence's end do no work, so the call costs
- * what the longest sequence costs per (batch, KV head) row it occupies.  Other arguments, routes
- * and errors as for tq_sdpa_int4_decode (EMPTY / CAPACITY refer to max_seq_len). */
+ * read by the kernels (the host never sees the values); each is clamped to [1, max_seq_len].
+ * max_seq_len (host, <= capacity) only bounds them.  With opts->n_splits == 0 the kernels plan the
+ * chunks themselves from the lengths, so that every block gets about the same number of tokens
+ * whatever the mix (the cost follows the SUM of the lengths); with n_splits > 0 the sequence range
+ * [0, max_seq_len) is cut into that many chunks and those past a sequence's end do no work.  Always
+ * two launches (partial kernel + merge kernel).  Other arguments and errors as for
+ * tq_sdpa_int4_decode (EMPTY / CAPACITY refer to max_seq_len). */
 int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads,
                                const int32_t* seq_lens, int32_t max_seq_len, float attn_scale,
                                void* out, void* workspace, size_t workspace_bytes,

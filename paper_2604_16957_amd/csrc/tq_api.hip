@@ -123,19 +123,31 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
 // *merged tells whether `out` has been written.
 int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
                 const int32_t* seq_lens, float attn_scale, void* out, void* workspace, const tq_decode_opts* opts,
-                int32_t* n_splits_out, bool* merged, void* stream, int32_t* tokens_per_split_out = nullptr) {
+                int32_t* n_splits_out, bool* merged, void* stream, DecodeParams* used = nullptr) {
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
   const int target = use_mfma ? kBlocksMfma : kBlocksValu;
   const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
-  if (tokens_per_split_out) *tokens_per_split_out = plan.tokens_per_split;
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   p.seq_lens = seq_lens;
+  p.batch = cache->batch;
+  if (seq_lens && !(opts && opts->n_splits > 0)) {
+    // per-sequence lengths, no chunk count asked for: the kernels plan the chunks themselves from the lengths,
+    // `target` chunks over all sequences of a KV head (a requested n_splits keeps the fixed chunking)
+    // per KV head: r rounds of target / H_kv chunks, r the smallest count that leaves at least half of them
+    // once every sequence has been granted its partial last chunk
+    const int per_round = std::max(1, (target + cache->n_kv_heads - 1) / cache->n_kv_heads);
+    const int rounds = std::max(1, (2 * cache->batch + per_round - 1) / per_round);
+    p.var_chunks = rounds * per_round;
+    p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;
+    p.n_splits = tq::kMaxSplits;
+  }
+  if (used) *used = p;
   if (n_splits_out) *n_splits_out = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool merge = out != nullptr && r.merge;
+  const bool merge = out != nullptr && r.merge && !seq_lens;
   if (merged) *merged = merge;
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, merge, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
@@ -263,20 +275,12 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
   if (rc != TQ_OK) return rc;
   if (!seq_lens) return TQ_ERR_NULL;
   if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
-  int32_t n_splits = 0, tokens_per_split = 0;
   bool merged = false;
-  rc = run_partial(cache, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, &n_splits, &merged,
-                   stream, &tokens_per_split);
+  DecodeParams p{};
+  rc = run_partial(cache, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, nullptr, &merged,
+                   stream, &p);
   if (rc != TQ_OK || merged) return rc;
-  DecodeParams p{};                               // the merge skips the chunks past each sequence's end
-  p.part_o = static_cast<float*>(workspace);
-  p.part_ml = p.part_o + tq::workspace_o_floats(cache->batch, n_q_heads, cache->head_dim);
-  p.out = static_cast<half_t*>(out);
-  p.n_q_heads = n_q_heads;
-  p.n_splits = n_splits;
-  p.seq_lens = seq_lens;
-  p.seq_len = max_seq_len;
-  p.tokens_per_split = tokens_per_split;
+  // the merge works out from the same lengths which chunks exist for each sequence
   return hip_rc(tq::launch_reduce(p, cache->batch, cache->head_dim, static_cast<hipStream_t>(stream)));
 }
 

@@ -238,7 +238,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, kq = lane >> 4;
   const int hl = c % GP, rep = c / GP;            // head and group replica of this lane's column / row
-  const int split = blockIdx.x, kv = blockIdx.y, b = blockIdx.z;
+  int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
+  const int kv = blockIdx.y;
+  if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
+    VarPlan vp;
+    if (!var_plan(p, blockIdx.x, vp)) return;
+    split = vp.chunk;
+    b = vp.b;
+    tokens_per_split = vp.chunk_tokens;
+    part_stride = kMaxSplits;
+  }
   const int G = p.gqa;
 
   char* const ring = smem + wave * (NS * C::STAGE);
@@ -247,14 +256,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
-  const int begin = split * p.tokens_per_split;
+  const int begin = split * tokens_per_split;
   // tokens this sequence attends: the common length, or its own (a chunk past its end is empty)
   const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
   // goes through and publishes an empty partial.)
   if (begin >= seq && p.merge_slot < 0) return;
-  const int end = max(begin, min(seq, begin + p.tokens_per_split));
+  const int end = max(begin, min(seq, begin + tokens_per_split));
   const int n_full = (end - begin) >> 5;          // whole 32-token supertiles of this chunk
   const bool has_tail = ((end - begin) & 31) != 0;  // only the sequence's last supertile can be ragged
   const int last_tok = seq - 1;
@@ -740,7 +749,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
       den = fmaf(lds_l[w * GP + h], e, den);
     }
-    const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * p.n_splits + split;
+    const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * part_stride + split;
     // device-scope stores: they go through to where every compute die sees them (the L2 caches of
     // different dies are not coherent with each other), so no cache-wide write-back is needed later
     st_dev(p.part_o + ph * D + j, num);
@@ -863,7 +872,7 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
     if (!mfma_can_merge(batch, p.n_kv_heads) || p.out == nullptr) return hipErrorInvalidValue;
     p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
   }
-  const dim3 grid(p.n_splits, p.n_kv_heads, batch);
+  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads, 1) : dim3(p.n_splits, p.n_kv_heads, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);

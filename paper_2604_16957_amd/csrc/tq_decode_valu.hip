@@ -32,11 +32,18 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   const int slot = wave * TPW + lane / LPT;
   const int grp = sub / 4;             // quantisation group of that piece
 
-  const int split = blockIdx.x;
+  int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
+  if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
+    VarPlan vp;
+    if (!var_plan(p, blockIdx.x, vp)) return;
+    split = vp.chunk;
+    b = vp.b;
+    tokens_per_split = vp.chunk_tokens;
+    part_stride = kMaxSplits;
+  }
   const int head_tiles = (p.gqa + kHeadTile - 1) / kHeadTile;
   const int kv = blockIdx.y / head_tiles;
   const int tile = blockIdx.y % head_tiles;
-  const int b = blockIdx.z;
   const int h0 = kv * p.gqa + tile * kHeadTile;          // first query head of this pass
   const int nh = min(kHeadTile, p.gqa - tile * kHeadTile);
 
@@ -64,10 +71,10 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
     for (int j = 0; j < 8; ++j) o[h][j] = 0.0f;
   }
 
-  const int begin = split * p.tokens_per_split;
+  const int begin = split * tokens_per_split;
   const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
   if (begin >= seq) return;                              // chunk past the end of its sequence: nothing to emit
-  const int end = min(seq, begin + p.tokens_per_split);
+  const int end = min(seq, begin + tokens_per_split);
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
 
   for (int t0 = begin; t0 < end; t0 += SPB) {
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
       num = fmaf(lds_o[w][h][j], e, num);
       den = fmaf(lds_l[w][h], e, den);
     }
-    const int64_t ph = ((int64_t)(b * p.n_q_heads + h0 + h) * p.n_splits + split);
+    const int64_t ph = ((int64_t)(b * p.n_q_heads + h0 + h) * part_stride + split);
     p.part_o[ph * D + j] = num;
     if (j == 0) { p.part_ml[ph * 2] = mg; p.part_ml[ph * 2 + 1] = den; }
   }
@@ -165,12 +172,15 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   constexpr int PARTS = 256 / D;
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   // chunks that exist for this sequence: all of them, or those that start before its own end
-  int n = p.n_splits;
-  if (p.seq_lens) {
-    const int seq = max(1, min(p.seq_lens[b], p.seq_len));
-    n = min(n, (seq + p.tokens_per_split - 1) / p.tokens_per_split);
+  int n = p.n_splits, part_stride = p.n_splits;
+  if (p.var_chunks > 0) {
+    const int c = var_chunk_tokens(p);
+    n = (var_len(p, b) + c - 1) / c;
+    part_stride = kMaxSplits;
+  } else if (p.seq_lens) {
+    n = min(n, (var_len(p, b) + p.tokens_per_split - 1) / p.tokens_per_split);
   }
-  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * p.n_splits;
+  const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * part_stride;
   __shared__ float w_c[kMaxSplits];
   __shared__ float red_m[4], red_l[4];
   __shared__ float acc_part[PARTS][D];
@@ -238,7 +248,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
 
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s) {
   const int head_tiles = (p.gqa + kHeadTile - 1) / kHeadTile;
-  const dim3 grid(p.n_splits, p.n_kv_heads * head_tiles, batch), block(256);
+  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads * head_tiles, 1)
+                                     : dim3(p.n_splits, p.n_kv_heads * head_tiles, batch);
+  const dim3 block(256);
   if (head_dim == 128) {
     if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<128, true>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((decode_partial_valu_kernel<128, false>), grid, block, 0, s, p);

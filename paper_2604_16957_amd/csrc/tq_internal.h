@@ -34,9 +34,47 @@ struct DecodeParams {
   int32_t row_stride;       // tokens between consecutive (b, kv head) rows
   int32_t seq_len, n_splits, tokens_per_split;   // seq_len: every sequence's length, or the bound of seq_lens
   float scale_log2;         // attn_scale * log2(e)
+  // Per-sequence lengths: the chunking is worked out ON THE DEVICE from seq_lens (see var_plan), so that
+  // every block gets about the same number of tokens whatever the mix of lengths.  var_chunks > 0 turns
+  // it on: blockIdx.x is then a slot in the list of all (sequence, chunk) pairs of one KV head, the
+  // partials are strided by kMaxSplits, and n_splits / tokens_per_split are not used.
+  int32_t batch, var_chunks, var_min_chunk;
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };
+
+#ifdef __HIPCC__
+// Device-side chunk plan for per-sequence lengths.  Chunk length C (a multiple of 32): the tokens of all
+// sequences spread over p.var_chunks - p.batch chunks (every sequence's last chunk is partial, so the
+// list then has at most p.var_chunks entries: the grid), at least p.var_min_chunk, and long enough that
+// no sequence needs more than kMaxSplits.  Slot s of the list "all chunks of sequence 0, then of sequence 1, ..."
+// -> (b, chunk); returns false past the end of the list.  Everything here is wave-uniform.
+struct VarPlan { int chunk_tokens, b, chunk; };
+__device__ inline int var_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
+__device__ inline int var_chunk_tokens(const DecodeParams& p) {
+  long long total = 0;
+  for (int b = 0; b < p.batch; ++b) total += var_len(p, b);
+  const int budget = p.var_chunks - p.batch;      // >= var_chunks / 2 by the host's choice of var_chunks
+  int c = (int)((total + budget - 1) / budget);
+  c = max(c, p.var_min_chunk);
+  c = max(c, (p.seq_len + kMaxSplits - 1) / kMaxSplits);
+  return (c + kTile - 1) / kTile * kTile;
+}
+__device__ inline bool var_plan(const DecodeParams& p, int slot, VarPlan& out) {
+  out.chunk_tokens = var_chunk_tokens(p);
+  int first = 0;
+  for (int b = 0; b < p.batch; ++b) {
+    const int n = (var_len(p, b) + out.chunk_tokens - 1) / out.chunk_tokens;
+    if (slot < first + n) {
+      out.b = b;
+      out.chunk = slot - first;
+      return true;
+    }
+    first += n;
+  }
+  return false;
+}
+#endif
 
 // Workspace carving: part_o first, then part_ml, both sized for kMaxSplits.
 inline size_t workspace_o_floats(int batch, int n_q_heads, int head_dim) {

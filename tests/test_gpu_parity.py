@@ -299,15 +299,18 @@ def test_decode_with_per_sequence_lengths(shape, variant):
             raise
         torch.cuda.synchronize()
         assert_close(out, ref, f"{shape} varlen variant={variant} n_splits={n_splits}")
-    # lengths outside [1, max_seq_len] are clamped to it; a common length gives the plain call's bits
+    # lengths outside [1, max_seq_len] are clamped to it; a common length with the same chunk count gives the
+    # plain call's bits
     odd = torch.tensor([0, -5, 10 ** 6, 4133, 2048, 31], dtype=torch.int32, device="cuda")
     clamped = [1, 1, max(lens), 4133, 2048, 31]
     out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), odd, max(lens), w.attn_scale, variant=variant)
     assert_close(out, _oracle_varlen(q, ocache, clamped, w.attn_scale), "clamped lengths")
     same = torch.full((len(lens),), 1000, dtype=torch.int32, device="cuda")
-    a = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant)
-    b = tq.tq_sdpa_int4_decode(cache, q.cuda(), 1000, w.attn_scale, variant=variant)
-    assert torch.equal(a, b)
+    a = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant, n_splits=3)
+    b = tq.tq_sdpa_int4_decode(cache, q.cuda(), 1000, w.attn_scale, variant=variant, n_splits=3)
+    assert torch.equal(a, b)                     # same chunking, same bits
+    c = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant)
+    assert_close(c, np16(b).astype(np.float64), "device-planned chunks vs fixed chunks")
 
 
 def test_append_at_per_sequence_positions():
