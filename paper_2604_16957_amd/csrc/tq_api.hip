@@ -112,7 +112,10 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
   const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
   if (variant == 2 && !scale_ok) return {false, false, false};
-  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok &&
+  // the matrix-core kernel addresses a (batch, KV head) row of codes with 32-bit byte offsets
+  const bool offsets_ok = (int64_t)seq_len * (cache->head_dim / 2) < (1ll << 31);
+  if (variant == 2 && !offsets_ok) return {false, false, false};
+  const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
                                          tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
   const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
   return {true, use_mfma,
