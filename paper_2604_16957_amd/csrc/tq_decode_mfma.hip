@@ -113,7 +113,12 @@ struct Cfg {
   // the block-merge area sits behind the rings where both fit into the 160 KB of a compute unit, else on top of them
   static constexpr bool ALIAS = RING + MERGE > 160 * 1024;
   static constexpr int OFF_MERGE = ALIAS ? 0 : RING;
-  static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE) : RING + MERGE;
+  // Where the query block of a wave lands before it is turned into operands: in an area of its own if
+  // there is room, so that the whole ring can be filled at once; else in the last ring slot.
+  static constexpr int QBLK = GP * D * 2;
+  static constexpr bool QSEP = !ALIAS && RING + MERGE + NW * QBLK <= 160 * 1024;
+  static constexpr int OFF_QBLK = RING + MERGE;
+  static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE) : RING + MERGE + (QSEP ? NW * QBLK : 0);
   // The fp16 scale and zero-point arrays are fetched dword by dword (two groups of one token), and the
   // direct loads may gather: with NA == 2 a lane needs exactly one dword per token, so the dwords are
   // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads.
@@ -354,11 +359,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int n_mine = count_of(n_full);
   const bool tail_mine = has_tail && count_of(n_full + 1) != n_mine;
 
-  // ---- prologue: the query rows of this KV head's group come in through the last ring slot (so that
-  //      every vector-memory operation of the kernel is one of the counted direct loads), then stages
-  //      0 .. NS-2 go out; the last slot is refilled once the query operands sit in registers.
+  // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
+  //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
+  //      Where the query block has to borrow the last ring slot, that slot is filled once the query
+  //      operands sit in registers.
+  constexpr int NPRE = C::QSEP ? NS : NS - 1;     // stages issued before the query operands are built
+  char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + C::OFF_V;
   {
-    const uint32_t l = ring_lds + (NS - 1) * C::STAGE + C::OFF_V;
+    const uint32_t l = C::QSEP ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + C::OFF_QBLK +
+                                     wave * C::QBLK
+                               : ring_lds + (NS - 1) * C::STAGE + C::OFF_V;
 #pragma unroll
     for (int u = 0; u < GP * D * 2 / 1024; ++u) {
       const int chunk = u * 64 + lane;            // 16-byte chunk of the [GP][D] fp16 query block
@@ -370,17 +380,17 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // phantom ones standing in when its supertiles run out, so every wait in the loop is the same.
   if (n_mine > 0) {
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
+    for (int s = 0; s < NPRE; ++s) {
       if (s < n_mine) issue(s, sidx_of(s));
       else issue_phantom(s);
     }
-    wait_loads<(NS - 1) * LPS>();
+    wait_loads<NPRE * LPS>();
   } else {
     wait_loads<0>();
   }
 
   // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
-  const _Float16* qh = reinterpret_cast<const _Float16*>(ring + (NS - 1) * C::STAGE + C::OFF_V) + hl * D;
+  const _Float16* qh = reinterpret_cast<const _Float16*>(q_area) + hl * D;
   half8v qraw[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
@@ -415,7 +425,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
-  if (n_mine > 0) {
+  if (!C::QSEP && n_mine > 0) {
     if (NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
     else issue_phantom(NS - 1);
   }
