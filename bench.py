@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--window", type=int, default=0, help="sliding window: attend only the last N tokens (0 = all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-baseline", action="store_true", help="skip the unfused GPU comparator")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled oracle check")
@@ -228,6 +229,11 @@ def main():
     out = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
     packed_bytes = w.packed_bytes if lens is None else int(lens.sum()) * Hkv * (w.packed_bytes // (B * Hkv * S))
     kw = dict(n_splits=args.n_splits, variant=args.variant)
+    if args.window > 0:                           # sliding window: only the attended tokens are streamed
+        if lens is not None:
+            sys.exit("bench.py: --window is offered for the fixed-length workloads")
+        kw["window"] = args.window
+        packed_bytes = packed_bytes // S * min(S, args.window)
 
     def append(j):                                # the step's new token goes to the end of every sequence
         if lens is None:
@@ -267,6 +273,7 @@ def main():
     fused = tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, **kw) == 1
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     n_splits = tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
+    lo = max(0, S - args.window) if args.window > 0 else 0     # first attended token
 
     def dominant(j):
         if fused or lens is not None:             # (no separate phase-1 entry point takes per-sequence lengths)
@@ -346,8 +353,8 @@ def main():
         ref = None
         def oracle_attend():
             if lens is None:
-                return oracle.attend_packed(q0.numpy(), kc, ks, kz, vc, vs, vz, seq_len=S, alpha=w.attn_scale,
-                                            nthreads=threads)
+                return oracle.attend_packed(q0.numpy(), *[a[:, :, lo:] for a in (kc, ks, kz, vc, vs, vz)], seq_len=S - lo,
+                                            alpha=w.attn_scale, nthreads=threads)
             return np.concatenate([oracle.attend_packed(q0.numpy()[b:b + 1], *[a[b:b + 1] for a in (kc, ks, kz, vc, vs, vz)],
                                                         seq_len=int(lens[b]), alpha=w.attn_scale, nthreads=threads)
                                    for b in range(B)], axis=0)
@@ -384,7 +391,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
-                   "n_splits": n_splits, "variant": args.variant, "decode_launches": 1 if fused else 2},
+                   "n_splits": n_splits, "variant": args.variant, "window": args.window,
+                   "decode_launches": 1 if fused else 2},
         "effective_GBps": round(packed_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100 * packed_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
         "packed_bytes_per_step": packed_bytes,

@@ -70,6 +70,9 @@ typedef struct tq_kv_cache {
 typedef struct tq_decode_opts {
   int32_t n_splits;  /* chunks the sequence is split into (Sec. 3.2); 0 = heuristic            */
   int32_t variant;   /* 0 = default kernel, 1 = generic vector-ALU kernel, 2 = matrix-core kernel */
+  int32_t window;    /* sliding-window attention (the Gemma local layers of Appendix A): > 0 = every
+                        sequence attends only its last `window` tokens, [len - window, len); 0 = all.
+                        tq_dequant_then_attend does not offer it (UNSUPPORTED).                  */
 } tq_decode_opts;
 
 /* Quantise and append (Sec. 2.1, Eq. 2-3; "quantize -> store" arm of Sec. 3.3).

@@ -24,7 +24,7 @@ class TqKvCacheStruct(ctypes.Structure):
 
 
 class TqDecodeOptsStruct(ctypes.Structure):
-    _fields_ = [("n_splits", ctypes.c_int32), ("variant", ctypes.c_int32)]
+    _fields_ = [("n_splits", ctypes.c_int32), ("variant", ctypes.c_int32), ("window", ctypes.c_int32)]
 
 
 class TqError(RuntimeError):
@@ -98,10 +98,10 @@ def tq_plan_splits(batch: int, n_kv_heads: int, seq_len: int) -> int:
 
 
 def tq_decode_launches(cache: "KVCache", n_q_heads: int, seq_len: int, attn_scale: float, n_splits: int = 0,
-                       variant: int = 0) -> int:
+                       variant: int = 0, window: int = 0) -> int:
     """Kernel launches one tq_sdpa_int4_decode call makes for this configuration (1 or 2; 0 = invalid)."""
     return int(raw().tq_decode_launches(ctypes.byref(cache.struct), int(n_q_heads), int(seq_len), float(attn_scale),
-                                        _opts(n_splits, variant)))
+                                        _opts(n_splits, variant, window)))
 
 
 class KVCache:
@@ -133,10 +133,10 @@ def _stream_ptr(stream) -> int:
     return s.cuda_stream
 
 
-def _opts(n_splits: int, variant: int):
-    if not n_splits and not variant:
+def _opts(n_splits: int, variant: int, window: int = 0):
+    if not n_splits and not variant and not window:
         return None
-    return ctypes.byref(TqDecodeOptsStruct(int(n_splits), int(variant)))
+    return ctypes.byref(TqDecodeOptsStruct(int(n_splits), int(variant), int(window)))
 
 
 def _check(rc: int, where: str):
@@ -169,7 +169,7 @@ def _workspace_for(cache: KVCache, n_q_heads: int, workspace):
 
 
 def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,
-                        workspace=None, n_splits: int = 0, variant: int = 0, stream=None) -> torch.Tensor:
+                        workspace=None, n_splits: int = 0, variant: int = 0, stream=None, window: int = 0) -> torch.Tensor:
     """q: fp16 [B, H_q, d] -> out fp16 [B, H_q, d]."""
     _need(q, torch.float16, "q")
     if out is None:
@@ -177,14 +177,14 @@ def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scal
     workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
     rc = raw().tq_sdpa_int4_decode(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
                                    float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
-                                   _opts(n_splits, variant), _stream_ptr(stream))
+                                   _opts(n_splits, variant, window), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode")
     return out
 
 
 def tq_sdpa_int4_decode_varlen(cache: KVCache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
                                attn_scale: float, out=None, workspace=None, n_splits: int = 0, variant: int = 0,
-                               stream=None) -> torch.Tensor:
+                               stream=None, window: int = 0) -> torch.Tensor:
     """q: fp16 [B, H_q, d]; seq_lens: int32 device tensor [B] -> out fp16 [B, H_q, d]."""
     _need(q, torch.float16, "q")
     _need(seq_lens, torch.int32, "seq_lens")
@@ -193,7 +193,8 @@ def tq_sdpa_int4_decode_varlen(cache: KVCache, q: torch.Tensor, seq_lens: torch.
     workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
     rc = raw().tq_sdpa_int4_decode_varlen(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]),
                                           seq_lens.data_ptr(), int(max_seq_len), float(attn_scale), out.data_ptr(),
-                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant), _stream_ptr(stream))
+                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window),
+                                          _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode_varlen")
     return out
 
@@ -210,13 +211,13 @@ def tq_quantize_kv_varlen(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tens
 
 
 def tq_sdpa_int4_partial(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, workspace: torch.Tensor,
-                         n_splits: int = 0, variant: int = 0, stream=None) -> int:
+                         n_splits: int = 0, variant: int = 0, stream=None, window: int = 0) -> int:
     """Phase 1 only; returns the number of chunks written into workspace."""
     _need(q, torch.float16, "q")
     n = ctypes.c_int32(0)
     rc = raw().tq_sdpa_int4_partial(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
                                     float(attn_scale), workspace.data_ptr(),
-                                    workspace.numel() * workspace.element_size(), _opts(n_splits, variant),
+                                    workspace.numel() * workspace.element_size(), _opts(n_splits, variant, window),
                                     ctypes.byref(n), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_partial")
     return n.value

@@ -67,7 +67,7 @@ int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len
   if (!aligned(q, 16) || (need_out && !aligned(out, 16)) || !aligned(workspace, 256)) return TQ_ERR_ALIGN;
   if (workspace_bytes < tq_workspace_bytes(c->batch, n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
   if (opts) {
-    if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0) return TQ_ERR_UNSUPPORTED;
+    if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0 || opts->window < 0) return TQ_ERR_UNSUPPORTED;
     if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, n_q_heads / c->n_kv_heads)) return TQ_ERR_UNSUPPORTED;
   }
   return TQ_OK;
@@ -107,6 +107,11 @@ struct Route { bool ok, use_mfma, merge; };
 // the stream: below this many packed bytes per call.
 constexpr int64_t kMergeInKernelMaxBytes = 48ll << 20;
 
+// tokens a sequence of length seq_len attends under the options' sliding window
+int windowed(int seq_len, const tq_decode_opts* opts) {
+  return (opts && opts->window > 0) ? std::min(seq_len, opts->window) : seq_len;
+}
+
 Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts) {
   const int variant = opts ? opts->variant : 0;
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
@@ -117,7 +122,7 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   if (variant == 2 && !offsets_ok) return {false, false, false};
   const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
                                          tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
-  const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
+  const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, cache->n_kv_heads, windowed(seq_len, opts), cache->head_dim);
   return {true, use_mfma,
           use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, cache->n_kv_heads)};
 }
@@ -131,11 +136,18 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
   const int target = use_mfma ? kBlocksMfma : kBlocksValu;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, target,
+  const int attended = windowed(seq_len, opts);   // chunks cover the attended tokens only
+  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, attended, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   p.seq_lens = seq_lens;
   p.batch = cache->batch;
+  if (seq_lens) {
+    p.window = opts ? opts->window : 0;           // the kernels window every sequence's own length
+  } else {
+    p.seq_len = attended;
+    p.start = seq_len - attended;
+  }
   if (seq_lens && !(opts && opts->n_splits > 0)) {
     // per-sequence lengths, no chunk count asked for: the kernels plan the chunks themselves from the lengths,
     // `target` chunks over all sequences of a KV head (a requested n_splits keeps the fixed chunking)
@@ -296,6 +308,7 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
   if (!aligned(dense_scratch, 16)) return TQ_ERR_ALIGN;
   const size_t need = tq_dense_scratch_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
   if (dense_scratch_bytes < need) return TQ_ERR_WORKSPACE;
+  if (opts && opts->window > 0) return TQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   half_t* k_dense = static_cast<half_t*>(dense_scratch);
   half_t* v_dense = k_dense + need / sizeof(half_t) / 2;

@@ -260,10 +260,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * (NS * C::STAGE);
 
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
-  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
+  // tokens this sequence attends: the common length, or its own (a chunk past its end is empty); with a
+  // sliding window the row simply starts `start` tokens later
+  const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;
+  const int start = p.seq_lens ? var_start(p, b) : p.start;
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
   const int begin = split * tokens_per_split;
-  // tokens this sequence attends: the common length, or its own (a chunk past its end is empty)
-  const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
   // goes through and publishes an empty partial.)

@@ -72,10 +72,10 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   }
 
   const int begin = split * tokens_per_split;
-  const int seq = p.seq_lens ? max(1, min(p.seq_lens[b], p.seq_len)) : p.seq_len;
+  const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;
   if (begin >= seq) return;                              // chunk past the end of its sequence: nothing to emit
   const int end = min(seq, begin + tokens_per_split);
-  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride;
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + (p.seq_lens ? var_start(p, b) : p.start);
 
   for (int t0 = begin; t0 < end; t0 += SPB) {
     const int t = t0 + slot;

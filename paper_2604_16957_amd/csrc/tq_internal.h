@@ -39,6 +39,10 @@ struct DecodeParams {
   // it on: blockIdx.x is then a slot in the list of all (sequence, chunk) pairs of one KV head, the
   // partials are strided by kMaxSplits, and n_splits / tokens_per_split are not used.
   int32_t batch, var_chunks, var_min_chunk;
+  // Sliding window: a sequence attends tokens [start, start + its length).  Common length: `start` (host)
+  // and seq_len already the windowed length.  Per-sequence lengths: window > 0 and the kernels derive
+  // both from seq_lens (var_len / var_start below).
+  int32_t start, window;
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };
@@ -50,7 +54,13 @@ struct DecodeParams {
 // no sequence needs more than kMaxSplits.  Slot s of the list "all chunks of sequence 0, then of sequence 1, ..."
 // -> (b, chunk); returns false past the end of the list.  Everything here is wave-uniform.
 struct VarPlan { int chunk_tokens, b, chunk; };
-__device__ inline int var_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
+__device__ inline int var_full_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
+// tokens sequence b attends, and the first of them
+__device__ inline int var_len(const DecodeParams& p, int b) {
+  const int n = var_full_len(p, b);
+  return p.window > 0 ? min(n, p.window) : n;
+}
+__device__ inline int var_start(const DecodeParams& p, int b) { return var_full_len(p, b) - var_len(p, b); }
 __device__ inline int var_chunk_tokens(const DecodeParams& p) {
   long long total = 0;
   for (int b = 0; b < p.batch; ++b) total += var_len(p, b);

@@ -89,6 +89,8 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(), opts=ctypes.byref(bad)) == E.TQ_ERR_UNSUPPORTED
     neg = B.TqDecodeOptsStruct(-1, 0)
     assert _decode(_cache(), opts=ctypes.byref(neg)) == E.TQ_ERR_UNSUPPORTED
+    negw = B.TqDecodeOptsStruct(0, 0, -3)
+    assert _decode(_cache(), opts=ctypes.byref(negw)) == E.TQ_ERR_UNSUPPORTED
 
 
 def test_quantize_rejects_bad_arguments_without_a_gpu():
@@ -122,6 +124,8 @@ def test_reduce_and_baseline_reject_bad_arguments_without_a_gpu():
     assert d(ctypes.byref(c), FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, None, need, None, None) == E.TQ_ERR_NULL
     assert d(ctypes.byref(c), FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, FAKE, need - 1, None, None) == E.TQ_ERR_WORKSPACE
     assert d(ctypes.byref(c), FAKE, 64, 2000, 0.1, FAKE, FAKE, wsb, FAKE, need, None, None) == E.TQ_ERR_CAPACITY
+    win = B.TqDecodeOptsStruct(0, 0, 128)         # the comparator has no sliding window
+    assert d(ctypes.byref(c), FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, FAKE, need, ctypes.byref(win), None) == E.TQ_ERR_UNSUPPORTED
 
 
 def test_varlen_entry_points_reject_bad_arguments_without_a_gpu():

@@ -339,3 +339,37 @@ def test_append_at_per_sequence_positions():
             if fits:
                 keep[p0:p0 + 3] = False
             assert (raw_g[b][:, keep] == 0xEE).all(), f"{name} sequence {b}: wrote outside its positions"
+
+
+# ---------------------------------------------------------------- sliding window
+
+def _oracle_window(q, ocache, lens, window, alpha):
+    """Attention over the last `window` tokens of every sequence: the oracle is given exactly those."""
+    rows = []
+    for b, n in enumerate(lens):
+        lo = max(0, n - window)
+        one = [a[b:b + 1, :, lo:n] for a in ocache]
+        rows.append(oracle.attend_packed(np16(q[b:b + 1]), *one, seq_len=n - lo, alpha=alpha))
+    return np.concatenate(rows, axis=0)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256"])
+def test_sliding_window(shape, variant):
+    S = 3000
+    w = wl.custom(seq_len=S, seed=81, **SHAPES[shape])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v, capacity=S + 5)
+    ocache = oracle_cache_from(k, v)
+    for window in (1, 31, 100, 1024, 2999, 3000, 5000):
+        out = _decode(cache, q, S, w.attn_scale, variant=variant, window=window)
+        ref = _oracle_window(q, ocache, [S] * w.batch, window, w.attn_scale)
+        assert_close(out, ref, f"{shape} window={window} variant={variant}")
+    if w.batch > 1:                               # every sequence windows its own length
+        lens = [2500, 77][:w.batch]
+        lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        for window, n_splits in ((1024, 0), (1024, 2), (50, 0), (4000, 0)):
+            out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, variant=variant,
+                                                window=window, n_splits=n_splits)
+            ref = _oracle_window(q, ocache, lens, window, w.attn_scale)
+            assert_close(out, ref, f"{shape} varlen window={window} variant={variant}")
