@@ -373,3 +373,63 @@ def test_sliding_window(shape, variant):
                                                 window=window, n_splits=n_splits)
             ref = _oracle_window(q, ocache, lens, window, w.attn_scale)
             assert_close(out, ref, f"{shape} varlen window={window} variant={variant}")
+
+
+# ---------------------------------------------------------------- streams and graphs
+
+def test_concurrent_calls_on_two_streams():
+    """Single-launch decodes in flight on two streams at once take different sets of arrival counters."""
+    w = wl.custom(seq_len=2500, seed=91, **SHAPES["g8_d128_b2_kv3"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
+    qd = q.cuda()
+    assert tq.tq_decode_launches(cache, qd.shape[1], w.seq_len, w.attn_scale) == 1
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ws = [torch.empty(tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
+          for _ in streams]
+    outs = [[torch.empty_like(qd) for _ in range(20)] for _ in streams]
+    torch.cuda.synchronize()
+    for i in range(20):
+        for s, wsp, o in zip(streams, ws, outs):
+            with torch.cuda.stream(s):
+                tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=o[i], workspace=wsp)
+    torch.cuda.synchronize()
+    first = np16(outs[0][0]).view(np.uint16)
+    assert_close(outs[0][0], ref, "two streams")
+    for o in outs:
+        for t in o:
+            assert np.array_equal(np16(t).view(np.uint16), first)
+
+
+def test_graph_capture_and_replay():
+    """A captured decode step (append + attend, both decode routes) replays to the eager result, with
+    eager work and synchronisations between the replays."""
+    for shape, S in (("g8_d128_b2_kv3", 1500), ("g2_d256", 700)):
+        w = wl.custom(seq_len=S, seed=92, **SHAPES[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k[:, :, :S - 1], v[:, :, :S - 1], capacity=S)
+        kn, vn = k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda()
+        qd = q.cuda()
+        ws = torch.empty(tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
+        out1, out2 = torch.empty_like(qd), torch.empty_like(qd)
+
+        def step():
+            tq.tq_quantize_kv(cache, kn, vn, S - 1)
+            tq.tq_sdpa_int4_decode(cache, qd, S, w.attn_scale, out=out1, workspace=ws)               # one launch
+            tq.tq_sdpa_int4_decode(cache, qd, S, w.attn_scale, out=out2, workspace=ws, variant=1)    # two launches
+
+        step()                                    # eager first: also does the one-time kernel attribute set-up
+        torch.cuda.synchronize()
+        want1, want2 = out1.clone(), out2.clone()
+        assert_close(want1, oracle_attend(q, oracle_cache_from(k, v), S, w.attn_scale), "eager step")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(4):
+            out1.zero_(); out2.zero_()
+            cache.k_codes[:, :, S - 1].zero_()    # the replay has to write the appended token again
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out1, want1) and torch.equal(out2, want2)
