@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2604_16957_amd as tq
 import tq_workloads as wl
-from gpu_common import (BASELINE_REL_L2, assert_cache_bit_exact, assert_close, errors, gpu_cache_from, make, np16, oracle_attend,
+from gpu_common import (BASELINE_REL_L2, MAX_ABS, REL_L2, assert_cache_bit_exact, assert_close, errors, gpu_cache_from, make, np16, oracle_attend,
                         oracle_cache_from)
 
 pytestmark = pytest.mark.gpu
@@ -433,3 +433,40 @@ def test_graph_capture_and_replay():
             g.replay()
             torch.cuda.synchronize()
             assert torch.equal(out1, want1) and torch.equal(out2, want2)
+
+
+# ---------------------------------------------------------------- many small random configurations
+
+def test_random_configurations_against_the_oracle():
+    """Seeded sweep over shapes, lengths, chunk counts, windows and per-sequence lengths: every
+    combination goes through whichever kernel the library picks and through the generic one."""
+    rng = np.random.default_rng(20260416)
+    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 4), (256, 2), (256, 1), (128, 16)]
+    for case in range(40):
+        d, G = shapes[rng.integers(len(shapes))]
+        Hkv = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 4))
+        S = int(rng.choice([1, 7, 32, 63, 64, 65, 255, 256, 257, 1000, 2047, 2049, 3333]))
+        cap = S + int(rng.integers(0, 40))
+        alpha = float(rng.choice([1.0 / np.sqrt(d), 1.0, 0.02]))
+        w = wl.custom(batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=S, seed=1000 + case,
+                      attn_scale=alpha, qk_std=float(rng.choice([1.0, 0.1])), outlier_channels=int(rng.choice([0, 4])))
+        q, k, v = make(w)
+        cache = gpu_cache_from(k, v, capacity=cap)
+        ocache = oracle_cache_from(k, v)
+        n_splits = int(rng.choice([0, 0, 1, 2, 5, 128]))
+        window = int(rng.choice([0, 0, 1, 50, 1500]))
+        use_lens = bool(rng.integers(2)) and B > 1
+        lens = [int(x) for x in rng.integers(1, S + 1, B)] if use_lens else [S] * B
+        ref = _oracle_window(q, ocache, lens, window if window > 0 else S, alpha)
+        what = f"case {case}: d={d} G={G} Hkv={Hkv} B={B} S={S} n_splits={n_splits} window={window} lens={lens}"
+        for variant in (0, 1):
+            if use_lens:
+                out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                                                    S, alpha, n_splits=n_splits, variant=variant, window=window)
+            else:
+                out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, alpha, n_splits=n_splits, variant=variant, window=window)
+            torch.cuda.synchronize()
+            max_abs, rel = errors(out, ref)
+            scale = max(1.0, float(np.abs(ref).max()))
+            assert max_abs <= MAX_ABS * scale and rel <= REL_L2, f"{what} variant={variant}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
