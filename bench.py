@@ -2,9 +2,9 @@
 """Benchmark of the int4 compressed-domain decode-attention hot path on one MI355X.
 
 A step = one pass of the whole hot path for one layer of the workload:
-  tq_quantize_kv (append one new token per sequence)  ->  tq_sdpa_int4_decode (fused int4 SDPA
-  over seq_len tokens: per-chunk partial results and their merge, one kernel where the matrix-core
-  kernel runs, else partial kernel + merge kernel).
+  quantise-append of one new token per sequence (Sec. 2.1)  ->  fused int4 SDPA over seq_len tokens
+  (Alg. 1, Eq. 6), through the one-call entry point tq_sdpa_int4_append_decode (the decode kernel takes
+  the new token in itself; --two-calls times tq_quantize_kv + tq_sdpa_int4_decode instead).
 Inputs are resident in HBM before the timed region.  Steps rotate over several distinct KV
 caches so that the 256 MB Infinity Cache cannot serve the stream (one 128K layer is 168 MB).
 
@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--window", type=int, default=0, help="sliding window: attend only the last N tokens (0 = all)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="time the step as tq_quantize_kv + tq_sdpa_int4_decode instead of tq_sdpa_int4_append_decode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-baseline", action="store_true", help="skip the unfused GPU comparator")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled oracle check")
@@ -99,8 +101,11 @@ def sweep(args):
 
     def step():
         for l in range(L):
-            tq.tq_quantize_kv(caches[l], news[l][0], news[l][1], S - 1)
-            tq.tq_sdpa_int4_decode(caches[l], qs[l], S, alpha, out=outs[l], workspace=ws)
+            if args.two_calls:
+                tq.tq_quantize_kv(caches[l], news[l][0], news[l][1], S - 1)
+                tq.tq_sdpa_int4_decode(caches[l], qs[l], S, alpha, out=outs[l], workspace=ws)
+            else:
+                tq.tq_sdpa_int4_append_decode(caches[l], news[l][0], news[l][1], qs[l], S, alpha, out=outs[l], workspace=ws)
 
     for _ in range(warmup):
         step()
@@ -166,7 +171,8 @@ def sweep(args):
         "data": "synthetic",
         "config": {"workload": f"sweep{L}: llama128k shape x {L} layers x batch {B}, one token appended per sequence per layer",
                    "batch": B, "layers": L, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "seq_len": S,
-                   "attn_scale": alpha, "group_size": 32, "n_splits": n_splits, "decode_launches": 1 if fused else 2},
+                   "attn_scale": alpha, "group_size": 32, "n_splits": n_splits, "decode_launches": 1 if fused else 2,
+                   "step_calls": "tq_quantize_kv + tq_sdpa_int4_decode" if args.two_calls else "tq_sdpa_int4_append_decode"},
         "effective_GBps": round(packed / (ms_per_step * 1e-3) / 1e9, 1),
         "pct_of_hbm_peak": round(100 * packed / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
         "packed_bytes_per_step": packed,
@@ -247,10 +253,16 @@ def main():
         else:
             tq.tq_sdpa_int4_decode_varlen(caches[j], qs[j], lens_dev, S, w.attn_scale, out=out, workspace=ws, **kw)
 
+    one_call = lens is None and not args.two_calls
+
     def step(i):
         j = i % args.buffers
-        append(j)
-        decode(j)
+        if one_call:                              # the step's token is quantised, stored and attended by one call
+            tq.tq_sdpa_int4_append_decode(caches[j], news[j][0], news[j][1], qs[j], S, w.attn_scale, out=out,
+                                          workspace=ws, **kw)
+        else:
+            append(j)
+            decode(j)
 
     # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
     for i in range(args.warmup):
@@ -392,6 +404,9 @@ def main():
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "window": args.window,
+                   "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
+                                  "tq_quantize_kv_varlen + tq_sdpa_int4_decode_varlen" if lens is not None else
+                                  "tq_quantize_kv + tq_sdpa_int4_decode"),
                    "decode_launches": 1 if fused else 2},
         "effective_GBps": round(packed_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "pct_of_hbm_peak": round(100 * packed_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),

@@ -109,6 +109,19 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
                         float attn_scale, void* out, void* workspace, size_t workspace_bytes,
                         const tq_decode_opts* opts, void* stream);
 
+/* One decode step in one call: tq_quantize_kv(cache, k_new, v_new, seq_len - 1, 1) followed by
+ * tq_sdpa_int4_decode(cache, q, ..., seq_len, ...), i.e. the new token of every sequence (k_new,
+ * v_new: fp16 [batch][n_kv_heads][1][head_dim]) is quantised, written at position seq_len - 1 and
+ * attended together with the seq_len - 1 cached ones.  Same stored bits and same result as the two
+ * calls; where the matrix-core kernel runs at head_dim 128 the append costs no launch of its own
+ * (the block that holds the end of a sequence quantises the token, stores it and adds its
+ * attention term from registers), otherwise the two kernels are launched one after the other.
+ * Errors: those of the two calls. */
+int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, const void* v_new,
+                               const void* q, int32_t n_q_heads, int32_t seq_len, float attn_scale,
+                               void* out, void* workspace, size_t workspace_bytes,
+                               const tq_decode_opts* opts, void* stream);
+
 /* The same with one length per sequence (continuous batching; the paper's kernel takes one
  * common N, Alg. 1): sequence b attends tokens [0, seq_lens[b]).  seq_lens: DEVICE int32 [batch],
  * read by the kernels (the host never sees the values); each is clamped to [1, max_seq_len].

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     tq_plan_splits,
     tq_quantize_kv,
     tq_quantize_kv_varlen,
+    tq_sdpa_int4_append_decode,
     tq_sdpa_int4_decode,
     tq_sdpa_int4_decode_varlen,
     tq_sdpa_int4_partial,

@@ -53,6 +53,7 @@ def raw():
         OP = ctypes.POINTER(TqDecodeOptsStruct)
         L.tq_quantize_kv.argtypes = [CP, P, P, I, I, P]
         L.tq_sdpa_int4_decode.argtypes = [CP, P, I, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_append_decode.argtypes = [CP, P, P, P, I, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_decode_varlen.argtypes = [CP, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_quantize_kv_varlen.argtypes = [CP, P, P, P, I, P]
         L.tq_sdpa_int4_partial.argtypes = [CP, P, I, I, F, P, SZ, OP, ctypes.POINTER(ctypes.c_int32), P]
@@ -179,6 +180,26 @@ def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scal
                                    float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
                                    _opts(n_splits, variant, window), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode")
+    return out
+
+
+def tq_sdpa_int4_append_decode(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, seq_len: int,
+                               attn_scale: float, out=None, workspace=None, n_splits: int = 0, variant: int = 0,
+                               stream=None, window: int = 0) -> torch.Tensor:
+    """One decode step: k_new, v_new fp16 [B, H_kv, 1, d] are written at seq_len - 1, then q attends seq_len tokens."""
+    _need(q, torch.float16, "q")
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    if k_new.shape != v_new.shape or tuple(k_new.shape) != (cache.batch, cache.n_kv_heads, 1, cache.head_dim):
+        raise ValueError("k_new/v_new must be [batch, n_kv_heads, 1, head_dim]")
+    if out is None:
+        out = torch.empty_like(q)
+    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
+    rc = raw().tq_sdpa_int4_append_decode(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(),
+                                          int(q.shape[1]), int(seq_len), float(attn_scale), out.data_ptr(),
+                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window),
+                                          _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_append_decode")
     return out
 
 

@@ -131,12 +131,19 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
 // *merged tells whether `out` has been written.
 int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
                 const int32_t* seq_lens, float attn_scale, void* out, void* workspace, const tq_decode_opts* opts,
-                int32_t* n_splits_out, bool* merged, void* stream, DecodeParams* used = nullptr) {
+                int32_t* n_splits_out, bool* merged, void* stream, DecodeParams* used = nullptr,
+                const void* k_new = nullptr, const void* v_new = nullptr, bool* appended = nullptr) {
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
   const int target = use_mfma ? kBlocksMfma : kBlocksValu;
-  const int attended = windowed(seq_len, opts);   // chunks cover the attended tokens only
+  int attended = windowed(seq_len, opts);         // chunks cover the attended tokens only
+  // append-and-attend in the kernel: the new token (the last attended one) does not come from the cache
+  const bool append = k_new != nullptr && use_mfma && !seq_lens && attended >= 2 &&
+                      tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
+  if (appended) *appended = append;
+  const int first = seq_len - attended;           // first attended token
+  if (append) --attended;
   const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, attended, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
@@ -146,7 +153,12 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
     p.window = opts ? opts->window : 0;           // the kernels window every sequence's own length
   } else {
     p.seq_len = attended;
-    p.start = seq_len - attended;
+    p.start = first;
+  }
+  if (append) {
+    p.k_new = static_cast<const half_t*>(k_new);
+    p.v_new = static_cast<const half_t*>(v_new);
+    p.append_pos = seq_len - 1;
   }
   if (seq_lens && !(opts && opts->n_splits > 0)) {
     // per-sequence lengths, no chunk count asked for: the kernels plan the chunks themselves from the lengths,
@@ -278,6 +290,33 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
   int32_t n_splits = 0;
   bool merged = false;
   rc = run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, out, workspace, opts, &n_splits, &merged, stream);
+  if (rc != TQ_OK || merged) return rc;
+  return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
+                             stream);
+}
+
+int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, const void* v_new, const void* q,
+                               int32_t n_q_heads, int32_t seq_len, float attn_scale, void* out, void* workspace,
+                               size_t workspace_bytes, const tq_decode_opts* opts, void* stream) {
+  int rc = check_decode(cache, q, n_q_heads, seq_len, out, workspace, workspace_bytes, opts, true);
+  if (rc != TQ_OK) return rc;
+  if (!k_new || !v_new) return TQ_ERR_NULL;
+  if (!aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
+  int32_t n_splits = 0;
+  bool merged = false, appended = false;
+  // first find out (without launching) whether the decode kernel will take the token in itself
+  {
+    const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+    if (!r.ok) return TQ_ERR_UNSUPPORTED;
+    appended = r.use_mfma && windowed(seq_len, opts) >= 2 &&
+               tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
+  }
+  if (!appended) {
+    rc = hip_rc(tq::launch_quantize(*cache, k_new, v_new, seq_len - 1, nullptr, 1, static_cast<hipStream_t>(stream)));
+    if (rc != TQ_OK) return rc;
+  }
+  rc = run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, out, workspace, opts, &n_splits, &merged, stream,
+                   nullptr, appended ? k_new : nullptr, appended ? v_new : nullptr);
   if (rc != TQ_OK || merged) return rc;
   return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
                              stream);

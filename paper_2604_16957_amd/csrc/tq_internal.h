@@ -43,11 +43,53 @@ struct DecodeParams {
   // and seq_len already the windowed length.  Per-sequence lengths: window > 0 and the kernels derive
   // both from seq_lens (var_len / var_start below).
   int32_t start, window;
+  // Append-and-attend in one launch (matrix-core kernel, d=128, common length): k_new / v_new non-null =
+  // one new token per sequence, fp16 [B][H_kv][1][D]; it is quantised and written at token append_pos of its
+  // row by the block of the last chunk, which also adds its attention term; seq_len then counts the cached
+  // tokens only.
+  const half_t* k_new;
+  const half_t* v_new;
+  int32_t append_pos;
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };
 
 #ifdef __HIPCC__
+// Sec. 2.1, Eq. 2-3 for one group of 32 values (fp16 inputs widened to fp32): the fp16 scale and zero-point
+// and the 32 codes, element j of packed word i in bits 4j..4j+3.  Every fp32 step is a separately rounded
+// operation (no contraction, correctly rounded divides), so the bits are the same wherever this runs.
+__device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[4], half_t& s16, half_t& z16) {
+#pragma clang fp contract(off)
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+  // Eq. 2: s = (max - min) / 15, stored as fp16; a scale that rounds to zero becomes 1.0
+  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  s16 = (half_t)s32;
+  if ((__builtin_bit_cast(uint16_t, s16) & 0x7FFFu) == 0) s16 = (half_t)1.0f;
+  const float sf = (float)s16;
+  // Eq. 2: z = -min / s from the STORED scale; saturate, and never store -0
+  const float z32 = __fdiv_rn(__fsub_rn(0.0f, mn), sf);
+  z16 = (half_t)z32;
+  uint16_t zb = __builtin_bit_cast(uint16_t, z16);
+  if ((zb & 0x7FFFu) == 0x7C00u) zb = (uint16_t)((zb & 0x8000u) | 0x7BFFu);
+  if (zb == 0x8000u) zb = 0;
+  z16 = __builtin_bit_cast(half_t, zb);
+  const float zf = (float)z16;
+  // Eq. 3: q = clamp(round_half_even(x / s + z), 0, 15)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float v = __fadd_rn(__fdiv_rn(x[8 * i + j], sf), zf);
+      const float r = fminf(fmaxf(rintf(v), 0.0f), 15.0f);
+      acc |= (uint32_t)r << (4 * j);
+    }
+    w[i] = acc;
+  }
+}
+
 // Device-side chunk plan for per-sequence lengths.  Chunk length C (a multiple of 32): the tokens of all
 // sequences spread over p.var_chunks - p.batch chunks (every sequence's last chunk is partial, so the
 // list then has at most p.var_chunks entries: the grid), at least p.var_min_chunk, and long enough that
@@ -105,6 +147,7 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 bool mfma_supported(int head_dim, int gqa);
 // With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
 bool mfma_can_merge(int batch, int n_kv_heads);
+bool mfma_can_append(int head_dim, int gqa);   // whether launch_partial_mfma honours k_new / v_new for this shape
 hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 

@@ -49,37 +49,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) x[8 * i + j] = (float)u.h[j];
   }
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-
-  // Eq. 2: s = (max - min) / 15, stored as fp16; a scale that rounds to zero becomes 1.0
-  const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
-  half_t s16 = (half_t)s32;
-  if ((__builtin_bit_cast(uint16_t, s16) & 0x7FFFu) == 0) s16 = (half_t)1.0f;
-  const float sf = (float)s16;
-  // Eq. 2: z = -min / s from the STORED scale; saturate, and never store -0
-  const float z32 = __fdiv_rn(__fsub_rn(0.0f, mn), sf);
-  half_t z16 = (half_t)z32;
-  uint16_t zb = __builtin_bit_cast(uint16_t, z16);
-  if ((zb & 0x7FFFu) == 0x7C00u) zb = (uint16_t)((zb & 0x8000u) | 0x7BFFu);
-  if (zb == 0x8000u) zb = 0;
-  z16 = __builtin_bit_cast(half_t, zb);
-  const float zf = (float)z16;
-
-  // Eq. 3: q = clamp(round_half_even(x / s + z), 0, 15); element j of a word in bits 4j..4j+3
   uint32_t w[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t acc = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float v = __fadd_rn(__fdiv_rn(x[8 * i + j], sf), zf);
-      const float r = fminf(fmaxf(rintf(v), 0.0f), 15.0f);
-      acc |= (uint32_t)r << (4 * j);
-    }
-    w[i] = acc;
-  }
+  half_t s16, z16;
+  quantize_group32(x, w, s16, z16);
   const int64_t row = bh * p.capacity + pos + t;
   *reinterpret_cast<uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2)) =
       make_uint4(w[0], w[1], w[2], w[3]);

@@ -147,6 +147,19 @@ def test_varlen_entry_points_reject_bad_arguments_without_a_gpu():
     assert q(ctypes.byref(c), FAKE, FAKE, FAKE + 1, 1, None) == E.TQ_ERR_ALIGN
 
 
+def test_append_decode_rejects_bad_arguments_without_a_gpu():
+    E = B
+    c = _cache()
+    wsb = tq.tq_workspace_bytes(1, 64, 128)
+    f = B.raw().tq_sdpa_int4_append_decode
+    assert f(ctypes.byref(c), None, FAKE, FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_NULL
+    assert f(ctypes.byref(c), FAKE, None, FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_NULL
+    assert f(ctypes.byref(c), FAKE, FAKE, None, 64, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_NULL
+    assert f(ctypes.byref(c), FAKE + 8, FAKE, FAKE, 64, 1024, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_ALIGN
+    assert f(ctypes.byref(c), FAKE, FAKE, FAKE, 64, 0, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_EMPTY
+    assert f(ctypes.byref(c), FAKE, FAKE, FAKE, 64, 1025, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_CAPACITY
+
+
 def test_decode_launch_count_query():
     f = B.raw().tq_decode_launches
     short = _cache()                                                  # 1024 tokens: launch-bound

@@ -470,3 +470,34 @@ def test_random_configurations_against_the_oracle():
             max_abs, rel = errors(out, ref)
             scale = max(1.0, float(np.abs(ref).max()))
             assert max_abs <= MAX_ABS * scale and rel <= REL_L2, f"{what} variant={variant}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
+
+
+# ---------------------------------------------------------------- one call per decode step
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g3_d128", "g2_d256"])
+def test_append_decode_in_one_call(shape, variant):
+    """tq_sdpa_int4_append_decode = quantise-append of the step's token + attention over all of them:
+    the stored bits equal the oracle's and the result matches the oracle over seq_len tokens, whether the
+    decode kernel takes the token in itself (matrix-core kernel, d=128) or two kernels are launched."""
+    for S, window, n_splits in ((1, 0, 0), (2, 0, 0), (33, 0, 0), (1000, 0, 3), (2500, 0, 0), (2500, 700, 0), (64, 1, 0)):
+        w = wl.custom(seq_len=S, seed=95 + S, **SHAPES[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k[:, :, :S - 1], v[:, :, :S - 1], capacity=S + 3, fill=0xEE) if S > 1 else None
+        if cache is None:
+            cache = tq.KVCache(w.batch, w.n_kv_heads, w.head_dim, S + 3)
+            for t in cache.tensors():
+                t.view(torch.uint8).fill_(0xEE)
+        kn, vn = k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda()
+        out = tq.tq_sdpa_int4_append_decode(cache, kn, vn, q.cuda(), S, w.attn_scale, variant=variant, window=window,
+                                            n_splits=n_splits)
+        torch.cuda.synchronize()
+        ocache = oracle_cache_from(k, v)
+        assert_cache_bit_exact(cache, ocache, S)
+        for t in cache.tensors():                 # nothing beyond the appended token is touched
+            assert bool((t.view(torch.uint8)[:, :, S:] == 0xEE).all())
+        ref = _oracle_window(q, ocache, [S] * w.batch, window if window > 0 else S, w.attn_scale)
+        assert_close(out, ref, f"{shape} append+decode S={S} window={window} variant={variant}")
+        again = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=variant, window=window, n_splits=n_splits)
+        a, b = np16(out).astype(np.float64), np16(again).astype(np.float64)
+        assert np.abs(a - b).max() <= 2.0 ** -9 * max(1.0, np.abs(b).max())   # same step through the two calls
