@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="llama128k",
                     help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | varlen8 (8 sequences of "
-                         "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | sweep80 "
+                         "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | paged8 (the same "
+                         "over a pool of 256-token pages in random order) | sweep80 "
                          "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
@@ -205,9 +206,11 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    varlen = args.workload == "varlen8"
+    paged = args.workload == "paged8"             # varlen8 with the sequences scattered over a pool of 256-token pages
+    varlen = args.workload == "varlen8" or paged
+    PT = 256
     if varlen:     # continuous batching: 8 sequences of the llama shape, lengths drawn in [4096, 32768]
-        w = wl.custom("varlen8", batch=8, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=32768, seed=1100,
+        w = wl.custom("paged8" if paged else "varlen8", batch=8, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=32768, seed=1100,
                       outlier_channels=4)
     else:
         w = wl.WORKLOADS[args.workload]
@@ -224,8 +227,16 @@ def main():
     for i in range(args.buffers):
         wi = wl.Workload(**{**w.__dict__, "seed": w.seed + 7777 * i})
         q, k, v = wl.make_inputs(wi, device=dev)
-        c = tq.KVCache(B, Hkv, d, S)
-        tq.tq_quantize_kv(c, k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(), 0)
+        if paged:                                 # a pool with exactly the pages the sequences need, in random order
+            gp = torch.Generator().manual_seed(w.seed + 99 + i)
+            table = torch.randperm(B * (S // PT), generator=gp).to(torch.int32).reshape(B, S // PT).to(dev)
+            c = tq.KVCache(B * (S // PT), Hkv, d, PT)
+            c.table = table
+            tq.tq_quantize_kv_paged(c, table, k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(),
+                                    torch.zeros(B, dtype=torch.int32, device=dev))
+        else:
+            c = tq.KVCache(B, Hkv, d, S)
+            tq.tq_quantize_kv(c, k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(), 0)
         news.append((k[:, :, S - 1:].contiguous(), v[:, :, S - 1:].contiguous()))
         caches.append(c)
         qs.append(q)
@@ -244,12 +255,17 @@ def main():
     def append(j):                                # the step's new token goes to the end of every sequence
         if lens is None:
             tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
+        elif paged:
+            tq.tq_quantize_kv_paged(caches[j], caches[j].table, news[j][0], news[j][1], pos_dev)
         else:
             tq.tq_quantize_kv_varlen(caches[j], news[j][0], news[j][1], pos_dev)
 
     def decode(j):
         if lens is None:
             tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
+        elif paged:
+            tq.tq_sdpa_int4_decode_paged(caches[j], caches[j].table, qs[j], lens_dev, S, w.attn_scale, out=out,
+                                         workspace=ws, **kw)
         else:
             tq.tq_sdpa_int4_decode_varlen(caches[j], qs[j], lens_dev, S, w.attn_scale, out=out, workspace=ws, **kw)
 
@@ -282,9 +298,9 @@ def main():
     # ---- dominant kernel: stream events around each of its launches.  Where the decode call is ONE
     #      launch (partials and chunk merge in the same kernel) that launch is timed; otherwise phase 1,
     #      the partial kernel, which tq_sdpa_int4_partial launches on its own.
-    fused = tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, **kw) == 1
+    fused = (not paged) and tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, **kw) == 1
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    n_splits = tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
+    n_splits = 0 if paged else tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
     lo = max(0, S - args.window) if args.window > 0 else 0     # first attended token
 
     def dominant(j):
@@ -381,17 +397,26 @@ def main():
                    "sample": f"whole {w.name} layer (attention over the packed cache, fp64 naive softmax), "
                              f"median of {reps} runs; quantise-append not included"}
         if not args.no_check:
-            c = tq.KVCache(B, Hkv, d, S)
-            tq.tq_quantize_kv(c, k0.to(dev), v0.to(dev), 0)
-            if lens is None:
-                o = tq.tq_sdpa_int4_decode(c, q0.to(dev), S, w.attn_scale, workspace=ws, **kw)
+            if paged:
+                table = caches[0].table
+                c = tq.KVCache(B * (S // PT), Hkv, d, PT)
+                tq.tq_quantize_kv_paged(c, table, k0.to(dev), v0.to(dev), torch.zeros(B, dtype=torch.int32, device=dev))
+                o = tq.tq_sdpa_int4_decode_paged(c, table, q0.to(dev), lens_dev, S, w.attn_scale, workspace=ws, **kw)
+                # read the pool back through the table: [B][pages][H_kv][PT][..] -> [B][H_kv][S][..]
+                back = lambda t: t[table.long()].permute(0, 2, 1, 3, 4).reshape(B, Hkv, S, -1).cpu().numpy()
+                got_k, got_v = back(c.k_codes), back(c.v_codes)
             else:
-                o = tq.tq_sdpa_int4_decode_varlen(c, q0.to(dev), lens_dev, S, w.attn_scale, workspace=ws, **kw)
+                c = tq.KVCache(B, Hkv, d, S)
+                tq.tq_quantize_kv(c, k0.to(dev), v0.to(dev), 0)
+                if lens is None:
+                    o = tq.tq_sdpa_int4_decode(c, q0.to(dev), S, w.attn_scale, workspace=ws, **kw)
+                else:
+                    o = tq.tq_sdpa_int4_decode_varlen(c, q0.to(dev), lens_dev, S, w.attn_scale, workspace=ws, **kw)
+                got_k, got_v = c.k_codes.cpu().numpy(), c.v_codes.cpu().numpy()
             torch.cuda.synchronize()
             diff = o.cpu().numpy().astype(np.float64) - ref
             check = {"max_abs": float(np.abs(diff).max()), "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(ref)),
-                     "codes_bit_exact": bool(np.array_equal(c.k_codes.cpu().numpy(), kc)
-                                             and np.array_equal(c.v_codes.cpu().numpy(), vc))}
+                     "codes_bit_exact": bool(np.array_equal(got_k, kc) and np.array_equal(got_v, vc))}
             check["ok"] = check["max_abs"] <= 2e-3 and check["rel_l2"] <= 1e-3 and check["codes_bit_exact"]
 
     line = {
@@ -405,6 +430,7 @@ def main():
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "window": args.window,
                    "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
+                                  "tq_quantize_kv_paged + tq_sdpa_int4_decode_paged" if paged else
                                   "tq_quantize_kv_varlen + tq_sdpa_int4_decode_varlen" if lens is not None else
                                   "tq_quantize_kv + tq_sdpa_int4_decode"),
                    "decode_launches": 1 if fused else 2},
@@ -416,6 +442,7 @@ def main():
                      "kernel": ("decode_partial_mfma_kernel: fused int4 attention over the chunks + in-kernel chunk merge "
                                 "(the whole tq_sdpa_int4_decode call)" if fused else
                                 "partial kernel (phase 1 of the decode)" if lens is None else
+                                "the whole tq_sdpa_int4_decode_paged call (partial kernel + merge kernel)" if paged else
                                 "the whole tq_sdpa_int4_decode_varlen call (partial kernel + merge kernel)"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -136,6 +136,27 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
                                void* out, void* workspace, size_t workspace_bytes,
                                const tq_decode_opts* opts, void* stream);
 
+/* Paged cache (what a decode server keeps: sequences grow page by page out of one pool).
+ * pool: a tq_kv_cache whose `batch` field counts PAGES and whose `capacity` is the page length in
+ * tokens (a power of two >= 32), arrays [n_pages][n_kv_heads][page_tokens][...] in the canonical
+ * layout.  block_table: DEVICE int32 [batch][max_blocks]; token t of sequence b lives in page
+ * block_table[b][t / page_tokens] at row t % page_tokens; only the entries a sequence's tokens
+ * reach are read, and they must name pages of the pool (not checked).  `batch` counts sequences
+ * (q, out, seq_lens, positions, k_new, v_new and the workspace are sized by it).
+ * tq_quantize_kv_paged: as tq_quantize_kv_varlen; a sequence whose tokens would not fit into its
+ * max_blocks pages is skipped.  tq_sdpa_int4_decode_paged: as tq_sdpa_int4_decode_varlen (device
+ * seq_lens, chunks planned on the device, two launches); max_seq_len <= max_blocks * page_tokens;
+ * opts->window is not offered (UNSUPPORTED).  Errors otherwise as for the varlen calls; SHAPE also
+ * for a page length that is not a power of two >= 32. */
+int tq_quantize_kv_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
+                         int32_t batch, const void* k_new, const void* v_new,
+                         const int32_t* positions, int32_t n_new, void* stream);
+int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
+                              int32_t batch, const void* q, int32_t n_q_heads,
+                              const int32_t* seq_lens, int32_t max_seq_len, float attn_scale,
+                              void* out, void* workspace, size_t workspace_bytes,
+                              const tq_decode_opts* opts, void* stream);
+
 /* The two phases of Sec. 3.2, separately callable (used for per-kernel timing).
  * partial: every chunk c writes (o_c, m_c, l_c) for each query head into workspace and
  * *n_splits_out (host int, may be NULL) receives the chunk count used.  reduce: merges

@@ -13,9 +13,11 @@ from .binding import (  # noqa: F401
     tq_kv_bytes,
     tq_plan_splits,
     tq_quantize_kv,
+    tq_quantize_kv_paged,
     tq_quantize_kv_varlen,
     tq_sdpa_int4_append_decode,
     tq_sdpa_int4_decode,
+    tq_sdpa_int4_decode_paged,
     tq_sdpa_int4_decode_varlen,
     tq_sdpa_int4_partial,
     tq_sdpa_int4_reduce,

@@ -53,6 +53,8 @@ def raw():
         OP = ctypes.POINTER(TqDecodeOptsStruct)
         L.tq_quantize_kv.argtypes = [CP, P, P, I, I, P]
         L.tq_sdpa_int4_decode.argtypes = [CP, P, I, I, F, P, P, SZ, OP, P]
+        L.tq_quantize_kv_paged.argtypes = [CP, P, I, I, P, P, P, I, P]
+        L.tq_sdpa_int4_decode_paged.argtypes = [CP, P, I, I, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_append_decode.argtypes = [CP, P, P, P, I, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_decode_varlen.argtypes = [CP, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_quantize_kv_varlen.argtypes = [CP, P, P, P, I, P]
@@ -229,6 +231,41 @@ def tq_quantize_kv_varlen(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tens
     rc = raw().tq_quantize_kv_varlen(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(),
                                      positions.data_ptr(), int(k_new.shape[2]), _stream_ptr(stream))
     _check(rc, "tq_quantize_kv_varlen")
+
+
+def tq_quantize_kv_paged(pool: KVCache, block_table: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                         positions: torch.Tensor, stream=None) -> None:
+    """pool: a KVCache whose batch dimension counts pages; block_table int32 [B, max_blocks] (device);
+    k_new, v_new fp16 [B, H_kv, n_new, d]; positions int32 [B] (device)."""
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    _need(positions, torch.int32, "positions")
+    _need(block_table, torch.int32, "block_table")
+    rc = raw().tq_quantize_kv_paged(ctypes.byref(pool.struct), block_table.data_ptr(), int(block_table.shape[1]),
+                                    int(block_table.shape[0]), k_new.data_ptr(), v_new.data_ptr(),
+                                    positions.data_ptr(), int(k_new.shape[2]), _stream_ptr(stream))
+    _check(rc, "tq_quantize_kv_paged")
+
+
+def tq_sdpa_int4_decode_paged(pool: KVCache, block_table: torch.Tensor, q: torch.Tensor, seq_lens: torch.Tensor,
+                              max_seq_len: int, attn_scale: float, out=None, workspace=None, n_splits: int = 0,
+                              variant: int = 0, stream=None) -> torch.Tensor:
+    """q: fp16 [B, H_q, d]; block_table int32 [B, max_blocks] and seq_lens int32 [B] on the device."""
+    _need(q, torch.float16, "q")
+    _need(seq_lens, torch.int32, "seq_lens")
+    _need(block_table, torch.int32, "block_table")
+    if out is None:
+        out = torch.empty_like(q)
+    need = tq_workspace_bytes(int(q.shape[0]), int(q.shape[1]), pool.head_dim)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = raw().tq_sdpa_int4_decode_paged(ctypes.byref(pool.struct), block_table.data_ptr(), int(block_table.shape[1]),
+                                         int(q.shape[0]), q.data_ptr(), int(q.shape[1]), seq_lens.data_ptr(),
+                                         int(max_seq_len), float(attn_scale), out.data_ptr(), workspace.data_ptr(),
+                                         workspace.numel() * workspace.element_size(), _opts(n_splits, variant),
+                                         _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_decode_paged")
+    return out
 
 
 def tq_sdpa_int4_partial(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, workspace: torch.Tensor,

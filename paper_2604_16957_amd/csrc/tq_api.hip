@@ -54,15 +54,17 @@ Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int targ
   return p;
 }
 
+// `room`: tokens a sequence can hold (the cache's capacity, or max_blocks pages of a paged pool)
 int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len, const void* out,
-                 const void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, bool need_out) {
+                 const void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, bool need_out,
+                 int64_t room = -1) {
   int rc = check_cache(c);
   if (rc == TQ_ERR_NULL) return rc;
   if (!q || (need_out && !out) || !workspace) return TQ_ERR_NULL;
   if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
   if (n_q_heads < 1 || n_q_heads % c->n_kv_heads != 0) return TQ_ERR_SHAPE;
   if (seq_len < 1) return TQ_ERR_EMPTY;
-  if (seq_len > c->capacity) return TQ_ERR_CAPACITY;
+  if (seq_len > (room >= 0 ? room : (int64_t)c->capacity)) return TQ_ERR_CAPACITY;
   if (rc == TQ_ERR_ALIGN) return rc;
   if (!aligned(q, 16) || (need_out && !aligned(out, 16)) || !aligned(workspace, 256)) return TQ_ERR_ALIGN;
   if (workspace_bytes < tq_workspace_bytes(c->batch, n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
@@ -132,7 +134,8 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
 int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
                 const int32_t* seq_lens, float attn_scale, void* out, void* workspace, const tq_decode_opts* opts,
                 int32_t* n_splits_out, bool* merged, void* stream, DecodeParams* used = nullptr,
-                const void* k_new = nullptr, const void* v_new = nullptr, bool* appended = nullptr) {
+                const void* k_new = nullptr, const void* v_new = nullptr, bool* appended = nullptr,
+                const tq::PagedView* pv = nullptr) {
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
@@ -154,6 +157,11 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
   } else {
     p.seq_len = attended;
     p.start = first;
+  }
+  if (pv) {
+    p.block_table = pv->block_table;
+    p.max_blocks = pv->max_blocks;
+    p.page_shift = pv->page_shift;
   }
   if (append) {
     p.k_new = static_cast<const half_t*>(k_new);
@@ -320,6 +328,58 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   if (rc != TQ_OK || merged) return rc;
   return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
                              stream);
+}
+
+// A pool of pages seen as a cache: `batch` sequences whose rows are pages of pool->capacity tokens.
+static int paged_view(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
+                      tq_kv_cache* view, tq::PagedView* pv) {
+  const int rc = check_cache(pool);
+  if (rc == TQ_ERR_NULL || !block_table) return TQ_ERR_NULL;
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
+  const int pt = pool->capacity;
+  if (pt < tq::kTile || (pt & (pt - 1)) != 0 || batch < 1 || max_blocks < 1) return TQ_ERR_SHAPE;
+  if (rc == TQ_ERR_ALIGN || !aligned(block_table, 4)) return TQ_ERR_ALIGN;
+  *view = *pool;
+  view->batch = batch;
+  int shift = 0;
+  while ((1 << shift) < pt) ++shift;
+  *pv = tq::PagedView{block_table, max_blocks, shift, batch};
+  return TQ_OK;
+}
+
+int tq_quantize_kv_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
+                         const void* k_new, const void* v_new, const int32_t* positions, int32_t n_new, void* stream) {
+  tq_kv_cache view;
+  tq::PagedView pv;
+  const int rc = paged_view(pool, block_table, max_blocks, batch, &view, &pv);
+  if (rc != TQ_OK) return rc;
+  if (!k_new || !v_new || !positions) return TQ_ERR_NULL;
+  if (n_new < 1) return TQ_ERR_EMPTY;
+  if ((int64_t)n_new > (int64_t)max_blocks * pool->capacity) return TQ_ERR_CAPACITY;
+  if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(positions, 4)) return TQ_ERR_ALIGN;
+  return hip_rc(tq::launch_quantize(view, k_new, v_new, 0, positions, n_new, static_cast<hipStream_t>(stream), &pv));
+}
+
+int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
+                              const void* q, int32_t n_q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                              float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                              const tq_decode_opts* opts, void* stream) {
+  tq_kv_cache view;
+  tq::PagedView pv;
+  int rc = paged_view(pool, block_table, max_blocks, batch, &view, &pv);
+  if (rc != TQ_OK) return rc;
+  rc = check_decode(&view, q, n_q_heads, max_seq_len, out, workspace, workspace_bytes, opts, true,
+                    (int64_t)max_blocks * pool->capacity);
+  if (rc != TQ_OK) return rc;
+  if (!seq_lens) return TQ_ERR_NULL;
+  if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
+  if (opts && opts->window > 0) return TQ_ERR_UNSUPPORTED;      // a window's first token need not start a supertile
+  bool merged = false;
+  DecodeParams p{};
+  rc = run_partial(&view, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, nullptr, &merged,
+                   stream, &p, nullptr, nullptr, nullptr, &pv);
+  if (rc != TQ_OK || merged) return rc;
+  return hip_rc(tq::launch_reduce(p, batch, view.head_dim, static_cast<hipStream_t>(stream)));
 }
 
 int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, const int32_t* seq_lens,

@@ -256,9 +256,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
     if (!var_plan(p, blockIdx.x, vp)) return;
-    split = vp.chunk;
-    b = vp.b;
-    tokens_per_split = vp.chunk_tokens;
+    split = __builtin_amdgcn_readfirstlane(vp.chunk);     // (wave-uniform by construction: tell the compiler)
+    b = __builtin_amdgcn_readfirstlane(vp.b);
+    tokens_per_split = __builtin_amdgcn_readfirstlane(vp.chunk_tokens);
     part_stride = kMaxSplits;
   }
   const int G = p.gqa;
@@ -272,7 +272,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // sliding window the row simply starts `start` tokens later
   const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;
   const int start = p.seq_lens ? var_start(p, b) : p.start;
-  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
+  // first row of the six arrays this block reads from: the sequence's own row (contiguous cache), or the
+  // pool's row 0 (paged cache: the page's rows are added supertile by supertile)
+  const bool paged = p.block_table != nullptr;
+  const int64_t row0 = paged ? 0 : (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
   const int begin = split * tokens_per_split;
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
@@ -288,6 +291,20 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
                            reinterpret_cast<const char*>(p.k_zero) + row0 * (NG * 2),
                            reinterpret_cast<const char*>(p.v_scale) + row0 * (NG * 2),
                            reinterpret_cast<const char*>(p.v_zero) + row0 * (NG * 2)};
+  // Where a supertile starts: in a contiguous cache, `tok0` tokens into the sequence's own row; in a paged
+  // one, in the page the block table names, at the token's offset inside the page (supertiles never
+  // straddle pages: a page is a multiple of 32 tokens and paged sequences start at token 0).
+  struct Bases { const char* k; const char* v; const char* s[4]; };
+  const Bases row_bases = {kc_row, vc_row, {sz_row[0], sz_row[1], sz_row[2], sz_row[3]}};
+  const int32_t* const tbl = paged ? p.block_table + (int64_t)b * p.max_blocks : nullptr;
+  const int page_mask = (1 << p.page_shift) - 1;
+  auto page_of = [&](int tok0) { return tbl[min(tok0 >> p.page_shift, p.max_blocks - 1)]; };
+  auto bases_of_page = [&](int page) -> Bases {   // row 0 of `page` for this KV head (a page is 2^page_shift rows)
+    const int64_t r = (int64_t)(page * p.n_kv_heads + kv) << p.page_shift;
+    const int64_t rc = r * TB, rs = r * (NG * 2);
+    return {row_bases.k + rc, row_bases.v + rc, {row_bases.s[0] + rs, row_bases.s[1] + rs, row_bases.s[2] + rs,
+                                                 row_bases.s[3] + rs}};
+  };
   const uint32_t koff = tok_of_row(c) * TB + kq * (D / 8);   // this lane's 16 B (x D/128) of a K tile
   // scale / zero-point arrays: destination dword u*64+lane of the stage comes from (token, dword) of the supertile
   uint32_t sz_tok[C::SZ / 256], sz_col[C::SZ / 256];
@@ -305,24 +322,37 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   uint32_t szoff[C::SZ / 256];
 #pragma unroll
   for (int u = 0; u < C::SZ / 256; ++u) szoff[u] = (sz_tok[u] * (NG / 2) + sz_col[u]) * 4;
-  auto issue_at = [&](uint32_t l, uint32_t off_c, uint32_t vk, uint32_t vv, const uint32_t (&vs)[C::SZ / 256]) {
+  auto issue_at = [&](uint32_t l, const Bases& B, uint32_t off_c, uint32_t vk, uint32_t vv,
+                      const uint32_t (&vs)[C::SZ / 256]) {
     const uint32_t off_s = off_c >> 3;            // (NG*2) / TB = 1/8: scale bytes per code byte
     if constexpr (D == 128) {
-      dma16_x2<1024>(kc_row, vk + off_c, l);                           // two K tiles: 1 KB apart on both sides
-      dma16_x2<1024>(vc_row, vv + off_c, l + C::OFF_V);
+      dma16_x2<1024>(B.k, vk + off_c, l);                              // two K tiles: 1 KB apart on both sides
+      dma16_x2<1024>(B.v, vv + off_c, l + C::OFF_V);
     } else {
-      dma16_x2<2048>(kc_row, vk + off_c, l);                           // first 16 B of each lane, tiles 0 and 1
-      dma16_x2o<16, 2064>(kc_row, vk + off_c, l + 1024 - 16);          // second 16 B: +16 in HBM, +1024 in LDS
-      dma16_x4(vc_row, vv + off_c, l + C::OFF_V);
+      dma16_x2<2048>(B.k, vk + off_c, l);                              // first 16 B of each lane, tiles 0 and 1
+      dma16_x2o<16, 2064>(B.k, vk + off_c, l + 1024 - 16);             // second 16 B: +16 in HBM, +1024 in LDS
+      dma16_x4(B.v, vv + off_c, l + C::OFF_V);
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int u = 0; u < C::SZ / 256; ++u) dma4(sz_row[a], vs[u] + off_s, l + C::OFF_KS + a * C::SZ + u * 256);
+      for (int u = 0; u < C::SZ / 256; ++u) dma4(B.s[a], vs[u] + off_s, l + C::OFF_KS + a * C::SZ + u * 256);
+  };
+  // supertile starting tok0 tokens into the sequence (page known in the paged case) -> ring slot at l
+  auto issue_tok = [&](uint32_t l, int tok0, int page, uint32_t vk, uint32_t vv, const uint32_t (&vs)[C::SZ / 256]) {
+    if (paged) issue_at(l, bases_of_page(page), (uint32_t)(tok0 & page_mask) * TB, vk, vv, vs);
+    else issue_at(l, row_bases, (uint32_t)tok0 * TB, vk, vv, vs);
   };
   auto issue_tail = [&](int slot, int sidx) {     // ragged last supertile: clamp every token to the last valid one
     const int base = begin + sidx * 32;
     const uint32_t l = ring_lds + slot * C::STAGE;
+    // token index -> row of the arrays below: the sequence's row, or the page that holds this supertile
+    const Bases B = paged ? bases_of_page(page_of(base)) : row_bases;
+    const int row_first = paged ? (base & ~page_mask) : 0;
+    const char* const kc_row = B.k - (int64_t)row_first * TB;
+    const char* const vc_row = B.v - (int64_t)row_first * TB;
+    const char* const sz_row[4] = {B.s[0] - (int64_t)row_first * (NG * 2), B.s[1] - (int64_t)row_first * (NG * 2),
+                                   B.s[2] - (int64_t)row_first * (NG * 2), B.s[3] - (int64_t)row_first * (NG * 2)};
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
@@ -345,9 +375,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       }
   };
   const uint32_t zero_vs[C::SZ / 256] = {};
-  auto off_of = [&](int sidx) { return (uint32_t)(begin + sidx * 32) * TB; };
-  auto issue = [&](int slot, int sidx) { issue_at(ring_lds + slot * C::STAGE, off_of(sidx), koff, lane16, szoff); };
-  auto issue_phantom = [&](int slot) { issue_at(ring_lds + slot * C::STAGE, off_of(0), 0u, 0u, zero_vs); };
+  auto tok_of = [&](int sidx) { return begin + sidx * 32; };
+  auto issue = [&](int slot, int sidx) {
+    const int tok0 = tok_of(sidx);
+    issue_tok(ring_lds + slot * C::STAGE, tok0, paged ? page_of(tok0) : 0, koff, lane16, szoff);
+  };
+  auto issue_phantom = [&](int slot) {
+    issue_tok(ring_lds + slot * C::STAGE, begin, paged ? page_of(begin) : 0, 0u, 0u, zero_vs);
+  };
   // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
   //      issues from its older wave first, so wave w gets through a supertile in about 7/9 of the time
   //      wave w+4 needs.  The chunk's supertiles are therefore dealt round-robin to the four SIMDs, and
@@ -508,7 +543,17 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // supertile NS, the first one issued inside the loop, and how to step from one supertile to the next:
   // position j in the wave's pattern of 9 (or 7) out of 16
   int nx_j = young ? NS % 7 : NS % 9;
-  uint32_t nx_off = off_of(sidx_of(NS));
+  int nx_tok = tok_of(sidx_of(NS));
+  // The page of the next supertile is looked up one supertile ahead of its use, by a scalar load the
+  // compiler does not wait for: the wait is the lgkmcnt(0) that precedes every issue in the loop (the
+  // value is threaded through that statement so that nothing reads it earlier).
+  auto page_ahead = [&](int tok0) {
+    int page;
+    const uint32_t byte = (uint32_t)min(tok0 >> p.page_shift, p.max_blocks - 1) * 4;
+    asm volatile("s_load_dword %0, %1, %2" : "=&s"(page) : "s"(tbl), "s"(byte) : "memory");
+    return page;
+  };
+  int nx_page = paged ? __builtin_amdgcn_readfirstlane(page_of(nx_tok)) : 0;
 
   // ---- running state
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
@@ -754,13 +799,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     }
     half8v pa[NA];
     softmax(sc, vr, pa);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // every LDS read of this slot has returned
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nx_page) :: "memory");   // every LDS read of this slot has returned
     if (i + NS < n_mine) {
-      issue_at(ring_lds + slot * C::STAGE, nx_off, koff, lane16, szoff);
+      issue_tok(ring_lds + slot * C::STAGE, nx_tok, nx_page, koff, lane16, szoff);
       // next supertile of the pattern: the older wave holds k = 0,2,..,14,15 of every 16, the younger 1,3,..,13
       const int step = young ? (nx_j < 6 ? 2 : 4) : (nx_j < 7 ? 2 : 1);
       nx_j = (nx_j == (young ? 6 : 8)) ? 0 : nx_j + 1;
-      nx_off += (uint32_t)step * (4 * 32 * TB);
+      nx_tok += step * (4 * 32);
+      if (paged) nx_page = page_ahead(nx_tok);
     } else {
       issue_phantom(slot);
     }

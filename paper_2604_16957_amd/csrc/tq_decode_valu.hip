@@ -80,7 +80,12 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   for (int t0 = begin; t0 < end; t0 += SPB) {
     const int t = t0 + slot;
     const bool valid = t < end;
-    const int64_t row = row0 + (valid ? t : end - 1);    // clamped: always a written token
+    const int tc = valid ? t : end - 1;                  // clamped: always a written token
+    int64_t row = row0 + tc;
+    if (p.block_table) {                                 // paged cache: the page the block table names for this token
+      const int page = p.block_table[(int64_t)b * p.max_blocks + (tc >> p.page_shift)];
+      row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (tc & ((1 << p.page_shift) - 1));
+    }
 
     float kf[8], vf[8];
     if constexpr (DENSE) {

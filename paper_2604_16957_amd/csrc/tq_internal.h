@@ -43,6 +43,11 @@ struct DecodeParams {
   // and seq_len already the windowed length.  Per-sequence lengths: window > 0 and the kernels derive
   // both from seq_lens (var_len / var_start below).
   int32_t start, window;
+  // Paged cache: block_table non-null = the six arrays are a POOL of pages, [n_pages][H_kv][row_stride] rows
+  // with row_stride = 2^page_shift tokens per page, and token t of sequence b lives in page
+  // block_table[b * max_blocks + (t >> page_shift)] at row t & (row_stride - 1).
+  const int32_t* block_table;
+  int32_t max_blocks, page_shift;
   // Append-and-attend in one launch (matrix-core kernel, d=128, common length): k_new / v_new non-null =
   // one new token per sequence, fp16 [B][H_kv][1][D]; it is quantised and written at token append_pos of its
   // row by the block of the last chunk, which also adds its attention term; seq_len then counts the cached
@@ -137,10 +142,13 @@ inline size_t workspace_ml_floats(int batch, int n_q_heads) {
 }
 
 // Launchers (each returns a hipError_t from hipGetLastError after the launch).
+// A paged view of a pool: sequence b's token t lives in page block_table[b * max_blocks + (t >> page_shift)].
+struct PagedView { const int32_t* block_table; int32_t max_blocks, page_shift, batch; };
+
 // pos_dev (device, [B]) non-null: sequence b is written at pos_dev[b]; a sequence whose tokens would not
-// fit into [0, capacity) is skipped
+// fit into [0, capacity) (paged: into its max_blocks pages) is skipped.  pv non-null: c is a pool of pages.
 hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos,
-                           const int32_t* pos_dev, int n_new, hipStream_t s);
+                           const int32_t* pos_dev, int n_new, hipStream_t s, const PagedView* pv = nullptr);
 hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_dense, half_t* v_dense,
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);

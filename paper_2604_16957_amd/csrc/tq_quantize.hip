@@ -20,6 +20,8 @@ struct QuantParams {
   half_t* zero[2];
   int32_t n_new, capacity, pos, head_dim, n_kv_heads;
   const int32_t* pos_dev;     // per-sequence positions (device, [B]) or null
+  const int32_t* block_table; // paged cache (see DecodeParams): [B][max_blocks] page numbers, or null
+  int32_t max_blocks, page_shift;
   int64_t groups_per_tensor;  // B*H_kv*n_new*(D/32)
 };
 
@@ -37,7 +39,8 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   int pos = p.pos;
   if (p.pos_dev) {
     pos = p.pos_dev[bh / p.n_kv_heads];
-    if (pos < 0 || pos > p.capacity - p.n_new) return;    // this sequence's tokens do not fit: nothing is written
+    const int64_t room = p.block_table ? ((int64_t)p.max_blocks << p.page_shift) : p.capacity;
+    if (pos < 0 || pos > room - p.n_new) return;          // this sequence's tokens do not fit: nothing is written
   }
 
   const uint4* src = reinterpret_cast<const uint4*>(p.src[which] + (vec * p.head_dim + g * kGroup));
@@ -52,7 +55,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   uint32_t w[4];
   half_t s16, z16;
   quantize_group32(x, w, s16, z16);
-  const int64_t row = bh * p.capacity + pos + t;
+  int64_t row = bh * p.capacity + pos + t;
+  if (p.block_table) {                                 // paged cache: capacity is the page length
+    const int tok = pos + t;
+    const int page = p.block_table[(bh / p.n_kv_heads) * p.max_blocks + (tok >> p.page_shift)];
+    row = ((int64_t)page * p.n_kv_heads + bh % p.n_kv_heads) * p.capacity + (tok & ((1 << p.page_shift) - 1));
+  }
   *reinterpret_cast<uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2)) =
       make_uint4(w[0], w[1], w[2], w[3]);
   p.scale[which][row * ng + g] = s16;
@@ -99,7 +107,7 @@ __global__ __launch_bounds__(256) void dequant_dense_kernel(DequantParams p) {
 }  // namespace
 
 hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos,
-                           const int32_t* pos_dev, int n_new, hipStream_t s) {
+                           const int32_t* pos_dev, int n_new, hipStream_t s, const PagedView* pv) {
   QuantParams p;
   p.src[0] = static_cast<const half_t*>(k_new);
   p.src[1] = static_cast<const half_t*>(v_new);
@@ -113,9 +121,13 @@ hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* 
   p.capacity = c.capacity;
   p.pos = pos;
   p.pos_dev = pos_dev;
+  p.block_table = pv ? pv->block_table : nullptr;
+  p.max_blocks = pv ? pv->max_blocks : 0;
+  p.page_shift = pv ? pv->page_shift : 0;
   p.n_kv_heads = c.n_kv_heads;
   p.head_dim = c.head_dim;
-  p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * n_new * (c.head_dim / kGroup);
+  const int batch = pv ? pv->batch : c.batch;            // in a paged pool c.batch counts pages, not sequences
+  p.groups_per_tensor = (int64_t)batch * c.n_kv_heads * n_new * (c.head_dim / kGroup);
   const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);
   hipLaunchKernelGGL(quantize_append_kernel, dim3(blocks, 2), dim3(256), 0, s, p);
   return hipGetLastError();

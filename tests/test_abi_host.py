@@ -160,6 +160,39 @@ def test_append_decode_rejects_bad_arguments_without_a_gpu():
     assert f(ctypes.byref(c), FAKE, FAKE, FAKE, 64, 1025, 0.1, FAKE, FAKE, wsb, None, None) == E.TQ_ERR_CAPACITY
 
 
+def test_paged_entry_points_reject_bad_arguments_without_a_gpu():
+    E = B
+    pool = _cache(batch=64, capacity=256)         # 64 pages of 256 tokens
+    wsb = tq.tq_workspace_bytes(4, 64, 128)
+    d = B.raw().tq_sdpa_int4_decode_paged
+    ok_args = lambda **kw: dict(dict(pool=pool, tbl=FAKE, mb=8, batch=4, q=FAKE, hq=64, lens=FAKE, S=2048, out=FAKE,
+                                     ws=FAKE, wsb=wsb, opts=None), **kw)
+
+    def call(**kw):
+        a = ok_args(**kw)
+        return d(ctypes.byref(a["pool"]), a["tbl"], a["mb"], a["batch"], a["q"], a["hq"], a["lens"], a["S"], 0.1,
+                 a["out"], a["ws"], a["wsb"], a["opts"], None)
+
+    assert call(tbl=None) == E.TQ_ERR_NULL
+    assert call(lens=None) == E.TQ_ERR_NULL
+    assert call(q=None) == E.TQ_ERR_NULL
+    assert call(pool=_cache(batch=64, capacity=200)) == E.TQ_ERR_SHAPE      # page length not a power of two
+    assert call(pool=_cache(batch=64, capacity=16)) == E.TQ_ERR_SHAPE       # shorter than a tile
+    assert call(batch=0) == E.TQ_ERR_SHAPE
+    assert call(mb=0) == E.TQ_ERR_SHAPE
+    assert call(S=2049) == E.TQ_ERR_CAPACITY                                # more than max_blocks pages hold
+    assert call(S=0) == E.TQ_ERR_EMPTY
+    assert call(tbl=FAKE + 2) == E.TQ_ERR_ALIGN
+    assert call(wsb=wsb - 1) == E.TQ_ERR_WORKSPACE
+    win = B.TqDecodeOptsStruct(0, 0, 128)
+    assert call(opts=ctypes.byref(win)) == E.TQ_ERR_UNSUPPORTED
+    qz = B.raw().tq_quantize_kv_paged
+    assert qz(ctypes.byref(pool), None, 8, 4, FAKE, FAKE, FAKE, 1, None) == E.TQ_ERR_NULL
+    assert qz(ctypes.byref(pool), FAKE, 8, 4, FAKE, FAKE, None, 1, None) == E.TQ_ERR_NULL
+    assert qz(ctypes.byref(pool), FAKE, 8, 4, FAKE, FAKE, FAKE, 0, None) == E.TQ_ERR_EMPTY
+    assert qz(ctypes.byref(pool), FAKE, 8, 4, FAKE, FAKE, FAKE, 2049, None) == E.TQ_ERR_CAPACITY
+
+
 def test_decode_launch_count_query():
     f = B.raw().tq_decode_launches
     short = _cache()                                                  # 1024 tokens: launch-bound

@@ -501,3 +501,74 @@ def test_append_decode_in_one_call(shape, variant):
         again = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=variant, window=window, n_splits=n_splits)
         a, b = np16(out).astype(np.float64), np16(again).astype(np.float64)
         assert np.abs(a - b).max() <= 2.0 ** -9 * max(1.0, np.abs(b).max())   # same step through the two calls
+
+
+# ---------------------------------------------------------------- paged cache
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("shape", ["g8_d128_kv2", "g2_d256"])
+def test_paged_cache(shape, variant):
+    """Sequences scattered page by page over a pool: fill and append through the block table, attend
+    with per-sequence lengths; the oracle gets each sequence's tokens gathered back in order."""
+    shapes = dict(SHAPES, g8_d128_kv2=dict(n_q_heads=16, n_kv_heads=2, head_dim=128, outlier_channels=4))
+    lens = [1000, 77, 2049, 256]
+    PT, max_blocks, n_pages = 256, 9, 40
+    w = wl.custom(batch=len(lens), seq_len=max(lens) + 1, seed=97, **shapes[shape])
+    q, k, v = make(w)                             # token max(lens) is the one appended later
+    B, Hkv, d = w.batch, w.n_kv_heads, w.head_dim
+    rng = np.random.default_rng(5)
+    table = rng.permutation(n_pages)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    table_dev = torch.from_numpy(table).cuda()
+    pool = tq.KVCache(n_pages, Hkv, d, PT)
+    for t in pool.tensors():
+        t.view(torch.uint8).fill_(0xEE)
+    S = max(lens)
+    zeros = torch.zeros(B, dtype=torch.int32, device="cuda")
+    tq.tq_quantize_kv_paged(pool, table_dev, k[:, :, :S].contiguous().cuda(), v[:, :, :S].contiguous().cuda(), zeros)
+    torch.cuda.synchronize()
+    ocache = oracle_cache_from(k, v)
+    names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero")
+
+    def gathered(b, n):                           # sequence b's first n tokens, read back through the table
+        out = []
+        for t in pool.tensors():
+            g = np16(t)
+            out.append(np.concatenate([g[table[b, j]] for j in range((n + PT - 1) // PT)], axis=1)[:, :n])
+        return out
+
+    for b in range(B):
+        for name, g, o in zip(names, gathered(b, S), ocache):
+            o = o[b, :, :S]
+            if g.dtype == np.float16:
+                g, o = g.view(np.uint16), o.view(np.uint16)
+            assert np.array_equal(g, o), f"{name} sequence {b}"
+    used = set(table[:, :(S + PT - 1) // PT].ravel().tolist())
+    for t in pool.tensors():                      # pages nobody's tokens reach stay untouched
+        raw_t = t.view(torch.uint8).cpu().numpy()
+        for page in range(n_pages):
+            if page not in used:
+                assert (raw_t[page] == 0xEE).all()
+
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    for n_splits in (0, 3):
+        try:
+            out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev, S, w.attn_scale,
+                                               n_splits=n_splits, variant=variant)
+        except tq.TqError as e:
+            if e.status == -6 and variant == 2:
+                pytest.skip("matrix-core kernel does not cover this shape")
+            raise
+        torch.cuda.synchronize()
+        assert_close(out, ref, f"{shape} paged variant={variant} n_splits={n_splits}")
+    # one decode step: every sequence appends its next token (the one stored at index max(lens) of the source)
+    # at its own position, then attends one token more
+    kn, vn = k[:, :, S:S + 1].contiguous().cuda(), v[:, :, S:S + 1].contiguous().cuda()
+    tq.tq_quantize_kv_paged(pool, table_dev, kn, vn, lens_dev)
+    out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev + 1, S + 1, w.attn_scale, variant=variant)
+    torch.cuda.synchronize()
+    rows = []
+    for b, n in enumerate(lens):
+        one = [np.concatenate([a[b:b + 1, :, :n], a[b:b + 1, :, S:S + 1]], axis=2) for a in ocache]
+        rows.append(oracle.attend_packed(np16(q[b:b + 1]), *one, seq_len=n + 1, alpha=w.attn_scale))
+    assert_close(out, np.concatenate(rows, axis=0), f"{shape} paged append+attend variant={variant}")
