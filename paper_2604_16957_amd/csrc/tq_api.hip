@@ -129,27 +129,51 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
           use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, cache->n_kv_heads)};
 }
 
+// One launch of phase 1: what to attend, and what came of it.
+struct PartialRequest {
+  const tq_kv_cache* cache;            // validated; for a paged pool: the view with batch = sequences
+  const void* q;
+  int32_t n_q_heads, seq_len;          // seq_len: the common length, or the bound of seq_lens
+  const int32_t* seq_lens = nullptr;   // device, per-sequence lengths
+  float attn_scale;
+  void* out = nullptr;                 // non-null: the kernel may merge the chunks itself and write it
+  void* workspace;
+  const tq_decode_opts* opts = nullptr;
+  const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it)
+  const void* v_new = nullptr;
+  const tq::PagedView* paged = nullptr;
+  void* stream = nullptr;
+  // results
+  int32_t n_splits = 0;
+  bool merged = false;                 // `out` has been written
+  DecodeParams params{};               // what the kernel was given (the merge kernel takes the same)
+};
+
+// Whether the decode kernel takes the step's new token in itself (else the append kernel runs first).
+bool appends_in_kernel(const tq_kv_cache* cache, int n_q_heads, int seq_len, const int32_t* seq_lens, const Route& r,
+                       const tq_decode_opts* opts) {
+  return r.use_mfma && !seq_lens && windowed(seq_len, opts) >= 2 &&
+         tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
+}
+
 // Phase 1 (and, with `out`, the whole decode where the matrix-core kernel can merge in place).
-// *merged tells whether `out` has been written.
-int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
-                const int32_t* seq_lens, float attn_scale, void* out, void* workspace, const tq_decode_opts* opts,
-                int32_t* n_splits_out, bool* merged, void* stream, DecodeParams* used = nullptr,
-                const void* k_new = nullptr, const void* v_new = nullptr, bool* appended = nullptr,
-                const tq::PagedView* pv = nullptr) {
-  const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+int run_partial(PartialRequest& rq) {
+  const tq_kv_cache* cache = rq.cache;
+  const tq_decode_opts* opts = rq.opts;
+  const int32_t* seq_lens = rq.seq_lens;
+  const int n_q_heads = rq.n_q_heads, seq_len = rq.seq_len;
+  const Route r = route_of(cache, n_q_heads, seq_len, rq.attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
   const int target = use_mfma ? kBlocksMfma : kBlocksValu;
   int attended = windowed(seq_len, opts);         // chunks cover the attended tokens only
   // append-and-attend in the kernel: the new token (the last attended one) does not come from the cache
-  const bool append = k_new != nullptr && use_mfma && !seq_lens && attended >= 2 &&
-                      tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
-  if (appended) *appended = append;
+  const bool append = rq.k_new != nullptr && appends_in_kernel(cache, n_q_heads, seq_len, seq_lens, r, opts);
   const int first = seq_len - attended;           // first attended token
   if (append) --attended;
   const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, attended, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
-  DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
+  DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan);
   p.seq_lens = seq_lens;
   p.batch = cache->batch;
   if (seq_lens) {
@@ -158,14 +182,14 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
     p.seq_len = attended;
     p.start = first;
   }
-  if (pv) {
-    p.block_table = pv->block_table;
-    p.max_blocks = pv->max_blocks;
-    p.page_shift = pv->page_shift;
+  if (rq.paged) {
+    p.block_table = rq.paged->block_table;
+    p.max_blocks = rq.paged->max_blocks;
+    p.page_shift = rq.paged->page_shift;
   }
   if (append) {
-    p.k_new = static_cast<const half_t*>(k_new);
-    p.v_new = static_cast<const half_t*>(v_new);
+    p.k_new = static_cast<const half_t*>(rq.k_new);
+    p.v_new = static_cast<const half_t*>(rq.v_new);
     p.append_pos = seq_len - 1;
   }
   if (seq_lens && !(opts && opts->n_splits > 0)) {
@@ -179,13 +203,35 @@ int run_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int3
     p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;
     p.n_splits = tq::kMaxSplits;
   }
-  if (used) *used = p;
-  if (n_splits_out) *n_splits_out = plan.n_splits;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool merge = out != nullptr && r.merge && !seq_lens;
-  if (merged) *merged = merge;
-  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, merge, s));
+  rq.params = p;
+  rq.n_splits = plan.n_splits;
+  hipStream_t s = static_cast<hipStream_t>(rq.stream);
+  rq.merged = rq.out != nullptr && r.merge && !seq_lens;
+  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
+}
+
+// Phase 2 after run_partial, unless the kernel has merged already.
+int finish_decode(const PartialRequest& rq, int rc) {
+  if (rc != TQ_OK || rq.merged) return rc;
+  return hip_rc(tq::launch_reduce(rq.params, rq.cache->batch, rq.cache->head_dim, static_cast<hipStream_t>(rq.stream)));
+}
+
+// A pool of pages seen as a cache: `batch` sequences whose rows are pages of pool->capacity tokens.
+int paged_view(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
+                      tq_kv_cache* view, tq::PagedView* pv) {
+  const int rc = check_cache(pool);
+  if (rc == TQ_ERR_NULL || !block_table) return TQ_ERR_NULL;
+  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
+  const int pt = pool->capacity;
+  if (pt < tq::kTile || (pt & (pt - 1)) != 0 || batch < 1 || max_blocks < 1) return TQ_ERR_SHAPE;
+  if (rc == TQ_ERR_ALIGN || !aligned(block_table, 4)) return TQ_ERR_ALIGN;
+  *view = *pool;
+  view->batch = batch;
+  int shift = 0;
+  while ((1 << shift) < pt) ++shift;
+  *pv = tq::PagedView{block_table, max_blocks, shift, batch};
+  return TQ_OK;
 }
 
 }  // namespace
@@ -270,8 +316,14 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
                          int32_t* n_splits_out, void* stream) {
   const int rc = check_decode(cache, q, n_q_heads, seq_len, nullptr, workspace, workspace_bytes, opts, false);
   if (rc != TQ_OK) return rc;
-  return run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, nullptr, workspace, opts, n_splits_out, nullptr,
-                     stream);
+  PartialRequest rq{cache, q, n_q_heads, seq_len};
+  rq.attn_scale = attn_scale;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  const int out_rc = run_partial(rq);
+  if (n_splits_out) *n_splits_out = rq.n_splits;
+  return out_rc;
 }
 
 int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits, const void* workspace,
@@ -295,12 +347,13 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
                         void* out, void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, void* stream) {
   int rc = check_decode(cache, q, n_q_heads, seq_len, out, workspace, workspace_bytes, opts, true);
   if (rc != TQ_OK) return rc;
-  int32_t n_splits = 0;
-  bool merged = false;
-  rc = run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, out, workspace, opts, &n_splits, &merged, stream);
-  if (rc != TQ_OK || merged) return rc;
-  return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
-                             stream);
+  PartialRequest rq{cache, q, n_q_heads, seq_len};
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  return finish_decode(rq, run_partial(rq));
 }
 
 int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, const void* v_new, const void* q,
@@ -310,41 +363,22 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   if (rc != TQ_OK) return rc;
   if (!k_new || !v_new) return TQ_ERR_NULL;
   if (!aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
-  int32_t n_splits = 0;
-  bool merged = false, appended = false;
-  // first find out (without launching) whether the decode kernel will take the token in itself
-  {
-    const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
-    if (!r.ok) return TQ_ERR_UNSUPPORTED;
-    appended = r.use_mfma && windowed(seq_len, opts) >= 2 &&
-               tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
-  }
-  if (!appended) {
+  const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+  if (!r.ok) return TQ_ERR_UNSUPPORTED;
+  PartialRequest rq{cache, q, n_q_heads, seq_len};
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  if (appends_in_kernel(cache, n_q_heads, seq_len, nullptr, r, opts)) {
+    rq.k_new = k_new;
+    rq.v_new = v_new;
+  } else {                                        // the append kernel first, then the plain decode
     rc = hip_rc(tq::launch_quantize(*cache, k_new, v_new, seq_len - 1, nullptr, 1, static_cast<hipStream_t>(stream)));
     if (rc != TQ_OK) return rc;
   }
-  rc = run_partial(cache, q, n_q_heads, seq_len, nullptr, attn_scale, out, workspace, opts, &n_splits, &merged, stream,
-                   nullptr, appended ? k_new : nullptr, appended ? v_new : nullptr);
-  if (rc != TQ_OK || merged) return rc;
-  return tq_sdpa_int4_reduce(cache->batch, n_q_heads, cache->head_dim, n_splits, workspace, workspace_bytes, out,
-                             stream);
-}
-
-// A pool of pages seen as a cache: `batch` sequences whose rows are pages of pool->capacity tokens.
-static int paged_view(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
-                      tq_kv_cache* view, tq::PagedView* pv) {
-  const int rc = check_cache(pool);
-  if (rc == TQ_ERR_NULL || !block_table) return TQ_ERR_NULL;
-  if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
-  const int pt = pool->capacity;
-  if (pt < tq::kTile || (pt & (pt - 1)) != 0 || batch < 1 || max_blocks < 1) return TQ_ERR_SHAPE;
-  if (rc == TQ_ERR_ALIGN || !aligned(block_table, 4)) return TQ_ERR_ALIGN;
-  *view = *pool;
-  view->batch = batch;
-  int shift = 0;
-  while ((1 << shift) < pt) ++shift;
-  *pv = tq::PagedView{block_table, max_blocks, shift, batch};
-  return TQ_OK;
+  return finish_decode(rq, run_partial(rq));
 }
 
 int tq_quantize_kv_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks, int32_t batch,
@@ -374,12 +408,15 @@ int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_tabl
   if (!seq_lens) return TQ_ERR_NULL;
   if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
   if (opts && opts->window > 0) return TQ_ERR_UNSUPPORTED;      // a window's first token need not start a supertile
-  bool merged = false;
-  DecodeParams p{};
-  rc = run_partial(&view, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, nullptr, &merged,
-                   stream, &p, nullptr, nullptr, nullptr, &pv);
-  if (rc != TQ_OK || merged) return rc;
-  return hip_rc(tq::launch_reduce(p, batch, view.head_dim, static_cast<hipStream_t>(stream)));
+  PartialRequest rq{&view, q, n_q_heads, max_seq_len};
+  rq.seq_lens = seq_lens;
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.paged = &pv;
+  rq.stream = stream;
+  return finish_decode(rq, run_partial(rq));
 }
 
 int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, const int32_t* seq_lens,
@@ -389,13 +426,14 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
   if (rc != TQ_OK) return rc;
   if (!seq_lens) return TQ_ERR_NULL;
   if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
-  bool merged = false;
-  DecodeParams p{};
-  rc = run_partial(cache, q, n_q_heads, max_seq_len, seq_lens, attn_scale, out, workspace, opts, nullptr, &merged,
-                   stream, &p);
-  if (rc != TQ_OK || merged) return rc;
-  // the merge works out from the same lengths which chunks exist for each sequence
-  return hip_rc(tq::launch_reduce(p, cache->batch, cache->head_dim, static_cast<hipStream_t>(stream)));
+  PartialRequest rq{cache, q, n_q_heads, max_seq_len};
+  rq.seq_lens = seq_lens;
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  return finish_decode(rq, run_partial(rq));       // the merge works out from the same lengths which chunks exist
 }
 
 int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
