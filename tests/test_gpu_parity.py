@@ -572,3 +572,33 @@ def test_paged_cache(shape, variant):
         one = [np.concatenate([a[b:b + 1, :, :n], a[b:b + 1, :, S:S + 1]], axis=2) for a in ocache]
         rows.append(oracle.attend_packed(np16(q[b:b + 1]), *one, seq_len=n + 1, alpha=w.attn_scale))
     assert_close(out, np.concatenate(rows, axis=0), f"{shape} paged append+attend variant={variant}")
+
+
+def test_many_sequences_with_their_own_lengths():
+    """More sequences than one round of blocks has chunks for: the device-side plan spreads them over
+    several rounds; contiguous rows and pages."""
+    B, Hkv, G, d = 40, 4, 8, 128
+    rng = np.random.default_rng(11)
+    lens = [int(x) for x in rng.integers(1, 700, B)]
+    lens[3], lens[17] = 1500, 1
+    S = max(lens)
+    w = wl.custom(batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=S, seed=98, outlier_channels=4)
+    q, k, v = make(w)
+    ocache = oracle_cache_from(k, v)
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    cache = gpu_cache_from(k, v)
+    for variant in (0, 1):
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, variant=variant)
+        torch.cuda.synchronize()
+        assert_close(out, ref, f"40 sequences, variant={variant}")
+    PT, max_blocks = 64, (S + 63) // 64
+    table = torch.from_numpy(rng.permutation(B * max_blocks).astype(np.int32).reshape(B, max_blocks)).cuda()
+    pool = tq.KVCache(B * max_blocks, Hkv, d, PT)
+    pad = max_blocks * PT - S
+    kp = torch.nn.functional.pad(k, (0, 0, 0, pad)).contiguous().cuda()
+    vp = torch.nn.functional.pad(v, (0, 0, 0, pad)).contiguous().cuda()
+    tq.tq_quantize_kv_paged(pool, table, kp, vp, torch.zeros(B, dtype=torch.int32, device="cuda"))
+    out = tq.tq_sdpa_int4_decode_paged(pool, table, q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "40 sequences, paged")
