@@ -36,7 +36,7 @@ enum {
   TQ_ERR_EMPTY = -3,       /* seq_len < 1 or n_new < 1                                          */
   TQ_ERR_CAPACITY = -4,    /* pos < 0, pos + n_new > capacity, or seq_len > capacity            */
   TQ_ERR_WORKSPACE = -5,   /* workspace / dense scratch smaller than the *_bytes() query says   */
-  TQ_ERR_UNSUPPORTED = -6, /* a shape or option the kernels do not cover (e.g. GQA ratio > 16)  */
+  TQ_ERR_UNSUPPORTED = -6, /* a shape or option the kernels do not cover (e.g. an unknown variant) */
   TQ_ERR_HIP = -7,         /* the HIP runtime reported an error at launch                       */
   TQ_ERR_ALIGN = -8        /* a data pointer is not 16-byte aligned (workspace: 256-byte)        */
 };

@@ -124,9 +124,11 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   if (variant == 2 && !offsets_ok) return {false, false, false};
   const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
                                          tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
-  const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, cache->n_kv_heads, windowed(seq_len, opts), cache->head_dim);
+  // (GQA groups larger than the kernel's tile: several blocks stream each KV head, counted as rows of their own)
+  const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, n_q_heads / cache->n_kv_heads) : 1);
+  const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, rows_per_batch, windowed(seq_len, opts), cache->head_dim);
   return {true, use_mfma,
-          use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, cache->n_kv_heads)};
+          use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, rows_per_batch)};
 }
 
 // One launch of phase 1: what to attend, and what came of it.
@@ -171,7 +173,9 @@ int run_partial(PartialRequest& rq) {
   const bool append = rq.k_new != nullptr && appends_in_kernel(cache, n_q_heads, seq_len, seq_lens, r, opts);
   const int first = seq_len - attended;           // first attended token
   if (append) --attended;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, attended, opts ? opts->n_splits : 0, target,
+  const int rows_per_batch =
+      cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, n_q_heads / cache->n_kv_heads) : 1);
+  const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
   DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan);
   p.seq_lens = seq_lens;
@@ -197,7 +201,7 @@ int run_partial(PartialRequest& rq) {
     // `target` chunks over all sequences of a KV head (a requested n_splits keeps the fixed chunking)
     // per KV head: r rounds of target / H_kv chunks, r the smallest count that leaves at least half of them
     // once every sequence has been granted its partial last chunk
-    const int per_round = std::max(1, (target + cache->n_kv_heads - 1) / cache->n_kv_heads);
+    const int per_round = std::max(1, (target + rows_per_batch - 1) / rows_per_batch);
     const int rounds = std::max(1, (2 * cache->batch + per_round - 1) / per_round);
     p.var_chunks = rounds * per_round;
     p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;

@@ -252,7 +252,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int c = lane & 15, kq = lane >> 4;
   const int hl = c % GP, rep = c / GP;            // head and group replica of this lane's column / row
   int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
-  const int kv = blockIdx.y;
+  const int kvv = blockIdx.y;                     // KV head x part of its query group (see kv_share)
+  const int kv = kvv / p.kv_share;                // the KV head whose rows are read
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
     if (!var_plan(p, blockIdx.x, vp)) return;
@@ -430,7 +431,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     for (int u = 0; u < GP * D * 2 / 1024; ++u) {
       const int chunk = u * 64 + lane;            // 16-byte chunk of the [GP][D] fp16 query block
       const int h = min(chunk / (D / 8), G - 1);
-      dma16_lane(p.q + (int64_t)(b * p.n_q_heads + kv * G + h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
+      dma16_lane(p.q + (int64_t)(b * p.n_q_heads + kvv * G + h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
     }
   }
   // A wave with work always has exactly NS stages out before its loop and issues one per supertile,
@@ -888,7 +889,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       num = fmaf(hat_v[j], e, num);
       den += e;
     }
-    const int64_t ph = (int64_t)(b * p.n_q_heads + kv * G + h) * part_stride + split;
+    const int64_t ph = (int64_t)(b * p.n_q_heads + kvv * G + h) * part_stride + split;
     // device-scope stores: they go through to where every compute die sees them (the L2 caches of
     // different dies are not coherent with each other), so no cache-wide write-back is needed later
     st_dev(p.part_o + ph * D + j, num);
@@ -905,7 +906,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   wait_loads<0>();                                // vmcnt counts stores too: this wave's partial has landed
   __syncthreads();                                // every wave's has; and nobody reads the block-merge area any more
   if (threadIdx.x == 0) {
-    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * p.n_kv_heads + kv];
+    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * (p.n_kv_heads * p.kv_share) + kvv];
     *is_last = atomicInc(ctr, (unsigned int)(n - 1)) == (unsigned int)(n - 1);   // wraps to 0 on the last arrival
   }
   __syncthreads();
@@ -913,7 +914,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float* const c_m = reinterpret_cast<float*>(smem) + 64;     // [G][n] chunk maxima, then chunk weights
   float* const c_l = c_m + GP * kMaxSplits;                    // [G][n] chunk sums
   float* const h_den = c_l + GP * kMaxSplits;                  // [G]
-  const int64_t head0 = (int64_t)b * p.n_q_heads + kv * G;
+  const int64_t head0 = (int64_t)b * p.n_q_heads + kvv * G;
   // Everything is asked for at once, so the merge is about one memory round trip long: the first 32
   // chunks of this thread's output elements (which do not need the weights yet) and the chunk maxima
   // and sums; the weights are worked out while the loads are in flight.
@@ -971,9 +972,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
 }
 
-int padded_gqa(int head_dim, int gqa) {
+int padded_gqa(int head_dim, int gqa) {           // columns a group of `gqa` heads takes in the tile; 0 = too many
   if (head_dim == 128) return gqa <= 4 ? 4 : (gqa <= 8 ? 8 : 0);
   return gqa <= 2 ? 2 : (gqa <= 4 ? 4 : 0);
+}
+int kv_share_of(int head_dim, int gqa) {          // smallest split of the group into equal parts that fit
+  if (gqa < 1 || (head_dim != 128 && head_dim != 256)) return 0;
+  const int cap = head_dim == 128 ? 8 : 4;
+  for (int share = (gqa + cap - 1) / cap; share <= gqa; ++share)
+    if (gqa % share == 0) return share;
+  return 0;
 }
 
 template <int D, int GP>
@@ -996,13 +1004,15 @@ hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-bool mfma_supported(int head_dim, int gqa) {
-  return (head_dim == 128 || head_dim == 256) && gqa >= 1 && padded_gqa(head_dim, gqa) != 0;
-}
+int mfma_kv_share(int head_dim, int gqa) { return kv_share_of(head_dim, gqa); }
+
+bool mfma_supported(int head_dim, int gqa) { return kv_share_of(head_dim, gqa) > 0; }
 
 bool mfma_can_merge(int batch, int n_kv_heads) { return (int64_t)batch * n_kv_heads <= kCountersPerSlot; }
 
 bool mfma_can_append(int head_dim, int gqa) {
+  const int share = kv_share_of(head_dim, gqa);
+  if (share != 1) return false;                   // (several blocks per KV head would all write the token)
   const int gp = padded_gqa(head_dim, gqa);
   if (head_dim == 128 && gp == 8) return Cfg<128, 8, 8>::QSEP;
   if (head_dim == 128 && gp == 4) return Cfg<128, 4, 8>::QSEP;
@@ -1015,12 +1025,16 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
                                hipStream_t s) {
   static std::atomic<unsigned int> next_slot{0};
   DecodeParams p = p_in;
+  p.kv_share = kv_share_of(head_dim, p.gqa);
+  if (p.kv_share < 1) return hipErrorNotSupported;
+  p.gqa /= p.kv_share;
+  const int rows_y = p.n_kv_heads * p.kv_share;
   p.merge_slot = -1;
   if (merge_in_kernel) {
-    if (!mfma_can_merge(batch, p.n_kv_heads) || p.out == nullptr) return hipErrorInvalidValue;
+    if (!mfma_can_merge(batch, rows_y) || p.out == nullptr) return hipErrorInvalidValue;
     p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
   }
-  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads, 1) : dim3(p.n_splits, p.n_kv_heads, batch);
+  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, rows_y, 1) : dim3(p.n_splits, rows_y, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);

@@ -31,6 +31,9 @@ struct DecodeParams {
   float* part_ml;           // [B][H_q][n_splits][2]   (running max in log2 units, sum of exp)
   half_t* out;              // [B][H_q][D]
   int32_t n_q_heads, n_kv_heads, gqa;
+  // Matrix-core kernel, GQA groups larger than its tile takes: kv_share blocks (blockIdx.y = kv * kv_share +
+  // part) stream the same KV head, each for gqa consecutive query heads (gqa then counts one block's heads).
+  int32_t kv_share;
   int32_t row_stride;       // tokens between consecutive (b, kv head) rows
   int32_t seq_len, n_splits, tokens_per_split;   // seq_len: every sequence's length, or the bound of seq_lens
   float scale_log2;         // attn_scale * log2(e)
@@ -153,6 +156,9 @@ hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_den
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);
 bool mfma_supported(int head_dim, int gqa);
+// How many blocks share the stream of one KV head for this GQA ratio (1 where the group fits one tile,
+// 0 = unsupported): the planner counts batch * n_kv_heads * share rows.
+int mfma_kv_share(int head_dim, int gqa);
 // With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
 bool mfma_can_merge(int batch, int n_kv_heads);
 bool mfma_can_append(int head_dim, int gqa);   // whether launch_partial_mfma honours k_new / v_new for this shape

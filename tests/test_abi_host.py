@@ -200,9 +200,9 @@ def test_decode_launch_count_query():
     generic = B.TqDecodeOptsStruct(0, 1)
     assert f(ctypes.byref(short), 64, 1024, 0.1, ctypes.byref(generic)) == 2
     assert f(ctypes.byref(short), 64, 1024, -0.1, None) == 2          # non-positive scale: generic kernel
-    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, None) == 2       # GQA ratio 16: no matrix-core tiling
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, None) == 1       # GQA ratio 16: two blocks per KV head
     forced = B.TqDecodeOptsStruct(0, 2)
-    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, ctypes.byref(forced)) == 0
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, ctypes.byref(forced)) == 1
     assert f(ctypes.byref(short), 64, 1024, -0.1, ctypes.byref(forced)) == 0
     assert f(ctypes.byref(short), 63, 1024, 0.1, None) == 0
     assert f(ctypes.byref(short), 64, 0, 0.1, None) == 0 and f(ctypes.byref(short), 64, 1025, 0.1, None) == 0

@@ -503,6 +503,36 @@ def test_append_decode_in_one_call(shape, variant):
         assert np.abs(a - b).max() <= 2.0 ** -9 * max(1.0, np.abs(b).max())   # same step through the two calls
 
 
+@pytest.mark.parametrize("variant", [0, 2])
+@pytest.mark.parametrize("shape", ["g16_d128_b2_kv2", "g12_d128", "g8_d256"])
+def test_gqa_groups_larger_than_the_matrix_core_tile(shape, variant):
+    """GQA ratios above the matrix-core kernel's tile (8 query heads at d=128, 4 at d=256): several blocks
+    stream each KV head, each with its share of the group; plain decode (merged in the kernel or by the
+    reduce launch), sliding window, per-sequence lengths and the one-call step all take that path."""
+    shapes = dict(g16_d128_b2_kv2=dict(batch=2, n_q_heads=32, n_kv_heads=2, head_dim=128, outlier_channels=4),
+                  g12_d128=dict(n_q_heads=12, n_kv_heads=1, head_dim=128),
+                  g8_d256=dict(batch=2, n_q_heads=24, n_kv_heads=3, head_dim=256, attn_scale=1.0, qk_std=0.1))
+    for S, window, n_splits in ((1, 0, 0), (33, 0, 0), (700, 0, 5), (4133, 0, 0), (4133, 900, 0), (20000, 0, 0)):
+        w = wl.custom(seq_len=S, seed=960 + S, **shapes[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k[:, :, :S - 1], v[:, :, :S - 1], capacity=S + 3) if S > 1 else \
+            tq.KVCache(w.batch, w.n_kv_heads, w.head_dim, S + 3)
+        kn, vn = k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda()
+        out = tq.tq_sdpa_int4_append_decode(cache, kn, vn, q.cuda(), S, w.attn_scale, variant=variant, window=window,
+                                            n_splits=n_splits)
+        torch.cuda.synchronize()
+        ocache = oracle_cache_from(k, v)
+        assert_cache_bit_exact(cache, ocache, S)
+        ref = _oracle_window(q, ocache, [S] * w.batch, window if window > 0 else S, w.attn_scale)
+        assert_close(out, ref, f"{shape} S={S} window={window} variant={variant}")
+        lens = [max(1, S - 13 * b) for b in range(w.batch)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S,
+                                            w.attn_scale, variant=variant, window=window)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_window(q, ocache, lens, window if window > 0 else S, w.attn_scale),
+                     f"{shape} per-sequence lengths S={S} window={window} variant={variant}")
+
+
 # ---------------------------------------------------------------- paged cache
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
