@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--window", type=int, default=0, help="sliding window: attend only the last N tokens (0 = all)")
+    ap.add_argument("--n-queries", type=int, default=1,
+                    help="query tokens per sequence and step (2..8: the step appends that many tokens and attends "
+                         "them causally, as in speculative verification; fixed-length workloads)")
     ap.add_argument("--two-calls", action="store_true",
                     help="time the step as tq_quantize_kv + tq_sdpa_int4_decode instead of tq_sdpa_int4_append_decode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
@@ -222,7 +225,11 @@ def main():
         lens[0] = S                               # the bound is attained
         lens_dev, pos_dev = lens.to(dev), (lens - 1).to(dev)
 
-    # ---- resident inputs: `buffers` caches, each pre-filled with S-1 tokens; the step appends token S-1
+    NQ = args.n_queries
+    if NQ > 1 and (lens is not None or args.window > 0):
+        sys.exit("bench.py: --n-queries is offered for the fixed-length workloads without a window")
+
+    # ---- resident inputs: `buffers` caches, each pre-filled with S-NQ tokens; the step appends the last NQ
     caches, qs, news = [], [], []
     for i in range(args.buffers):
         wi = wl.Workload(**{**w.__dict__, "seed": w.seed + 7777 * i})
@@ -236,14 +243,14 @@ def main():
                                     torch.zeros(B, dtype=torch.int32, device=dev))
         else:
             c = tq.KVCache(B, Hkv, d, S)
-            tq.tq_quantize_kv(c, k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(), 0)
-        news.append((k[:, :, S - 1:].contiguous(), v[:, :, S - 1:].contiguous()))
+            tq.tq_quantize_kv(c, k[:, :, :S - NQ].contiguous(), v[:, :, :S - NQ].contiguous(), 0)
+        news.append((k[:, :, S - NQ:].contiguous(), v[:, :, S - NQ:].contiguous()))
         caches.append(c)
-        qs.append(q)
+        qs.append(q if NQ == 1 else wl.make_queries(wi, NQ, device=dev))
         del k, v
     torch.cuda.synchronize()
-    ws = torch.empty(tq.tq_workspace_bytes(B, Hq, d), dtype=torch.uint8, device=dev)
-    out = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
+    ws = torch.empty(tq.tq_workspace_bytes(B * NQ, Hq, d), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(qs[0])
     packed_bytes = w.packed_bytes if lens is None else int(lens.sum()) * Hkv * (w.packed_bytes // (B * Hkv * S))
     kw = dict(n_splits=args.n_splits, variant=args.variant)
     if args.window > 0:                           # sliding window: only the attended tokens are streamed
@@ -254,7 +261,7 @@ def main():
 
     def append(j):                                # the step's new token goes to the end of every sequence
         if lens is None:
-            tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - 1)
+            tq.tq_quantize_kv(caches[j], news[j][0], news[j][1], S - NQ)
         elif paged:
             tq.tq_quantize_kv_paged(caches[j], caches[j].table, news[j][0], news[j][1], pos_dev)
         else:
@@ -298,7 +305,7 @@ def main():
     # ---- dominant kernel: stream events around each of its launches.  Where the decode call is ONE
     #      launch (partials and chunk merge in the same kernel) that launch is timed; otherwise phase 1,
     #      the partial kernel, which tq_sdpa_int4_partial launches on its own.
-    fused = (not paged) and tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, **kw) == 1
+    fused = (not paged) and tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, n_queries=NQ, **kw) == 1
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     n_splits = 0 if paged else tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
     lo = max(0, S - args.window) if args.window > 0 else 0     # first attended token
@@ -316,7 +323,7 @@ def main():
         dominant(j)
         evs[i][1].record()
         if not fused and lens is None:
-            tq.tq_sdpa_int4_reduce(B, Hq, d, n_splits, ws, out)
+            tq.tq_sdpa_int4_reduce(B * NQ, Hq, d, n_splits, ws, out)
     torch.cuda.synchronize()
     k_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
     kernel_us_bracketed = statistics.fmean(k_us)
@@ -342,7 +349,7 @@ def main():
 
     # ---- unfused comparator on the same inputs
     baseline = None
-    if not args.no_baseline and lens is None:
+    if not args.no_baseline and lens is None and NQ == 1:
         dense = torch.empty(tq.tq_dense_scratch_bytes(B, Hkv, S, d), dtype=torch.uint8, device=dev)
         nb = max(3, min(20, args.steps // 10))
         for i in range(2):
@@ -374,12 +381,18 @@ def main():
     if not args.no_cpu or not args.no_check:
         import oracle
         q0, k0, v0 = wl.make_inputs(w, device="cpu")           # the named workload's own bits
+        if NQ > 1:
+            q0 = wl.make_queries(w, NQ, device="cpu")
         kc, ks, kz = oracle.quantize(k0.numpy())
         vc, vs, vz = oracle.quantize(v0.numpy())
         threads = oracle.default_threads()
         reps, times = 3, []
         ref = None
         def oracle_attend():
+            if NQ > 1:                            # query token t attends the first S - (NQ - 1 - t) tokens
+                rows = [oracle.attend_packed(q0.numpy()[:, t], kc, ks, kz, vc, vs, vz, seq_len=S - (NQ - 1 - t),
+                                             alpha=w.attn_scale, nthreads=threads) for t in range(NQ)]
+                return np.stack(rows, axis=1)
             if lens is None:
                 return oracle.attend_packed(q0.numpy(), *[a[:, :, lo:] for a in (kc, ks, kz, vc, vs, vz)], seq_len=S - lo,
                                             alpha=w.attn_scale, nthreads=threads)
@@ -428,7 +441,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
-                   "n_splits": n_splits, "variant": args.variant, "window": args.window,
+                   "n_splits": n_splits, "variant": args.variant, "window": args.window, "n_queries": NQ,
                    "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
                                   "tq_quantize_kv_paged + tq_sdpa_int4_decode_paged" if paged else
                                   "tq_quantize_kv_varlen + tq_sdpa_int4_decode_varlen" if lens is not None else

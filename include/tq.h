@@ -73,6 +73,18 @@ typedef struct tq_decode_opts {
   int32_t window;    /* sliding-window attention (the Gemma local layers of Appendix A): > 0 = every
                         sequence attends only its last `window` tokens, [len - window, len); 0 = all.
                         tq_dequant_then_attend does not offer it (UNSUPPORTED).                  */
+  int32_t n_queries; /* query tokens per sequence, 0 or 1 = one (the decode step of Sec. 3.3, S_q = 1).
+                        2..8 = a short run of new tokens (speculative verification, a chunk of prefill),
+                        which Sec. 3.3 sends to the unfused path and this library attends in the fused
+                        kernel: the queries are the LAST n_queries tokens of the sequence (already in the
+                        cache, or appended by the call) and causal among themselves, i.e. query t attends
+                        tokens [0, len - (n_queries - 1 - t)).  q and out are then fp16
+                        [batch][n_queries][n_q_heads][head_dim]; size the workspace with
+                        tq_workspace_bytes(batch * n_queries, ...) and pass batch * n_queries as `batch`
+                        to tq_sdpa_int4_reduce; k_new / v_new of tq_sdpa_int4_append_decode are
+                        [batch][n_kv_heads][n_queries][head_dim].  Every sequence length must be at least
+                        n_queries.  Matrix-core kernel only (variant 1, attn_scale <= 0, a window, and
+                        tq_dequant_then_attend answer UNSUPPORTED).                               */
 } tq_decode_opts;
 
 /* Quantise and append (Sec. 2.1, Eq. 2-3; "quantize -> store" arm of Sec. 3.3).

@@ -24,7 +24,8 @@ class TqKvCacheStruct(ctypes.Structure):
 
 
 class TqDecodeOptsStruct(ctypes.Structure):
-    _fields_ = [("n_splits", ctypes.c_int32), ("variant", ctypes.c_int32), ("window", ctypes.c_int32)]
+    _fields_ = [("n_splits", ctypes.c_int32), ("variant", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("n_queries", ctypes.c_int32)]
 
 
 class TqError(RuntimeError):
@@ -101,10 +102,10 @@ def tq_plan_splits(batch: int, n_kv_heads: int, seq_len: int) -> int:
 
 
 def tq_decode_launches(cache: "KVCache", n_q_heads: int, seq_len: int, attn_scale: float, n_splits: int = 0,
-                       variant: int = 0, window: int = 0) -> int:
+                       variant: int = 0, window: int = 0, n_queries: int = 1) -> int:
     """Kernel launches one tq_sdpa_int4_decode call makes for this configuration (1 or 2; 0 = invalid)."""
     return int(raw().tq_decode_launches(ctypes.byref(cache.struct), int(n_q_heads), int(seq_len), float(attn_scale),
-                                        _opts(n_splits, variant, window)))
+                                        _opts(n_splits, variant, window, n_queries)))
 
 
 class KVCache:
@@ -136,10 +137,17 @@ def _stream_ptr(stream) -> int:
     return s.cuda_stream
 
 
-def _opts(n_splits: int, variant: int, window: int = 0):
-    if not n_splits and not variant and not window:
+def _opts(n_splits: int, variant: int, window: int = 0, n_queries: int = 1):
+    if not n_splits and not variant and not window and n_queries <= 1:
         return None
-    return ctypes.byref(TqDecodeOptsStruct(int(n_splits), int(variant), int(window)))
+    return ctypes.byref(TqDecodeOptsStruct(int(n_splits), int(variant), int(window), int(n_queries)))
+
+
+def _queries(q: torch.Tensor):
+    """q is [B, H_q, d] (one query token per sequence) or [B, n_queries, H_q, d] -> (n_queries, H_q)."""
+    if q.dim() == 4:
+        return int(q.shape[1]), int(q.shape[2])
+    return 1, int(q.shape[1])
 
 
 def _check(rc: int, where: str):
@@ -164,8 +172,8 @@ def tq_quantize_kv(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, pos
     _check(rc, "tq_quantize_kv")
 
 
-def _workspace_for(cache: KVCache, n_q_heads: int, workspace):
-    need = tq_workspace_bytes(cache.batch, n_q_heads, cache.head_dim)
+def _workspace_for(cache: KVCache, n_q_heads: int, workspace, n_queries: int = 1):
+    need = tq_workspace_bytes(cache.batch * n_queries, n_q_heads, cache.head_dim)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=cache.k_codes.device)
     return workspace, workspace.numel() * workspace.element_size()
@@ -173,14 +181,16 @@ def _workspace_for(cache: KVCache, n_q_heads: int, workspace):
 
 def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,
                         workspace=None, n_splits: int = 0, variant: int = 0, stream=None, window: int = 0) -> torch.Tensor:
-    """q: fp16 [B, H_q, d] -> out fp16 [B, H_q, d]."""
+    """q: fp16 [B, H_q, d] -> out fp16 [B, H_q, d]; or q [B, n_queries, H_q, d] = the sequence's last
+    n_queries tokens, causal among themselves -> out of the same shape."""
     _need(q, torch.float16, "q")
     if out is None:
         out = torch.empty_like(q)
-    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
-    rc = raw().tq_sdpa_int4_decode(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
+    nq, hq = _queries(q)
+    workspace, wbytes = _workspace_for(cache, hq, workspace, nq)
+    rc = raw().tq_sdpa_int4_decode(ctypes.byref(cache.struct), q.data_ptr(), hq, int(seq_len),
                                    float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
-                                   _opts(n_splits, variant, window), _stream_ptr(stream))
+                                   _opts(n_splits, variant, window, nq), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode")
     return out
 
@@ -188,18 +198,20 @@ def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scal
 def tq_sdpa_int4_append_decode(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, seq_len: int,
                                attn_scale: float, out=None, workspace=None, n_splits: int = 0, variant: int = 0,
                                stream=None, window: int = 0) -> torch.Tensor:
-    """One decode step: k_new, v_new fp16 [B, H_kv, 1, d] are written at seq_len - 1, then q attends seq_len tokens."""
+    """One decode step: k_new, v_new fp16 [B, H_kv, n_queries, d] are written at the end of the seq_len tokens,
+    then q ([B, H_q, d], or [B, n_queries, H_q, d]) attends them."""
     _need(q, torch.float16, "q")
     _need(k_new, torch.float16, "k_new")
     _need(v_new, torch.float16, "v_new")
-    if k_new.shape != v_new.shape or tuple(k_new.shape) != (cache.batch, cache.n_kv_heads, 1, cache.head_dim):
-        raise ValueError("k_new/v_new must be [batch, n_kv_heads, 1, head_dim]")
+    nq, hq = _queries(q)
+    if k_new.shape != v_new.shape or tuple(k_new.shape) != (cache.batch, cache.n_kv_heads, nq, cache.head_dim):
+        raise ValueError("k_new/v_new must be [batch, n_kv_heads, n_queries, head_dim]")
     if out is None:
         out = torch.empty_like(q)
-    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
+    workspace, wbytes = _workspace_for(cache, hq, workspace, nq)
     rc = raw().tq_sdpa_int4_append_decode(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(),
-                                          int(q.shape[1]), int(seq_len), float(attn_scale), out.data_ptr(),
-                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window),
+                                          hq, int(seq_len), float(attn_scale), out.data_ptr(),
+                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window, nq),
                                           _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_append_decode")
     return out
@@ -208,15 +220,16 @@ def tq_sdpa_int4_append_decode(cache: KVCache, k_new: torch.Tensor, v_new: torch
 def tq_sdpa_int4_decode_varlen(cache: KVCache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
                                attn_scale: float, out=None, workspace=None, n_splits: int = 0, variant: int = 0,
                                stream=None, window: int = 0) -> torch.Tensor:
-    """q: fp16 [B, H_q, d]; seq_lens: int32 device tensor [B] -> out fp16 [B, H_q, d]."""
+    """q: fp16 [B, H_q, d] or [B, n_queries, H_q, d]; seq_lens: int32 device tensor [B] -> out like q."""
     _need(q, torch.float16, "q")
     _need(seq_lens, torch.int32, "seq_lens")
     if out is None:
         out = torch.empty_like(q)
-    workspace, wbytes = _workspace_for(cache, q.shape[1], workspace)
-    rc = raw().tq_sdpa_int4_decode_varlen(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]),
+    nq, hq = _queries(q)
+    workspace, wbytes = _workspace_for(cache, hq, workspace, nq)
+    rc = raw().tq_sdpa_int4_decode_varlen(ctypes.byref(cache.struct), q.data_ptr(), hq,
                                           seq_lens.data_ptr(), int(max_seq_len), float(attn_scale), out.data_ptr(),
-                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window),
+                                          workspace.data_ptr(), wbytes, _opts(n_splits, variant, window, nq),
                                           _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode_varlen")
     return out
@@ -250,19 +263,21 @@ def tq_quantize_kv_paged(pool: KVCache, block_table: torch.Tensor, k_new: torch.
 def tq_sdpa_int4_decode_paged(pool: KVCache, block_table: torch.Tensor, q: torch.Tensor, seq_lens: torch.Tensor,
                               max_seq_len: int, attn_scale: float, out=None, workspace=None, n_splits: int = 0,
                               variant: int = 0, stream=None) -> torch.Tensor:
-    """q: fp16 [B, H_q, d]; block_table int32 [B, max_blocks] and seq_lens int32 [B] on the device."""
+    """q: fp16 [B, H_q, d] or [B, n_queries, H_q, d]; block_table int32 [B, max_blocks] and seq_lens int32 [B]
+    on the device."""
     _need(q, torch.float16, "q")
     _need(seq_lens, torch.int32, "seq_lens")
     _need(block_table, torch.int32, "block_table")
     if out is None:
         out = torch.empty_like(q)
-    need = tq_workspace_bytes(int(q.shape[0]), int(q.shape[1]), pool.head_dim)
+    nq, hq = _queries(q)
+    need = tq_workspace_bytes(int(q.shape[0]) * nq, hq, pool.head_dim)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     rc = raw().tq_sdpa_int4_decode_paged(ctypes.byref(pool.struct), block_table.data_ptr(), int(block_table.shape[1]),
-                                         int(q.shape[0]), q.data_ptr(), int(q.shape[1]), seq_lens.data_ptr(),
+                                         int(q.shape[0]), q.data_ptr(), hq, seq_lens.data_ptr(),
                                          int(max_seq_len), float(attn_scale), out.data_ptr(), workspace.data_ptr(),
-                                         workspace.numel() * workspace.element_size(), _opts(n_splits, variant),
+                                         workspace.numel() * workspace.element_size(), _opts(n_splits, variant, 0, nq),
                                          _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode_paged")
     return out
@@ -273,9 +288,10 @@ def tq_sdpa_int4_partial(cache: KVCache, q: torch.Tensor, seq_len: int, attn_sca
     """Phase 1 only; returns the number of chunks written into workspace."""
     _need(q, torch.float16, "q")
     n = ctypes.c_int32(0)
-    rc = raw().tq_sdpa_int4_partial(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
+    nq, hq = _queries(q)
+    rc = raw().tq_sdpa_int4_partial(ctypes.byref(cache.struct), q.data_ptr(), hq, int(seq_len),
                                     float(attn_scale), workspace.data_ptr(),
-                                    workspace.numel() * workspace.element_size(), _opts(n_splits, variant, window),
+                                    workspace.numel() * workspace.element_size(), _opts(n_splits, variant, window, nq),
                                     ctypes.byref(n), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_partial")
     return n.value

@@ -54,6 +54,13 @@ Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int targ
   return p;
 }
 
+// query tokens per sequence the options ask for
+int queries_of(const tq_decode_opts* opts) { return (opts && opts->n_queries > 1) ? opts->n_queries : 1; }
+// query rows that share one KV head
+int rows_of(const tq_kv_cache* c, int n_q_heads, const tq_decode_opts* opts) {
+  return n_q_heads / c->n_kv_heads * queries_of(opts);
+}
+
 // `room`: tokens a sequence can hold (the cache's capacity, or max_blocks pages of a paged pool)
 int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len, const void* out,
                  const void* workspace, size_t workspace_bytes, const tq_decode_opts* opts, bool need_out,
@@ -63,20 +70,23 @@ int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len
   if (!q || (need_out && !out) || !workspace) return TQ_ERR_NULL;
   if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return rc;
   if (n_q_heads < 1 || n_q_heads % c->n_kv_heads != 0) return TQ_ERR_SHAPE;
-  if (seq_len < 1) return TQ_ERR_EMPTY;
+  if (seq_len < queries_of(opts)) return TQ_ERR_EMPTY;   // (every query token is one of the sequence's tokens)
   if (seq_len > (room >= 0 ? room : (int64_t)c->capacity)) return TQ_ERR_CAPACITY;
   if (rc == TQ_ERR_ALIGN) return rc;
   if (!aligned(q, 16) || (need_out && !aligned(out, 16)) || !aligned(workspace, 256)) return TQ_ERR_ALIGN;
-  if (workspace_bytes < tq_workspace_bytes(c->batch, n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
   if (opts) {
     if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0 || opts->window < 0) return TQ_ERR_UNSUPPORTED;
-    if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, n_q_heads / c->n_kv_heads)) return TQ_ERR_UNSUPPORTED;
+    if (opts->n_queries < 0 || opts->n_queries > tq::kMaxQueries) return TQ_ERR_UNSUPPORTED;
+    // several query tokens: matrix-core kernel only, and every row attends from the sequence's first token
+    if (opts->n_queries > 1 && (opts->variant == 1 || opts->window > 0)) return TQ_ERR_UNSUPPORTED;
+    if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, rows_of(c, n_q_heads, opts))) return TQ_ERR_UNSUPPORTED;
   }
+  if (workspace_bytes < tq_workspace_bytes(c->batch * queries_of(opts), n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
   return TQ_OK;
 }
 
 DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len, float attn_scale,
-                         void* out, void* workspace, const Plan& plan) {
+                         void* out, void* workspace, const Plan& plan, int n_queries = 1) {
   DecodeParams p{};
   p.k_codes = static_cast<const uint8_t*>(c->k_codes);
   p.v_codes = static_cast<const uint8_t*>(c->v_codes);
@@ -87,8 +97,9 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
   p.q = static_cast<const half_t*>(q);
   p.out = static_cast<half_t*>(out);
   p.part_o = static_cast<float*>(workspace);
-  p.part_ml = p.part_o + tq::workspace_o_floats(c->batch, n_q_heads, c->head_dim);
+  p.part_ml = p.part_o + tq::workspace_o_floats(c->batch * n_queries, n_q_heads, c->head_dim);
   p.n_q_heads = n_q_heads;
+  p.n_queries = n_queries;
   p.n_kv_heads = c->n_kv_heads;
   p.gqa = n_q_heads / c->n_kv_heads;
   p.row_stride = c->capacity;
@@ -122,10 +133,12 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   // the matrix-core kernel addresses a (batch, KV head) row of codes with 32-bit byte offsets
   const bool offsets_ok = (int64_t)seq_len * (cache->head_dim / 2) < (1ll << 31);
   if (variant == 2 && !offsets_ok) return {false, false, false};
+  const int rows = rows_of(cache, n_q_heads, opts);
   const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
-                                         tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads));
-  // (GQA groups larger than the kernel's tile: several blocks stream each KV head, counted as rows of their own)
-  const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, n_q_heads / cache->n_kv_heads) : 1);
+                                         tq::mfma_supported(cache->head_dim, rows));
+  if (!use_mfma && queries_of(opts) > 1) return {false, false, false};
+  // (more query rows than the kernel's tile holds: several blocks stream each KV head, counted as rows of their own)
+  const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, rows) : 1);
   const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, rows_per_batch, windowed(seq_len, opts), cache->head_dim);
   return {true, use_mfma,
           use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, rows_per_batch)};
@@ -154,7 +167,7 @@ struct PartialRequest {
 // Whether the decode kernel takes the step's new token in itself (else the append kernel runs first).
 bool appends_in_kernel(const tq_kv_cache* cache, int n_q_heads, int seq_len, const int32_t* seq_lens, const Route& r,
                        const tq_decode_opts* opts) {
-  return r.use_mfma && !seq_lens && windowed(seq_len, opts) >= 2 &&
+  return r.use_mfma && !seq_lens && windowed(seq_len, opts) >= 2 && queries_of(opts) == 1 &&
          tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
 }
 
@@ -174,10 +187,11 @@ int run_partial(PartialRequest& rq) {
   const int first = seq_len - attended;           // first attended token
   if (append) --attended;
   const int rows_per_batch =
-      cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, n_q_heads / cache->n_kv_heads) : 1);
+      cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : 1);
   const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
                                 use_mfma ? 8 : 1);
-  DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan);
+  DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan,
+                               queries_of(opts));
   p.seq_lens = seq_lens;
   p.batch = cache->batch;
   if (seq_lens) {
@@ -270,7 +284,8 @@ int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t 
   if (rc != TQ_OK && rc != TQ_ERR_ALIGN) return 0;
   if (n_q_heads < 1 || n_q_heads % cache->n_kv_heads != 0 || seq_len < 1 || seq_len > cache->capacity) return 0;
   if (opts && (opts->variant < 0 || opts->variant > 2)) return 0;
-  if (opts && opts->variant == 2 && !tq::mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads)) return 0;
+  if (opts && (opts->n_queries < 0 || opts->n_queries > tq::kMaxQueries || seq_len < queries_of(opts))) return 0;
+  if (opts && opts->variant == 2 && !tq::mfma_supported(cache->head_dim, rows_of(cache, n_q_heads, opts))) return 0;
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return 0;
   return r.merge ? 1 : 2;
@@ -379,7 +394,9 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {                                        // the append kernel first, then the plain decode
-    rc = hip_rc(tq::launch_quantize(*cache, k_new, v_new, seq_len - 1, nullptr, 1, static_cast<hipStream_t>(stream)));
+    const int n_new = queries_of(opts);
+    rc = hip_rc(tq::launch_quantize(*cache, k_new, v_new, seq_len - n_new, nullptr, n_new,
+                                    static_cast<hipStream_t>(stream)));
     if (rc != TQ_OK) return rc;
   }
   return finish_decode(rq, run_partial(rq));
@@ -449,7 +466,7 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
   if (!aligned(dense_scratch, 16)) return TQ_ERR_ALIGN;
   const size_t need = tq_dense_scratch_bytes(cache->batch, cache->n_kv_heads, seq_len, cache->head_dim);
   if (dense_scratch_bytes < need) return TQ_ERR_WORKSPACE;
-  if (opts && opts->window > 0) return TQ_ERR_UNSUPPORTED;
+  if (opts && (opts->window > 0 || opts->n_queries > 1)) return TQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   half_t* k_dense = static_cast<half_t*>(dense_scratch);
   half_t* v_dense = k_dense + need / sizeof(half_t) / 2;

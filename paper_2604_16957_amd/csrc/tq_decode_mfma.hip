@@ -263,6 +263,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     part_stride = kMaxSplits;
   }
   const int G = p.gqa;
+  // Several query tokens per sequence (they are the sequence's last NQ tokens and causal among themselves):
+  // a KV head then has NQ * GF query rows, row r = t * GF + g for query token t and head g of the group,
+  // cut into kv_share parts of G rows; this block holds rows part * G .. part * G + G - 1.
+  const int NQ = p.n_queries, GF = p.gqa_full;
+  const int part = kvv - kv * p.kv_share;
+  auto query_token = [&](int h) { return NQ > 1 ? min(part * G + h, NQ * GF - 1) / GF : 0; };
+  auto query_row = [&](int h) -> int64_t {        // row of q / out / the partials that tile row h stands for
+    const int r = part * G + h, t = query_token(h);
+    return (int64_t)(b * NQ + t) * p.n_q_heads + kv * GF + (r - t * GF);
+  };
 
   char* const ring = smem + wave * (NS * C::STAGE);
   const uint32_t ring_lds =
@@ -283,9 +293,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // goes through and publishes an empty partial.)
   if (begin >= seq && p.merge_slot < 0) return;
   const int end = max(begin, min(seq, begin + tokens_per_split));
-  const int n_full = (end - begin) >> 5;          // whole 32-token supertiles of this chunk
-  const bool has_tail = ((end - begin) & 31) != 0;  // only the sequence's last supertile can be ragged
+  // `seq` is what the last query token attends; query token t attends NQ - 1 - t tokens fewer.  Supertiles
+  // that every row attends in full take the fast path; the sequence's last one or two (ragged, or holding
+  // tokens some rows must not see) take the masked path.
+  const int n_full = max(0, min(end, seq - (NQ - 1)) - begin) >> 5;
+  const int n_tail = ((end - begin + 31) >> 5) - n_full;   // 0, 1 or 2 (NQ <= 8)
   const int last_tok = seq - 1;
+  const int end_col = min(end, seq - (NQ - 1 - query_token(hl)));   // first token this lane's column must not see
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
   const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),
@@ -403,7 +417,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
   };
   const int n_mine = count_of(n_full);
-  const bool tail_mine = has_tail && count_of(n_full + 1) != n_mine;
+  bool tail_mine[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
 
   // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
@@ -431,7 +447,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     for (int u = 0; u < GP * D * 2 / 1024; ++u) {
       const int chunk = u * 64 + lane;            // 16-byte chunk of the [GP][D] fp16 query block
       const int h = min(chunk / (D / 8), G - 1);
-      dma16_lane(p.q + (int64_t)(b * p.n_q_heads + kvv * G + h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
+      dma16_lane(p.q + query_row(h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
     }
   }
   // A wave with work always has exactly NS stages out before its loop and issues one per supertile,
@@ -664,7 +680,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         if constexpr (GR >= 8) x = row_ror_add<2>(x);
         if constexpr (TAIL) {
           const int tok = begin + sidx * 32 + 16 * t + tok_of_row(4 * kq + i);
-          x = (tok < end) ? x : -INFINITY;
+          x = (tok < end_col) ? x : -INFINITY;
         }
         sc[t][i] = x;
       }
@@ -705,7 +721,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
             for (int i = 0; i < 4; ++i) oacc[cs][m][a][i] *= fr[i];
     }
-    const float mk = m_run * kappa;
+    const float mk = fmaxf(m_run * kappa, -3.0e38f);         // (finite also for a column that has seen no token yet)
     float pr[2][4];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -815,14 +831,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     slot = next;
   }
   wait_loads<0>();                                           // phantom stages included: the rings are quiet
-  if (tail_mine) {                                           // the ragged last supertile of the sequence
+#pragma unroll 1
+  for (int u = 0; u < 2; ++u) {                              // the masked last supertile(s) of the sequence
+    if (!tail_mine[u]) continue;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    issue_tail(0, n_full);
+    issue_tail(0, n_full + u);
     wait_loads<0>();
     load_k(0, kr);
     load_v(0, vr);
     float sc[2][4];
-    scores(kr, n_full, std::true_type{}, sc);
+    scores(kr, n_full + u, std::true_type{}, sc);
     half8v pa[NA];
     softmax(sc, vr, pa);
     pv(vr, pa);
@@ -837,10 +855,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
   float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
   if constexpr (C::ALIAS) __syncthreads();                   // everybody is done reading the rings
-  const bool active = n_mine > 0 || tail_mine;
+  const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1];
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
-    lds_m[wave * GP + hl] = active ? m_run * kappa : kNegBig;
+    // (a row whose tokens were all masked still has the initial reference: it counts as empty)
+    lds_m[wave * GP + hl] = (active && m_run > kNegBig) ? m_run * kappa : kNegBig;
     lds_l[wave * GP + hl] = active ? l_tot : 0.0f;
   }
 #pragma unroll
@@ -889,7 +908,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       num = fmaf(hat_v[j], e, num);
       den += e;
     }
-    const int64_t ph = (int64_t)(b * p.n_q_heads + kvv * G + h) * part_stride + split;
+    const int64_t ph = query_row(h) * part_stride + split;
     // device-scope stores: they go through to where every compute die sees them (the L2 caches of
     // different dies are not coherent with each other), so no cache-wide write-back is needed later
     st_dev(p.part_o + ph * D + j, num);
@@ -914,7 +933,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float* const c_m = reinterpret_cast<float*>(smem) + 64;     // [G][n] chunk maxima, then chunk weights
   float* const c_l = c_m + GP * kMaxSplits;                    // [G][n] chunk sums
   float* const h_den = c_l + GP * kMaxSplits;                  // [G]
-  const int64_t head0 = (int64_t)b * p.n_q_heads + kvv * G;
   // Everything is asked for at once, so the merge is about one memory round trip long: the first 32
   // chunks of this thread's output elements (which do not need the weights yet) and the chunk maxima
   // and sums; the weights are worked out while the loads are in flight.
@@ -924,12 +942,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int idx = threadIdx.x + e * NW * 64, h = idx / D, j = idx % D;
-    const float* src = p.part_o + (head0 + (h < G ? h : 0)) * n * D + j;
+    const float* src = p.part_o + query_row(h < G ? h : 0) * n * D + j;
 #pragma unroll
     for (int u = 0; u < FIRST; ++u) pre[e][u] = ld_dev(src + (int64_t)(u < n ? u : n - 1) * D);
   }
   for (int idx = threadIdx.x; idx < G * n; idx += NW * 64) {
-    const float* ml = p.part_ml + (head0 * n + idx) * 2;                 // [h][c] is contiguous
+    const float* ml = p.part_ml + (query_row(idx / n) * n + idx % n) * 2;
     c_m[(idx / n) * kMaxSplits + idx % n] = ld_dev(ml);
     c_l[(idx / n) * kMaxSplits + idx % n] = ld_dev(ml + 1);
   }
@@ -954,7 +972,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   for (int e = 0; e < PER; ++e) {
     const int idx = threadIdx.x + e * NW * 64, h = idx / D, j = idx % D;
     if (h >= G) continue;
-    const float* src = p.part_o + (head0 + h) * n * D + j;
+    const int64_t row = query_row(h);
+    const float* src = p.part_o + row * n * D + j;
     const float* w = c_m + h * kMaxSplits;
     float num = 0.0f;
 #pragma unroll
@@ -968,17 +987,19 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       for (int u = 0; u < 8; ++u) num = fmaf(v[u], w[cc + u], num);
     }
     for (; cc < n; ++cc) num = fmaf(ld_dev(src + (int64_t)cc * D), w[cc], num);
-    p.out[(head0 + h) * D + j] = (half_t)(num / h_den[h]);
+    p.out[row * D + j] = (half_t)(num / h_den[h]);
   }
 }
 
 int padded_gqa(int head_dim, int gqa) {           // columns a group of `gqa` heads takes in the tile; 0 = too many
   if (head_dim == 128) return gqa <= 4 ? 4 : (gqa <= 8 ? 8 : 0);
-  return gqa <= 2 ? 2 : (gqa <= 4 ? 4 : 0);
+  return gqa <= 2 ? 2 : 0;
 }
 int kv_share_of(int head_dim, int gqa) {          // smallest split of the group into equal parts that fit
   if (gqa < 1 || (head_dim != 128 && head_dim != 256)) return 0;
-  const int cap = head_dim == 128 ? 8 : 4;
+  // d=256: a tile of 4 rows needs more registers than a lane has (its loop spills), and two blocks of 2 rows
+  // that stream the same KV head are faster than one of 4 (measured: 52.9 us against 69.0 us at 64/16 heads, 32K)
+  const int cap = head_dim == 128 ? 8 : 2;
   for (int share = (gqa + cap - 1) / cap; share <= gqa; ++share)
     if (gqa % share == 0) return share;
   return 0;
@@ -1016,7 +1037,6 @@ bool mfma_can_append(int head_dim, int gqa) {
   const int gp = padded_gqa(head_dim, gqa);
   if (head_dim == 128 && gp == 8) return Cfg<128, 8, 8>::QSEP;
   if (head_dim == 128 && gp == 4) return Cfg<128, 4, 8>::QSEP;
-  if (head_dim == 256 && gp == 4) return Cfg<256, 4, 8>::QSEP;
   if (head_dim == 256 && gp == 2) return Cfg<256, 2, 8>::QSEP;
   return false;
 }
@@ -1025,9 +1045,12 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
                                hipStream_t s) {
   static std::atomic<unsigned int> next_slot{0};
   DecodeParams p = p_in;
-  p.kv_share = kv_share_of(head_dim, p.gqa);
+  if (p.n_queries < 1) p.n_queries = 1;
+  if (p.n_queries > kMaxQueries || (p.n_queries > 1 && p.k_new != nullptr)) return hipErrorNotSupported;
+  p.gqa_full = p.gqa;
+  p.kv_share = kv_share_of(head_dim, p.gqa * p.n_queries);
   if (p.kv_share < 1) return hipErrorNotSupported;
-  p.gqa /= p.kv_share;
+  p.gqa = p.gqa * p.n_queries / p.kv_share;
   const int rows_y = p.n_kv_heads * p.kv_share;
   p.merge_slot = -1;
   if (merge_in_kernel) {
@@ -1038,7 +1061,6 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);
-  if (head_dim == 256 && gp == 4) return launch<256, 4>(p, grid, s);
   if (head_dim == 256 && gp == 2) return launch<256, 2>(p, grid, s);
   return hipErrorNotSupported;
 }

@@ -9,6 +9,8 @@
 // 8 query heads of the GQA group in registers (Alg. 1, lines 3-11).  Slots are merged with
 // wave shuffles, waves through LDS, and the block writes ONE un-normalised partial
 // (o_c, m_c, l_c) per query head (Sec. 3.2).  Scores live in log2 units so exp is exp2.
+#include <algorithm>
+
 #include "tq_internal.h"
 
 namespace tq {
@@ -175,15 +177,19 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 template <int D>
 __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   constexpr int PARTS = 256 / D;
+  // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   // chunks that exist for this sequence: all of them, or those that start before its own end
   int n = p.n_splits, part_stride = p.n_splits;
-  if (p.var_chunks > 0) {
-    const int c = var_chunk_tokens(p);
-    n = (var_len(p, b) + c - 1) / c;
-    part_stride = kMaxSplits;
-  } else if (p.seq_lens) {
-    n = min(n, (var_len(p, b) + p.tokens_per_split - 1) / p.tokens_per_split);
+  if (p.seq_lens) {
+    const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
+    if (p.var_chunks > 0) {
+      const int c = var_chunk_tokens(p);
+      n = (var_len(p, sequence) + c - 1) / c;
+      part_stride = kMaxSplits;
+    } else {
+      n = min(n, (var_len(p, sequence) + p.tokens_per_split - 1) / p.tokens_per_split);
+    }
   }
   const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * part_stride;
   __shared__ float w_c[kMaxSplits];
@@ -267,7 +273,7 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 }
 
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
-  const dim3 grid(p.n_q_heads, batch);
+  const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
   return hipGetLastError();

@@ -12,6 +12,7 @@ namespace tq {
 constexpr int kGroup = 32;        // elements per quantisation group (Sec. 2.1)
 constexpr int kMaxSplits = 128;   // upper bound on sequence chunks (Sec. 3.2); sizes the workspace
 constexpr int kTile = 32;         // chunk boundaries are multiples of this many tokens
+constexpr int kMaxQueries = 8;    // query tokens per sequence in one call (the masked path covers two supertiles)
 
 typedef _Float16 half_t;
 
@@ -25,15 +26,19 @@ struct DecodeParams {
   const half_t* v_zero;
   const half_t* k_dense;    // comparator only: [B][H_kv][row_stride][D]
   const half_t* v_dense;
-  const half_t* q;          // [B][H_q][D]
+  const half_t* q;          // [B][n_queries][H_q][D]
   const int32_t* seq_lens;  // device, [B], or null: tokens each sequence attends (clamped to [1, seq_len])
-  float* part_o;            // [B][H_q][n_splits][D]   un-normalised chunk outputs
-  float* part_ml;           // [B][H_q][n_splits][2]   (running max in log2 units, sum of exp)
-  half_t* out;              // [B][H_q][D]
+  float* part_o;            // [B][n_queries][H_q][n_splits][D]   un-normalised chunk outputs
+  float* part_ml;           // [B][n_queries][H_q][n_splits][2]   (running max in log2 units, sum of exp)
+  half_t* out;              // [B][n_queries][H_q][D]
   int32_t n_q_heads, n_kv_heads, gqa;
-  // Matrix-core kernel, GQA groups larger than its tile takes: kv_share blocks (blockIdx.y = kv * kv_share +
-  // part) stream the same KV head, each for gqa consecutive query heads (gqa then counts one block's heads).
-  int32_t kv_share;
+  // Query tokens per sequence (>= 1): the sequence's last n_queries tokens, query t attending all tokens up
+  // to its own (n_queries - 1 - t fewer than the sequence holds).  Matrix-core kernel only.
+  int32_t n_queries;
+  // Matrix-core kernel: a KV head has n_queries * gqa_full query rows (gqa_full = H_q / H_kv).  Where that is
+  // more than its tile takes, kv_share blocks (blockIdx.y = kv * kv_share + part) stream the same KV head,
+  // each for gqa consecutive rows (gqa then counts one block's rows).
+  int32_t kv_share, gqa_full;
   int32_t row_stride;       // tokens between consecutive (b, kv head) rows
   int32_t seq_len, n_splits, tokens_per_split;   // seq_len: every sequence's length, or the bound of seq_lens
   float scale_log2;         // attn_scale * log2(e)

@@ -533,6 +533,109 @@ def test_gqa_groups_larger_than_the_matrix_core_tile(shape, variant):
                      f"{shape} per-sequence lengths S={S} window={window} variant={variant}")
 
 
+# ---------------------------------------------------------------- several query tokens per sequence
+
+def _queries_for(w, nq):
+    """nq query tokens per sequence, [B, nq, H_q, d]: token t is the workload's query drawn with seed + 7 t."""
+    import dataclasses
+    qs = [make(dataclasses.replace(w, seed=w.seed + 7 * t))[0] for t in range(nq)]
+    return torch.stack(qs, dim=1).contiguous()
+
+
+def _oracle_causal(q4, ocache, lens, alpha):
+    """Query token t of sequence b attends the first lens[b] - (nq - 1 - t) tokens: the definition, row by row."""
+    nq = q4.shape[1]
+    out = np.empty(tuple(q4.shape), dtype=np.float64)
+    for b, n in enumerate(lens):
+        one = [a[b:b + 1] for a in ocache]
+        for t in range(nq):
+            out[b, t] = oracle.attend_packed(np16(q4[b:b + 1, t]), *one, seq_len=n - (nq - 1 - t), alpha=alpha)[0]
+    return out
+
+
+@pytest.mark.parametrize("nq", [2, 3, 4, 8])
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256", "g3_d128", "g16_d128", "g4_d256"])
+def test_several_query_tokens(shape, nq):
+    """n_queries > 1: the sequence's last nq tokens as queries, causal among themselves, against the oracle
+    row by row; lengths around the 32-token supertile boundaries put the masked tokens in one supertile, in
+    two, and in a chunk of their own."""
+    for S, n_splits in ((nq, 0), (31, 0), (33, 0), (63, 0), (64, 0), (65, 0), (66, 0), (71, 0), (1000, 0), (1030, 4),
+                        (4133, 0), (20002, 0)):
+        if S < nq:
+            continue
+        w = wl.custom(seq_len=S, seed=1200 + S + nq, **SHAPES[shape])
+        _, k, v = make(w)
+        q4 = _queries_for(w, nq)
+        cache = gpu_cache_from(k, v, capacity=S + 3)
+        ocache = oracle_cache_from(k, v)
+        out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, n_splits=n_splits)
+        torch.cuda.synchronize()
+        assert tuple(out.shape) == tuple(q4.shape)
+        ref = _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale)
+        assert_close(out, ref, f"{shape} nq={nq} S={S}")
+        # the last query token is the plain decode step over S tokens
+        last = tq.tq_sdpa_int4_decode(cache, q4[:, nq - 1].contiguous().cuda(), S, w.attn_scale, n_splits=n_splits)
+        a, b = np16(out[:, nq - 1]).astype(np.float64), np16(last).astype(np.float64)
+        assert np.abs(a - b).max() <= 2.0 ** -9 * max(1.0, np.abs(b).max())
+
+
+@pytest.mark.parametrize("nq", [2, 5])
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256"])
+def test_several_query_tokens_append_varlen_and_two_phase(shape, nq):
+    """The other entry points with n_queries > 1: append the nq tokens and attend in one call (stored bits equal
+    the oracle's); per-sequence lengths; phase 1 and phase 2 called separately."""
+    for S in (nq, 77, 2500):
+        w = wl.custom(seq_len=S, seed=1300 + S + nq, **SHAPES[shape])
+        _, k, v = make(w)
+        q4 = _queries_for(w, nq)
+        ocache = oracle_cache_from(k, v)
+        cache = tq.KVCache(w.batch, w.n_kv_heads, w.head_dim, S + 3)
+        for t in cache.tensors():
+            t.view(torch.uint8).fill_(0xEE)
+        if S > nq:
+            tq.tq_quantize_kv(cache, k[:, :, :S - nq].contiguous().cuda(), v[:, :, :S - nq].contiguous().cuda(), 0)
+        kn, vn = k[:, :, S - nq:].contiguous().cuda(), v[:, :, S - nq:].contiguous().cuda()
+        out = tq.tq_sdpa_int4_append_decode(cache, kn, vn, q4.cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_cache_bit_exact(cache, ocache, S)
+        for t in cache.tensors():
+            assert bool((t.view(torch.uint8)[:, :, S:] == 0xEE).all())
+        assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale), f"{shape} append nq={nq} S={S}")
+        # per-sequence lengths (each at least nq)
+        lens = [max(nq, S - 29 * b) for b in range(w.batch)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q4.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale), f"{shape} varlen nq={nq} S={S}")
+        # the two phases on their own: rows of the workspace and of `out` are (sequence, query token) pairs
+        ws = torch.empty(tq.tq_workspace_bytes(w.batch * nq, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
+        n = tq.tq_sdpa_int4_partial(cache, q4.cuda(), S, w.attn_scale, ws)
+        out2 = torch.empty_like(q4, device="cuda")
+        tq.tq_sdpa_int4_reduce(w.batch * nq, w.n_q_heads, w.head_dim, n, ws, out2)
+        torch.cuda.synchronize()
+        assert_close(out2, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale), f"{shape} two-phase nq={nq} S={S}")
+
+
+def test_several_query_tokens_rejections():
+    w = wl.custom(seq_len=100, seed=5, **SHAPES["g8_d128"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    q4 = _queries_for(w, 3).cuda()
+    for kw in (dict(variant=1), dict(window=50)):
+        with pytest.raises(tq.TqError) as e:
+            tq.tq_sdpa_int4_decode(cache, q4, 100, w.attn_scale, **kw)
+        assert e.value.status == -6
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q4, 2, w.attn_scale)          # fewer tokens than queries
+    assert e.value.status == -3
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q4, 100, -1.0)                # the generic kernel's case
+    assert e.value.status == -6
+    q9 = torch.zeros(1, 9, 8, 128, dtype=torch.float16, device="cuda")
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q9, 100, w.attn_scale)
+    assert e.value.status == -6
+
+
 # ---------------------------------------------------------------- paged cache
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
@@ -581,6 +684,11 @@ def test_paged_cache(shape, variant):
 
     lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
     ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    if variant != 1:                              # several query tokens per sequence over the paged pool
+        q4 = _queries_for(w, 3)
+        out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q4.cuda(), lens_dev, S, w.attn_scale, variant=variant)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale), f"{shape} paged, 3 query tokens")
     for n_splits in (0, 3):
         try:
             out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev, S, w.attn_scale,

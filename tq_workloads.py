@@ -102,6 +102,19 @@ def make_inputs(w: Workload, device="cpu"):
     return q.to(torch.float16), k, v
 
 
+def make_queries(w: Workload, n_queries: int, device="cpu"):
+    """Queries for the sequence's last n_queries tokens, fp16 [B, n_queries, H_q, d]: the last one is the
+    workload's own query (the first draw of make_inputs), the earlier ones are drawn alike from seeds of
+    their own."""
+    dev = torch.device(device)
+    rows = []
+    for t in range(n_queries):
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed if t == n_queries - 1 else w.seed * 7919 + 500 + t)
+        rows.append(_randn((w.batch, w.n_q_heads, w.head_dim), gen, dev, w.qk_std).to(torch.float16))
+    return torch.stack(rows, dim=1).contiguous()
+
+
 def make_new_token(w: Workload, step: int = 0, device="cpu"):
     """One appended token per sequence: (k_new, v_new) fp16 [B,H_kv,1,d], seeded from the
     workload seed and the step number."""
