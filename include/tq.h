@@ -31,7 +31,7 @@ extern "C" {
 enum {
   TQ_OK = 0,
   TQ_ERR_NULL = -1,        /* a required pointer is NULL                                        */
-  TQ_ERR_SHAPE = -2,       /* head_dim not in {128,256}, group_size != 32, batch/heads < 1,
+  TQ_ERR_SHAPE = -2,       /* head_dim not in {128,256,512}, group_size != 32, batch/heads < 1,
                               n_q_heads not a multiple of n_kv_heads, unknown layout            */
   TQ_ERR_EMPTY = -3,       /* seq_len < 1 or n_new < 1                                          */
   TQ_ERR_CAPACITY = -4,    /* pos < 0, pos + n_new > capacity, or seq_len > capacity            */
@@ -60,7 +60,7 @@ typedef struct tq_kv_cache {
   void* v_zero;
   int32_t batch;
   int32_t n_kv_heads;
-  int32_t head_dim;    /* 128 or 256 */
+  int32_t head_dim;    /* 128, 256 or 512 (512: generic kernel only, one query token) */
   int32_t group_size;  /* 32 */
   int32_t capacity;    /* tokens allocated per (batch, kv head) */
   int32_t layout;      /* TQ_LAYOUT_CANONICAL */

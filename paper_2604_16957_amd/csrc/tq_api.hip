@@ -13,10 +13,13 @@ using tq::half_t;
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// head dimensions the kernels are built for (512: the generic kernel only)
+inline bool head_dim_ok(int d) { return d == 128 || d == 256 || d == 512; }
+
 int check_cache(const tq_kv_cache* c) {
   if (!c) return TQ_ERR_NULL;
   if (!c->k_codes || !c->v_codes || !c->k_scale || !c->k_zero || !c->v_scale || !c->v_zero) return TQ_ERR_NULL;
-  if (c->head_dim != 128 && c->head_dim != 256) return TQ_ERR_SHAPE;
+  if (!head_dim_ok(c->head_dim)) return TQ_ERR_SHAPE;
   if (c->group_size != tq::kGroup) return TQ_ERR_SHAPE;
   if (c->batch < 1 || c->n_kv_heads < 1 || c->capacity < 1) return TQ_ERR_SHAPE;
   if (c->layout != TQ_LAYOUT_CANONICAL) return TQ_ERR_SHAPE;
@@ -257,13 +260,13 @@ int paged_view(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_
 extern "C" {
 
 size_t tq_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim) {
-  if (batch < 1 || n_q_heads < 1 || (head_dim != 128 && head_dim != 256)) return 0;
+  if (batch < 1 || n_q_heads < 1 || !head_dim_ok(head_dim)) return 0;
   return (tq::workspace_o_floats(batch, n_q_heads, head_dim) + tq::workspace_ml_floats(batch, n_q_heads)) *
          sizeof(float);
 }
 
 size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim) {
-  if (batch < 1 || n_kv_heads < 1 || seq_len < 1 || (head_dim != 128 && head_dim != 256)) return 0;
+  if (batch < 1 || n_kv_heads < 1 || seq_len < 1 || !head_dim_ok(head_dim)) return 0;
   return (size_t)2 * batch * n_kv_heads * seq_len * head_dim * sizeof(half_t);
 }
 
@@ -348,7 +351,7 @@ int tq_sdpa_int4_partial(const tq_kv_cache* cache, const void* q, int32_t n_q_he
 int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int32_t n_splits, const void* workspace,
                         size_t workspace_bytes, void* out, void* stream) {
   if (!workspace || !out) return TQ_ERR_NULL;
-  if (batch < 1 || n_q_heads < 1 || (head_dim != 128 && head_dim != 256)) return TQ_ERR_SHAPE;
+  if (batch < 1 || n_q_heads < 1 || !head_dim_ok(head_dim)) return TQ_ERR_SHAPE;
   if (n_splits < 1) return TQ_ERR_EMPTY;
   if (n_splits > tq::kMaxSplits) return TQ_ERR_UNSUPPORTED;
   if (!aligned(workspace, 256) || !aligned(out, 16)) return TQ_ERR_ALIGN;

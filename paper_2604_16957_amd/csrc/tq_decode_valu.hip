@@ -16,7 +16,8 @@
 namespace tq {
 namespace {
 
-constexpr int kHeadTile = 8;       // query heads per block pass
+// query heads per block pass: 8, or 4 at d=512 (the block merge keeps 4 waves x heads x d floats in LDS)
+constexpr int head_tile(int d) { return d <= 256 ? 8 : 4; }
 constexpr float kNegBig = -1.0e30f;  // "no token seen yet" running max (finite: no inf-inf)
 
 union Pack16 { uint4 v; half_t h[8]; };
@@ -27,6 +28,7 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   constexpr int TPW = 64 / LPT;        // token slots per wave
   constexpr int SPB = 4 * TPW;         // token slots per block
   constexpr int NG = D / kGroup;
+  constexpr int kHeadTile = head_tile(D);
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -175,8 +177,9 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 // in LDS; the weighted sum over chunks is split over 256/D thread groups with independent,
 // unrolled loads, so the kernel is a handful of memory round trips long.
 template <int D>
-__global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
-  constexpr int PARTS = 256 / D;
+__global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams p) {
+  constexpr int THREADS = D > 256 ? D : 256, WAVES = THREADS / 64;
+  constexpr int PARTS = THREADS / D;
   // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   // chunks that exist for this sequence: all of them, or those that start before its own end
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   }
   const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * part_stride;
   __shared__ float w_c[kMaxSplits];
-  __shared__ float red_m[4], red_l[4];
+  __shared__ float red_m[WAVES], red_l[WAVES];
   __shared__ float acc_part[PARTS][D];
 
   // the first chunks of this thread's output element are asked for before anything else: they do not
@@ -219,7 +222,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
   if ((tid & 63) == 0) red_m[tid >> 6] = mw;
   __syncthreads();
-  const float mg = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  float mg = red_m[0];
+#pragma unroll
+  for (int w = 1; w < WAVES; ++w) mg = fmaxf(mg, red_m[w]);
   const float w = exp2f(m - mg);
   if (tid < n) w_c[tid] = w;
   float lw = l * w;
@@ -227,7 +232,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
   for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
   if ((tid & 63) == 0) red_l[tid >> 6] = lw;
   __syncthreads();
-  const float den = (red_l[0] + red_l[1]) + (red_l[2] + red_l[3]);
+  float den = (red_l[0] + red_l[1]) + (red_l[2] + red_l[3]);
+#pragma unroll
+  for (int w = 4; w < WAVES; w += 4) den += (red_l[w] + red_l[w + 1]) + (red_l[w + 2] + red_l[w + 3]);
 
   float num = 0.0f;
 #pragma unroll
@@ -258,16 +265,19 @@ __global__ __launch_bounds__(256) void reduce_kernel(DecodeParams p) {
 }  // namespace
 
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s) {
-  const int head_tiles = (p.gqa + kHeadTile - 1) / kHeadTile;
+  const int head_tiles = (p.gqa + head_tile(head_dim) - 1) / head_tile(head_dim);
   const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads * head_tiles, 1)
                                      : dim3(p.n_splits, p.n_kv_heads * head_tiles, batch);
   const dim3 block(256);
   if (head_dim == 128) {
     if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<128, true>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((decode_partial_valu_kernel<128, false>), grid, block, 0, s, p);
-  } else {
+  } else if (head_dim == 256) {
     if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<256, true>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((decode_partial_valu_kernel<256, false>), grid, block, 0, s, p);
+  } else {
+    if (dense) hipLaunchKernelGGL((decode_partial_valu_kernel<512, true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((decode_partial_valu_kernel<512, false>), grid, block, 0, s, p);
   }
   return hipGetLastError();
 }
@@ -275,7 +285,8 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
+  else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((reduce_kernel<512>), grid, dim3(512), 0, s, p);
   return hipGetLastError();
 }
 

@@ -636,6 +636,50 @@ def test_several_query_tokens_rejections():
     assert e.value.status == -6
 
 
+# ---------------------------------------------------------------- head_dim 512
+
+@pytest.mark.parametrize("shape", ["g4_d512", "g32_d512"])
+def test_head_dim_512(shape):
+    """d = 512 (the global-attention configuration of the kernel table in the appendix, GQA 32): quantiser bit-exact,
+    the generic kernel for the attention (the matrix-core kernel is not built for it), every entry point."""
+    shapes = dict(g4_d512=dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=512, attn_scale=1.0, qk_std=0.1),
+                  g32_d512=dict(n_q_heads=32, n_kv_heads=1, head_dim=512, attn_scale=1.0, qk_std=0.1))
+    for S in (1, 33, 1000, 4133):
+        w = wl.custom(seq_len=S, seed=1400 + S, **shapes[shape])
+        q, k, v = make(w)
+        ocache = oracle_cache_from(k, v)
+        cache = tq.KVCache(w.batch, w.n_kv_heads, w.head_dim, S + 3)
+        for t in cache.tensors():
+            t.view(torch.uint8).fill_(0xEE)
+        if S > 1:
+            tq.tq_quantize_kv(cache, k[:, :, :S - 1].contiguous().cuda(), v[:, :, :S - 1].contiguous().cuda(), 0)
+        kn, vn = k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda()
+        out = tq.tq_sdpa_int4_append_decode(cache, kn, vn, q.cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_cache_bit_exact(cache, ocache, S)
+        for t in cache.tensors():
+            assert bool((t.view(torch.uint8)[:, :, S:] == 0xEE).all())
+        ref = oracle_attend(q, ocache, S, w.attn_scale)
+        assert_close(out, ref, f"{shape} S={S}")
+        for n_splits in (1, 3, 128):
+            assert_close(tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, n_splits=n_splits), ref,
+                         f"{shape} S={S} n_splits={n_splits}")
+        lens = [max(1, S - 17 * b) for b in range(w.batch)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_varlen(q, ocache, lens, w.attn_scale), f"{shape} per-sequence lengths S={S}")
+        win = max(1, S // 3)
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, window=win)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_window(q, ocache, [S] * w.batch, win, w.attn_scale), f"{shape} window S={S}")
+        base = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(base, ref, f"{shape} comparator S={S}", rel_l2=BASELINE_REL_L2)
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2)
+    assert e.value.status == -6
+
+
 # ---------------------------------------------------------------- paged cache
 
 @pytest.mark.parametrize("variant", [0, 1, 2])

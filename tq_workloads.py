@@ -12,6 +12,8 @@ own kernel benchmark is shape-only, and neither weights nor activations exist he
             KV head scaled x8 (outlier channels; indices = first 4 of a seeded permutation)
   llama128k as llama8k with S=131072 (the headline shape)
   gemma32k  B1, 32/16 heads, d=256, S=32768, alpha=1.0; q,K ~ N(0,0.1^2), V ~ N(0,1)
+  global512_32k  B1, 32 query heads on 1 KV head (GQA 32), d=512, S=32768, alpha=1.0; values as gemma32k
+            (the global-attention column of the kernel configuration table, Appendix A)
 """
 from __future__ import annotations
 
@@ -55,6 +57,7 @@ WORKLOADS = {
     "llama128k": Workload("llama128k", 1, 64, 8, 128, 131072, 1.0 / math.sqrt(128), 1003,
                           outlier_channels=4),
     "gemma32k": Workload("gemma32k", 1, 32, 16, 256, 32768, 1.0, 1004, qk_std=0.1),
+    "global512_32k": Workload("global512_32k", 1, 32, 1, 512, 32768, 1.0, 1006, qk_std=0.1),
 }
 
 
