@@ -441,8 +441,8 @@ def test_random_configurations_against_the_oracle():
     """Seeded sweep over shapes, lengths, chunk counts, windows and per-sequence lengths: every
     combination goes through whichever kernel the library picks and through the generic one."""
     rng = np.random.default_rng(20260416)
-    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 4), (256, 2), (256, 1), (128, 16)]
-    for case in range(40):
+    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 4), (256, 2), (256, 1), (128, 16), (128, 12), (256, 6), (512, 2)]
+    for case in range(60):
         d, G = shapes[rng.integers(len(shapes))]
         Hkv = int(rng.integers(1, 4))
         B = int(rng.integers(1, 4))
@@ -470,6 +470,39 @@ def test_random_configurations_against_the_oracle():
             max_abs, rel = errors(out, ref)
             scale = max(1.0, float(np.abs(ref).max()))
             assert max_abs <= MAX_ABS * scale and rel <= REL_L2, f"{what} variant={variant}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
+
+
+def test_random_configurations_with_several_query_tokens():
+    """The same kind of sweep with 2 ... 8 causal query tokens per sequence (matrix-core kernel only)."""
+    rng = np.random.default_rng(20260417)
+    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 2), (256, 1), (128, 16), (256, 3)]
+    for case in range(40):
+        d, G = shapes[rng.integers(len(shapes))]
+        Hkv = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 4))
+        nq = int(rng.integers(2, 9))
+        S = max(nq, int(rng.choice([2, 8, 31, 32, 33, 40, 63, 64, 65, 70, 255, 256, 257, 263, 1000, 2047, 2049, 3333])))
+        alpha = float(rng.choice([1.0 / np.sqrt(d), 1.0, 0.02]))
+        w = wl.custom(batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=S, seed=3000 + case,
+                      attn_scale=alpha, qk_std=float(rng.choice([1.0, 0.1])), outlier_channels=int(rng.choice([0, 4])))
+        _, k, v = make(w)
+        q4 = _queries_for(w, nq)
+        cache = gpu_cache_from(k, v, capacity=S + int(rng.integers(0, 40)))
+        ocache = oracle_cache_from(k, v)
+        n_splits = int(rng.choice([0, 0, 1, 2, 5, 128]))
+        use_lens = bool(rng.integers(2)) and B > 1
+        lens = [int(x) for x in rng.integers(nq, S + 1, B)] if use_lens else [S] * B
+        ref = _oracle_causal(q4, ocache, lens, alpha)
+        what = f"case {case}: d={d} G={G} Hkv={Hkv} B={B} S={S} nq={nq} n_splits={n_splits} lens={lens}"
+        if use_lens:
+            out = tq.tq_sdpa_int4_decode_varlen(cache, q4.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                                                S, alpha, n_splits=n_splits)
+        else:
+            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, alpha, n_splits=n_splits)
+        torch.cuda.synchronize()
+        max_abs, rel = errors(out, ref)
+        scale = max(1.0, float(np.abs(ref).max()))
+        assert max_abs <= MAX_ABS * scale and rel <= REL_L2, f"{what}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
 
 
 # ---------------------------------------------------------------- one call per decode step
