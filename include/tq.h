@@ -83,7 +83,8 @@ typedef struct tq_decode_opts {
                         tq_workspace_bytes(batch * n_queries, ...) and pass batch * n_queries as `batch`
                         to tq_sdpa_int4_reduce; k_new / v_new of tq_sdpa_int4_append_decode are
                         [batch][n_kv_heads][n_queries][head_dim].  Every sequence length must be at least
-                        n_queries.  Matrix-core kernel only (variant 1, attn_scale <= 0, a window, and
+                        n_queries.  With a window, query t attends the last `window` of its tokens.
+                        Matrix-core kernel only (variant 1, attn_scale <= 0, head_dim 512 and
                         tq_dequant_then_attend answer UNSUPPORTED).                               */
 } tq_decode_opts;
 

@@ -80,8 +80,7 @@ int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len
   if (opts) {
     if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0 || opts->window < 0) return TQ_ERR_UNSUPPORTED;
     if (opts->n_queries < 0 || opts->n_queries > tq::kMaxQueries) return TQ_ERR_UNSUPPORTED;
-    // several query tokens: matrix-core kernel only, and every row attends from the sequence's first token
-    if (opts->n_queries > 1 && (opts->variant == 1 || opts->window > 0)) return TQ_ERR_UNSUPPORTED;
+    if (opts->n_queries > 1 && opts->variant == 1) return TQ_ERR_UNSUPPORTED;   // matrix-core kernel only
     if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, rows_of(c, n_q_heads, opts))) return TQ_ERR_UNSUPPORTED;
   }
   if (workspace_bytes < tq_workspace_bytes(c->batch * queries_of(opts), n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
@@ -124,8 +123,9 @@ struct Route { bool ok, use_mfma, merge; };
 constexpr int64_t kMergeInKernelMaxBytes = 48ll << 20;
 
 // tokens a sequence of length seq_len attends under the options' sliding window
+// (several query tokens: the span all rows together attend, the earliest row's window start to the end)
 int windowed(int seq_len, const tq_decode_opts* opts) {
-  return (opts && opts->window > 0) ? std::min(seq_len, opts->window) : seq_len;
+  return (opts && opts->window > 0) ? std::min(seq_len, opts->window + queries_of(opts) - 1) : seq_len;
 }
 
 Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts) {
@@ -198,11 +198,13 @@ int run_partial(PartialRequest& rq) {
   p.seq_lens = seq_lens;
   p.batch = cache->batch;
   if (seq_lens) {
-    p.window = opts ? opts->window : 0;           // the kernels window every sequence's own length
+    // the kernels window every sequence's own length
+    p.window = (opts && opts->window > 0) ? opts->window + queries_of(opts) - 1 : 0;
   } else {
     p.seq_len = attended;
     p.start = first;
   }
+  p.row_window = (opts && queries_of(opts) > 1) ? opts->window : 0;
   if (rq.paged) {
     p.block_table = rq.paged->block_table;
     p.max_blocks = rq.paged->max_blocks;

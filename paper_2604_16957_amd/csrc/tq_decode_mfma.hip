@@ -287,12 +287,17 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // pool's row 0 (paged cache: the page's rows are added supertile by supertile)
   const bool paged = p.block_table != nullptr;
   const int64_t row0 = paged ? 0 : (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
-  const int begin = split * tokens_per_split;
+  const int begin0 = split * tokens_per_split;    // first token of the chunk
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
   // goes through and publishes an empty partial.)
-  if (begin >= seq && p.merge_slot < 0) return;
-  const int end = max(begin, min(seq, begin + tokens_per_split));
+  if (begin0 >= seq && p.merge_slot < 0) return;
+  const int end = max(begin0, min(seq, begin0 + tokens_per_split));
+  // Several query tokens under a sliding window: the rows start at different tokens (row t one token after
+  // row t - 1), all inside the sequence's first attended supertile; that supertile then takes the masked path
+  // too (wave 0, after its other work) and the fast path starts one supertile later.
+  const bool head = NQ > 1 && p.row_window > 0 && split == 0 && end > begin0;
+  const int begin = begin0 + (head ? 32 : 0);     // origin of the supertile indices below
   // `seq` is what the last query token attends; query token t attends NQ - 1 - t tokens fewer.  Supertiles
   // that every row attends in full take the fast path; the sequence's last one or two (ragged, or holding
   // tokens some rows must not see) take the masked path.
@@ -300,6 +305,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int n_tail = ((end - begin + 31) >> 5) - n_full;   // 0, 1 or 2 (NQ <= 8)
   const int last_tok = seq - 1;
   const int end_col = min(end, seq - (NQ - 1 - query_token(hl)));   // first token this lane's column must not see
+  // ... and, under a window, the first one it sees: its own length less the window, relative to the row start
+  const int lo_col = head ? max(0, start + seq - (NQ - 1 - query_token(hl)) - p.row_window) - start : 0;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
   const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     issue_tok(ring_lds + slot * C::STAGE, tok0, paged ? page_of(tok0) : 0, koff, lane16, szoff);
   };
   auto issue_phantom = [&](int slot) {
-    issue_tok(ring_lds + slot * C::STAGE, begin, paged ? page_of(begin) : 0, 0u, 0u, zero_vs);
+    issue_tok(ring_lds + slot * C::STAGE, begin0, paged ? page_of(begin0) : 0, 0u, 0u, zero_vs);
   };
   // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
   //      issues from its older wave first, so wave w gets through a supertile in about 7/9 of the time
@@ -417,9 +424,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
   };
   const int n_mine = count_of(n_full);
-  bool tail_mine[2];
+  bool tail_mine[3];                              // [2]: the masked FIRST supertile (see `head`)
 #pragma unroll
   for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
+  tail_mine[2] = head && wave == 0;
 
   // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
@@ -680,7 +688,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         if constexpr (GR >= 8) x = row_ror_add<2>(x);
         if constexpr (TAIL) {
           const int tok = begin + sidx * 32 + 16 * t + tok_of_row(4 * kq + i);
-          x = (tok < end_col) ? x : -INFINITY;
+          x = (tok >= lo_col && tok < end_col) ? x : -INFINITY;
         }
         sc[t][i] = x;
       }
@@ -832,15 +840,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   wait_loads<0>();                                           // phantom stages included: the rings are quiet
 #pragma unroll 1
-  for (int u = 0; u < 2; ++u) {                              // the masked last supertile(s) of the sequence
-    if (!tail_mine[u]) continue;
+  for (int u = 0; u < 3; ++u) {                              // the masked supertiles: the sequence's last one or two,
+    if (!tail_mine[u]) continue;                             // and under a window its first
+    const int sidx = u < 2 ? n_full + u : -1;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    issue_tail(0, n_full + u);
+    issue_tail(0, sidx);
     wait_loads<0>();
     load_k(0, kr);
     load_v(0, vr);
     float sc[2][4];
-    scores(kr, n_full + u, std::true_type{}, sc);
+    scores(kr, sidx, std::true_type{}, sc);
     half8v pa[NA];
     softmax(sc, vr, pa);
     pv(vr, pa);
@@ -855,7 +864,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
   float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
   if constexpr (C::ALIAS) __syncthreads();                   // everybody is done reading the rings
-  const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1];
+  const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1] || tail_mine[2];
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
     // (a row whose tokens were all masked still has the initial reference: it counts as empty)

@@ -51,6 +51,9 @@ struct DecodeParams {
   // and seq_len already the windowed length.  Per-sequence lengths: window > 0 and the kernels derive
   // both from seq_lens (var_len / var_start below).
   int32_t start, window;
+  // Several query tokens under a window: `window` above (and `start` / seq_len) describe the span all rows
+  // together attend, window + n_queries - 1 tokens; row_window is the window of one row (0 = none).
+  int32_t row_window;
   // Paged cache: block_table non-null = the six arrays are a POOL of pages, [n_pages][H_kv][row_stride] rows
   // with row_stride = 2^page_shift tokens per page, and token t of sequence b lives in page
   // block_table[b * max_blocks + (t >> page_shift)] at row t & (row_stride - 1).

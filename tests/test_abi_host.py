@@ -94,15 +94,14 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(), opts=ctypes.byref(neg)) == E.TQ_ERR_UNSUPPORTED
     negw = B.TqDecodeOptsStruct(0, 0, -3)
     assert _decode(_cache(), opts=ctypes.byref(negw)) == E.TQ_ERR_UNSUPPORTED
-    # several query tokens per sequence: 0 and 1 mean one; more than 8, a negative count, the generic kernel
-    # or a window are refused; the workspace holds batch * n_queries rows; a sequence holds all its queries
+    # several query tokens per sequence: 0 and 1 mean one; more than 8, a negative count and the generic kernel
+    # are refused; the workspace holds batch * n_queries rows; a sequence holds all its queries
     ws3 = tq.tq_workspace_bytes(3, 64, 128)
     for nq, kw, want in ((9, {}, E.TQ_ERR_UNSUPPORTED), (-1, {}, E.TQ_ERR_UNSUPPORTED),
                          (3, dict(wsb=ws3 - 1), E.TQ_ERR_WORKSPACE), (3, dict(wsb=ws3, S=2), E.TQ_ERR_EMPTY)):
         o = B.TqDecodeOptsStruct(0, 0, 0, nq)
         assert _decode(_cache(), opts=ctypes.byref(o), **kw) == want
     assert _decode(_cache(), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 1, 0, 3)), wsb=ws3) == E.TQ_ERR_UNSUPPORTED
-    assert _decode(_cache(), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 0, 64, 3)), wsb=ws3) == E.TQ_ERR_UNSUPPORTED
     f = B.raw().tq_decode_launches
     c = _cache()
     assert f(ctypes.byref(c), 64, 1024, 0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 4))) == 1

@@ -492,13 +492,14 @@ def test_random_configurations_with_several_query_tokens():
         n_splits = int(rng.choice([0, 0, 1, 2, 5, 128]))
         use_lens = bool(rng.integers(2)) and B > 1
         lens = [int(x) for x in rng.integers(nq, S + 1, B)] if use_lens else [S] * B
-        ref = _oracle_causal(q4, ocache, lens, alpha)
-        what = f"case {case}: d={d} G={G} Hkv={Hkv} B={B} S={S} nq={nq} n_splits={n_splits} lens={lens}"
+        window = int(rng.choice([0, 0, 1, 9, 50, 1500]))
+        ref = _oracle_causal(q4, ocache, lens, alpha, window)
+        what = f"case {case}: d={d} G={G} Hkv={Hkv} B={B} S={S} nq={nq} n_splits={n_splits} window={window} lens={lens}"
         if use_lens:
             out = tq.tq_sdpa_int4_decode_varlen(cache, q4.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
-                                                S, alpha, n_splits=n_splits)
+                                                S, alpha, n_splits=n_splits, window=window)
         else:
-            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, alpha, n_splits=n_splits)
+            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, alpha, n_splits=n_splits, window=window)
         torch.cuda.synchronize()
         max_abs, rel = errors(out, ref)
         scale = max(1.0, float(np.abs(ref).max()))
@@ -575,14 +576,17 @@ def _queries_for(w, nq):
     return torch.stack(qs, dim=1).contiguous()
 
 
-def _oracle_causal(q4, ocache, lens, alpha):
-    """Query token t of sequence b attends the first lens[b] - (nq - 1 - t) tokens: the definition, row by row."""
+def _oracle_causal(q4, ocache, lens, alpha, window=0):
+    """Query token t of sequence b attends the first lens[b] - (nq - 1 - t) tokens, under a sliding window the
+    last `window` of those: the definition, row by row (the oracle is handed exactly the attended slice)."""
     nq = q4.shape[1]
     out = np.empty(tuple(q4.shape), dtype=np.float64)
     for b, n in enumerate(lens):
-        one = [a[b:b + 1] for a in ocache]
         for t in range(nq):
-            out[b, t] = oracle.attend_packed(np16(q4[b:b + 1, t]), *one, seq_len=n - (nq - 1 - t), alpha=alpha)[0]
+            hi = n - (nq - 1 - t)
+            lo = max(0, hi - window) if window > 0 else 0
+            one = [a[b:b + 1, :, lo:hi] for a in ocache]
+            out[b, t] = oracle.attend_packed(np16(q4[b:b + 1, t]), *one, seq_len=hi - lo, alpha=alpha)[0]
     return out
 
 
@@ -610,6 +614,12 @@ def test_several_query_tokens(shape, nq):
         last = tq.tq_sdpa_int4_decode(cache, q4[:, nq - 1].contiguous().cuda(), S, w.attn_scale, n_splits=n_splits)
         a, b = np16(out[:, nq - 1]).astype(np.float64), np16(last).astype(np.float64)
         assert np.abs(a - b).max() <= 2.0 ** -9 * max(1.0, np.abs(b).max())
+        # sliding window: every query token attends the last `window` tokens up to its own
+        for window in (1, 5, 32, 40, 700):
+            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, n_splits=n_splits, window=window)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale, window),
+                         f"{shape} nq={nq} S={S} window={window}")
 
 
 @pytest.mark.parametrize("nq", [2, 5])
@@ -636,9 +646,12 @@ def test_several_query_tokens_append_varlen_and_two_phase(shape, nq):
         assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale), f"{shape} append nq={nq} S={S}")
         # per-sequence lengths (each at least nq)
         lens = [max(nq, S - 29 * b) for b in range(w.batch)]
-        out = tq.tq_sdpa_int4_decode_varlen(cache, q4.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale)
-        torch.cuda.synchronize()
-        assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale), f"{shape} varlen nq={nq} S={S}")
+        for window in (0, 3, 50):
+            out = tq.tq_sdpa_int4_decode_varlen(cache, q4.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S,
+                                                w.attn_scale, window=window)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale, window),
+                         f"{shape} varlen nq={nq} S={S} window={window}")
         # the two phases on their own: rows of the workspace and of `out` are (sequence, query token) pairs
         ws = torch.empty(tq.tq_workspace_bytes(w.batch * nq, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
         n = tq.tq_sdpa_int4_partial(cache, q4.cuda(), S, w.attn_scale, ws)
@@ -653,10 +666,9 @@ def test_several_query_tokens_rejections():
     q, k, v = make(w)
     cache = gpu_cache_from(k, v)
     q4 = _queries_for(w, 3).cuda()
-    for kw in (dict(variant=1), dict(window=50)):
-        with pytest.raises(tq.TqError) as e:
-            tq.tq_sdpa_int4_decode(cache, q4, 100, w.attn_scale, **kw)
-        assert e.value.status == -6
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q4, 100, w.attn_scale, variant=1)
+    assert e.value.status == -6
     with pytest.raises(tq.TqError) as e:
         tq.tq_sdpa_int4_decode(cache, q4, 2, w.attn_scale)          # fewer tokens than queries
     assert e.value.status == -3
