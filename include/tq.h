@@ -158,9 +158,9 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
  * (q, out, seq_lens, positions, k_new, v_new and the workspace are sized by it).
  * tq_quantize_kv_paged: as tq_quantize_kv_varlen; a sequence whose tokens would not fit into its
  * max_blocks pages is skipped.  tq_sdpa_int4_decode_paged: as tq_sdpa_int4_decode_varlen (device
- * seq_lens, chunks planned on the device, two launches); max_seq_len <= max_blocks * page_tokens;
- * opts->window is not offered (UNSUPPORTED).  Errors otherwise as for the varlen calls; SHAPE also
- * for a page length that is not a power of two >= 32. */
+ * seq_lens, chunks planned on the device, two launches, opts->window and opts->n_queries as there);
+ * max_seq_len <= max_blocks * page_tokens.  Errors as for the varlen calls; SHAPE also for a page
+ * length that is not a power of two >= 32. */
 int tq_quantize_kv_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
                          int32_t batch, const void* k_new, const void* v_new,
                          const int32_t* positions, int32_t n_new, void* stream);

@@ -262,7 +262,7 @@ def tq_quantize_kv_paged(pool: KVCache, block_table: torch.Tensor, k_new: torch.
 
 def tq_sdpa_int4_decode_paged(pool: KVCache, block_table: torch.Tensor, q: torch.Tensor, seq_lens: torch.Tensor,
                               max_seq_len: int, attn_scale: float, out=None, workspace=None, n_splits: int = 0,
-                              variant: int = 0, stream=None) -> torch.Tensor:
+                              variant: int = 0, stream=None, window: int = 0) -> torch.Tensor:
     """q: fp16 [B, H_q, d] or [B, n_queries, H_q, d]; block_table int32 [B, max_blocks] and seq_lens int32 [B]
     on the device."""
     _need(q, torch.float16, "q")
@@ -277,7 +277,7 @@ def tq_sdpa_int4_decode_paged(pool: KVCache, block_table: torch.Tensor, q: torch
     rc = raw().tq_sdpa_int4_decode_paged(ctypes.byref(pool.struct), block_table.data_ptr(), int(block_table.shape[1]),
                                          int(q.shape[0]), q.data_ptr(), hq, seq_lens.data_ptr(),
                                          int(max_seq_len), float(attn_scale), out.data_ptr(), workspace.data_ptr(),
-                                         workspace.numel() * workspace.element_size(), _opts(n_splits, variant, 0, nq),
+                                         workspace.numel() * workspace.element_size(), _opts(n_splits, variant, window, nq),
                                          _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode_paged")
     return out

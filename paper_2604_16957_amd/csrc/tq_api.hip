@@ -185,6 +185,8 @@ int run_partial(PartialRequest& rq) {
   const bool use_mfma = r.use_mfma;
   const int target = use_mfma ? kBlocksMfma : kBlocksValu;
   int attended = windowed(seq_len, opts);         // chunks cover the attended tokens only
+  // (paged cache: counted from the supertile boundary before the window, see var_start)
+  if (rq.paged && attended < seq_len) attended = std::min(seq_len, attended + tq::kTile - 1);
   // append-and-attend in the kernel: the new token (the last attended one) does not come from the cache
   const bool append = rq.k_new != nullptr && appends_in_kernel(cache, n_q_heads, seq_len, seq_lens, r, opts);
   const int first = seq_len - attended;           // first attended token
@@ -433,7 +435,6 @@ int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_tabl
   if (rc != TQ_OK) return rc;
   if (!seq_lens) return TQ_ERR_NULL;
   if (!aligned(seq_lens, 4)) return TQ_ERR_ALIGN;
-  if (opts && opts->window > 0) return TQ_ERR_UNSUPPORTED;      // a window's first token need not start a supertile
   PartialRequest rq{&view, q, n_q_heads, max_seq_len};
   rq.seq_lens = seq_lens;
   rq.attn_scale = attn_scale;

@@ -286,6 +286,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // first row of the six arrays this block reads from: the sequence's own row (contiguous cache), or the
   // pool's row 0 (paged cache: the page's rows are added supertile by supertile)
   const bool paged = p.block_table != nullptr;
+  // paged cache: token indices below count from `start` as well, but the rows are found page by page; the
+  // window's first token may lie up to 31 tokens after `start` (see var_start)
+  const int lead = (paged && p.seq_lens) ? var_first(p, b) - start : 0;
+  const int pstart = paged ? start : 0;           // added to a token index where a page is looked up
   const int64_t row0 = paged ? 0 : (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
   const int begin0 = split * tokens_per_split;    // first token of the chunk
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
@@ -296,17 +300,19 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // Several query tokens under a sliding window: the rows start at different tokens (row t one token after
   // row t - 1), all inside the sequence's first attended supertile; that supertile then takes the masked path
   // too (wave 0, after its other work) and the fast path starts one supertile later.
-  const bool head = NQ > 1 && p.row_window > 0 && split == 0 && end > begin0;
+  // The same goes for a paged cache under a window, whose first supertile holds `lead` tokens before the window.
+  const bool head = ((NQ > 1 && p.row_window > 0) || lead > 0) && split == 0 && end > begin0;
   const int begin = begin0 + (head ? 32 : 0);     // origin of the supertile indices below
   // `seq` is what the last query token attends; query token t attends NQ - 1 - t tokens fewer.  Supertiles
   // that every row attends in full take the fast path; the sequence's last one or two (ragged, or holding
   // tokens some rows must not see) take the masked path.
   const int n_full = max(0, min(end, seq - (NQ - 1)) - begin) >> 5;
   const int n_tail = ((end - begin + 31) >> 5) - n_full;   // 0, 1 or 2 (NQ <= 8)
-  const int last_tok = seq - 1;
+  const int last_tok = pstart + seq - 1;
   const int end_col = min(end, seq - (NQ - 1 - query_token(hl)));   // first token this lane's column must not see
   // ... and, under a window, the first one it sees: its own length less the window, relative to the row start
-  const int lo_col = head ? max(0, start + seq - (NQ - 1 - query_token(hl)) - p.row_window) - start : 0;
+  const int lo_col = !head ? 0 : (NQ > 1 && p.row_window > 0)
+                                     ? max(0, start + seq - (NQ - 1 - query_token(hl)) - p.row_window) - start : lead;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
   const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),
@@ -366,7 +372,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     else issue_at(l, row_bases, (uint32_t)tok0 * TB, vk, vv, vs);
   };
   auto issue_tail = [&](int slot, int sidx) {     // ragged last supertile: clamp every token to the last valid one
-    const int base = begin + sidx * 32;
+    const int base = pstart + begin + sidx * 32;
     const uint32_t l = ring_lds + slot * C::STAGE;
     // token index -> row of the arrays below: the sequence's row, or the page that holds this supertile
     const Bases B = paged ? bases_of_page(page_of(base)) : row_bases;
@@ -397,13 +403,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       }
   };
   const uint32_t zero_vs[C::SZ / 256] = {};
-  auto tok_of = [&](int sidx) { return begin + sidx * 32; };
+  auto tok_of = [&](int sidx) { return pstart + begin + sidx * 32; };
   auto issue = [&](int slot, int sidx) {
     const int tok0 = tok_of(sidx);
     issue_tok(ring_lds + slot * C::STAGE, tok0, paged ? page_of(tok0) : 0, koff, lane16, szoff);
   };
   auto issue_phantom = [&](int slot) {
-    issue_tok(ring_lds + slot * C::STAGE, begin0, paged ? page_of(begin0) : 0, 0u, 0u, zero_vs);
+    issue_tok(ring_lds + slot * C::STAGE, pstart + begin0, paged ? page_of(pstart + begin0) : 0, 0u, 0u, zero_vs);
   };
   // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
   //      issues from its older wave first, so wave w gets through a supertile in about 7/9 of the time

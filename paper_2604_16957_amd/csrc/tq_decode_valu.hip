@@ -79,16 +79,20 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;
   if (begin >= seq) return;                              // chunk past the end of its sequence: nothing to emit
   const int end = min(seq, begin + tokens_per_split);
-  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + (p.seq_lens ? var_start(p, b) : p.start);
+  const int start = p.seq_lens ? var_start(p, b) : p.start;
+  // paged cache under a window: the chunks count from a supertile boundary up to 31 tokens before the window
+  const int lead = (p.block_table && p.seq_lens) ? var_first(p, b) - start : 0;
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
 
   for (int t0 = begin; t0 < end; t0 += SPB) {
     const int t = t0 + slot;
-    const bool valid = t < end;
-    const int tc = valid ? t : end - 1;                  // clamped: always a written token
+    const bool valid = t < end && t >= lead;
+    const int tc = t < end ? t : end - 1;                // clamped: always a written token
     int64_t row = row0 + tc;
     if (p.block_table) {                                 // paged cache: the page the block table names for this token
-      const int page = p.block_table[(int64_t)b * p.max_blocks + (tc >> p.page_shift)];
-      row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (tc & ((1 << p.page_shift) - 1));
+      const int ta = start + tc;
+      const int page = p.block_table[(int64_t)b * p.max_blocks + (ta >> p.page_shift)];
+      row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & ((1 << p.page_shift) - 1));
     }
 
     float kf[8], vf[8];

@@ -113,12 +113,18 @@ __device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[
 // -> (b, chunk); returns false past the end of the list.  Everything here is wave-uniform.
 struct VarPlan { int chunk_tokens, b, chunk; };
 __device__ inline int var_full_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
-// tokens sequence b attends, and the first of them
-__device__ inline int var_len(const DecodeParams& p, int b) {
+// The first token sequence b attends; the token its chunks are counted from (the same, except in a paged
+// cache, where it is rounded down to a supertile boundary so that no supertile straddles two pages: the
+// kernels mask the tokens in between); and the tokens from there to the sequence's end.
+__device__ inline int var_first(const DecodeParams& p, int b) {
   const int n = var_full_len(p, b);
-  return p.window > 0 ? min(n, p.window) : n;
+  return p.window > 0 ? n - min(n, p.window) : 0;
 }
-__device__ inline int var_start(const DecodeParams& p, int b) { return var_full_len(p, b) - var_len(p, b); }
+__device__ inline int var_start(const DecodeParams& p, int b) {
+  const int f = var_first(p, b);
+  return p.block_table ? f & ~(kTile - 1) : f;
+}
+__device__ inline int var_len(const DecodeParams& p, int b) { return var_full_len(p, b) - var_start(p, b); }
 __device__ inline int var_chunk_tokens(const DecodeParams& p) {
   long long total = 0;
   for (int b = 0; b < p.batch; ++b) total += var_len(p, b);

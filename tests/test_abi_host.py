@@ -200,8 +200,6 @@ def test_paged_entry_points_reject_bad_arguments_without_a_gpu():
     assert call(S=0) == E.TQ_ERR_EMPTY
     assert call(tbl=FAKE + 2) == E.TQ_ERR_ALIGN
     assert call(wsb=wsb - 1) == E.TQ_ERR_WORKSPACE
-    win = B.TqDecodeOptsStruct(0, 0, 128)
-    assert call(opts=ctypes.byref(win)) == E.TQ_ERR_UNSUPPORTED
     qz = B.raw().tq_quantize_kv_paged
     assert qz(ctypes.byref(pool), None, 8, 4, FAKE, FAKE, FAKE, 1, None) == E.TQ_ERR_NULL
     assert qz(ctypes.byref(pool), FAKE, 8, 4, FAKE, FAKE, None, 1, None) == E.TQ_ERR_NULL

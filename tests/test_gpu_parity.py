@@ -778,6 +778,26 @@ def test_paged_cache(shape, variant):
         out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q4.cuda(), lens_dev, S, w.attn_scale, variant=variant)
         torch.cuda.synchronize()
         assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale), f"{shape} paged, 3 query tokens")
+    # sliding window over pages: the window's first token need not start a supertile (nor a page)
+    for window in (1, 31, 32, 100, 257, 1500, 5000):
+        for n_splits in (0, 4):
+            try:
+                out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev, S, w.attn_scale, variant=variant,
+                                                   window=window, n_splits=n_splits)
+            except tq.TqError as e:
+                if e.status == -6 and variant == 2:
+                    pytest.skip("matrix-core kernel does not cover this shape")
+                raise
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_window(q, ocache, lens, window, w.attn_scale),
+                         f"{shape} paged window={window} variant={variant} n_splits={n_splits}")
+        if variant != 1:
+            q4 = _queries_for(w, 3)
+            out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q4.cuda(), lens_dev, S, w.attn_scale, variant=variant,
+                                               window=window)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_causal(q4, ocache, lens, w.attn_scale, window),
+                         f"{shape} paged, 3 query tokens, window={window}")
     for n_splits in (0, 3):
         try:
             out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev, S, w.attn_scale,
