@@ -372,18 +372,22 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   auto issue_at = [&](uint32_t l, const Bases& B, uint32_t off_c, uint32_t vk, uint32_t vv,
                       const uint32_t (&vs)[C::SZ / 256]) {
     const uint32_t off_s = off_c >> 3;            // (NG*2) / TB = 1/8: scale bytes per code byte
+    // the supertile's offset goes into the (scalar) base, not into the per-lane offsets: scalar adds are free
+    // next to a vector ALU that is the kernel's bottleneck
+    const char* const bk = B.k + off_c;
+    const char* const bv = B.v + off_c;
     if constexpr (D == 128) {
-      dma16_x2<NT, 1024>(B.k, vk + off_c, l);                          // two K tiles: 1 KB apart on both sides
-      dma16_x2<NT, 1024>(B.v, vv + off_c, l + C::OFF_V);
+      dma16_x2<NT, 1024>(bk, vk, l);                                   // two K tiles: 1 KB apart on both sides
+      dma16_x2<NT, 1024>(bv, vv, l + C::OFF_V);
     } else {
-      dma16_x2<NT, 2048>(B.k, vk + off_c, l);                          // first 16 B of each lane, tiles 0 and 1
-      dma16_x2o<NT, 16, 2064>(B.k, vk + off_c, l + 1024 - 16);         // second 16 B: +16 in HBM, +1024 in LDS
-      dma16_x4<NT>(B.v, vv + off_c, l + C::OFF_V);
+      dma16_x2<NT, 2048>(bk, vk, l);                                   // first 16 B of each lane, tiles 0 and 1
+      dma16_x2o<NT, 16, 2064>(bk, vk, l + 1024 - 16);                  // second 16 B: +16 in HBM, +1024 in LDS
+      dma16_x4<NT>(bv, vv, l + C::OFF_V);
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int u = 0; u < C::SZ / 256; ++u) dma4<NT>(B.s[a], vs[u] + off_s, l + C::OFF_KS + a * C::SZ + u * 256);
+      for (int u = 0; u < C::SZ / 256; ++u) dma4<NT>(B.s[a] + off_s, vs[u], l + C::OFF_KS + a * C::SZ + u * 256);
   };
   // supertile starting tok0 tokens into the sequence (page known in the paged case) -> ring slot at l
   auto issue_tok = [&](uint32_t l, int tok0, int page, uint32_t vk, uint32_t vv, const uint32_t (&vs)[C::SZ / 256]) {
