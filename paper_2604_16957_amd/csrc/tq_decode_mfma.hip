@@ -17,6 +17,7 @@
 // of its K phase, the next supertile's K part during the current softmax / P V phase).  The ring is
 // only two stages deep on purpose: once the last byte has landed every wave still has `ring depth`
 // supertiles to compute, and at 16 supertiles per wave that drain outweighs a deeper prefetch.
+// The stream is read once, and its loads say so (non-temporal cache policy, template parameter NT).
 //
 // Exactness: codes 0..15 enter the MFMA as fp16 SUBNORMALS (the nibble sits in the low mantissa
 // bits, value c*2^-24, or c*2^-20 for a nibble at bit 4) so unpacking is one AND per pair of
@@ -51,10 +52,16 @@
 //   it reads the same packed word of 8 tokens and transposes 8x8 nibbles with two v_perm_b32 stages;
 //   the nibble-level stage is free because the unpack masks already separate even and odd nibbles.
 //
-// Work split: grid (n_splits, H_kv, B), 8 waves per block, one block per compute unit; the waves of
-// a block share the chunk's 32-token supertiles in a fixed pattern (9:7 between the older and the
-// younger wave of a SIMD, see the kernel), keep private online-softmax state, and are merged through
-// LDS so that the block writes one partial (o_c, m_c, l_c) per query head.
+// Work split: grid (n_splits, H_kv * kv_share, B), 8 waves per block, one block per compute unit; the
+// waves of a block share the chunk's 32-token supertiles in a fixed pattern (9:7 between the older and
+// the younger wave of a SIMD, see the kernel), keep private online-softmax state, and are merged through
+// LDS so that the block writes one partial (o_c, m_c, l_c) per query row.
+//
+// Query rows: the tile's GP columns take the G heads of the GQA group (Sec. 3.1), or, with several query
+// tokens per sequence (the sequence's last n_queries tokens, causal among themselves), the n_queries * G
+// rows (token, head) of one KV head; rows beyond one tile go to further blocks on the same KV head
+// (kv_share of them).  Per-row limits (causal end, window start) only exist in the masked path that the
+// ragged last supertile takes anyway.
 #include <atomic>
 #include <type_traits>
 
