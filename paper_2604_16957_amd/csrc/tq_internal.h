@@ -71,39 +71,43 @@ struct DecodeParams {
 };
 
 #ifdef __HIPCC__
-// Sec. 2.1, Eq. 2-3 for one group of 32 values (fp16 inputs widened to fp32): the fp16 scale and zero-point
-// and the 32 codes, element j of packed word i in bits 4j..4j+3.  Every fp32 step is a separately rounded
-// operation (no contraction, correctly rounded divides), so the bits are the same wherever this runs.
-__device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[4], half_t& s16, half_t& z16) {
+// Sec. 2.1, Eq. 2-3.  Every fp32 step is a separately rounded operation (no contraction, correctly rounded
+// divides), so the bits are the same wherever this runs.
+// Eq. 2 from a group's min and max: s = (max - min) / 15 stored as fp16 (a scale that rounds to zero becomes
+// 1.0), z = -min / s from the STORED scale (saturated, never -0).
+__device__ inline void quantize_scale_zero(float mn, float mx, half_t& s16, half_t& z16) {
 #pragma clang fp contract(off)
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-  // Eq. 2: s = (max - min) / 15, stored as fp16; a scale that rounds to zero becomes 1.0
   const float s32 = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
   s16 = (half_t)s32;
   if ((__builtin_bit_cast(uint16_t, s16) & 0x7FFFu) == 0) s16 = (half_t)1.0f;
-  const float sf = (float)s16;
-  // Eq. 2: z = -min / s from the STORED scale; saturate, and never store -0
-  const float z32 = __fdiv_rn(__fsub_rn(0.0f, mn), sf);
+  const float z32 = __fdiv_rn(__fsub_rn(0.0f, mn), (float)s16);
   z16 = (half_t)z32;
   uint16_t zb = __builtin_bit_cast(uint16_t, z16);
   if ((zb & 0x7FFFu) == 0x7C00u) zb = (uint16_t)((zb & 0x8000u) | 0x7BFFu);
   if (zb == 0x8000u) zb = 0;
   z16 = __builtin_bit_cast(half_t, zb);
-  const float zf = (float)z16;
-  // Eq. 3: q = clamp(round_half_even(x / s + z), 0, 15)
+}
+// Eq. 3 for 8 consecutive elements: q = clamp(round_half_even(x / s + z), 0, 15), element j in bits 4j..4j+3
+__device__ inline uint32_t quantize_word(const float* x, float sf, float zf) {
+#pragma clang fp contract(off)
+  uint32_t acc = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t acc = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float v = __fadd_rn(__fdiv_rn(x[8 * i + j], sf), zf);
-      const float r = fminf(fmaxf(rintf(v), 0.0f), 15.0f);
-      acc |= (uint32_t)r << (4 * j);
-    }
-    w[i] = acc;
+  for (int j = 0; j < 8; ++j) {
+    const float v = __fadd_rn(__fdiv_rn(x[j], sf), zf);
+    const float r = fminf(fmaxf(rintf(v), 0.0f), 15.0f);
+    acc |= (uint32_t)r << (4 * j);
   }
+  return acc;
+}
+// One group of 32 values (fp16 inputs widened to fp32): the fp16 scale and zero-point and the 32 codes.
+__device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[4], half_t& s16, half_t& z16) {
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+  quantize_scale_zero(mn, mx, s16, z16);
+  const float sf = (float)s16, zf = (float)z16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = quantize_word(x + 8 * i, sf, zf);
 }
 
 // Device-side chunk plan for per-sequence lengths.  Chunk length C (a multiple of 32): the tokens of all
