@@ -186,41 +186,37 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
   constexpr int PARTS = THREADS / D;
   // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  // chunks that exist for this sequence: all of them, or those that start before its own end
-  int n = p.n_splits, part_stride = p.n_splits;
-  if (p.seq_lens) {
-    const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
-    if (p.var_chunks > 0) {
-      const int c = var_chunk_tokens(p);
-      n = (var_len(p, sequence) + c - 1) / c;
-      part_stride = kMaxSplits;
-    } else {
-      n = min(n, (var_len(p, sequence) + p.tokens_per_split - 1) / p.tokens_per_split);
-    }
-  }
+  const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;   // chunk slots a row has in the workspace
   const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * part_stride;
   __shared__ float w_c[kMaxSplits];
   __shared__ float red_m[WAVES], red_l[WAVES];
   __shared__ float acc_part[PARTS][D];
 
-  // the first chunks of this thread's output element are asked for before anything else: they do not
-  // depend on the weights, so the kernel is about one memory round trip long
+  // The first chunks of this thread's output element, and the chunks' (m, l), are asked for before anything
+  // else: they depend neither on the weights nor on how many chunks the sequence has (slots past its last
+  // chunk hold stale values, read and then ignored), so the kernel is about one memory round trip long and
+  // the chunk plan below is worked out while the loads are in flight.
   constexpr int FIRST = 16;
   const int j = tid % D, part = tid / D;
   const float* src = p.part_o + ph0 * D + j;
   float pre[FIRST];
 #pragma unroll
-  for (int u = 0; u < FIRST; ++u) {
-    const int c = part + u * PARTS;
-    pre[u] = src[(int64_t)(c < n ? c : n - 1) * D];
-  }
+  for (int u = 0; u < FIRST; ++u) pre[u] = src[(int64_t)min(part + u * PARTS, part_stride - 1) * D];
+  float2 ml = {kNegBig, 0.0f};
+  if (tid < part_stride) ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
 
-  float m = kNegBig, l = 0.0f;
-  if (tid < n) {
-    const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
-    m = ml.x;
-    l = ml.y;
+  // chunks that exist for this sequence: all of them, or those that start before its own end
+  int n = p.n_splits;
+  if (p.seq_lens) {
+    const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
+    if (p.var_chunks > 0) {
+      const int c = var_chunk_tokens(p);
+      n = (var_len(p, sequence) + c - 1) / c;
+    } else {
+      n = min(n, (var_len(p, sequence) + p.tokens_per_split - 1) / p.tokens_per_split);
+    }
   }
+  const float m = tid < n ? ml.x : kNegBig, l = tid < n ? ml.y : 0.0f;
   float mw = m;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
@@ -244,7 +240,7 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
 #pragma unroll
   for (int u = 0; u < FIRST; ++u) {
     const int c = part + u * PARTS;
-    num = fmaf(pre[u], c < n ? w_c[c] : 0.0f, num);
+    num = c < n ? fmaf(pre[u], w_c[c], num) : num;
   }
   int c = part + FIRST * PARTS;
   for (; c + 7 * PARTS < n; c += 8 * PARTS) {

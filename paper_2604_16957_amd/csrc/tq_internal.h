@@ -110,11 +110,10 @@ __device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[
   for (int i = 0; i < 4; ++i) w[i] = quantize_word(x + 8 * i, sf, zf);
 }
 
-// Device-side chunk plan for per-sequence lengths.  Chunk length C (a multiple of 32): the tokens of all
-// sequences spread over p.var_chunks - p.batch chunks (every sequence's last chunk is partial, so the
-// list then has at most p.var_chunks entries: the grid), at least p.var_min_chunk, and long enough that
-// no sequence needs more than kMaxSplits.  Slot s of the list "all chunks of sequence 0, then of sequence 1, ..."
-// -> (b, chunk); returns false past the end of the list.  Everything here is wave-uniform.
+// Device-side chunk plan for per-sequence lengths.  One chunk length C for all sequences (var_chunk_tokens
+// below), so that the list "all chunks of sequence 0, then of sequence 1, ..." has at most p.var_chunks
+// entries: the grid.  Slot s of that list -> (b, chunk); returns false past the end of the list.
+// Everything here is wave-uniform.
 struct VarPlan { int chunk_tokens, b, chunk; };
 __device__ inline int var_full_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
 // The first token sequence b attends; the token its chunks are counted from (the same, except in a paged
@@ -129,26 +128,72 @@ __device__ inline int var_start(const DecodeParams& p, int b) {
   return p.block_table ? f & ~(kTile - 1) : f;
 }
 __device__ inline int var_len(const DecodeParams& p, int b) { return var_full_len(p, b) - var_start(p, b); }
-__device__ inline int var_chunk_tokens(const DecodeParams& p) {
-  long long total = 0;
-  for (int b = 0; b < p.batch; ++b) total += var_len(p, b);
-  const int budget = p.var_chunks - p.batch;      // >= var_chunks / 2 by the host's choice of var_chunks
-  int c = (int)((total + budget - 1) / budget);
-  c = max(c, p.var_min_chunk);
-  c = max(c, (p.seq_len + kMaxSplits - 1) / kMaxSplits);
-  return (c + kTile - 1) / kTile * kTile;
+// sum of x over the 64 lanes of the wave (the same value in every lane; all lanes must be active)
+__device__ inline int wave_sum(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x128, 0xF, 0xF, false);   // row_ror:8, 4, 2, 1: sum of each row of 16
+  x += __builtin_amdgcn_update_dpp(0, x, 0x124, 0xF, 0xF, false);
+  x += __builtin_amdgcn_update_dpp(0, x, 0x122, 0xF, 0xF, false);
+  x += __builtin_amdgcn_update_dpp(0, x, 0x121, 0xF, 0xF, false);
+  return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) + __builtin_amdgcn_readlane(x, 32) +
+         __builtin_amdgcn_readlane(x, 48);
 }
+// Tokens sequence (64 tile + lane) attends, 0 past the batch: the planner below keeps one sequence per lane.
+__device__ inline int var_len_of_lane(const DecodeParams& p, int tile) {
+  const int b = tile * 64 + (int)(threadIdx.x & 63);
+  return b < p.batch ? var_len(p, b) : 0;
+}
+// The chunk length: the smallest multiple of 32 tokens for which all sequences together need at most
+// p.var_chunks chunks (the grid), not below p.var_min_chunk and long enough that no sequence needs more than
+// kMaxSplits.  Lane l looks after sequences l, l + 64, ... (the first of them stays in a register: len0); the
+// count for a candidate length is a wave-wide sum, and the candidates are bisected between total / var_chunks
+// (too short unless every sequence ends on a chunk boundary) and total / (var_chunks - batch) (always enough:
+// a sequence wastes less than one chunk).  Called by whole waves at the start of a kernel; every wave of
+// every kernel of a call gets the same answer.
+__device__ inline int var_chunk_tokens(const DecodeParams& p, int len0) {
+  const int tiles = (p.batch + 63) >> 6;
+  long long mine = len0;
+  for (int t = 1; t < tiles; ++t) mine += var_len_of_lane(p, t);
+  const long long total = ((long long)wave_sum((int)(mine >> 24)) << 24) + wave_sum((int)(mine & 0xFFFFFF));
+  const int floor_c = max(p.var_min_chunk, (p.seq_len + kMaxSplits - 1) / kMaxSplits);
+  auto round_up = [](long long c) { return (int)((c + kTile - 1) / kTile * kTile); };
+  const int budget = p.var_chunks - p.batch;      // >= var_chunks / 2 by the host's choice of var_chunks
+  int hi = round_up(max((long long)floor_c, (total + budget - 1) / budget));
+  int lo = round_up(max((long long)floor_c, (total + p.var_chunks - 1) / p.var_chunks));
+  while (lo < hi) {
+    const int mid = (lo + (hi - lo) / 2) / kTile * kTile;        // lo <= mid < hi, a multiple of 32
+    int n = (len0 + mid - 1) / mid;
+    for (int t = 1; t < tiles; ++t) n += (var_len_of_lane(p, t) + mid - 1) / mid;
+    if (wave_sum(n) <= p.var_chunks) hi = mid;
+    else lo = mid + kTile;
+  }
+  return hi;
+}
+__device__ inline int var_chunk_tokens(const DecodeParams& p) { return var_chunk_tokens(p, var_len_of_lane(p, 0)); }
+// Slot of the chunk list -> (sequence, chunk of it); false past the end of the list.  The chunk counts sit one
+// sequence per lane; the list is walked with scalar reads of those lanes (no memory access, no division).
 __device__ inline bool var_plan(const DecodeParams& p, int slot, VarPlan& out) {
-  out.chunk_tokens = var_chunk_tokens(p);
+  const int len0 = var_len_of_lane(p, 0);
+  const int c = var_chunk_tokens(p, len0);
+  out.chunk_tokens = c;
+  const int tiles = (p.batch + 63) >> 6;
   int first = 0;
-  for (int b = 0; b < p.batch; ++b) {
-    const int n = (var_len(p, b) + out.chunk_tokens - 1) / out.chunk_tokens;
-    if (slot < first + n) {
-      out.b = b;
-      out.chunk = slot - first;
-      return true;
+  for (int t = 0; t < tiles; ++t) {
+    const int n = ((t == 0 ? len0 : var_len_of_lane(p, t)) + c - 1) / c;    // this lane's sequence: its chunks
+    const int in_tile = wave_sum(n);
+    if (slot < first + in_tile) {
+      const int lanes = min(64, p.batch - t * 64);
+      for (int i = 0; i < lanes; ++i) {
+        const int ni = __builtin_amdgcn_readlane(n, i);
+        if (slot < first + ni) {
+          out.b = t * 64 + i;
+          out.chunk = slot - first;
+          return true;
+        }
+        first += ni;
+      }
+      return false;                               // (not reached: the tile's counts add up to in_tile)
     }
-    first += n;
+    first += in_tile;
   }
   return false;
 }
