@@ -932,7 +932,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   __syncthreads();
 
-  // ---- merge the waves, write one partial per query head (Sec. 3.2)
+  // ---- merge the waves, write one partial per query head (Sec. 3.2); where the sequence is a single
+  //      chunk and the kernel is to produce the output, that partial, normalised, IS the output
+  const bool direct = p.merge_slot >= 0 && p.n_splits == 1;
   for (int idx = threadIdx.x; idx < G * D; idx += NW * 64) {
     const int h = idx / D, j = idx % D;
     const float unit = (j & 1) ? 0x1p20f : 0x1p24f;          // odd dims were read from the high nibble position
@@ -953,13 +955,17 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       num = fmaf(hat_v[j], e, num);
       den += e;
     }
+    if (direct) {
+      p.out[query_row(h) * D + j] = (half_t)(num / den);
+      continue;
+    }
     const int64_t ph = query_row(h) * part_stride + split;
     // device-scope stores: they go through to where every compute die sees them (the L2 caches of
     // different dies are not coherent with each other), so no cache-wide write-back is needed later
     st_dev(p.part_o + ph * D + j, num);
     if (j == 0) { st_dev(p.part_ml + ph * 2, mg); st_dev(p.part_ml + ph * 2 + 1, den); }
   }
-  if (p.merge_slot < 0) return;
+  if (p.merge_slot < 0 || direct) return;
 
   // ---- chunk merge (Eq. 6) by whichever block of this (b, kv head) finishes last.  A block publishes
   //      its partial (device-scope stores, waited for), then counts itself in; the one that sees all
