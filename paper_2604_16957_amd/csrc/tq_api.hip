@@ -38,16 +38,21 @@ constexpr int kBlocksValu = 512;   // generic kernel: 4-wave blocks, two per com
 // then take in at most 64 tiles, which bounds the rounding they pick up however long the sequence is.
 constexpr int kMaxChunkTokens = 16384;
 
-// Chunks of whole 32-token tiles, `target_blocks` blocks in all, never an empty chunk; with
-// `tiles_per_block_min` > 1 short sequences get fewer, fuller blocks (one tile per wave at least).
+// Chunks of whole 32-token tiles, never an empty chunk.  The blocks of a launch run in rounds of
+// `target_blocks` (what the chip holds at once): as many chunks as fill one round without spilling into a
+// second (a 257th block would wait for a whole block's time), or, where that makes chunks longer than
+// kMaxChunkTokens, as many as fill the fewest rounds that do not.  With `tiles_per_block_min` > 1 short
+// sequences get fewer, fuller blocks (one tile per wave at least).
 Plan plan_splits(int batch, int n_kv_heads, int seq_len, int requested, int target_blocks, int tiles_per_block_min) {
   const int tiles = (seq_len + tq::kTile - 1) / tq::kTile;
   int n = requested;
   if (n <= 0) {
     const int64_t rows = (int64_t)batch * n_kv_heads;
-    n = (int)std::max<int64_t>(1, (target_blocks + rows - 1) / rows);
+    const int64_t need = (seq_len + kMaxChunkTokens - 1) / kMaxChunkTokens;
+    const int64_t rounds = std::max<int64_t>(1, (need * rows + target_blocks - 1) / target_blocks);
+    n = (int)std::max<int64_t>({1, need, rounds * target_blocks / rows});
     n = std::min(n, std::max(1, tiles / tiles_per_block_min));
-    n = std::max(n, (seq_len + kMaxChunkTokens - 1) / kMaxChunkTokens);
+    n = (int)std::max<int64_t>(n, need);
   }
   n = std::max(1, std::min({n, tiles, tq::kMaxSplits}));
   const int tiles_per = (tiles + n - 1) / n;
@@ -222,7 +227,7 @@ int run_partial(PartialRequest& rq) {
     // `target` chunks over all sequences of a KV head (a requested n_splits keeps the fixed chunking)
     // per KV head: r rounds of target / H_kv chunks, r the smallest count that leaves at least half of them
     // once every sequence has been granted its partial last chunk
-    const int per_round = std::max(1, (target + rows_per_batch - 1) / rows_per_batch);
+    const int per_round = std::max(1, target / rows_per_batch);          // (one round never spills into a second)
     const int rounds = std::max(1, (2 * cache->batch + per_round - 1) / per_round);
     p.var_chunks = rounds * per_round;
     p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;
