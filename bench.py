@@ -54,6 +54,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-baseline", action="store_true", help="skip the unfused GPU comparator")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled oracle check")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the read-stream probe")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of packed_bytes (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -340,6 +341,30 @@ def main():
     kernel_us = e0.elapsed_time(e1) * 1e3 / args.steps
     achieved = packed_bytes / (kernel_us * 1e-6) / 1e9
 
+    # ---- what the machine delivers for a read-once stream of this size: the library's read probe (non-temporal
+    #      loads, nothing else) over rotating buffers of the same number of bytes, timed like the kernel
+    ceiling = None
+    unit16 = 16 << 20
+    probe_bytes = packed_bytes // unit16 * unit16
+    if probe_bytes > 0 and not args.no_ceiling:
+        bufs = [torch.empty(probe_bytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(args.buffers)]
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for i in range(args.warmup):
+            tq.tq_probe_read_stream(bufs[i % args.buffers], sink)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            tq.tq_probe_read_stream(bufs[i % args.buffers], sink)
+        e1.record()
+        torch.cuda.synchronize()
+        probe_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        probe_gbps = probe_bytes / (probe_us * 1e-6) / 1e9
+        ceiling = {"kernel": "tq_probe_read_stream (read-only, non-temporal loads)", "bytes_per_launch": probe_bytes,
+                   "us_per_launch": round(probe_us, 3), "GBps": round(probe_gbps, 1),
+                   "frac_of_peak": round(probe_gbps / HBM_PEAK_GBPS, 4),
+                   "decode_kernel_vs_this": round(achieved / probe_gbps, 4)}
+        del bufs
+
     if args.calibrate_copy:      # known traffic: reads packed_bytes, writes packed_bytes
         src = torch.empty(packed_bytes, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -463,7 +488,8 @@ def main():
                      "traffic": None, "kernel_us_mean": round(kernel_us, 3),
                      "kernel_us_bracketed_mean": round(kernel_us_bracketed, 3),
                      "kernel_us_bracketed_median": round(statistics.median(k_us), 3),
-                     "algorithmic_bytes_per_launch": packed_bytes},
+                     "algorithmic_bytes_per_launch": packed_bytes,
+                     "measured_read_stream": ceiling},
         "cpu_baseline": cpu,
         "unfused_gpu_baseline": baseline,
         "oracle_check": check,

@@ -227,5 +227,6 @@ bool mfma_can_merge(int batch, int n_kv_heads);
 bool mfma_can_append(int head_dim, int gqa);   // whether launch_partial_mfma honours k_new / v_new for this shape
 hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
+hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 }  // namespace tq

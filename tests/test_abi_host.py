@@ -228,6 +228,15 @@ def test_decode_launch_count_query():
     assert f(ctypes.byref(big), 64, 16, 0.1, None) == 2
 
 
+def test_read_probe_rejects_bad_arguments_without_a_gpu():
+    f = B.raw().tq_probe_read_stream
+    assert f(None, 1 << 24, FAKE, None) == B.TQ_ERR_NULL
+    assert f(FAKE, 1 << 24, None, None) == B.TQ_ERR_NULL
+    assert f(FAKE + 8, 1 << 24, FAKE, None) == B.TQ_ERR_ALIGN
+    assert f(FAKE, 0, FAKE, None) == B.TQ_ERR_SHAPE
+    assert f(FAKE, (1 << 24) + 16, FAKE, None) == B.TQ_ERR_SHAPE
+
+
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "_LIB_PATH", tmp_path / "nope.so")

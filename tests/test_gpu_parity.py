@@ -849,3 +849,12 @@ def test_many_sequences_with_their_own_lengths():
     out = tq.tq_sdpa_int4_decode_paged(pool, table, q.cuda(), lens_dev, S, w.attn_scale)
     torch.cuda.synchronize()
     assert_close(out, ref, "40 sequences, paged")
+
+
+def test_read_probe_runs_and_leaves_its_sink_alone():
+    """The measurement aid reads its buffer and stores nothing (the XOR of a constant fill is not the magic value)."""
+    src = torch.full((1 << 24,), 7, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tq.tq_probe_read_stream(src, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0 and bool((src == 7).all())
