@@ -148,8 +148,11 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   // (more query rows than the kernel's tile holds: several blocks stream each KV head, counted as rows of their own)
   const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, rows) : 1);
   const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, rows_per_batch, windowed(seq_len, opts), cache->head_dim);
+  // a sequence that is one chunk needs no merge at all: the kernel writes the output itself, whatever the size
+  const bool single = use_mfma && plan_splits(cache->batch, rows_per_batch, windowed(seq_len, opts),
+                                               opts ? opts->n_splits : 0, kBlocksMfma, 8).n_splits == 1;
   return {true, use_mfma,
-          use_mfma && bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, rows_per_batch)};
+          use_mfma && (bytes <= kMergeInKernelMaxBytes || single) && tq::mfma_can_merge(cache->batch, rows_per_batch)};
 }
 
 // One launch of phase 1: what to attend, and what came of it.

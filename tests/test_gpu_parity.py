@@ -858,3 +858,16 @@ def test_read_probe_runs_and_leaves_its_sink_alone():
     tq.tq_probe_read_stream(src, sink)
     torch.cuda.synchronize()
     assert int(sink.item()) == 0 and bool((src == 7).all())
+
+
+def test_many_short_sequences_take_the_single_chunk_route():
+    """More (sequence, KV head) rows than the chip has compute units: every sequence is one chunk and the kernel
+    writes the output itself, in one launch, also above the size where longer sequences get a merge kernel."""
+    w = wl.custom(batch=40, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=1500, seed=1500, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    assert tq.tq_kv_bytes(w.batch, w.n_kv_heads, w.seq_len, w.head_dim) > 48 << 20
+    assert tq.tq_decode_launches(cache, w.n_q_heads, w.seq_len, w.attn_scale) == 1
+    out = tq.tq_sdpa_int4_decode(cache, q.cuda(), w.seq_len, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "40 sequences of 1500 tokens")
