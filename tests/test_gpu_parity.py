@@ -871,3 +871,20 @@ def test_many_short_sequences_take_the_single_chunk_route():
     out = tq.tq_sdpa_int4_decode(cache, q.cuda(), w.seq_len, w.attn_scale)
     torch.cuda.synchronize()
     assert_close(out, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "40 sequences of 1500 tokens")
+
+
+def test_quarter_million_tokens():
+    """A context longer than any benchmark shape (the paper's largest fitting context is 236K tokens): the chunk
+    cap holds every accumulator to 16K tokens, so the error does not grow with the length."""
+    S = 250_007
+    w = wl.custom(n_q_heads=8, n_kv_heads=1, head_dim=128, seq_len=S, seed=2500, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    assert_cache_bit_exact(cache, ocache, S)
+    ref = oracle_attend(q, ocache, S, w.attn_scale)
+    for variant in (0, 1):
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=variant)
+        torch.cuda.synchronize()
+        max_abs, rel = assert_close(out, ref, f"S={S} variant={variant}")
+        print(f"\nS={S} variant={variant}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}")
