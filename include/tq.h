@@ -113,9 +113,10 @@ int tq_quantize_kv_varlen(const tq_kv_cache* cache, const void* k_new, const voi
  * Same result as tq_sdpa_int4_partial followed by tq_sdpa_int4_reduce on the same stream (up to the
  * order of the fp32 sums of the merge).  For short sequences, where launch overhead outweighs the
  * stream (see tq_decode_launches), the matrix-core kernel does both in ONE launch: the block that
- * finishes a (batch, KV head) last merges its chunks in place.  That path keeps its arrival counters in device memory owned by the
- * library (16 sets, taken in turn, left zero by every launch): at most 16 decode calls may be
- * in flight on one device at the same time.
+ * finishes a (batch, KV head) last merges its chunks in place (a sequence that is a single chunk
+ * needs no merge: its block writes out).  That path keeps its arrival counters in device memory
+ * owned by the library (16 sets, taken in turn, left zero by every launch): at most 16 decode calls
+ * may be in flight on one device at the same time.
  * Errors: NULL, SHAPE, EMPTY (seq_len < 1), CAPACITY (seq_len > capacity), WORKSPACE,
  * UNSUPPORTED, HIP. */
 int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
@@ -125,8 +126,10 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
 /* One decode step in one call: tq_quantize_kv(cache, k_new, v_new, seq_len - 1, 1) followed by
  * tq_sdpa_int4_decode(cache, q, ..., seq_len, ...), i.e. the new token of every sequence (k_new,
  * v_new: fp16 [batch][n_kv_heads][1][head_dim]) is quantised, written at position seq_len - 1 and
- * attended together with the seq_len - 1 cached ones.  Same stored bits and same result as the two
- * calls; where the matrix-core kernel runs at head_dim 128 the append costs no launch of its own
+ * attended together with the seq_len - 1 cached ones (with opts->n_queries = n > 1: n new tokens,
+ * written at seq_len - n .. seq_len - 1, each attended by its own query).  Same stored bits and same
+ * result as the two calls; where the matrix-core kernel runs at head_dim 128, one query token and at
+ * most 8 query heads per KV head, the append costs no launch of its own
  * (the block that holds the end of a sequence quantises the token, stores it and adds its
  * attention term from registers), otherwise the two kernels are launched one after the other.
  * Errors: those of the two calls. */
