@@ -165,8 +165,8 @@ struct PartialRequest {
   void* out = nullptr;                 // non-null: the kernel may merge the chunks itself and write it
   void* workspace;
   const tq_decode_opts* opts = nullptr;
-  const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it)
-  const void* v_new = nullptr;
+  const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it);
+  const void* v_new = nullptr;         // taken in by the decode kernel where it can, else by the merge kernel
   const tq::PagedView* paged = nullptr;
   void* stream = nullptr;
   // results
@@ -197,8 +197,10 @@ int run_partial(PartialRequest& rq) {
   if (rq.paged && attended < seq_len) attended = std::min(seq_len, attended + tq::kTile - 1);
   // append-and-attend in the kernel: the new token (the last attended one) does not come from the cache
   const bool append = rq.k_new != nullptr && appends_in_kernel(cache, n_q_heads, seq_len, seq_lens, r, opts);
+  // ... or in the merge kernel, which then has to run
+  const bool append_in_merge = rq.k_new != nullptr && !append;
   const int first = seq_len - attended;           // first attended token
-  if (append) --attended;
+  if (append || append_in_merge) --attended;
   const int rows_per_batch =
       cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : 1);
   const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
@@ -237,9 +239,14 @@ int run_partial(PartialRequest& rq) {
     p.n_splits = tq::kMaxSplits;
   }
   rq.params = p;
+  if (append_in_merge) {
+    rq.params.k_new = static_cast<const half_t*>(rq.k_new);
+    rq.params.v_new = static_cast<const half_t*>(rq.v_new);
+    rq.params.append_pos = seq_len - 1;
+  }
   rq.n_splits = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(rq.stream);
-  rq.merged = rq.out != nullptr && r.merge && !seq_lens;
+  rq.merged = rq.out != nullptr && r.merge && !seq_lens && !append_in_merge;
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
 }
@@ -412,7 +419,10 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   rq.workspace = workspace;
   rq.opts = opts;
   rq.stream = stream;
-  if (appends_in_kernel(cache, n_q_heads, seq_len, nullptr, r, opts)) {
+  // The token is taken in by the decode kernel where that kernel can (one launch fewer, nothing read back), else
+  // by the merge kernel (one query token, at least one cached token to attend); else the append kernel runs first.
+  if (appends_in_kernel(cache, n_q_heads, seq_len, nullptr, r, opts) ||
+      (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2)) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {                                        // the append kernel first, then the plain decode

@@ -217,12 +217,64 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
     }
   }
   const float m = tid < n ? ml.x : kNegBig, l = tid < n ? ml.y : 0.0f;
+
+  // Append-and-attend in the merge (p.k_new set; one query token, common length): the step's new token is not in
+  // the chunks.  Every block quantises it for its KV head with the device function the append kernel uses (same
+  // bits; Sec. 2.1), the block of the group's first query head stores it, and its attention term enters Eq. 6
+  // as one more chunk: m = its score, l = 1, o = its dequantised V.
+  constexpr int NG = D / kGroup;
+  __shared__ float hat[2][D];
+  __shared__ float red_a[WAVES];
+  const bool appending = p.k_new != nullptr;
+  float a_new = kNegBig;
+  if (appending) {
+    const int kv = h / p.gqa;
+    if (tid < 8 * NG) {                           // four lanes per group of 32 elements, eight elements each
+      const int which = tid / (4 * NG), g = (tid >> 2) % NG, part4 = tid & 3;   // 0 = K, 1 = V
+      const half_t* src = (which ? p.v_new : p.k_new) + (int64_t)(b * p.n_kv_heads + kv) * D + g * kGroup + part4 * 8;
+      Pack16 u;
+      u.v = *reinterpret_cast<const uint4*>(src);
+      float x[8];
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) x[jj] = (float)u.h[jj];
+      float mn = x[0], mx = x[0];
+#pragma unroll
+      for (int jj = 1; jj < 8; ++jj) { mn = fminf(mn, x[jj]); mx = fmaxf(mx, x[jj]); }
+      // the group's min and max: over the four lanes (exact in any order)
+      mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
+      mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
+      half_t s16, z16;
+      quantize_scale_zero(mn, mx, s16, z16);
+      const float sf = (float)s16, zf = (float)z16;
+      const uint32_t w = quantize_word(x, sf, zf);
+      if (h % p.gqa == 0) {
+        const int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + p.append_pos;
+        uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes) + row * (D / 2) + g * (kGroup / 2);
+        reinterpret_cast<uint32_t*>(codes)[part4] = w;
+        if (part4 == 0) const_cast<half_t*>(which ? p.v_scale : p.k_scale)[row * NG + g] = s16;
+        if (part4 == 1) const_cast<half_t*>(which ? p.v_zero : p.k_zero)[row * NG + g] = z16;
+      }
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj)
+        hat[which][g * kGroup + part4 * 8 + jj] = ((float)((w >> (4 * jj)) & 0xFu) - zf) * sf;   // Eq. 3
+    }
+    __syncthreads();
+    float prod = tid < D ? (float)p.q[(int64_t)(b * p.n_q_heads + h) * D + tid] * hat[0][tid] : 0.0f;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) prod += __shfl_xor(prod, off);
+    if ((tid & 63) == 0) red_a[tid >> 6] = prod;
+    __syncthreads();
+    float dot = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) dot += red_a[w];
+    a_new = dot * p.scale_log2;
+  }
   float mw = m;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
   if ((tid & 63) == 0) red_m[tid >> 6] = mw;
   __syncthreads();
-  float mg = red_m[0];
+  float mg = fmaxf(red_m[0], a_new);
 #pragma unroll
   for (int w = 1; w < WAVES; ++w) mg = fmaxf(mg, red_m[w]);
   const float w = exp2f(m - mg);
@@ -237,6 +289,11 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
   for (int w = 4; w < WAVES; w += 4) den += (red_l[w] + red_l[w + 1]) + (red_l[w + 2] + red_l[w + 3]);
 
   float num = 0.0f;
+  if (appending) {
+    const float w_new = exp2f(a_new - mg);
+    den += w_new;
+    if (part == 0) num = w_new * hat[1][j];
+  }
 #pragma unroll
   for (int u = 0; u < FIRST; ++u) {
     const int c = part + u * PARTS;
