@@ -128,11 +128,10 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
  * v_new: fp16 [batch][n_kv_heads][1][head_dim]) is quantised, written at position seq_len - 1 and
  * attended together with the seq_len - 1 cached ones (with opts->n_queries = n > 1: n new tokens,
  * written at seq_len - n .. seq_len - 1, each attended by its own query).  Same stored bits and same
- * result as the two calls.  With one query token the append costs no launch of its own: where the
- * matrix-core kernel runs at head_dim 128 with at most 8 query heads per KV head, the block that
- * holds the end of a sequence quantises the token, stores it and adds its attention term from
- * registers; elsewhere the merge kernel does the same.  Otherwise (several query tokens, a window
- * or sequence of one token) the append kernel is launched first.
+ * result as the two calls.  With one query token the append costs no launch of its own: the decode
+ * kernel attends the cached tokens, and the merge kernel quantises the new one, stores it and adds
+ * its attention term from registers.  Otherwise (several query tokens, a window or sequence of one
+ * token) the append kernel is launched first.
  * Errors: those of the two calls. */
 int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, const void* v_new,
                                const void* q, int32_t n_q_heads, int32_t seq_len, float attn_scale,

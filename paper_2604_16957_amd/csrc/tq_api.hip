@@ -165,8 +165,8 @@ struct PartialRequest {
   void* out = nullptr;                 // non-null: the kernel may merge the chunks itself and write it
   void* workspace;
   const tq_decode_opts* opts = nullptr;
-  const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it);
-  const void* v_new = nullptr;         // taken in by the decode kernel where it can, else by the merge kernel
+  const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it),
+  const void* v_new = nullptr;         // taken in by the merge kernel, which then has to run
   const tq::PagedView* paged = nullptr;
   void* stream = nullptr;
   // results
@@ -174,13 +174,6 @@ struct PartialRequest {
   bool merged = false;                 // `out` has been written
   DecodeParams params{};               // what the kernel was given (the merge kernel takes the same)
 };
-
-// Whether the decode kernel takes the step's new token in itself (else the append kernel runs first).
-bool appends_in_kernel(const tq_kv_cache* cache, int n_q_heads, int seq_len, const int32_t* seq_lens, const Route& r,
-                       const tq_decode_opts* opts) {
-  return r.use_mfma && !seq_lens && windowed(seq_len, opts) >= 2 && queries_of(opts) == 1 &&
-         tq::mfma_can_append(cache->head_dim, n_q_heads / cache->n_kv_heads);
-}
 
 // Phase 1 (and, with `out`, the whole decode where the matrix-core kernel can merge in place).
 int run_partial(PartialRequest& rq) {
@@ -195,12 +188,10 @@ int run_partial(PartialRequest& rq) {
   int attended = windowed(seq_len, opts);         // chunks cover the attended tokens only
   // (paged cache: counted from the supertile boundary before the window, see var_start)
   if (rq.paged && attended < seq_len) attended = std::min(seq_len, attended + tq::kTile - 1);
-  // append-and-attend in the kernel: the new token (the last attended one) does not come from the cache
-  const bool append = rq.k_new != nullptr && appends_in_kernel(cache, n_q_heads, seq_len, seq_lens, r, opts);
-  // ... or in the merge kernel, which then has to run
-  const bool append_in_merge = rq.k_new != nullptr && !append;
+  // append-and-attend: the new token (the last attended one) does not come from the cache
+  const bool append_in_merge = rq.k_new != nullptr;
   const int first = seq_len - attended;           // first attended token
-  if (append || append_in_merge) --attended;
+  if (append_in_merge) --attended;
   const int rows_per_batch =
       cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : 1);
   const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
@@ -221,11 +212,6 @@ int run_partial(PartialRequest& rq) {
     p.block_table = rq.paged->block_table;
     p.max_blocks = rq.paged->max_blocks;
     p.page_shift = rq.paged->page_shift;
-  }
-  if (append) {
-    p.k_new = static_cast<const half_t*>(rq.k_new);
-    p.v_new = static_cast<const half_t*>(rq.v_new);
-    p.append_pos = seq_len - 1;
   }
   if (seq_lens && !(opts && opts->n_splits > 0)) {
     // per-sequence lengths, no chunk count asked for: the kernels plan the chunks themselves from the lengths,
@@ -419,10 +405,9 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   rq.workspace = workspace;
   rq.opts = opts;
   rq.stream = stream;
-  // The token is taken in by the decode kernel where that kernel can (one launch fewer, nothing read back), else
-  // by the merge kernel (one query token, at least one cached token to attend); else the append kernel runs first.
-  if (appends_in_kernel(cache, n_q_heads, seq_len, nullptr, r, opts) ||
-      (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2)) {
+  // The merge kernel takes the token in (one query token, at least one cached token to attend: no append launch,
+  // nothing read back); else the append kernel runs first.
+  if (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {                                        // the append kernel first, then the plain decode

@@ -1,7 +1,5 @@
 // Matrix-core fused int4 decode attention for gfx950 (phase 1 of Sec. 3.2: per-chunk partials; for
-// short sequences also phase 2, the chunk merge of Eq. 6, done by the block that finishes last; and,
-// on request, the quantise-append of the step's new token, Sec. 2.1, done by the block that holds the
-// end of the sequence, which adds the token's attention term from registers instead of reading it back).
+// short sequences also phase 2, the chunk merge of Eq. 6, done by the block that finishes last).
 //
 // Why matrix cores: with a GQA group of G query heads every stored element is used by G heads;
 // at G=8 and d=128 that is 25.6 flop per HBM byte, above the vector-ALU ridge of the chip, so the
@@ -127,13 +125,7 @@ struct Cfg {
   static constexpr int QBLK = GP * D * 2;
   static constexpr bool QSEP = !ALIAS && RING + MERGE + NW * QBLK <= 160 * 1024;
   static constexpr int OFF_QBLK = RING + MERGE;
-  // Append-and-attend (offered where the query area is separate): the new token's fp16 K and V land at
-  // OFF_NEW; its dequantised V and its per-head scores wait at OFF_HAT for the block merge.
-  static constexpr int OFF_NEW = OFF_QBLK + NW * QBLK;
-  static constexpr int OFF_HAT = OFF_NEW + 2 * D * 2;
-  static constexpr int HAT = (D + 16) * 4;
-  static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE)
-                                    : RING + MERGE + (QSEP ? NW * QBLK + 2 * D * 2 + HAT : 0);
+  static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE) : RING + MERGE + (QSEP ? NW * QBLK : 0);
   // The fp16 scale and zero-point arrays are fetched dword by dword (two groups of one token), and the
   // direct loads may gather: with NA == 2 a lane needs exactly one dword per token, so the dwords are
   // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads.
@@ -469,18 +461,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
   //      Where the query block has to borrow the last ring slot, that slot is filled once the query
   //      operands sit in registers.
-  // Append-and-attend: the block of the last chunk also takes in the sequence's new token; its last wave
-  // (a younger one, which has slack) fetches, quantises and stores it and works out its attention term.
-  const bool appender = C::QSEP && p.k_new != nullptr && split == p.n_splits - 1;
-  if (appender && wave == NW - 1) {
-    const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + C::OFF_NEW;
-    const int64_t tok = (int64_t)(b * p.n_kv_heads + kv) * D;
-#pragma unroll
-    for (int u = 0; u < D / 128; ++u) {
-      dma4_lane(reinterpret_cast<const char*>(p.k_new + tok) + u * 256 + lane * 4, l + u * 256);
-      dma4_lane(reinterpret_cast<const char*>(p.v_new + tok) + u * 256 + lane * 4, l + 2 * D + u * 256);
-    }
-  }
   constexpr int NPRE = C::QSEP ? NS : NS - 1;     // stages issued before the query operands are built
   char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + C::OFF_V;
   {
@@ -542,60 +522,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
-  if constexpr (C::QSEP) {
-    if (appender && wave == NW - 1) {
-      // lanes 0..NG-1: the K groups of the new token, lanes NG..2NG-1: its V groups (Sec. 2.1, one group each)
-      float* const hat_v = reinterpret_cast<float*>(smem + C::OFF_HAT);    // [D] dequantised V of the new token
-      float* const hat_m = hat_v + D;                                      // [GP] its scores, log2 units
-      const int which = lane / NG, g = lane % NG;
-      float dot[GP];
-#pragma unroll
-      for (int h = 0; h < GP; ++h) dot[h] = 0.0f;
-      if (lane < 2 * NG) {
-        const half8v* src = reinterpret_cast<const half8v*>(smem + C::OFF_NEW + (which * D + g * kGroup) * 2);
-        float x[kGroup];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const half8v u = src[i];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[8 * i + j] = (float)u[j];
-        }
-        uint32_t w[4];
-        half_t s16, z16;
-        quantize_group32(x, w, s16, z16);
-        const int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + p.append_pos;
-        uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes) + row * TB + g * (kGroup / 2);
-        *reinterpret_cast<uint4v*>(codes) = uint4v{w[0], w[1], w[2], w[3]};
-        const_cast<half_t*>(which ? p.v_scale : p.k_scale)[row * NG + g] = s16;
-        const_cast<half_t*>(which ? p.v_zero : p.k_zero)[row * NG + g] = z16;
-        const float sf = (float)s16, zf = (float)z16;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[8 * i + j] = ((float)((w[i] >> (4 * j)) & 0xFu) - zf) * sf;   // Eq. 3
-        if (which == 1) {
-#pragma unroll
-          for (int j = 0; j < kGroup; ++j) hat_v[g * kGroup + j] = x[j];
-        } else {
-          const _Float16* qrow = reinterpret_cast<const _Float16*>(q_area) + g * kGroup;
-#pragma unroll
-          for (int h = 0; h < GP; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const half8v u = *reinterpret_cast<const half8v*>(qrow + h * D + i * 8);
-#pragma unroll
-              for (int j = 0; j < 8; ++j) dot[h] = fmaf((float)u[j], x[8 * i + j], dot[h]);
-            }
-        }
-      }
-#pragma unroll
-      for (int h = 0; h < GP; ++h) {              // sum over the NG lanes that hold K groups (the others hold 0)
-#pragma unroll
-        for (int off = 1; off < NG; off <<= 1) dot[h] += __shfl_xor(dot[h], off);
-        if (lane == 0) hat_m[h] = h < G ? dot[h] * p.scale_log2 : kNegBig;
-      }
-    }
-  }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
   if (!C::QSEP && n_mine > 0) {
     if (NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
@@ -941,19 +867,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     float mg = lds_m[h];
 #pragma unroll
     for (int w = 1; w < NW; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
-    const float* hat_v = reinterpret_cast<const float*>(smem + C::OFF_HAT);
-    if (appender) mg = fmaxf(mg, hat_v[D + h]);
     float num = 0.0f, den = 0.0f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
       num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
       den = fmaf(lds_l[w * GP + h], e, den);
-    }
-    if (appender) {                               // the new token: weight e^(a - m), value its dequantised V (Alg. 1)
-      const float e = __builtin_amdgcn_exp2f(hat_v[D + h] - mg);
-      num = fmaf(hat_v[j], e, num);
-      den += e;
     }
     if (direct) {
       p.out[query_row(h) * D + j] = (half_t)(num / den);
@@ -1087,22 +1006,12 @@ bool mfma_supported(int head_dim, int gqa) { return kv_share_of(head_dim, gqa) >
 
 bool mfma_can_merge(int batch, int n_kv_heads) { return (int64_t)batch * n_kv_heads <= kCountersPerSlot; }
 
-bool mfma_can_append(int head_dim, int gqa) {
-  const int share = kv_share_of(head_dim, gqa);
-  if (share != 1) return false;                   // (several blocks per KV head would all write the token)
-  const int gp = padded_gqa(head_dim, gqa);
-  if (head_dim == 128 && gp == 8) return Cfg<128, 8, 8>::QSEP;
-  if (head_dim == 128 && gp == 4) return Cfg<128, 4, 8>::QSEP;
-  if (head_dim == 256 && gp == 2) return Cfg<256, 2, 8>::QSEP;
-  return false;
-}
-
 hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim, bool merge_in_kernel,
                                hipStream_t s) {
   static std::atomic<unsigned int> next_slot{0};
   DecodeParams p = p_in;
   if (p.n_queries < 1) p.n_queries = 1;
-  if (p.n_queries > kMaxQueries || (p.n_queries > 1 && p.k_new != nullptr)) return hipErrorNotSupported;
+  if (p.n_queries > kMaxQueries) return hipErrorNotSupported;
   p.gqa_full = p.gqa;
   p.kv_share = kv_share_of(head_dim, p.gqa * p.n_queries);
   if (p.kv_share < 1) return hipErrorNotSupported;

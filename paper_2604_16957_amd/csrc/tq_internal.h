@@ -59,10 +59,9 @@ struct DecodeParams {
   // block_table[b * max_blocks + (t >> page_shift)] at row t & (row_stride - 1).
   const int32_t* block_table;
   int32_t max_blocks, page_shift;
-  // Append-and-attend in one launch (matrix-core kernel, d=128, common length): k_new / v_new non-null =
-  // one new token per sequence, fp16 [B][H_kv][1][D]; it is quantised and written at token append_pos of its
-  // row by the block of the last chunk, which also adds its attention term; seq_len then counts the cached
-  // tokens only.
+  // Append-and-attend (merge kernel, one query token, common length): k_new / v_new non-null = one new token per
+  // sequence, fp16 [B][H_kv][1][D], not among the tokens the chunks cover; the merge kernel quantises it, writes it
+  // at token append_pos of its row and adds its attention term to Eq. 6.
   const half_t* k_new;
   const half_t* v_new;
   int32_t append_pos;
@@ -224,7 +223,6 @@ bool mfma_supported(int head_dim, int gqa);
 int mfma_kv_share(int head_dim, int gqa);
 // With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
 bool mfma_can_merge(int batch, int n_kv_heads);
-bool mfma_can_append(int head_dim, int gqa);   // whether launch_partial_mfma honours k_new / v_new for this shape
 hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
