@@ -285,6 +285,13 @@ def main():
         if one_call:                              # the step's token is quantised, stored and attended by one call
             tq.tq_sdpa_int4_append_decode(caches[j], news[j][0], news[j][1], qs[j], S, w.attn_scale, out=out,
                                           workspace=ws, **kw)
+        elif lens is not None and not args.two_calls:
+            if paged:
+                tq.tq_sdpa_int4_append_decode_paged(caches[j], caches[j].table, news[j][0], news[j][1], qs[j], lens_dev, S,
+                                                    w.attn_scale, out=out, workspace=ws, **kw)
+            else:
+                tq.tq_sdpa_int4_append_decode_varlen(caches[j], news[j][0], news[j][1], qs[j], lens_dev, S, w.attn_scale,
+                                                     out=out, workspace=ws, **kw)
         else:
             append(j)
             decode(j)
@@ -469,6 +476,8 @@ def main():
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "window": args.window, "n_queries": NQ,
                    "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
+                                  "tq_sdpa_int4_append_decode_paged" if paged and not args.two_calls else
+                                  "tq_sdpa_int4_append_decode_varlen" if lens is not None and not args.two_calls else
                                   "tq_quantize_kv_paged + tq_sdpa_int4_decode_paged" if paged else
                                   "tq_quantize_kv_varlen + tq_sdpa_int4_decode_varlen" if lens is not None else
                                   "tq_quantize_kv + tq_sdpa_int4_decode"),

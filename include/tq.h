@@ -152,6 +152,18 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
                                void* out, void* workspace, size_t workspace_bytes,
                                const tq_decode_opts* opts, void* stream);
 
+/* One decode step with per-sequence lengths, in one call: as tq_sdpa_int4_append_decode, but seq_lens[b]
+ * (DEVICE int32 [batch], each in [n_queries, max_seq_len]) is sequence b's length INCLUDING its new token(s),
+ * which are written at its last position(s) and attended together with its cached ones; the same result and
+ * the same stored bits as tq_quantize_kv_varlen at seq_lens[b] - n followed by tq_sdpa_int4_decode_varlen.
+ * With one query token (and no window of a single token) the merge kernel takes the token in: two launches
+ * instead of three.  tq_sdpa_int4_append_decode_paged (declared with the paged calls below) is the same over a
+ * pool of pages.  Errors: those of the two calls. */
+int tq_sdpa_int4_append_decode_varlen(const tq_kv_cache* cache, const void* k_new, const void* v_new,
+                                      const void* q, int32_t n_q_heads, const int32_t* seq_lens,
+                                      int32_t max_seq_len, float attn_scale, void* out, void* workspace,
+                                      size_t workspace_bytes, const tq_decode_opts* opts, void* stream);
+
 /* Paged cache (what a decode server keeps: sequences grow page by page out of one pool).
  * pool: a tq_kv_cache whose `batch` field counts PAGES and whose `capacity` is the page length in
  * tokens (a power of two >= 32), arrays [n_pages][n_kv_heads][page_tokens][...] in the canonical
@@ -167,6 +179,11 @@ int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t 
 int tq_quantize_kv_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
                          int32_t batch, const void* k_new, const void* v_new,
                          const int32_t* positions, int32_t n_new, void* stream);
+int tq_sdpa_int4_append_decode_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
+                                     int32_t batch, const void* k_new, const void* v_new, const void* q,
+                                     int32_t n_q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                     float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                                     const tq_decode_opts* opts, void* stream);
 int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
                               int32_t batch, const void* q, int32_t n_q_heads,
                               const int32_t* seq_lens, int32_t max_seq_len, float attn_scale,

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     tq_quantize_kv_paged,
     tq_quantize_kv_varlen,
     tq_sdpa_int4_append_decode,
+    tq_sdpa_int4_append_decode_paged,
+    tq_sdpa_int4_append_decode_varlen,
     tq_sdpa_int4_decode,
     tq_sdpa_int4_decode_paged,
     tq_sdpa_int4_decode_varlen,

@@ -58,6 +58,8 @@ def raw():
         L.tq_sdpa_int4_decode_paged.argtypes = [CP, P, I, I, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_append_decode.argtypes = [CP, P, P, P, I, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_decode_varlen.argtypes = [CP, P, I, P, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_append_decode_varlen.argtypes = [CP, P, P, P, I, P, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_append_decode_paged.argtypes = [CP, P, I, I, P, P, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_quantize_kv_varlen.argtypes = [CP, P, P, P, I, P]
         L.tq_sdpa_int4_partial.argtypes = [CP, P, I, I, F, P, SZ, OP, ctypes.POINTER(ctypes.c_int32), P]
         L.tq_sdpa_int4_reduce.argtypes = [I, I, I, I, P, SZ, P, P]
@@ -234,6 +236,56 @@ def tq_sdpa_int4_decode_varlen(cache: KVCache, q: torch.Tensor, seq_lens: torch.
                                           workspace.data_ptr(), wbytes, _opts(n_splits, variant, window, nq),
                                           _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode_varlen")
+    return out
+
+
+def tq_sdpa_int4_append_decode_varlen(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor,
+                                      seq_lens: torch.Tensor, max_seq_len: int, attn_scale: float, out=None,
+                                      workspace=None, n_splits: int = 0, variant: int = 0, stream=None,
+                                      window: int = 0) -> torch.Tensor:
+    """One decode step with per-sequence lengths (int32 device tensor [B], each counting the new token): k_new,
+    v_new fp16 [B, H_kv, n_queries, d] go to the end of every sequence, then q attends."""
+    _need(q, torch.float16, "q")
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    _need(seq_lens, torch.int32, "seq_lens")
+    nq, hq = _queries(q)
+    if k_new.shape != v_new.shape or tuple(k_new.shape) != (cache.batch, cache.n_kv_heads, nq, cache.head_dim):
+        raise ValueError("k_new/v_new must be [batch, n_kv_heads, n_queries, head_dim]")
+    if out is None:
+        out = torch.empty_like(q)
+    workspace, wbytes = _workspace_for(cache, hq, workspace, nq)
+    rc = raw().tq_sdpa_int4_append_decode_varlen(ctypes.byref(cache.struct), k_new.data_ptr(), v_new.data_ptr(),
+                                                 q.data_ptr(), hq, seq_lens.data_ptr(), int(max_seq_len),
+                                                 float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
+                                                 _opts(n_splits, variant, window, nq), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_append_decode_varlen")
+    return out
+
+
+def tq_sdpa_int4_append_decode_paged(pool: KVCache, block_table: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                                     q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int, attn_scale: float,
+                                     out=None, workspace=None, n_splits: int = 0, variant: int = 0, stream=None,
+                                     window: int = 0) -> torch.Tensor:
+    """The same over a pool of pages: block_table int32 [B, max_blocks] on the device."""
+    _need(q, torch.float16, "q")
+    _need(k_new, torch.float16, "k_new")
+    _need(v_new, torch.float16, "v_new")
+    _need(seq_lens, torch.int32, "seq_lens")
+    _need(block_table, torch.int32, "block_table")
+    nq, hq = _queries(q)
+    if out is None:
+        out = torch.empty_like(q)
+    need = tq_workspace_bytes(int(q.shape[0]) * nq, hq, pool.head_dim)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = raw().tq_sdpa_int4_append_decode_paged(ctypes.byref(pool.struct), block_table.data_ptr(),
+                                                int(block_table.shape[1]), int(q.shape[0]), k_new.data_ptr(),
+                                                v_new.data_ptr(), q.data_ptr(), hq, seq_lens.data_ptr(),
+                                                int(max_seq_len), float(attn_scale), out.data_ptr(),
+                                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                _opts(n_splits, variant, window, nq), _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_append_decode_paged")
     return out
 
 

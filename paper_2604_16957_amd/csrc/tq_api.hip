@@ -201,8 +201,10 @@ int run_partial(PartialRequest& rq) {
   p.seq_lens = seq_lens;
   p.batch = cache->batch;
   if (seq_lens) {
-    // the kernels window every sequence's own length
-    p.window = (opts && opts->window > 0) ? opts->window + queries_of(opts) - 1 : 0;
+    // the kernels window every sequence's own length (append-and-attend: the lengths count the new token, the
+    // chunks and the window over them do not)
+    p.len_bias = append_in_merge ? -1 : 0;
+    p.window = (opts && opts->window > 0) ? opts->window + queries_of(opts) - 1 + p.len_bias : 0;
   } else {
     p.seq_len = attended;
     p.start = first;
@@ -454,6 +456,69 @@ int tq_sdpa_int4_decode_paged(const tq_kv_cache* pool, const int32_t* block_tabl
   rq.paged = &pv;
   rq.stream = stream;
   return finish_decode(rq, run_partial(rq));
+}
+
+namespace {
+// One decode step with per-sequence lengths that count the step's new token: the merge kernel takes the token
+// in where it can (one query token; a window, if any, of at least two tokens), else the append kernel runs first.
+int append_decode_with_lengths(PartialRequest& rq, const void* k_new, const void* v_new) {
+  const tq_decode_opts* opts = rq.opts;
+  if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2) {
+    rq.k_new = k_new;
+    rq.v_new = v_new;
+  } else {
+    const int n_new = queries_of(opts);
+    const int rc = hip_rc(tq::launch_quantize(*rq.cache, k_new, v_new, -n_new, rq.seq_lens, n_new,
+                                              static_cast<hipStream_t>(rq.stream), rq.paged));
+    if (rc != TQ_OK) return rc;
+  }
+  return finish_decode(rq, run_partial(rq));
+}
+}  // namespace
+
+int tq_sdpa_int4_append_decode_varlen(const tq_kv_cache* cache, const void* k_new, const void* v_new, const void* q,
+                                      int32_t n_q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                      float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                                      const tq_decode_opts* opts, void* stream) {
+  int rc = check_decode(cache, q, n_q_heads, max_seq_len, out, workspace, workspace_bytes, opts, true);
+  if (rc != TQ_OK) return rc;
+  if (!seq_lens || !k_new || !v_new) return TQ_ERR_NULL;
+  if (!aligned(seq_lens, 4) || !aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
+  if (!route_of(cache, n_q_heads, max_seq_len, attn_scale, opts).ok) return TQ_ERR_UNSUPPORTED;
+  PartialRequest rq{cache, q, n_q_heads, max_seq_len};
+  rq.seq_lens = seq_lens;
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  return append_decode_with_lengths(rq, k_new, v_new);
+}
+
+int tq_sdpa_int4_append_decode_paged(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_blocks,
+                                     int32_t batch, const void* k_new, const void* v_new, const void* q,
+                                     int32_t n_q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                     float attn_scale, void* out, void* workspace, size_t workspace_bytes,
+                                     const tq_decode_opts* opts, void* stream) {
+  tq_kv_cache view;
+  tq::PagedView pv;
+  int rc = paged_view(pool, block_table, max_blocks, batch, &view, &pv);
+  if (rc != TQ_OK) return rc;
+  rc = check_decode(&view, q, n_q_heads, max_seq_len, out, workspace, workspace_bytes, opts, true,
+                    (int64_t)max_blocks * pool->capacity);
+  if (rc != TQ_OK) return rc;
+  if (!seq_lens || !k_new || !v_new) return TQ_ERR_NULL;
+  if (!aligned(seq_lens, 4) || !aligned(k_new, 16) || !aligned(v_new, 16)) return TQ_ERR_ALIGN;
+  if (!route_of(&view, n_q_heads, max_seq_len, attn_scale, opts).ok) return TQ_ERR_UNSUPPORTED;
+  PartialRequest rq{&view, q, n_q_heads, max_seq_len};
+  rq.seq_lens = seq_lens;
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = workspace;
+  rq.opts = opts;
+  rq.paged = &pv;
+  rq.stream = stream;
+  return append_decode_with_lengths(rq, k_new, v_new);
 }
 
 int tq_sdpa_int4_decode_varlen(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, const int32_t* seq_lens,

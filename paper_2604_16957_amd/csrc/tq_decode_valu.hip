@@ -207,6 +207,7 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
 
   // chunks that exist for this sequence: all of them, or those that start before its own end
   int n = p.n_splits;
+  int append_pos = p.append_pos;
   if (p.seq_lens) {
     const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
     if (p.var_chunks > 0) {
@@ -215,6 +216,11 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
     } else {
       n = min(n, (var_len(p, sequence) + p.tokens_per_split - 1) / p.tokens_per_split);
     }
+    // append-and-attend: the sequence's length counts the new token, which goes to its last position; a
+    // sequence with no cached token has no chunk (the one the decode kernel made up is ignored)
+    const int total = max(1, min(p.seq_lens[sequence], p.seq_len));
+    append_pos = total - 1;
+    if (total + p.len_bias < 1) n = 0;
   }
   const float m = tid < n ? ml.x : kNegBig, l = tid < n ? ml.y : 0.0f;
 
@@ -248,7 +254,11 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
       const float sf = (float)s16, zf = (float)z16;
       const uint32_t w = quantize_word(x, sf, zf);
       if (h % p.gqa == 0) {
-        const int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + p.append_pos;
+        int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + append_pos;
+        if (p.block_table) {                       // paged cache: the page the block table names for that position
+          const int page = p.block_table[(int64_t)b * p.max_blocks + (append_pos >> p.page_shift)];
+          row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (append_pos & ((1 << p.page_shift) - 1));
+        }
         uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes) + row * (D / 2) + g * (kGroup / 2);
         reinterpret_cast<uint32_t*>(codes)[part4] = w;
         if (part4 == 0) const_cast<half_t*>(which ? p.v_scale : p.k_scale)[row * NG + g] = s16;

@@ -62,9 +62,12 @@ struct DecodeParams {
   // Append-and-attend (merge kernel, one query token, common length): k_new / v_new non-null = one new token per
   // sequence, fp16 [B][H_kv][1][D], not among the tokens the chunks cover; the merge kernel quantises it, writes it
   // at token append_pos of its row and adds its attention term to Eq. 6.
+  // With per-sequence lengths the lengths COUNT the new token (len_bias = -1: the chunks cover one token fewer)
+  // and it is written at each sequence's own last position.
   const half_t* k_new;
   const half_t* v_new;
   int32_t append_pos;
+  int32_t len_bias;
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };
@@ -114,7 +117,9 @@ __device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[
 // entries: the grid.  Slot s of that list -> (b, chunk); returns false past the end of the list.
 // Everything here is wave-uniform.
 struct VarPlan { int chunk_tokens, b, chunk; };
-__device__ inline int var_full_len(const DecodeParams& p, int b) { return max(1, min(p.seq_lens[b], p.seq_len)); }
+__device__ inline int var_full_len(const DecodeParams& p, int b) {
+  return max(1, min(p.seq_lens[b], p.seq_len) + p.len_bias);
+}
 // The first token sequence b attends; the token its chunks are counted from (the same, except in a paged
 // cache, where it is rounded down to a supertile boundary so that no supertile straddles two pages: the
 // kernels mask the tokens in between); and the tokens from there to the sequence's end.
@@ -210,7 +215,7 @@ inline size_t workspace_ml_floats(int batch, int n_q_heads) {
 // A paged view of a pool: sequence b's token t lives in page block_table[b * max_blocks + (t >> page_shift)].
 struct PagedView { const int32_t* block_table; int32_t max_blocks, page_shift, batch; };
 
-// pos_dev (device, [B]) non-null: sequence b is written at pos_dev[b]; a sequence whose tokens would not
+// pos_dev (device, [B]) non-null: sequence b is written at pos_dev[b] + pos; a sequence whose tokens would not
 // fit into [0, capacity) (paged: into its max_blocks pages) is skipped.  pv non-null: c is a pool of pages.
 hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* v_new, int pos,
                            const int32_t* pos_dev, int n_new, hipStream_t s, const PagedView* pv = nullptr);

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   const int t = (int)(vec % p.n_new);
   int pos = p.pos;
   if (p.pos_dev) {
-    pos = p.pos_dev[bh / p.n_kv_heads];
+    pos = p.pos_dev[bh / p.n_kv_heads] + p.pos;
     const int64_t room = p.block_table ? ((int64_t)p.max_blocks << p.page_shift) : p.capacity;
     if (pos < 0 || pos > room - p.n_new) return;          // this sequence's tokens do not fit: nothing is written
   }

@@ -228,6 +228,32 @@ def test_decode_launch_count_query():
     assert f(ctypes.byref(big), 64, 16, 0.1, None) == 2
 
 
+def test_append_decode_with_lengths_rejects_bad_arguments_without_a_gpu():
+    E = B
+    c = _cache()
+    wsb = tq.tq_workspace_bytes(1, 64, 128)
+    f = B.raw().tq_sdpa_int4_append_decode_varlen
+    ok = dict(k=FAKE, v=FAKE, q=FAKE, lens=FAKE, S=1024, out=FAKE, ws=FAKE, wsb=wsb)
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(ctypes.byref(c), a["k"], a["v"], a["q"], 64, a["lens"], a["S"], 0.1, a["out"], a["ws"], a["wsb"], None, None)
+    assert call(k=None) == E.TQ_ERR_NULL and call(v=None) == E.TQ_ERR_NULL and call(lens=None) == E.TQ_ERR_NULL
+    assert call(q=None) == E.TQ_ERR_NULL and call(out=None) == E.TQ_ERR_NULL
+    assert call(S=0) == E.TQ_ERR_EMPTY and call(S=1025) == E.TQ_ERR_CAPACITY
+    assert call(k=FAKE + 8) == E.TQ_ERR_ALIGN and call(lens=FAKE + 2) == E.TQ_ERR_ALIGN
+    assert call(wsb=wsb - 1) == E.TQ_ERR_WORKSPACE
+    g = B.raw().tq_sdpa_int4_append_decode_paged
+    pool = _cache(batch=64, capacity=256)
+    wsb4 = tq.tq_workspace_bytes(4, 64, 128)
+    def callp(**kw):
+        a = dict(dict(tbl=FAKE, mb=8, k=FAKE, v=FAKE, lens=FAKE, S=2048, wsb=wsb4), **kw)
+        return g(ctypes.byref(pool), a["tbl"], a["mb"], 4, a["k"], a["v"], FAKE, 64, a["lens"], a["S"], 0.1, FAKE, FAKE,
+                 a["wsb"], None, None)
+    assert callp(tbl=None) == E.TQ_ERR_NULL and callp(k=None) == E.TQ_ERR_NULL and callp(lens=None) == E.TQ_ERR_NULL
+    assert callp(S=2049) == E.TQ_ERR_CAPACITY and callp(mb=0) == E.TQ_ERR_SHAPE
+    assert callp(wsb=wsb4 - 1) == E.TQ_ERR_WORKSPACE and callp(v=FAKE + 4) == E.TQ_ERR_ALIGN
+
+
 def test_read_probe_rejects_bad_arguments_without_a_gpu():
     f = B.raw().tq_probe_read_stream
     assert f(None, 1 << 24, FAKE, None) == B.TQ_ERR_NULL

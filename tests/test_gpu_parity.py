@@ -888,3 +888,92 @@ def test_quarter_million_tokens():
         torch.cuda.synchronize()
         max_abs, rel = assert_close(out, ref, f"S={S} variant={variant}")
         print(f"\nS={S} variant={variant}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}")
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("shape", ["g8_d128_b4_kv2", "g2_d256_b4"])
+def test_append_decode_with_per_sequence_lengths(shape, variant):
+    """One decode step for a batch whose sequences have their own lengths (each counting its new token), contiguous
+    and paged: stored bits equal the oracle's at every sequence's own last position, nothing else is touched, the
+    result equals the oracle's over each sequence's tokens; one sequence has no cached token at all."""
+    shapes = dict(g8_d128_b4_kv2=dict(batch=4, n_q_heads=16, n_kv_heads=2, head_dim=128, outlier_channels=4),
+                  g2_d256_b4=dict(batch=4, n_q_heads=4, n_kv_heads=2, head_dim=256, attn_scale=1.0, qk_std=0.1))
+    lens = [1500, 1, 2049, 321]                   # lengths INCLUDING the new token
+    S, PT, max_blocks, n_pages = max(lens), 256, 9, 40
+    w = wl.custom(seq_len=S, seed=1700, **shapes[shape])
+    q, k, v = make(w)
+    B, Hkv, d = w.batch, w.n_kv_heads, w.head_dim
+    # sequence b's tokens are k[b, :, :lens[b]]; its new token is the last of them
+    kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    ocache = oracle_cache_from(k, v)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    cached = torch.tensor([n - 1 for n in lens], dtype=torch.int32, device="cuda")
+    names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero")
+    for window in (0, 1, 2, 300):                 # (a window of one token: the append kernel runs first)
+        ref = _oracle_window(q, ocache, lens, window if window > 0 else S, w.attn_scale)
+        # ---- contiguous rows
+        cache = tq.KVCache(B, Hkv, d, S + 3)
+        for t in cache.tensors():
+            t.view(torch.uint8).fill_(0xEE)
+        tq.tq_quantize_kv(cache, k.cuda(), v.cuda(), 0)       # everything, then the last token of every sequence is
+        for t in cache.tensors():                             # wiped again: the call under test has to write it
+            for b in range(B):
+                t.view(torch.uint8)[b, :, lens[b] - 1:] = 0xEE
+        out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale,
+                                                   variant=variant, window=window)
+        torch.cuda.synchronize()
+        for name, g, o in zip(names, cache.tensors(), ocache):
+            g = np16(g)
+            for b in range(B):
+                gb, ob = g[b, :, :lens[b]], o[b, :, :lens[b]]
+                if gb.dtype == np.float16:
+                    gb, ob = gb.view(np.uint16), ob.view(np.uint16)
+                assert np.array_equal(gb, ob), f"{name} sequence {b}"
+        for t in cache.tensors():
+            for b in range(B):
+                assert bool((t.view(torch.uint8)[b, :, lens[b]:] == 0xEE).all())
+        assert_close(out, ref, f"{shape} append + decode, own lengths, window={window} variant={variant}")
+        # ---- the same over pages in random order
+        rng = np.random.default_rng(11)
+        table = rng.permutation(n_pages)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+        table_dev = torch.from_numpy(table).cuda()
+        pool = tq.KVCache(n_pages, Hkv, d, PT)
+        for t in pool.tensors():
+            t.view(torch.uint8).fill_(0xEE)
+        # fill every sequence up to its own cached length: one call per distinct length (positions 0, n_new tokens)
+        for b in range(B):
+            if lens[b] > 1:
+                one = torch.from_numpy(table[b:b + 1]).cuda()
+                tq.tq_quantize_kv_paged(pool, one, k[b:b + 1, :, :lens[b] - 1].contiguous().cuda(),
+                                        v[b:b + 1, :, :lens[b] - 1].contiguous().cuda(),
+                                        torch.zeros(1, dtype=torch.int32, device="cuda"))
+        out = tq.tq_sdpa_int4_append_decode_paged(pool, table_dev, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale,
+                                                  variant=variant, window=window)
+        torch.cuda.synchronize()
+        assert_close(out, ref, f"{shape} paged append + decode, window={window} variant={variant}")
+        for name, t, o in zip(names, pool.tensors(), ocache):
+            g = np16(t)
+            for b in range(B):
+                n = lens[b]
+                got = np.concatenate([g[table[b, j]] for j in range((n + PT - 1) // PT)], axis=1)[:, :n]
+                want = o[b, :, :n]
+                if got.dtype == np.float16:
+                    got, want = got.view(np.uint16), want.view(np.uint16)
+                assert np.array_equal(got, want), f"paged {name} sequence {b}"
+    del cached
+    # two query tokens per sequence (the append kernel runs first): lengths count both new tokens
+    if variant == 0:
+        lens2 = [1500, 2, 2049, 321]
+        q4 = _queries_for(w, 2)
+        kn2 = torch.stack([k[b, :, lens2[b] - 2:lens2[b]] for b in range(B)]).contiguous()
+        vn2 = torch.stack([v[b, :, lens2[b] - 2:lens2[b]] for b in range(B)]).contiguous()
+        cache = tq.KVCache(B, Hkv, d, S + 3)
+        tq.tq_quantize_kv(cache, k.cuda(), v.cuda(), 0)
+        for t in cache.tensors():
+            for b in range(B):
+                t.view(torch.uint8)[b, :, lens2[b] - 2:] = 0xEE
+        out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn2.cuda(), vn2.cuda(), q4.cuda(),
+                                                   torch.tensor(lens2, dtype=torch.int32, device="cuda"), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_causal(q4, ocache, lens2, w.attn_scale), f"{shape} append of two tokens, own lengths")
