@@ -120,7 +120,7 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
 int hip_rc(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
 // Which kernel a decode call takes, and whether that kernel can also do the chunk merge.
-struct Route { bool ok, use_mfma, merge; };
+struct Route { bool ok, use_mfma, merge, single; };   // single: every sequence is one chunk (no merge needed at all)
 // The in-kernel merge ends the kernel with a chain of device-wide round trips (publish the partial,
 // count in, read all partials) that one block walks alone: about 5 us, against about 3.5 us for the
 // separate merge kernel plus its launch.  It pays where the call is bound by launch overhead, not by
@@ -137,22 +137,23 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   const int variant = opts ? opts->variant : 0;
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
   const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
-  if (variant == 2 && !scale_ok) return {false, false, false};
+  if (variant == 2 && !scale_ok) return {false, false, false, false};
   // the matrix-core kernel addresses a (batch, KV head) row of codes with 32-bit byte offsets
   const bool offsets_ok = (int64_t)seq_len * (cache->head_dim / 2) < (1ll << 31);
-  if (variant == 2 && !offsets_ok) return {false, false, false};
+  if (variant == 2 && !offsets_ok) return {false, false, false, false};
   const int rows = rows_of(cache, n_q_heads, opts);
   const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
                                          tq::mfma_supported(cache->head_dim, rows));
-  if (!use_mfma && queries_of(opts) > 1) return {false, false, false};
+  if (!use_mfma && queries_of(opts) > 1) return {false, false, false, false};
   // (more query rows than the kernel's tile holds: several blocks stream each KV head, counted as rows of their own)
   const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, rows) : 1);
   const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, rows_per_batch, windowed(seq_len, opts), cache->head_dim);
   // a sequence that is one chunk needs no merge at all: the kernel writes the output itself, whatever the size
   const bool single = use_mfma && plan_splits(cache->batch, rows_per_batch, windowed(seq_len, opts),
                                                opts ? opts->n_splits : 0, kBlocksMfma, 8).n_splits == 1;
-  return {true, use_mfma,
-          use_mfma && (bytes <= kMergeInKernelMaxBytes || single) && tq::mfma_can_merge(cache->batch, rows_per_batch)};
+  const bool merge =
+      use_mfma && (bytes <= kMergeInKernelMaxBytes || single) && tq::mfma_can_merge(cache->batch, rows_per_batch);
+  return {true, use_mfma, merge, single && merge};
 }
 
 // One launch of phase 1: what to attend, and what came of it.
@@ -408,8 +409,9 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   rq.opts = opts;
   rq.stream = stream;
   // The merge kernel takes the token in (one query token, at least one cached token to attend: no append launch,
-  // nothing read back); else the append kernel runs first.
-  if (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2) {
+  // nothing read back); else the append kernel runs first.  Where every sequence is a single chunk there is no
+  // merge kernel to begin with (the decode kernel writes the output itself): the append kernel, then that.
+  if (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2 && !r.single) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {                                        // the append kernel first, then the plain decode
