@@ -152,7 +152,7 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   const bool single = use_mfma && plan_splits(cache->batch, rows_per_batch, windowed(seq_len, opts),
                                                opts ? opts->n_splits : 0, kBlocksMfma, 8).n_splits == 1;
   const bool merge =
-      use_mfma && (bytes <= kMergeInKernelMaxBytes || single) && tq::mfma_can_merge(cache->batch, rows_per_batch);
+      use_mfma && (single || (bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, rows_per_batch)));
   return {true, use_mfma, merge, single && merge};
 }
 
@@ -236,6 +236,11 @@ int run_partial(PartialRequest& rq) {
   rq.n_splits = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(rq.stream);
   rq.merged = rq.out != nullptr && r.merge && !seq_lens && !append_in_merge;
+  if (rq.merged && use_mfma && plan.n_splits == 1 && !rq.paged) {
+    // more single-chunk rows than the chip holds blocks: pack 2, 4 or 8 of them into a block
+    const int64_t total = (int64_t)cache->batch * rows_per_batch;
+    p.waves_per_row = total > 4 * target ? 1 : total > 2 * target ? 2 : total > target ? 4 : 8;
+  }
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
 }

@@ -270,7 +270,21 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int c = lane & 15, kq = lane >> 4;
   const int hl = c % GP, rep = c / GP;            // head and group replica of this lane's column / row
   int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
-  const int kvv = blockIdx.y;                     // KV head x part of its query group (see kv_share)
+  int kvv = blockIdx.y;                           // KV head x part of its query group (see kv_share)
+  // Many short sequences (more (sequence, KV head) rows than the chip holds blocks, each a single chunk): a block
+  // takes NW / W rows, W waves each, instead of one; blockIdx.y then counts groups of rows of the list
+  // [batch][KV head x part].  A wave past the end of the list has no tokens and only keeps the barriers company.
+  const int W = p.waves_per_row;                  // NW: the whole block on one row
+  const bool whole = W == NW;
+  bool row_valid = true;
+  if (!whole) {
+    const int rows_y = p.n_kv_heads * p.kv_share, total = p.batch * rows_y;
+    const int row = blockIdx.y * (NW / W) + wave / W;
+    row_valid = row < total;
+    const int r = min(row, total - 1);
+    b = __builtin_amdgcn_readfirstlane(r / rows_y);
+    kvv = __builtin_amdgcn_readfirstlane(r - (r / rows_y) * rows_y);
+  }
   const int kv = kvv / p.kv_share;                // the KV head whose rows are read
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
@@ -299,7 +313,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
   // tokens this sequence attends: the common length, or its own (a chunk past its end is empty); with a
   // sliding window the row simply starts `start` tokens later
-  const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;
+  const int seq = !row_valid ? 0 : p.seq_lens ? var_len(p, b) : p.seq_len;
   const int start = p.seq_lens ? var_start(p, b) : p.start;
   // first row of the six arrays this block reads from: the sequence's own row (contiguous cache), or the
   // pool's row 0 (paged cache: the page's rows are added supertile by supertile)
@@ -442,12 +456,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //      the clamped path.
   static_assert(NW == 8, "the work split assumes two waves per SIMD");
   const int simd = wave & 3, young = wave >> 2;
+  const int sub = wave % W;                       // (several rows per block: the W waves of a row take its supertiles in turn)
   auto sidx_of = [&](int i) {                     // i-th supertile of this wave -> supertile of the chunk
+    if (!whole) return W * i + sub;
     const int blk = young ? i / 7 : i / 9, j = i - blk * (young ? 7 : 9);
     const int k = 16 * blk + (young ? 2 * j + 1 : (j < 8 ? 2 * j : 15));
     return 4 * k + simd;
   };
   auto count_of = [&](int n) {                    // how many of the chunk's first n supertiles are this wave's
+    if (!whole) return n > sub ? (n - sub + W - 1) / W : 0;
     const int K = n > simd ? (n - simd + 3) >> 2 : 0, r = K & 15;
     return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
   };
@@ -455,7 +472,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   bool tail_mine[3];                              // [2]: the masked FIRST supertile (see `head`)
 #pragma unroll
   for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
-  tail_mine[2] = head && wave == 0;
+  tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
 
   // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
@@ -792,7 +809,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       // next supertile of the pattern: the older wave holds k = 0,2,..,14,15 of every 16, the younger 1,3,..,13
       const int step = young ? (nx_j < 6 ? 2 : 4) : (nx_j < 7 ? 2 : 1);
       nx_j = (nx_j == (young ? 6 : 8)) ? 0 : nx_j + 1;
-      nx_tok += step * (4 * 32);
+      nx_tok += whole ? step * (4 * 32) : W * 32;
       if (paged) nx_page = page_ahead(nx_tok);
     } else {
       issue_phantom(slot);
@@ -861,6 +878,25 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- merge the waves, write one partial per query head (Sec. 3.2); where the sequence is a single
   //      chunk and the kernel is to produce the output, that partial, normalised, IS the output
   const bool direct = p.merge_slot >= 0 && p.n_splits == 1;
+  if (!whole) {                                   // several rows per block: the W waves of a row merge among themselves
+    if (row_valid) {                              // (always a single chunk whose result is the output)
+      const int w0 = wave - sub;
+      for (int idx = sub * 64 + lane; idx < G * D; idx += W * 64) {
+        const int h = idx / D, j = idx % D;
+        const float unit = (j & 1) ? 0x1p20f : 0x1p24f;
+        float mg = lds_m[w0 * GP + h];
+        for (int w = 1; w < W; ++w) mg = fmaxf(mg, lds_m[(w0 + w) * GP + h]);
+        float num = 0.0f, den = 0.0f;
+        for (int w = w0; w < w0 + W; ++w) {
+          const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
+          num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
+          den = fmaf(lds_l[w * GP + h], e, den);
+        }
+        p.out[query_row(h) * D + j] = (half_t)(num / den);
+      }
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < G * D; idx += NW * 64) {
     const int h = idx / D, j = idx % D;
     const float unit = (j & 1) ? 0x1p20f : 0x1p24f;          // odd dims were read from the high nibble position
@@ -1019,10 +1055,17 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
   const int rows_y = p.n_kv_heads * p.kv_share;
   p.merge_slot = -1;
   if (merge_in_kernel) {
-    if (!mfma_can_merge(batch, rows_y) || p.out == nullptr) return hipErrorInvalidValue;
+    if ((p.n_splits > 1 && !mfma_can_merge(batch, rows_y)) || p.out == nullptr) return hipErrorInvalidValue;
     p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
   }
-  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, rows_y, 1) : dim3(p.n_splits, rows_y, batch);
+  if (p.waves_per_row != 1 && p.waves_per_row != 2 && p.waves_per_row != 4) p.waves_per_row = 8;
+  // several rows per block: only where every row is one chunk and the kernel writes the output itself
+  if (p.waves_per_row != 8 && (p.merge_slot < 0 || p.n_splits != 1 || p.var_chunks > 0 || p.block_table))
+    return hipErrorInvalidValue;
+  const int rows_per_block = 8 / p.waves_per_row;
+  const dim3 grid = p.var_chunks > 0      ? dim3(p.var_chunks, rows_y, 1)
+                    : rows_per_block > 1 ? dim3(1, (batch * rows_y + rows_per_block - 1) / rows_per_block, 1)
+                                         : dim3(p.n_splits, rows_y, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);

@@ -68,6 +68,9 @@ struct DecodeParams {
   const half_t* v_new;
   int32_t append_pos;
   int32_t len_bias;
+  // Matrix-core kernel, many single-chunk rows: 1, 2 or 4 = a block takes 8 / waves_per_row (sequence, KV head)
+  // rows with that many waves each (grid.y counts groups of rows); anything else = one row per block.
+  int32_t waves_per_row;
   int32_t merge_slot;       // matrix-core kernel: >= 0 selects a set of arrival counters and makes the last
                             // block of every (b, kv head) merge the chunks and write `out`; < 0: partials only
 };

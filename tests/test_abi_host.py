@@ -224,8 +224,8 @@ def test_decode_launch_count_query():
     long = _cache(capacity=131072)                                    # stream-bound: separate merge kernel
     assert f(ctypes.byref(long), 64, 131072, 0.1, None) == 2
     assert f(ctypes.byref(long), 64, 8192, 0.1, None) == 1
-    big = _cache(batch=512)                                           # more (batch, KV head) rows than counters
-    assert f(ctypes.byref(big), 64, 16, 0.1, None) == 2
+    big = _cache(batch=512)                                           # 4096 rows of one chunk each: no merge at all
+    assert f(ctypes.byref(big), 64, 16, 0.1, None) == 1
 
 
 def test_append_decode_with_lengths_rejects_bad_arguments_without_a_gpu():

@@ -977,3 +977,33 @@ def test_append_decode_with_per_sequence_lengths(shape, variant):
                                                    torch.tensor(lens2, dtype=torch.int32, device="cuda"), S, w.attn_scale)
         torch.cuda.synchronize()
         assert_close(out, _oracle_causal(q4, ocache, lens2, w.attn_scale), f"{shape} append of two tokens, own lengths")
+
+
+@pytest.mark.parametrize("shape", ["g8_d128", "g2_d256", "g16_d128", "g3_d128"])
+def test_more_rows_than_blocks_are_packed_several_to_a_block(shape):
+    """Batches whose (sequence, KV head) rows outnumber the compute units, every row a single chunk: 2, 4 or 8
+    rows share a block (4, 2 or 1 waves each).  Lengths cover no full supertile, ragged tails, and more supertiles
+    than a row has waves; the row count does not fill the last block; also with a window and several query tokens."""
+    shapes = dict(g8_d128=dict(n_q_heads=16, n_kv_heads=2, head_dim=128, outlier_channels=4),
+                  g2_d256=dict(n_q_heads=4, n_kv_heads=2, head_dim=256, attn_scale=1.0, qk_std=0.1),
+                  g16_d128=dict(n_q_heads=16, n_kv_heads=1, head_dim=128),
+                  g3_d128=dict(n_q_heads=6, n_kv_heads=2, head_dim=128))
+    for batch in (131, 300, 700):                 # x 2 rows (x 2 parts at GQA 16): 4, 2 and 1 waves per row
+        for S in (5, 100, 517):
+            w = wl.custom(batch=batch, seq_len=S, seed=1800 + S + batch, **shapes[shape])
+            q, k, v = make(w)
+            cache = gpu_cache_from(k, v, capacity=S + 2)
+            ocache = oracle_cache_from(k, v)
+            assert tq.tq_decode_launches(cache, w.n_q_heads, S, w.attn_scale) == 1
+            out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale)
+            torch.cuda.synchronize()
+            assert_close(out, oracle_attend(q, ocache, S, w.attn_scale), f"{shape} batch={batch} S={S}")
+            win = max(1, S // 2)
+            out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, window=win)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_window(q, ocache, [S] * batch, win, w.attn_scale), f"{shape} batch={batch} S={S} window")
+            if S >= 100 and batch == 300:
+                q4 = _queries_for(w, 2)
+                out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale)
+                torch.cuda.synchronize()
+                assert_close(out, _oracle_causal(q4, ocache, [S] * batch, w.attn_scale), f"{shape} batch={batch} S={S}, 2 queries")
