@@ -105,6 +105,7 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
   p.out = static_cast<half_t*>(out);
   p.part_o = static_cast<float*>(workspace);
   p.part_ml = p.part_o + tq::workspace_o_floats(c->batch * n_queries, n_q_heads, c->head_dim);
+  p.plan = reinterpret_cast<int32_t*>(p.part_ml + tq::workspace_ml_floats(c->batch * n_queries, n_q_heads));
   p.n_q_heads = n_q_heads;
   p.n_queries = n_queries;
   p.n_kv_heads = c->n_kv_heads;
@@ -226,6 +227,8 @@ int run_partial(PartialRequest& rq) {
     p.var_chunks = rounds * per_round;
     p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;
     p.n_splits = tq::kMaxSplits;
+    // many sequences: the slots of several rounds share blocks (2, 4 or 8 to a block) and run in one
+    if (use_mfma) p.waves_per_row = rounds > 4 ? 1 : rounds > 2 ? 2 : rounds > 1 ? 4 : 8;
   }
   rq.params = p;
   if (append_in_merge) {
@@ -274,8 +277,9 @@ extern "C" {
 
 size_t tq_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim) {
   if (batch < 1 || n_q_heads < 1 || !head_dim_ok(head_dim)) return 0;
+  // partial outputs, their (m, l), and one cache line for the device-side chunk plan
   return (tq::workspace_o_floats(batch, n_q_heads, head_dim) + tq::workspace_ml_floats(batch, n_q_heads)) *
-         sizeof(float);
+             sizeof(float) + 256;
 }
 
 size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim) {

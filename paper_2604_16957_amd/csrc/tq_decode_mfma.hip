@@ -271,13 +271,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int hl = c % GP, rep = c / GP;            // head and group replica of this lane's column / row
   int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
   int kvv = blockIdx.y;                           // KV head x part of its query group (see kv_share)
-  // Many short sequences (more (sequence, KV head) rows than the chip holds blocks, each a single chunk): a block
-  // takes NW / W rows, W waves each, instead of one; blockIdx.y then counts groups of rows of the list
-  // [batch][KV head x part].  A wave past the end of the list has no tokens and only keeps the barriers company.
-  const int W = p.waves_per_row;                  // NW: the whole block on one row
+  // Many short sequences (more units of work than the chip holds blocks): a block takes NW / W of them, W waves
+  // each, instead of one.  With a common length a unit is a (sequence, KV head) row of a single chunk, and
+  // blockIdx.y counts groups of rows of the list [batch][KV head x part]; with per-sequence lengths a unit is a
+  // slot of the chunk list, and blockIdx.x counts groups of slots.  A wave past the end of its list has no tokens
+  // and only keeps the barriers company.
+  const int W = p.waves_per_row;                  // NW: the whole block on one unit
   const bool whole = W == NW;
   bool row_valid = true;
-  if (!whole) {
+  if (!whole && p.var_chunks == 0) {
     const int rows_y = p.n_kv_heads * p.kv_share, total = p.batch * rows_y;
     const int row = blockIdx.y * (NW / W) + wave / W;
     row_valid = row < total;
@@ -288,7 +290,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int kv = kvv / p.kv_share;                // the KV head whose rows are read
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
-    if (!var_plan(p, blockIdx.x, vp)) return;
+    vp.b = 0;
+    vp.chunk = 0;
+    const bool listed = var_plan(p, whole ? blockIdx.x : blockIdx.x * (NW / W) + wave / W, vp);
+    if (whole && !listed) return;                 // (with several units per block nobody leaves before the barriers)
+    row_valid = listed;
     split = __builtin_amdgcn_readfirstlane(vp.chunk);     // (wave-uniform by construction: tell the compiler)
     b = __builtin_amdgcn_readfirstlane(vp.b);
     tokens_per_split = __builtin_amdgcn_readfirstlane(vp.chunk_tokens);
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
   // goes through and publishes an empty partial.)
-  if (begin0 >= seq && p.merge_slot < 0) return;
+  if (whole && begin0 >= seq && p.merge_slot < 0) return;
   const int end = max(begin0, min(seq, begin0 + tokens_per_split));
   // Several query tokens under a sliding window: the rows start at different tokens (row t one token after
   // row t - 1), all inside the sequence's first attended supertile; that supertile then takes the masked path
@@ -878,8 +884,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- merge the waves, write one partial per query head (Sec. 3.2); where the sequence is a single
   //      chunk and the kernel is to produce the output, that partial, normalised, IS the output
   const bool direct = p.merge_slot >= 0 && p.n_splits == 1;
-  if (!whole) {                                   // several rows per block: the W waves of a row merge among themselves
-    if (row_valid) {                              // (always a single chunk whose result is the output)
+  if (!whole) {                                   // several units per block: the W waves of one merge among themselves
+    if (row_valid) {                              // (a single-chunk row: the output; a slot of the chunk list: its partial)
       const int w0 = wave - sub;
       for (int idx = sub * 64 + lane; idx < G * D; idx += W * 64) {
         const int h = idx / D, j = idx % D;
@@ -892,7 +898,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
           num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
           den = fmaf(lds_l[w * GP + h], e, den);
         }
-        p.out[query_row(h) * D + j] = (half_t)(num / den);
+        if (direct) {
+          p.out[query_row(h) * D + j] = (half_t)(num / den);
+        } else {
+          const int64_t ph = query_row(h) * part_stride + split;
+          st_dev(p.part_o + ph * D + j, num);
+          if (j == 0) { st_dev(p.part_ml + ph * 2, mg); st_dev(p.part_ml + ph * 2 + 1, den); }
+        }
       }
     }
     return;
@@ -1059,13 +1071,13 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
     p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
   }
   if (p.waves_per_row != 1 && p.waves_per_row != 2 && p.waves_per_row != 4) p.waves_per_row = 8;
-  // several rows per block: only where every row is one chunk and the kernel writes the output itself
-  if (p.waves_per_row != 8 && (p.merge_slot < 0 || p.n_splits != 1 || p.var_chunks > 0 || p.block_table))
+  // several units per block: single-chunk rows whose output the kernel writes itself, or the slots of a chunk list
+  if (p.waves_per_row != 8 && p.var_chunks == 0 && (p.merge_slot < 0 || p.n_splits != 1 || p.block_table))
     return hipErrorInvalidValue;
-  const int rows_per_block = 8 / p.waves_per_row;
-  const dim3 grid = p.var_chunks > 0      ? dim3(p.var_chunks, rows_y, 1)
-                    : rows_per_block > 1 ? dim3(1, (batch * rows_y + rows_per_block - 1) / rows_per_block, 1)
-                                         : dim3(p.n_splits, rows_y, batch);
+  const int per_block = 8 / p.waves_per_row;
+  const dim3 grid = p.var_chunks > 0 ? dim3((p.var_chunks + per_block - 1) / per_block, rows_y, 1)
+                    : per_block > 1  ? dim3(1, (batch * rows_y + per_block - 1) / per_block, 1)
+                                     : dim3(p.n_splits, rows_y, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);

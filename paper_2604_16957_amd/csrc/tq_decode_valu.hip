@@ -192,36 +192,31 @@ __global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams 
   __shared__ float red_m[WAVES], red_l[WAVES];
   __shared__ float acc_part[PARTS][D];
 
-  // The first chunks of this thread's output element, and the chunks' (m, l), are asked for before anything
-  // else: they depend neither on the weights nor on how many chunks the sequence has (slots past its last
-  // chunk hold stale values, read and then ignored), so the kernel is about one memory round trip long and
-  // the chunk plan below is worked out while the loads are in flight.
-  constexpr int FIRST = 16;
-  const int j = tid % D, part = tid / D;
-  const float* src = p.part_o + ph0 * D + j;
-  float pre[FIRST];
-#pragma unroll
-  for (int u = 0; u < FIRST; ++u) pre[u] = src[(int64_t)min(part + u * PARTS, part_stride - 1) * D];
-  float2 ml = {kNegBig, 0.0f};
-  if (tid < part_stride) ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
-
-  // chunks that exist for this sequence: all of them, or those that start before its own end
+  // chunks that exist for this sequence: all of them, or those that start before its own end (with a plan made
+  // on the device: its chunk length, which the decode kernel left in the workspace)
   int n = p.n_splits;
   int append_pos = p.append_pos;
   if (p.seq_lens) {
     const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
-    if (p.var_chunks > 0) {
-      const int c = var_chunk_tokens(p);
-      n = (var_len(p, sequence) + c - 1) / c;
-    } else {
-      n = min(n, (var_len(p, sequence) + p.tokens_per_split - 1) / p.tokens_per_split);
-    }
+    const int c = p.var_chunks > 0 ? *p.plan : p.tokens_per_split;
+    n = min(n, (var_len(p, sequence) + c - 1) / c);
     // append-and-attend: the sequence's length counts the new token, which goes to its last position; a
     // sequence with no cached token has no chunk (the one the decode kernel made up is ignored)
     const int total = max(1, min(p.seq_lens[sequence], p.seq_len));
     append_pos = total - 1;
     if (total + p.len_bias < 1) n = 0;
   }
+  // The first chunks of this thread's output element, and the chunks' (m, l), are asked for before anything
+  // else: they do not depend on the weights, so the kernel is about one memory round trip long (two with
+  // per-sequence lengths, which have to arrive first).
+  constexpr int FIRST = 16;
+  const int j = tid % D, part = tid / D;
+  const float* src = p.part_o + ph0 * D + j;
+  float pre[FIRST];
+#pragma unroll
+  for (int u = 0; u < FIRST; ++u) pre[u] = src[(int64_t)min(part + u * PARTS, max(n, 1) - 1) * D];
+  float2 ml = {kNegBig, 0.0f};
+  if (tid < n) ml = *reinterpret_cast<const float2*>(p.part_ml + (ph0 + tid) * 2);
   const float m = tid < n ? ml.x : kNegBig, l = tid < n ? ml.y : 0.0f;
 
   // Append-and-attend in the merge (p.k_new set; one query token, common length): the step's new token is not in

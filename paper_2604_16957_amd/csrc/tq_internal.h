@@ -31,6 +31,7 @@ struct DecodeParams {
   float* part_o;            // [B][n_queries][H_q][n_splits][D]   un-normalised chunk outputs
   float* part_ml;           // [B][n_queries][H_q][n_splits][2]   (running max in log2 units, sum of exp)
   half_t* out;              // [B][n_queries][H_q][D]
+  int32_t* plan;            // one int behind part_ml: the chunk length of a device-planned launch, for the merge kernel
   int32_t n_q_heads, n_kv_heads, gqa;
   // Query tokens per sequence (>= 1): the sequence's last n_queries tokens, query t attending all tokens up
   // to its own (n_queries - 1 - t fewer than the sequence holds).  Matrix-core kernel only.
@@ -149,17 +150,26 @@ __device__ inline int var_len_of_lane(const DecodeParams& p, int tile) {
   const int b = tile * 64 + (int)(threadIdx.x & 63);
   return b < p.batch ? var_len(p, b) : 0;
 }
+// The planner keeps one sequence per lane: the lengths of the first 64 * kPlanTiles sequences stay in registers
+// (batches up to 256), those of larger batches are re-read where needed.
+constexpr int kPlanTiles = 4;
+struct VarLens { int len[kPlanTiles]; };
+__device__ inline void var_lens_load(const DecodeParams& p, VarLens& L) {
+#pragma unroll
+  for (int t = 0; t < kPlanTiles; ++t) L.len[t] = t * 64 < p.batch ? var_len_of_lane(p, t) : 0;
+}
 // The chunk length: the smallest multiple of 32 tokens for which all sequences together need at most
 // p.var_chunks chunks (the grid), not below p.var_min_chunk and long enough that no sequence needs more than
-// kMaxSplits.  Lane l looks after sequences l, l + 64, ... (the first of them stays in a register: len0); the
-// count for a candidate length is a wave-wide sum, and the candidates are bisected between total / var_chunks
-// (too short unless every sequence ends on a chunk boundary) and total / (var_chunks - batch) (always enough:
-// a sequence wastes less than one chunk).  Called by whole waves at the start of a kernel; every wave of
-// every kernel of a call gets the same answer.
-__device__ inline int var_chunk_tokens(const DecodeParams& p, int len0) {
+// kMaxSplits.  The count for a candidate length is a wave-wide sum, and the candidates are bisected between
+// total / var_chunks (too short unless every sequence ends on a chunk boundary) and
+// total / (var_chunks - batch) (always enough: a sequence wastes less than one chunk).  Called by whole waves
+// at the start of a kernel; every wave of a launch gets the same answer.
+__device__ inline int var_chunk_tokens(const DecodeParams& p, const VarLens& L) {
   const int tiles = (p.batch + 63) >> 6;
-  long long mine = len0;
-  for (int t = 1; t < tiles; ++t) mine += var_len_of_lane(p, t);
+  long long mine = 0;
+#pragma unroll
+  for (int t = 0; t < kPlanTiles; ++t) mine += L.len[t];
+  for (int t = kPlanTiles; t < tiles; ++t) mine += var_len_of_lane(p, t);
   const long long total = ((long long)wave_sum((int)(mine >> 24)) << 24) + wave_sum((int)(mine & 0xFFFFFF));
   const int floor_c = max(p.var_min_chunk, (p.seq_len + kMaxSplits - 1) / kMaxSplits);
   auto round_up = [](long long c) { return (int)((c + kTile - 1) / kTile * kTile); };
@@ -168,41 +178,49 @@ __device__ inline int var_chunk_tokens(const DecodeParams& p, int len0) {
   int lo = round_up(max((long long)floor_c, (total + p.var_chunks - 1) / p.var_chunks));
   while (lo < hi) {
     const int mid = (lo + (hi - lo) / 2) / kTile * kTile;        // lo <= mid < hi, a multiple of 32
-    int n = (len0 + mid - 1) / mid;
-    for (int t = 1; t < tiles; ++t) n += (var_len_of_lane(p, t) + mid - 1) / mid;
+    int n = 0;
+#pragma unroll
+    for (int t = 0; t < kPlanTiles; ++t)
+      if (t < tiles) n += (L.len[t] + mid - 1) / mid;
+    for (int t = kPlanTiles; t < tiles; ++t) n += (var_len_of_lane(p, t) + mid - 1) / mid;
     if (wave_sum(n) <= p.var_chunks) hi = mid;
     else lo = mid + kTile;
   }
   return hi;
 }
-__device__ inline int var_chunk_tokens(const DecodeParams& p) { return var_chunk_tokens(p, var_len_of_lane(p, 0)); }
 // Slot of the chunk list -> (sequence, chunk of it); false past the end of the list.  The chunk counts sit one
-// sequence per lane; the list is walked with scalar reads of those lanes (no memory access, no division).
+// sequence per lane; the tile of 64 sequences that holds the slot is found with wave-wide sums, the sequence
+// inside it with a prefix sum over the lanes.  The chunk length goes to p.plan for the merge kernel.
 __device__ inline bool var_plan(const DecodeParams& p, int slot, VarPlan& out) {
-  const int len0 = var_len_of_lane(p, 0);
-  const int c = var_chunk_tokens(p, len0);
+  VarLens L;
+  var_lens_load(p, L);
+  const int c = var_chunk_tokens(p, L);
   out.chunk_tokens = c;
-  const int tiles = (p.batch + 63) >> 6;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *p.plan = c;
+  const int tiles = (p.batch + 63) >> 6, lane = threadIdx.x & 63;
   int first = 0;
-  for (int t = 0; t < tiles; ++t) {
-    const int n = ((t == 0 ? len0 : var_len_of_lane(p, t)) + c - 1) / c;    // this lane's sequence: its chunks
+  bool found = false;
+  auto visit = [&](int t, int len) {              // tile t: does it hold the slot?  (wave-uniform)
+    const int n = (len + c - 1) / c;              // this lane's sequence: its chunks
     const int in_tile = wave_sum(n);
     if (slot < first + in_tile) {
-      const int lanes = min(64, p.batch - t * 64);
-      for (int i = 0; i < lanes; ++i) {
-        const int ni = __builtin_amdgcn_readlane(n, i);
-        if (slot < first + ni) {
-          out.b = t * 64 + i;
-          out.chunk = slot - first;
-          return true;
-        }
-        first += ni;
+      int incl = n;                               // inclusive prefix sum over the lanes
+      for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d);
+        if (lane >= d) incl += y;
       }
-      return false;                               // (not reached: the tile's counts add up to in_tile)
+      const int i = __ffsll((unsigned long long)__ballot(slot < first + incl)) - 1;   // first lane past the slot
+      out.b = t * 64 + i;
+      out.chunk = slot - first - (__builtin_amdgcn_readlane(incl, i) - __builtin_amdgcn_readlane(n, i));
+      found = true;
     }
     first += in_tile;
-  }
-  return false;
+  };
+#pragma unroll
+  for (int t = 0; t < kPlanTiles; ++t)
+    if (t < tiles && !found) visit(t, L.len[t]);
+  for (int t = kPlanTiles; t < tiles && !found; ++t) visit(t, var_len_of_lane(p, t));
+  return found;
 }
 #endif
 
