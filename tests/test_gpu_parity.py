@@ -1007,3 +1007,37 @@ def test_more_rows_than_blocks_are_packed_several_to_a_block(shape):
                 out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale)
                 torch.cuda.synchronize()
                 assert_close(out, _oracle_causal(q4, ocache, [S] * batch, w.attn_scale), f"{shape} batch={batch} S={S}, 2 queries")
+
+
+def test_eighty_sequences_with_their_own_lengths_and_a_step():
+    """Enough (sequence, head) rows that the chunk list's slots share blocks and the merge kernel takes four heads
+    per block: plain decode and the one-call step (append + attend) with per-sequence lengths, against the oracle."""
+    rng = np.random.default_rng(80)
+    B, S = 80, 1800
+    lens = [int(x) for x in rng.integers(1, S + 1, B)]
+    lens[0], lens[1] = S, 1
+    w = wl.custom(batch=B, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=S, seed=1900, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "80 sequences, own lengths")
+    # the step: wipe every sequence's last token, hand it over as the new one
+    kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    for t in cache.tensors():
+        for b in range(B):
+            t.view(torch.uint8)[b, :, lens[b] - 1] = 0xEE
+    out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "80 sequences, own lengths, append + decode")
+    for name, g, o in zip(("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"), cache.tensors(), ocache):
+        g = np16(g)
+        for b in range(B):
+            gb, ob = g[b, :, :lens[b]], o[b, :, :lens[b]]
+            if gb.dtype == np.float16:
+                gb, ob = gb.view(np.uint16), ob.view(np.uint16)
+            assert np.array_equal(gb, ob), f"{name} sequence {b}"
