@@ -13,7 +13,7 @@ using tq::half_t;
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// head dimensions the kernels are built for (512: the generic kernel only)
+// head dimensions the kernels are built for
 inline bool head_dim_ok(int d) { return d == 128 || d == 256 || d == 512; }
 
 int check_cache(const tq_kv_cache* c) {
@@ -33,6 +33,7 @@ struct Plan { int n_splits, tokens_per_split; };
 
 constexpr int kBlocksMfma = 256;   // matrix-core kernel: 8-wave blocks, one per compute unit
 constexpr int kBlocksValu = 512;   // generic kernel: 4-wave blocks, two per compute unit
+constexpr int kBlocksWide = 512;   // head_dim 512 matrix-core kernel: 4-wave blocks, two per compute unit
 
 // A chunk is never longer than this many tokens under the heuristic: the fp32 accumulators of one wave
 // then take in at most 64 tiles, which bounds the rounding they pick up however long the sequence is.
@@ -85,8 +86,10 @@ int check_decode(const tq_kv_cache* c, const void* q, int n_q_heads, int seq_len
   if (opts) {
     if (opts->variant < 0 || opts->variant > 2 || opts->n_splits < 0 || opts->window < 0) return TQ_ERR_UNSUPPORTED;
     if (opts->n_queries < 0 || opts->n_queries > tq::kMaxQueries) return TQ_ERR_UNSUPPORTED;
-    if (opts->n_queries > 1 && opts->variant == 1) return TQ_ERR_UNSUPPORTED;   // matrix-core kernel only
-    if (opts->variant == 2 && !tq::mfma_supported(c->head_dim, rows_of(c, n_q_heads, opts))) return TQ_ERR_UNSUPPORTED;
+    if (opts->n_queries > 1 && opts->variant == 1) return TQ_ERR_UNSUPPORTED;   // matrix-core kernels only
+    if (opts->variant == 2 && !tq::wide_supported(c->head_dim) &&
+        !tq::mfma_supported(c->head_dim, rows_of(c, n_q_heads, opts)))
+      return TQ_ERR_UNSUPPORTED;
   }
   if (workspace_bytes < tq_workspace_bytes(c->batch * queries_of(opts), n_q_heads, c->head_dim)) return TQ_ERR_WORKSPACE;
   return TQ_OK;
@@ -121,7 +124,8 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
 int hip_rc(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
 // Which kernel a decode call takes, and whether that kernel can also do the chunk merge.
-struct Route { bool ok, use_mfma, merge, single; };   // single: every sequence is one chunk (no merge needed at all)
+// single: every sequence is one chunk (no merge needed at all); wide: the head_dim 512 matrix-core kernel
+struct Route { bool ok, use_mfma, merge, single, wide; };
 // The in-kernel merge ends the kernel with a chain of device-wide round trips (publish the partial,
 // count in, read all partials) that one block walks alone: about 5 us, against about 3.5 us for the
 // separate merge kernel plus its launch.  It pays where the call is bound by launch overhead, not by
@@ -138,14 +142,17 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   const int variant = opts ? opts->variant : 0;
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
   const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
-  if (variant == 2 && !scale_ok) return {false, false, false, false};
+  if (variant == 2 && !scale_ok) return {false, false, false, false, false};
+  // head_dim 512: its own matrix-core kernel (any finite scale), partials merged by the merge kernel
+  if (variant != 1 && tq::wide_supported(cache->head_dim) && std::isfinite(attn_scale))
+    return {true, false, false, false, true};
   // the matrix-core kernel addresses a (batch, KV head) row of codes with 32-bit byte offsets
   const bool offsets_ok = (int64_t)seq_len * (cache->head_dim / 2) < (1ll << 31);
-  if (variant == 2 && !offsets_ok) return {false, false, false, false};
+  if (variant == 2 && !offsets_ok) return {false, false, false, false, false};
   const int rows = rows_of(cache, n_q_heads, opts);
   const bool use_mfma = variant == 2 || (variant == 0 && scale_ok && offsets_ok &&
                                          tq::mfma_supported(cache->head_dim, rows));
-  if (!use_mfma && queries_of(opts) > 1) return {false, false, false, false};
+  if (!use_mfma && queries_of(opts) > 1) return {false, false, false, false, false};
   // (more query rows than the kernel's tile holds: several blocks stream each KV head, counted as rows of their own)
   const int rows_per_batch = cache->n_kv_heads * std::max(1, use_mfma ? tq::mfma_kv_share(cache->head_dim, rows) : 1);
   const int64_t bytes = (int64_t)tq_kv_bytes(cache->batch, rows_per_batch, windowed(seq_len, opts), cache->head_dim);
@@ -154,7 +161,7 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
                                                opts ? opts->n_splits : 0, kBlocksMfma, 8).n_splits == 1;
   const bool merge =
       use_mfma && (single || (bytes <= kMergeInKernelMaxBytes && tq::mfma_can_merge(cache->batch, rows_per_batch)));
-  return {true, use_mfma, merge, single && merge};
+  return {true, use_mfma, merge, single && merge, false};
 }
 
 // One launch of phase 1: what to attend, and what came of it.
@@ -186,7 +193,7 @@ int run_partial(PartialRequest& rq) {
   const Route r = route_of(cache, n_q_heads, seq_len, rq.attn_scale, opts);
   if (!r.ok) return TQ_ERR_UNSUPPORTED;
   const bool use_mfma = r.use_mfma;
-  const int target = use_mfma ? kBlocksMfma : kBlocksValu;
+  const int target = use_mfma ? kBlocksMfma : r.wide ? kBlocksWide : kBlocksValu;
   int attended = windowed(seq_len, opts);         // chunks cover the attended tokens only
   // (paged cache: counted from the supertile boundary before the window, see var_start)
   if (rq.paged && attended < seq_len) attended = std::min(seq_len, attended + tq::kTile - 1);
@@ -194,10 +201,13 @@ int run_partial(PartialRequest& rq) {
   const bool append_in_merge = rq.k_new != nullptr;
   const int first = seq_len - attended;           // first attended token
   if (append_in_merge) --attended;
+  const int row_tiles = r.wide ? tq::wide_row_tiles(rows_of(cache, n_q_heads, opts),
+                                                    (int64_t)cache->batch * cache->n_kv_heads, std::max(1, attended))
+                               : 1;
   const int rows_per_batch =
-      cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : 1);
+      cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : row_tiles);
   const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
-                                use_mfma ? 8 : 1);
+                                use_mfma ? 8 : r.wide ? 2 : 1);
   DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan,
                                queries_of(opts));
   p.seq_lens = seq_lens;
@@ -225,7 +235,7 @@ int run_partial(PartialRequest& rq) {
     const int per_round = std::max(1, target / rows_per_batch);          // (one round never spills into a second)
     const int rounds = std::max(1, (2 * cache->batch + per_round - 1) / per_round);
     p.var_chunks = rounds * per_round;
-    p.var_min_chunk = use_mfma ? 8 * tq::kTile : tq::kTile;
+    p.var_min_chunk = use_mfma ? 8 * tq::kTile : r.wide ? 2 * tq::kTile : tq::kTile;
     p.n_splits = tq::kMaxSplits;
     // many sequences: the slots of several rounds share blocks (2, 4 or 8 to a block) and run in one
     if (use_mfma) p.waves_per_row = rounds > 4 ? 1 : rounds > 2 ? 2 : rounds > 1 ? 4 : 8;
@@ -245,6 +255,10 @@ int run_partial(PartialRequest& rq) {
     p.waves_per_row = total > 4 * target ? 1 : total > 2 * target ? 2 : total > target ? 4 : 8;
   }
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
+  if (r.wide) {
+    p.kv_share = row_tiles;
+    return hip_rc(tq::launch_partial_wide(p, cache->batch, cache->head_dim, s));
+  }
   return hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, false, s));
 }
 
@@ -305,7 +319,9 @@ int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t 
   if (n_q_heads < 1 || n_q_heads % cache->n_kv_heads != 0 || seq_len < 1 || seq_len > cache->capacity) return 0;
   if (opts && (opts->variant < 0 || opts->variant > 2)) return 0;
   if (opts && (opts->n_queries < 0 || opts->n_queries > tq::kMaxQueries || seq_len < queries_of(opts))) return 0;
-  if (opts && opts->variant == 2 && !tq::mfma_supported(cache->head_dim, rows_of(cache, n_q_heads, opts))) return 0;
+  if (opts && opts->variant == 2 && !tq::wide_supported(cache->head_dim) &&
+      !tq::mfma_supported(cache->head_dim, rows_of(cache, n_q_heads, opts)))
+    return 0;
   const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
   if (!r.ok) return 0;
   return r.merge ? 1 : 2;

@@ -1,0 +1,388 @@
+// Matrix-core fused int4 decode attention for head_dim 512 (the global-attention column of the kernel
+// configuration table, Appendix A: 32 query heads on one KV head), phase 1 of Sec. 3.2.
+//
+// At d = 512 a KV head's query group is a tile of 16 or 32 rows, every fetched byte is used by all of them,
+// and the work is arithmetic, not traffic: both contractions of Alg. 1 (lines 5 and 9) run on
+// v_mfma_f32_16x16x32_f16 for all rows of the tile at once, and the vector ALU prepares each operand once
+// per block, whatever the number of rows.
+//
+// One block = one chunk of one KV head x one tile of query rows; 4 waves that split the HEAD DIMENSION:
+// wave w owns dims 128w .. 128w+127, i.e. quantisation groups 4w .. 4w+3.
+//   scores  S^T = K Q^T (rows = 16 tokens, columns = 16 query rows), one MFMA per group: lane (kq, c) feeds
+//           packed word kq of the group of token c, its codes as fp16 SUBNORMALS (value c 2^-24, or c 2^-20
+//           for a nibble at bit 4: two ANDs per word pair, and the products and their sum are exact in the
+//           fp32 accumulator).  Scale and zero-point are applied to the accumulator in fp32,
+//             q.k^ = sum_g s_g (q_g.c_g - z_g sum(q_g)),
+//           so the scores carry no fp16 rounding of K (they are exponentiated: an error there is an error of
+//           the same relative size in a weight).  The four waves exchange their partial scores through LDS
+//           (one barrier per 32 tokens, two buffers) and every wave adds them up in the same order, so all
+//           four hold the same scores, bit for bit, and run the same online softmax.
+//   P V     rows = query rows, columns = dims: the accumulator layout of S^T (lane = query row, four
+//           tokens per lane and 16-token tile) IS the A-operand layout of P, so probabilities never move
+//           between lanes.  Lane (kq, c) reads packed word 16w + c of its 8 tokens, transposes 8 x 8
+//           nibbles with two byte-permute stages and DEQUANTISES them into fp16 operands ((c - z) s of Eq. 3
+//           with packed fp16 arithmetic: 1024 + c built by OR-ing the nibble into the mantissa of fp16 1024,
+//           minus 1024 (exact), times s plus -(z s); scale and zero-point differ per token: they sit
+//           pairwise in registers), one B operand per dim of the word; the wave accumulates its 128 output
+//           dims for every row of the tile, and no merge between the waves is needed.  (V enters the output
+//           linearly, so its fp16 rounding stays at the size of the fp16 rounding of the output itself.)
+// Loads go straight from global memory into registers, one 32-token step ahead of the arithmetic.
+//
+// Query rows: n_queries * G rows (t, g) per KV head (several query tokens: the sequence's last n_queries
+// tokens, causal among themselves), cut into tiles of 16 * RT rows; each row has its own [first, end) of
+// visible tokens, applied to the scores of every step.
+#include <algorithm>
+
+#include "tq_internal.h"
+
+namespace tq {
+namespace {
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int D = 512;
+constexpr int NG = D / kGroup;        // 16 groups per token
+constexpr int TB = D / 2;             // bytes of codes per token
+constexpr float kNegBig = -1.0e30f;   // "no token seen yet" (finite: no inf - inf)
+constexpr uint32_t kNib = 0x000F000Fu;     // one nibble in each half of a dword
+constexpr uint32_t kMagic = 0x64006400u;   // fp16 pair (1024, 1024): OR-ing a nibble into the mantissa gives 1024 + c
+
+// two codes (bits 0-3 and 16-19 of `bits`) -> the fp16 pair (c - z) s, with s and -(z s) given per half
+__device__ __forceinline__ uint32_t dequant2(uint32_t bits, half2v s, half2v nzs) {
+  const uint32_t x = (bits & kNib) | kMagic;
+  const half2v c = __builtin_bit_cast(half2v, x) - half2v{(half_t)1024.0f, (half_t)1024.0f};   // exact
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(c, s, nzs));
+}
+__device__ __forceinline__ half8v as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return __builtin_bit_cast(half8v, uint4v{a, b, c, d});
+}
+__device__ __forceinline__ float4v mfma16(half8v a, half8v b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+// -(z s) as fp16, from the stored fp16 zero-point and scale (one rounding)
+__device__ __forceinline__ half_t neg_zs(half_t z, half_t s) { return (half_t)(-((float)z * (float)s)); }
+
+// What one 32-token step needs from the cache, per lane (kq, c) of wave w.
+// Token slot i of a lane: token 4kq + i of the step's first 16-token tile (i < 4), of its second (i >= 4).
+struct Step {
+  uint32_t kw[2][4];     // K codes of token 16t + c: packed word kq of groups 4w .. 4w+3
+  uint2 ks[2][4], kz[2][4];   // scales and zero-points of those four groups (fp16 x 4), token 16t + 4kq + i
+  uint32_t vw[8];        // V codes of token slot i: packed word 16w + c (group 4w + c/4)
+  half_t vs[8], vz[8];
+};
+
+template <int RT>
+__global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p) {
+  __shared__ float4v s_part[2][4][RT * 2][64];    // [buffer][wave][row tile, token tile][lane]
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = lane & 15, kq = lane >> 4;
+
+  int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
+  if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
+    VarPlan vp;
+    if (!var_plan(p, blockIdx.x, vp)) return;
+    split = vp.chunk;
+    b = vp.b;
+    tokens_per_split = vp.chunk_tokens;
+    part_stride = kMaxSplits;
+  }
+  const int tiles = p.kv_share;                   // row tiles per KV head
+  const int kv = blockIdx.y / tiles, tile = blockIdx.y - kv * tiles;
+  const int NQ = p.n_queries, GF = p.gqa, rows_total = NQ * GF;
+
+  const int seq = p.seq_lens ? var_len(p, b) : p.seq_len;       // tokens the LAST query token attends, from `start`
+  const int start = p.seq_lens ? var_start(p, b) : p.start;
+  const bool paged = p.block_table != nullptr;
+  // paged cache under a window: the chunks count from a 32-token boundary up to 31 tokens before the window
+  const int lead = (paged && p.seq_lens) ? var_first(p, b) - start : 0;
+  const int begin = split * tokens_per_split;
+  if (begin >= seq) return;                       // chunk past the end of its sequence: nothing to emit
+  const int end = min(seq, begin + tokens_per_split);
+  const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
+
+  // ---- this lane's column of each row tile: which (query token, head) it is and which tokens it sees
+  int64_t qrow[RT];
+  bool rvalid[RT];
+  int lo_col[RT], end_col[RT];
+  auto row_of = [&](int r, int64_t& out_row, int& t_q) {        // tile row -> row of q / out / the partials
+    t_q = r / GF;
+    out_row = (int64_t)(b * NQ + t_q) * p.n_q_heads + kv * GF + (r - t_q * GF);
+  };
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = (tile * RT + rt) * 16 + c;
+    rvalid[rt] = r < rows_total;
+    int t_q;
+    row_of(min(r, rows_total - 1), qrow[rt], t_q);
+    // query token t attends NQ - 1 - t tokens fewer than the last one; under a window its own last `row_window`
+    const int own_end = seq - (NQ - 1 - t_q);
+    end_col[rt] = rvalid[rt] ? min(end, own_end) : begin;
+    lo_col[rt] = (NQ > 1 && p.row_window > 0) ? max(0, start + own_end - p.row_window) - start : lead;
+  }
+
+  // ---- query operands: B of S^T = K Q^T, MFMA m = group 4w + m, this lane's k-slots = its dims 8kq .. 8kq+7.
+  //      k-slot order of an unpacked word: dims 0,4,1,5,2,6,3,7; the nibbles at bit 4 carry c 2^-20, so their
+  //      query entries are pre-divided by 16.  qsum: 2^-24 sum of q over the group (for the zero-point term).
+  half8v qb[RT][4];
+  float qsum[RT][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const half8v x = *reinterpret_cast<const half8v*>(p.q + qrow[rt] * D + 32 * (4 * wave + m) + 8 * kq);
+      const half_t sixteenth = (half_t)0.0625f;
+      half8v y = {x[0], x[4], x[1] * sixteenth, x[5] * sixteenth, x[2], x[6], x[3] * sixteenth, x[7] * sixteenth};
+      float sum = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += (float)x[e];
+      sum += __shfl_xor(sum, 16);                 // the other three words of the group (same value in all four lanes)
+      sum += __shfl_xor(sum, 32);
+      if (!rvalid[rt]) { y = half8v{0, 0, 0, 0, 0, 0, 0, 0}; sum = 0.0f; }
+      qb[rt][m] = y;
+      qsum[rt][m] = sum * 0x1p-24f;
+    }
+  const float raw_to_log2 = p.scale_log2 * 0x1p24f;              // accumulator units -> log2 units
+
+  // ---- loads of one step.  tok0: first token of the step, counted from `start`, a multiple of 32 past
+  //      `begin`; tokens at or past `end` are clamped to the last one (their scores are masked).
+  //      Paged cache: start + tok0 is a multiple of 32 and a page a multiple of 32 tokens, so a step lies
+  //      in one page.
+  const int page_mask = paged ? (1 << p.page_shift) - 1 : 0;
+  auto load_step = [&](int tok0, Step& st) {
+    int64_t base = row0 + tok0;
+    if (paged) {
+      const int ta = start + tok0;
+      const int page = p.block_table[(int64_t)b * p.max_blocks + min(ta >> p.page_shift, p.max_blocks - 1)];
+      base = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & page_mask);
+    }
+    const int last = end - 1 - tok0;              // >= 0
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int64_t row = base + min(16 * t + c, last);
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        st.kw[t][m] = *reinterpret_cast<const uint32_t*>(p.k_codes + row * TB + 16 * (4 * wave + m) + 4 * kq);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {               // the accumulator rows of this lane: tokens 16t + 4kq + i
+        const int64_t r = base + min(16 * t + 4 * kq + i, last);
+        st.ks[t][i] = *reinterpret_cast<const uint2*>(p.k_scale + r * NG + 4 * wave);
+        st.kz[t][i] = *reinterpret_cast<const uint2*>(p.k_zero + r * NG + 4 * wave);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t row = base + min(16 * (i >> 2) + 4 * kq + (i & 3), last);
+      st.vw[i] = *reinterpret_cast<const uint32_t*>(p.v_codes + row * TB + 4 * (16 * wave + c));
+      st.vs[i] = p.v_scale[row * NG + 4 * wave + (c >> 2)];
+      st.vz[i] = p.v_zero[row * NG + 4 * wave + (c >> 2)];
+    }
+  };
+
+  // ---- running state (Alg. 1 lines 2-3), scores in log2 units
+  float m_run[RT], l_run[RT];                     // per column (query row); l: this lane's share of the sum
+  float4v oacc[RT][8];                            // rows 4kq+i of the tile, dim 8(16w+c) + index
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    m_run[rt] = kNegBig;
+    l_run[rt] = 0.0f;
+#pragma unroll
+    for (int mm = 0; mm < 8; ++mm) oacc[rt][mm] = float4v{0, 0, 0, 0};
+  }
+
+  const int n_steps = (end - begin + 31) >> 5;
+  Step cur;
+  load_step(begin, cur);
+  for (int it = 0; it < n_steps; ++it) {
+    const int tok0 = begin + 32 * it;
+    Step nxt;
+    if (it + 1 < n_steps) load_step(tok0 + 32, nxt);
+    else nxt = cur;
+
+    // -- this wave's share of the scores (Alg. 1 line 5): its four groups of K against the query rows,
+    //    per-group scale and zero-point applied in fp32 (accumulator units: 2^-24)
+    float4v sacc[RT][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      float4v acc[RT][4];
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const uint32_t w = cur.kw[t][m], w8 = w >> 8;
+        const half8v a = as_half8(w & kNib, w & (kNib << 4), w8 & kNib, w8 & (kNib << 4));
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt][m] = mfma16(a, qb[rt][m], float4v{0, 0, 0, 0});
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t sw[2] = {cur.ks[t][i].x, cur.ks[t][i].y}, zw[2] = {cur.kz[t][i].x, cur.kz[t][i].y};
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          float x = 0.0f;
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            const float sg = (float)__builtin_bit_cast(half_t, (uint16_t)(sw[m >> 1] >> (16 * (m & 1))));
+            const float zg = (float)__builtin_bit_cast(half_t, (uint16_t)(zw[m >> 1] >> (16 * (m & 1))));
+            x = fmaf(sg, fmaf(-zg, qsum[rt][m], acc[rt][m][i]), x);
+          }
+          sacc[rt][t][i] = x;
+        }
+      }
+    }
+    const int buf = it & 1;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) s_part[buf][wave][rt * 2 + t][lane] = sacc[rt][t];
+    __syncthreads();
+
+    // -- online softmax (Alg. 1 lines 6-8, 10), the same in all four waves
+    half8v pa[RT];
+    float corr[RT];
+    bool moved = false;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      float sc[2][4];
+      bool ok[2][4];
+      float mx = kNegBig;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const float4v x = (s_part[buf][0][rt * 2 + t][lane] + s_part[buf][1][rt * 2 + t][lane]) +
+                          (s_part[buf][2][rt * 2 + t][lane] + s_part[buf][3][rt * 2 + t][lane]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = tok0 + 16 * t + 4 * kq + i;
+          ok[t][i] = tok >= lo_col[rt] && tok < end_col[rt];
+          sc[t][i] = x[i] * raw_to_log2;
+          mx = ok[t][i] ? fmaxf(mx, sc[t][i]) : mx;
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[rt], mx);
+      moved = moved || m_new > m_run[rt];
+      corr[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+      m_run[rt] = m_new;
+      float sum = 0.0f;
+      float pr[2][4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pr[t][i] = ok[t][i] ? __builtin_amdgcn_exp2f(sc[t][i] - m_new) : 0.0f;
+          sum += pr[t][i];
+        }
+      l_run[rt] = fmaf(l_run[rt], corr[rt], sum);
+      // k-slots 2i, 2i+1: token slots i and 4+i
+      pa[rt] = half8v{(half_t)pr[0][0], (half_t)pr[1][0], (half_t)pr[0][1], (half_t)pr[1][1],
+                      (half_t)pr[0][2], (half_t)pr[1][2], (half_t)pr[0][3], (half_t)pr[1][3]};
+    }
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {               // some row's maximum moved: rescale (Alg. 1 line 9)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        float fr[4];                                             // accumulator row 4kq+i is the column of lane 4kq+i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fr[i] = __shfl(corr[rt], 4 * kq + i);
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) oacc[rt][mm][i] *= fr[i];
+      }
+    }
+
+    // -- P V (Alg. 1 line 9): 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens, dequantised per token pair
+    {
+      uint32_t x[8], y[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[i] = __builtin_amdgcn_perm(cur.vw[i + 4], cur.vw[i], 0x05040100u);
+        x[i + 4] = __builtin_amdgcn_perm(cur.vw[i + 4], cur.vw[i], 0x07060302u);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if ((i & 2) == 0) {
+          y[i] = __builtin_amdgcn_perm(x[i + 2], x[i], 0x06020400u);
+          y[i + 2] = __builtin_amdgcn_perm(x[i + 2], x[i], 0x07030501u);
+        }
+      // y[2I+a]: byte M = token slot 2M+a, low nibble dim 2I, high nibble dim 2I+1 of the packed word
+      half2v s[4], nzs[4];                                       // k-slot pair i: token slots i and 4+i
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        s[i] = half2v{cur.vs[i], cur.vs[i + 4]};
+        nzs[i] = half2v{neg_zs(cur.vz[i], cur.vs[i]), neg_zs(cur.vz[i + 4], cur.vs[i + 4])};
+      }
+#pragma unroll
+      for (int I = 0; I < 4; ++I) {
+        const uint32_t r0 = y[2 * I], r1 = y[2 * I + 1];
+        const half8v v_even = as_half8(dequant2(r0, s[0], nzs[0]), dequant2(r1, s[1], nzs[1]),
+                                       dequant2(r0 >> 8, s[2], nzs[2]), dequant2(r1 >> 8, s[3], nzs[3]));
+        const half8v v_odd = as_half8(dequant2(r0 >> 4, s[0], nzs[0]), dequant2(r1 >> 4, s[1], nzs[1]),
+                                      dequant2(r0 >> 12, s[2], nzs[2]), dequant2(r1 >> 12, s[3], nzs[3]));
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          oacc[rt][2 * I] = mfma16(pa[rt], v_even, oacc[rt][2 * I]);
+          oacc[rt][2 * I + 1] = mfma16(pa[rt], v_odd, oacc[rt][2 * I + 1]);
+        }
+      }
+    }
+    cur = nxt;
+  }
+
+  // ---- the chunk's partial (o_c, m_c, l_c) per query row (Sec. 3.2), un-normalised
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (wave == 0 && kq == 0 && rvalid[rt]) {
+      const int64_t ph = qrow[rt] * part_stride + split;
+      p.part_ml[ph * 2] = m_run[rt];
+      p.part_ml[ph * 2 + 1] = l_tot;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = (tile * RT + rt) * 16 + 4 * kq + i;
+      if (r >= rows_total) continue;
+      int64_t orow;
+      int t_q;
+      row_of(r, orow, t_q);
+      float4v* dst = reinterpret_cast<float4v*>(p.part_o + (orow * part_stride + split) * D + 8 * (16 * wave + c));
+      dst[0] = float4v{oacc[rt][0][i], oacc[rt][1][i], oacc[rt][2][i], oacc[rt][3][i]};
+      dst[1] = float4v{oacc[rt][4][i], oacc[rt][5][i], oacc[rt][6][i], oacc[rt][7][i]};
+    }
+  }
+}
+
+}  // namespace
+
+bool wide_supported(int head_dim) { return head_dim == D; }
+
+// Row tiles per KV head for `rows` query rows: tiles of 32 rows where that still leaves the chip enough
+// blocks (`units` = batch x KV heads, `tokens` = the longest sequence), else tiles of 16.
+int wide_row_tiles(int rows, int64_t units, int tokens) {
+  const int t16 = (rows + 15) / 16, t32 = (rows + 31) / 32;
+  const int64_t max_splits = std::max(1, std::min(kMaxSplits, tokens / 64));
+  return (rows > 16 && units * t32 * max_splits >= 512) ? t32 : t16;
+}
+
+hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim, hipStream_t s) {
+  DecodeParams p = p_in;
+  if (head_dim != D || p.gqa < 1 || p.kv_share < 1) return hipErrorInvalidValue;
+  if (p.n_queries < 1) p.n_queries = 1;
+  if (p.n_queries > kMaxQueries) return hipErrorInvalidValue;
+  const int rows = p.n_queries * p.gqa;
+  const int per_tile = (rows + p.kv_share - 1) / p.kv_share;
+  if (per_tile > 32) return hipErrorInvalidValue;
+  const int rt = per_tile > 16 ? 2 : 1;
+  if ((int64_t)p.kv_share * 16 * rt < rows) return hipErrorInvalidValue;
+  if (p.block_table && (p.page_shift < 5 || !p.seq_lens)) return hipErrorInvalidValue;   // a step must not straddle pages
+  const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads * p.kv_share, 1)
+                                     : dim3(p.n_splits, p.n_kv_heads * p.kv_share, batch);
+  if (rt == 2) hipLaunchKernelGGL((decode_partial_wide_kernel<2>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((decode_partial_wide_kernel<1>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace tq

@@ -250,6 +250,11 @@ int mfma_kv_share(int head_dim, int gqa);
 // With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
 bool mfma_can_merge(int batch, int n_kv_heads);
 hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
+// head_dim 512: matrix-core kernel whose blocks take a tile of 16 or 32 query rows of one KV head
+// (p.kv_share = row tiles per KV head, from wide_row_tiles; p.gqa = H_q / H_kv; p.n_queries query tokens).
+bool wide_supported(int head_dim);
+int wide_row_tiles(int rows, int64_t units, int tokens);
+hipError_t launch_partial_wide(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 

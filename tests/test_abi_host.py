@@ -73,8 +73,8 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(), ws=None) == E.TQ_ERR_NULL
     assert _decode(_cache(head_dim=64)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(head_dim=192)) == E.TQ_ERR_SHAPE
-    assert _decode(_cache(head_dim=512), wsb=tq.tq_workspace_bytes(1, 64, 512), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 2))) \
-        == E.TQ_ERR_UNSUPPORTED                                          # no matrix-core kernel at d = 512
+    assert _decode(_cache(head_dim=512), wsb=tq.tq_workspace_bytes(1, 64, 512), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 1, 0, 2))) \
+        == E.TQ_ERR_UNSUPPORTED                                          # several query tokens: matrix-core kernels only
     assert _decode(_cache(head_dim=1024)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(group_size=64)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(batch=0)) == E.TQ_ERR_SHAPE

@@ -686,7 +686,7 @@ def test_several_query_tokens_rejections():
 @pytest.mark.parametrize("shape", ["g4_d512", "g32_d512"])
 def test_head_dim_512(shape):
     """d = 512 (the global-attention configuration of the kernel table in the appendix, GQA 32): quantiser bit-exact,
-    the generic kernel for the attention (the matrix-core kernel is not built for it), every entry point."""
+    its own matrix-core kernel (query rows in tiles of 16 or 32) and the generic kernel, every entry point."""
     shapes = dict(g4_d512=dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=512, attn_scale=1.0, qk_std=0.1),
                   g32_d512=dict(n_q_heads=32, n_kv_heads=1, head_dim=512, attn_scale=1.0, qk_std=0.1))
     for S in (1, 33, 1000, 4133):
@@ -720,9 +720,9 @@ def test_head_dim_512(shape):
         base = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale)
         torch.cuda.synchronize()
         assert_close(base, ref, f"{shape} comparator S={S}", rel_l2=BASELINE_REL_L2)
-    with pytest.raises(tq.TqError) as e:
-        tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2)
-    assert e.value.status == -6
+        for variant in (1, 2):                    # the generic kernel, and the head_dim 512 matrix-core kernel by name
+            assert_close(tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=variant), ref,
+                         f"{shape} S={S} variant={variant}")
 
 
 # ---------------------------------------------------------------- paged cache
