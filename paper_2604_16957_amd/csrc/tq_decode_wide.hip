@@ -20,10 +20,10 @@
 //   P V     rows = query rows, columns = dims: the accumulator layout of S^T (lane = query row, four
 //           tokens per lane and 16-token tile) IS the A-operand layout of P, so probabilities never move
 //           between lanes.  Lane (kq, c) reads packed word 16w + c of its 8 tokens, transposes 8 x 8
-//           nibbles with two byte-permute stages and DEQUANTISES them into fp16 operands ((c - z) s of Eq. 3
-//           with packed fp16 arithmetic: 1024 + c built by OR-ing the nibble into the mantissa of fp16 1024,
-//           minus 1024 (exact), times s plus -(z s); scale and zero-point differ per token: they sit
-//           pairwise in registers), one B operand per dim of the word; the wave accumulates its 128 output
+//           nibbles with two byte-permute stages and DEQUANTISES them into fp16 operands ((c - z) s of Eq. 3:
+//           1024 + c built by OR-ing the nibble into the mantissa of fp16 1024, then one mixed-precision FMA
+//           per element, (1024 + c) s - (1024 + z) s in fp32, rounded once to fp16; scale and zero-point
+//           differ per token), one B operand per dim of the word; the wave accumulates its 128 output
 //           dims for every row of the tile, and no merge between the waves is needed.  (V enters the output
 //           linearly, so its fp16 rounding stays at the size of the fp16 rounding of the output itself.)
 // Loads go straight from global memory into registers, one 32-token step ahead of the arithmetic.
@@ -50,11 +50,19 @@ constexpr float kNegBig = -1.0e30f;   // "no token seen yet" (finite: no inf - i
 constexpr uint32_t kNib = 0x000F000Fu;     // one nibble in each half of a dword
 constexpr uint32_t kMagic = 0x64006400u;   // fp16 pair (1024, 1024): OR-ing a nibble into the mantissa gives 1024 + c
 
-// two codes (bits 0-3 and 16-19 of `bits`) -> the fp16 pair (c - z) s, with s and -(z s) given per half
-__device__ __forceinline__ uint32_t dequant2(uint32_t bits, half2v s, half2v nzs) {
-  const uint32_t x = (bits & kNib) | kMagic;
-  const half2v c = __builtin_bit_cast(half2v, x) - half2v{(half_t)1024.0f, (half_t)1024.0f};   // exact
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(c, s, nzs));
+// Scale and offset of one token's group for dequant2: (1024 + c) s + t with t = -(1024 + z) s  =  (c - z) s.
+// z s and 1024 s are exact in fp32, their sum is rounded at 2^-24 of 1024 s: far below an fp16 ulp of the result.
+struct ScaleOffset { float s, t; };
+__device__ __forceinline__ ScaleOffset scale_offset(half_t s16, half_t z16) {
+  const float s = (float)s16;
+  return {s, -fmaf(1024.0f, s, (float)z16 * s)};
+}
+// two codes (bits 0-3 and 16-19 of `bits`) -> the fp16 pair of their values (c - z) s (Eq. 3), each computed in
+// fp32 and rounded ONCE (fp16 sources, fp32 arithmetic, fp16 result: one mixed-precision FMA per element)
+__device__ __forceinline__ uint32_t dequant2(uint32_t bits, ScaleOffset lo, ScaleOffset hi) {
+  const half2v x = __builtin_bit_cast(half2v, (bits & kNib) | kMagic);     // (1024 + c_lo, 1024 + c_hi), exact
+  const half2v r = {(half_t)fmaf((float)x[0], lo.s, lo.t), (half_t)fmaf((float)x[1], hi.s, hi.t)};
+  return __builtin_bit_cast(uint32_t, r);
 }
 __device__ __forceinline__ half8v as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return __builtin_bit_cast(half8v, uint4v{a, b, c, d});
@@ -62,8 +70,6 @@ __device__ __forceinline__ half8v as_half8(uint32_t a, uint32_t b, uint32_t c, u
 __device__ __forceinline__ float4v mfma16(half8v a, half8v b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
-// -(z s) as fp16, from the stored fp16 zero-point and scale (one rounding)
-__device__ __forceinline__ half_t neg_zs(half_t z, half_t s) { return (half_t)(-((float)z * (float)s)); }
 
 // What one 32-token step needs from the cache, per lane (kq, c) of wave w.
 // Token slot i of a lane: token 4kq + i of the step's first 16-token tile (i < 4), of its second (i >= 4).
@@ -308,19 +314,16 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
           y[i + 2] = __builtin_amdgcn_perm(x[i + 2], x[i], 0x07030501u);
         }
       // y[2I+a]: byte M = token slot 2M+a, low nibble dim 2I, high nibble dim 2I+1 of the packed word
-      half2v s[4], nzs[4];                                       // k-slot pair i: token slots i and 4+i
+      ScaleOffset so[8];                                         // per token slot; k-slot pair i: token slots i and 4+i
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        s[i] = half2v{cur.vs[i], cur.vs[i + 4]};
-        nzs[i] = half2v{neg_zs(cur.vz[i], cur.vs[i]), neg_zs(cur.vz[i + 4], cur.vs[i + 4])};
-      }
+      for (int i = 0; i < 8; ++i) so[i] = scale_offset(cur.vs[i], cur.vz[i]);
 #pragma unroll
       for (int I = 0; I < 4; ++I) {
         const uint32_t r0 = y[2 * I], r1 = y[2 * I + 1];
-        const half8v v_even = as_half8(dequant2(r0, s[0], nzs[0]), dequant2(r1, s[1], nzs[1]),
-                                       dequant2(r0 >> 8, s[2], nzs[2]), dequant2(r1 >> 8, s[3], nzs[3]));
-        const half8v v_odd = as_half8(dequant2(r0 >> 4, s[0], nzs[0]), dequant2(r1 >> 4, s[1], nzs[1]),
-                                      dequant2(r0 >> 12, s[2], nzs[2]), dequant2(r1 >> 12, s[3], nzs[3]));
+        const half8v v_even = as_half8(dequant2(r0, so[0], so[4]), dequant2(r1, so[1], so[5]),
+                                       dequant2(r0 >> 8, so[2], so[6]), dequant2(r1 >> 8, so[3], so[7]));
+        const half8v v_odd = as_half8(dequant2(r0 >> 4, so[0], so[4]), dequant2(r1 >> 4, so[1], so[5]),
+                                      dequant2(r0 >> 12, so[2], so[6]), dequant2(r1 >> 12, so[3], so[7]));
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           oacc[rt][2 * I] = mfma16(pa[rt], v_even, oacc[rt][2 * I]);

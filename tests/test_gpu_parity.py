@@ -97,6 +97,12 @@ SHAPES = {
     "g4_d256": dict(n_q_heads=4, n_kv_heads=1, head_dim=256),
     "g3_d128": dict(n_q_heads=6, n_kv_heads=2, head_dim=128),
     "g16_d128": dict(n_q_heads=16, n_kv_heads=1, head_dim=128),
+    # d = 512 rows have four times the elements, and a row that attends one or two tokens IS (nearly) a value vector:
+    # with V ~ N(0,1) some outputs then exceed 4, where the fp16 output's own spacing (2^-8) is twice the absolute
+    # tolerance.  These shapes serve the masking edge cases, so V gets half the spread.
+    "g4_d512_b2_kv2": dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=512, attn_scale=1.0, qk_std=0.1, v_std=0.5),
+    "g32_d512": dict(n_q_heads=32, n_kv_heads=1, head_dim=512, attn_scale=1.0, qk_std=0.1, v_std=0.5),
+    "g6_d512": dict(n_q_heads=6, n_kv_heads=1, head_dim=512, v_std=0.5),
 }
 
 
@@ -441,8 +447,9 @@ def test_random_configurations_against_the_oracle():
     """Seeded sweep over shapes, lengths, chunk counts, windows and per-sequence lengths: every
     combination goes through whichever kernel the library picks and through the generic one."""
     rng = np.random.default_rng(20260416)
-    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 4), (256, 2), (256, 1), (128, 16), (128, 12), (256, 6), (512, 2)]
-    for case in range(60):
+    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 4), (256, 2), (256, 1), (128, 16), (128, 12), (256, 6), (512, 2),
+              (512, 20), (512, 32)]
+    for case in range(70):
         d, G = shapes[rng.integers(len(shapes))]
         Hkv = int(rng.integers(1, 4))
         B = int(rng.integers(1, 4))
@@ -475,8 +482,8 @@ def test_random_configurations_against_the_oracle():
 def test_random_configurations_with_several_query_tokens():
     """The same kind of sweep with 2 ... 8 causal query tokens per sequence (matrix-core kernel only)."""
     rng = np.random.default_rng(20260417)
-    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 2), (256, 1), (128, 16), (256, 3)]
-    for case in range(40):
+    shapes = [(128, 8), (128, 4), (128, 3), (128, 1), (256, 2), (256, 1), (128, 16), (256, 3), (512, 2), (512, 5), (512, 8)]
+    for case in range(50):
         d, G = shapes[rng.integers(len(shapes))]
         Hkv = int(rng.integers(1, 4))
         B = int(rng.integers(1, 4))
@@ -623,7 +630,7 @@ def test_several_query_tokens(shape, nq):
 
 
 @pytest.mark.parametrize("nq", [2, 5])
-@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256"])
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256", "g4_d512_b2_kv2"])
 def test_several_query_tokens_append_varlen_and_two_phase(shape, nq):
     """The other entry points with n_queries > 1: append the nq tokens and attend in one call (stored bits equal
     the oracle's); per-sequence lengths; phase 1 and phase 2 called separately."""
@@ -725,10 +732,36 @@ def test_head_dim_512(shape):
                          f"{shape} S={S} variant={variant}")
 
 
+@pytest.mark.parametrize("nq", [2, 3, 8])
+@pytest.mark.parametrize("shape", ["g4_d512_b2_kv2", "g32_d512", "g6_d512"])
+def test_head_dim_512_several_query_tokens(shape, nq):
+    """d = 512 with n_queries > 1: the rows (query token, head) of a KV head fill one tile of 16 or 32 rows or
+    several (32 heads x 8 tokens: 256 rows); every row has its own causal end and, under a window, its own start."""
+    for S, n_splits in ((nq, 0), (33, 0), (64, 0), (71, 0), (1000, 0), (1030, 4), (2500, 0)):
+        if S < nq:
+            continue
+        w = wl.custom(seq_len=S, seed=1500 + S + nq, **SHAPES[shape])
+        _, k, v = make(w)
+        q4 = _queries_for(w, nq)
+        cache = gpu_cache_from(k, v, capacity=S + 3)
+        ocache = oracle_cache_from(k, v)
+        out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, n_splits=n_splits)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale), f"{shape} nq={nq} S={S}")
+        for window in (1, 5, 40, 700):
+            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, n_splits=n_splits, window=window)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale, window),
+                         f"{shape} nq={nq} S={S} window={window}")
+    with pytest.raises(tq.TqError) as e:
+        tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, variant=1)
+    assert e.value.status == -6
+
+
 # ---------------------------------------------------------------- paged cache
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
-@pytest.mark.parametrize("shape", ["g8_d128_kv2", "g2_d256"])
+@pytest.mark.parametrize("shape", ["g8_d128_kv2", "g2_d256", "g6_d512"])
 def test_paged_cache(shape, variant):
     """Sequences scattered page by page over a pool: fill and append through the block table, attend
     with per-sequence lengths; the oracle gets each sequence's tokens gathered back in order."""
