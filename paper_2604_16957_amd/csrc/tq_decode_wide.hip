@@ -26,7 +26,13 @@
 //           differ per token), one B operand per dim of the word; the wave accumulates its 128 output
 //           dims for every row of the tile, and no merge between the waves is needed.  (V enters the output
 //           linearly, so its fp16 rounding stays at the size of the fp16 rounding of the output itself.)
-// Loads go straight from global memory into registers, one 32-token step ahead of the arithmetic.
+// Data path: the packed stream goes from global memory straight into LDS (global_load_lds_dwordx4, no
+// registers in between), a ring of NSTG stages of one 32-token step each, filled NSTG - 1 steps ahead of the
+// arithmetic by all four waves together.  The source address of such a load is free per lane while its
+// LDS destination is linear, so K codes land as [group][token] (the order the A operands are read in:
+// no bank conflicts) and the rest lands as it lies in HBM, V codes with 64 B of padding per four tokens.
+// A wave waits for its own loads of the next stage before the step's one barrier, so behind the barrier
+// the whole stage is there for everybody, and the stage read two steps ago is free to be refilled.
 //
 // Query rows: n_queries * G rows (t, g) per KV head (several query tokens: the sequence's last n_queries
 // tokens, causal among themselves), cut into tiles of 16 * RT rows; each row has its own [first, end) of
@@ -71,18 +77,42 @@ __device__ __forceinline__ float4v mfma16(half8v a, half8v b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// What one 32-token step needs from the cache, per lane (kq, c) of wave w.
+// What one 32-token step needs from its stage, per lane (kq, c) of wave w.
 // Token slot i of a lane: token 4kq + i of the step's first 16-token tile (i < 4), of its second (i >= 4).
-struct Step {
+struct StepK {
   uint32_t kw[2][4];     // K codes of token 16t + c: packed word kq of groups 4w .. 4w+3
   uint2 ks[2][4], kz[2][4];   // scales and zero-points of those four groups (fp16 x 4), token 16t + 4kq + i
+};
+struct StepV {
   uint32_t vw[8];        // V codes of token slot i: packed word 16w + c (group 4w + c/4)
   half_t vs[8], vz[8];
 };
 
-template <int RT>
+// One stage of the ring: a 32-token step of one KV head.
+constexpr int kStageK = 0;                        // K codes, 16-byte pieces [group 16][token 32]
+constexpr int kStageV = 32 * TB;                  // V codes, as in HBM, eight loads of 4 tokens, 64 B apart
+constexpr int kVChunk = 4 * TB + 64;
+constexpr int kStageS = kStageV + 8 * kVChunk;    // k_scale, k_zero, v_scale, v_zero: [token 32][group 16] fp16 each
+constexpr int kStageBytes = kStageS + 4 * 32 * NG * 2;
+constexpr int kLoadsPerStage = 5;                 // per lane: 2 K, 2 V, 1 scale array (wave w: array w)
+
+// direct global -> LDS load of 16 B per lane: lane l's bytes land at lds_base + 16 l (M0 carries the base)
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {    // until at most N vector-memory loads of this wave are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// RT: 16-row tiles per block.  NSTG: stages of the ring (3 with 16 rows: two blocks fit a compute unit's LDS and
+// registers and cover each other's waits; more where a compute unit gets one block anyway).
+template <int RT, int NSTG>
 __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p) {
+  static_assert(NSTG >= 3 && NSTG <= 6, "ring depth");
   __shared__ float4v s_part[2][4][RT * 2][64];    // [buffer][wave][row tile, token tile][lane]
+  __shared__ __attribute__((aligned(16))) char ring[NSTG * kStageBytes];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -92,9 +122,9 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
     if (!var_plan(p, blockIdx.x, vp)) return;
-    split = vp.chunk;
-    b = vp.b;
-    tokens_per_split = vp.chunk_tokens;
+    split = __builtin_amdgcn_readfirstlane(vp.chunk);           // (wave-uniform by construction: tell the compiler)
+    b = __builtin_amdgcn_readfirstlane(vp.b);
+    tokens_per_split = __builtin_amdgcn_readfirstlane(vp.chunk_tokens);
     part_stride = kMaxSplits;
   }
   const int tiles = p.kv_share;                   // row tiles per KV head
@@ -131,6 +161,88 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
     lo_col[rt] = (NQ > 1 && p.row_window > 0) ? max(0, start + own_end - p.row_window) - start : lead;
   }
 
+  // ---- one step of the chunk -> its stage of the ring: kLoadsPerStage loads per lane, all 256 lanes.
+  //      Step j starts 32 j tokens past `begin`; tokens at or past `end` are clamped to the last one (their
+  //      scores are masked).  Paged cache: start + the step's first token is a multiple of 32 and a page a
+  //      multiple of 32 tokens, so a step lies in one page.
+  const int page_mask = paged ? (1 << p.page_shift) - 1 : 0;
+  const int32_t* const tbl = paged ? p.block_table + (int64_t)b * p.max_blocks : nullptr;
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
+  const char* const sz_array = reinterpret_cast<const char*>(wave == 0 ? p.k_scale : wave == 1 ? p.k_zero
+                                                             : wave == 2 ? p.v_scale : p.v_zero);
+  auto issue_step = [&](int j) {
+    const int tok0 = begin + 32 * j;
+    int64_t base = row0 + tok0;                   // wave-uniform
+    if (paged) {
+      // the page of this step: a scalar load (a vector load here would make the compiler wait for every
+      // outstanding load of the ring)
+      const int ta = start + tok0;
+      const uint32_t byte = (uint32_t)min(ta >> p.page_shift, p.max_blocks - 1) * 4;
+      int page;
+      asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(page) : "s"(tbl), "s"(byte) : "memory");
+      base = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & page_mask);
+    }
+    const int last = end - 1 - tok0;              // >= 0: the step's last valid token
+    const uint32_t l = ring_lds + (j % NSTG) * kStageBytes;
+    const char* const kc = reinterpret_cast<const char*>(p.k_codes) + base * TB;
+    const char* const vc = reinterpret_cast<const char*>(p.v_codes) + base * TB;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      // K: piece (group g, token t) goes to position 32 g + t; this lane fills position 256 u + threadIdx.x
+      const int g = 8 * u + 2 * wave + (lane >> 5), t = min(lane & 31, last);
+      dma16(kc, (uint32_t)(t * TB + g * 16), l + kStageK + (256 * u + 64 * wave) * 16);
+      // V: load r = 4u + wave brings tokens 4r .. 4r+3 whole; this lane's piece: token 4r + lane/16, bytes 16 (lane%16)
+      const int r = 4 * u + wave, tv = min(4 * r + (lane >> 4), last);
+      dma16(vc, (uint32_t)(tv * TB + (lane & 15) * 16), l + kStageV + r * kVChunk);
+    }
+    // scale / zero-point array `wave`: token lane/2, half lane%2 of its 32 bytes
+    dma16(sz_array + base * (NG * 2), (uint32_t)(min(lane >> 1, last) * (NG * 2) + (lane & 1) * 16),
+          l + kStageS + wave * (32 * NG * 2));
+  };
+  auto read_k = [&](int j, StepK& st) {
+    const char* const stg = ring + (j % NSTG) * kStageBytes;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+        st.kw[t][m] = *reinterpret_cast<const uint32_t*>(stg + kStageK + ((4 * wave + m) * 32 + 16 * t + c) * 16 + 4 * kq);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {               // the accumulator rows of this lane: tokens 16t + 4kq + i
+        const int tok = 16 * t + 4 * kq + i;
+        st.ks[t][i] = *reinterpret_cast<const uint2*>(stg + kStageS + tok * (NG * 2) + 8 * wave);
+        st.kz[t][i] = *reinterpret_cast<const uint2*>(stg + kStageS + 32 * NG * 2 + tok * (NG * 2) + 8 * wave);
+      }
+    }
+  };
+  auto read_v = [&](int j, StepV& st) {
+    const char* const stg = ring + (j % NSTG) * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {                 // token 16 (i/4) + 4 kq + i%4: load 4 (i/4) + kq, its token i%4
+      const int tok = 16 * (i >> 2) + 4 * kq + (i & 3);
+      st.vw[i] = *reinterpret_cast<const uint32_t*>(stg + kStageV + (4 * (i >> 2) + kq) * kVChunk + (i & 3) * TB +
+                                                    4 * (16 * wave + c));
+      st.vs[i] = *reinterpret_cast<const half_t*>(stg + kStageS + 2 * 32 * NG * 2 + tok * (NG * 2) + 2 * (4 * wave + (c >> 2)));
+      st.vz[i] = *reinterpret_cast<const half_t*>(stg + kStageS + 3 * 32 * NG * 2 + tok * (NG * 2) + 2 * (4 * wave + (c >> 2)));
+    }
+  };
+
+  // ---- running state (Alg. 1 lines 2-3), scores in log2 units
+  float m_run[RT], l_run[RT];                     // per column (query row); l: this lane's share of the sum
+  float4v oacc[RT][8];                            // rows 4kq+i of the tile, dim 8(16w+c) + index
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    m_run[rt] = kNegBig;
+    l_run[rt] = 0.0f;
+#pragma unroll
+    for (int mm = 0; mm < 8; ++mm) oacc[rt][mm] = float4v{0, 0, 0, 0};
+  }
+
+  // ---- prologue: the first NSTG - 1 steps are on their way while the query operands are built
+  const int n_steps = (end - begin + 31) >> 5;
+#pragma unroll
+  for (int j = 0; j < NSTG - 1; ++j)
+    if (j < n_steps) issue_step(j);
+
   // ---- query operands: B of S^T = K Q^T, MFMA m = group 4w + m, this lane's k-slots = its dims 8kq .. 8kq+7.
   //      k-slot order of an unpacked word: dims 0,4,1,5,2,6,3,7; the nibbles at bit 4 carry c 2^-20, so their
   //      query entries are pre-divided by 16.  qsum: 2^-24 sum of q over the group (for the zero-point term).
@@ -154,60 +266,13 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
     }
   const float raw_to_log2 = p.scale_log2 * 0x1p24f;              // accumulator units -> log2 units
 
-  // ---- loads of one step.  tok0: first token of the step, counted from `start`, a multiple of 32 past
-  //      `begin`; tokens at or past `end` are clamped to the last one (their scores are masked).
-  //      Paged cache: start + tok0 is a multiple of 32 and a page a multiple of 32 tokens, so a step lies
-  //      in one page.
-  const int page_mask = paged ? (1 << p.page_shift) - 1 : 0;
-  auto load_step = [&](int tok0, Step& st) {
-    int64_t base = row0 + tok0;
-    if (paged) {
-      const int ta = start + tok0;
-      const int page = p.block_table[(int64_t)b * p.max_blocks + min(ta >> p.page_shift, p.max_blocks - 1)];
-      base = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & page_mask);
-    }
-    const int last = end - 1 - tok0;              // >= 0
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int64_t row = base + min(16 * t + c, last);
-#pragma unroll
-      for (int m = 0; m < 4; ++m)
-        st.kw[t][m] = *reinterpret_cast<const uint32_t*>(p.k_codes + row * TB + 16 * (4 * wave + m) + 4 * kq);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {               // the accumulator rows of this lane: tokens 16t + 4kq + i
-        const int64_t r = base + min(16 * t + 4 * kq + i, last);
-        st.ks[t][i] = *reinterpret_cast<const uint2*>(p.k_scale + r * NG + 4 * wave);
-        st.kz[t][i] = *reinterpret_cast<const uint2*>(p.k_zero + r * NG + 4 * wave);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int64_t row = base + min(16 * (i >> 2) + 4 * kq + (i & 3), last);
-      st.vw[i] = *reinterpret_cast<const uint32_t*>(p.v_codes + row * TB + 4 * (16 * wave + c));
-      st.vs[i] = p.v_scale[row * NG + 4 * wave + (c >> 2)];
-      st.vz[i] = p.v_zero[row * NG + 4 * wave + (c >> 2)];
-    }
-  };
+  wait_loads<0>();
+  __syncthreads();                                // the prologue's stages have landed, everybody's part of them
 
-  // ---- running state (Alg. 1 lines 2-3), scores in log2 units
-  float m_run[RT], l_run[RT];                     // per column (query row); l: this lane's share of the sum
-  float4v oacc[RT][8];                            // rows 4kq+i of the tile, dim 8(16w+c) + index
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    m_run[rt] = kNegBig;
-    l_run[rt] = 0.0f;
-#pragma unroll
-    for (int mm = 0; mm < 8; ++mm) oacc[rt][mm] = float4v{0, 0, 0, 0};
-  }
-
-  const int n_steps = (end - begin + 31) >> 5;
-  Step cur;
-  load_step(begin, cur);
   for (int it = 0; it < n_steps; ++it) {
     const int tok0 = begin + 32 * it;
-    Step nxt;
-    if (it + 1 < n_steps) load_step(tok0 + 32, nxt);
-    else nxt = cur;
+    StepK cur;
+    read_k(it, cur);
 
     // -- this wave's share of the scores (Alg. 1 line 5): its four groups of K against the query rows,
     //    per-group scale and zero-point applied in fp32 (accumulator units: 2^-24)
@@ -243,7 +308,17 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int t = 0; t < 2; ++t) s_part[buf][wave][rt * 2 + t][lane] = sacc[rt][t];
+    // The step's one barrier.  Before it every wave makes sure that its own loads of stage it + 1 have landed
+    // (loads complete in order; only the stages issued after that one may still be out), so behind it the
+    // whole of stage it + 1 is there for everybody; and everybody is done with stage it - 1, which is refilled.
+    switch (min(NSTG - 3, max(0, n_steps - it - 2))) {           // stages issued after stage it + 1
+      case 3: wait_loads<3 * kLoadsPerStage>(); break;
+      case 2: wait_loads<2 * kLoadsPerStage>(); break;
+      case 1: wait_loads<1 * kLoadsPerStage>(); break;
+      default: wait_loads<0>(); break;
+    }
     __syncthreads();
+    if (it + NSTG - 1 < n_steps) issue_step(it + NSTG - 1);
 
     // -- online softmax (Alg. 1 lines 6-8, 10), the same in all four waves
     half8v pa[RT];
@@ -301,11 +376,13 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
 
     // -- P V (Alg. 1 line 9): 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens, dequantised per token pair
     {
+      StepV curv;
+      read_v(it, curv);
       uint32_t x[8], y[8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        x[i] = __builtin_amdgcn_perm(cur.vw[i + 4], cur.vw[i], 0x05040100u);
-        x[i + 4] = __builtin_amdgcn_perm(cur.vw[i + 4], cur.vw[i], 0x07060302u);
+        x[i] = __builtin_amdgcn_perm(curv.vw[i + 4], curv.vw[i], 0x05040100u);
+        x[i + 4] = __builtin_amdgcn_perm(curv.vw[i + 4], curv.vw[i], 0x07060302u);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i)
@@ -316,7 +393,7 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
       // y[2I+a]: byte M = token slot 2M+a, low nibble dim 2I, high nibble dim 2I+1 of the packed word
       ScaleOffset so[8];                                         // per token slot; k-slot pair i: token slots i and 4+i
 #pragma unroll
-      for (int i = 0; i < 8; ++i) so[i] = scale_offset(cur.vs[i], cur.vz[i]);
+      for (int i = 0; i < 8; ++i) so[i] = scale_offset(curv.vs[i], curv.vz[i]);
 #pragma unroll
       for (int I = 0; I < 4; ++I) {
         const uint32_t r0 = y[2 * I], r1 = y[2 * I + 1];
@@ -331,7 +408,6 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
         }
       }
     }
-    cur = nxt;
   }
 
   // ---- the chunk's partial (o_c, m_c, l_c) per query row (Sec. 3.2), un-normalised
@@ -383,8 +459,11 @@ hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim
   if (p.block_table && (p.page_shift < 5 || !p.seq_lens)) return hipErrorInvalidValue;   // a step must not straddle pages
   const dim3 grid = p.var_chunks > 0 ? dim3(p.var_chunks, p.n_kv_heads * p.kv_share, 1)
                                      : dim3(p.n_splits, p.n_kv_heads * p.kv_share, batch);
-  if (rt == 2) hipLaunchKernelGGL((decode_partial_wide_kernel<2>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((decode_partial_wide_kernel<1>), grid, dim3(256), 0, s, p);
+  // more blocks than compute units: shallow rings, two blocks per unit (16-row tiles); else one block with a deep ring
+  const bool crowded = (int64_t)grid.x * grid.y * grid.z > 256;
+  if (rt == 2) hipLaunchKernelGGL((decode_partial_wide_kernel<2, 5>), grid, dim3(256), 0, s, p);
+  else if (crowded) hipLaunchKernelGGL((decode_partial_wide_kernel<1, 3>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((decode_partial_wide_kernel<1, 6>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
