@@ -38,6 +38,7 @@
 // tokens, causal among themselves), cut into tiles of 16 * RT rows; each row has its own [first, end) of
 // visible tokens, applied to the scores of every step.
 #include <algorithm>
+#include <type_traits>
 
 #include "tq_internal.h"
 
@@ -66,7 +67,9 @@ __device__ __forceinline__ ScaleOffset scale_offset(half_t s16, half_t z16) {
 // two codes (bits 0-3 and 16-19 of `bits`) -> the fp16 pair of their values (c - z) s (Eq. 3), each computed in
 // fp32 and rounded ONCE (fp16 sources, fp32 arithmetic, fp16 result: one mixed-precision FMA per element)
 __device__ __forceinline__ uint32_t dequant2(uint32_t bits, ScaleOffset lo, ScaleOffset hi) {
-  const half2v x = __builtin_bit_cast(half2v, (bits & kNib) | kMagic);     // (1024 + c_lo, 1024 + c_hi), exact
+  uint32_t u;                                                   // (bits & kNib) | kMagic in one instruction
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(u) : "v"(bits), "v"(kNib), "v"(kMagic));
+  const half2v x = __builtin_bit_cast(half2v, u);               // (1024 + c_lo, 1024 + c_hi), exact
   const half2v r = {(half_t)fmaf((float)x[0], lo.s, lo.t), (half_t)fmaf((float)x[1], hi.s, hi.t)};
   return __builtin_bit_cast(uint32_t, r);
 }
@@ -160,6 +163,20 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
     end_col[rt] = rvalid[rt] ? min(end, own_end) : begin;
     lo_col[rt] = (NQ > 1 && p.row_window > 0) ? max(0, start + own_end - p.row_window) - start : lead;
   }
+  // the tokens that every row of the tile sees: [lo_all, end_all) (columns past the last row do not count)
+  int lo_all = 0, end_all = end;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    lo_all = max(lo_all, rvalid[rt] ? lo_col[rt] : 0);
+    end_all = min(end_all, rvalid[rt] ? end_col[rt] : end);
+  }
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    lo_all = max(lo_all, __shfl_xor(lo_all, off));
+    end_all = min(end_all, __shfl_xor(end_all, off));
+  }
+  lo_all = __builtin_amdgcn_readfirstlane(lo_all);
+  end_all = __builtin_amdgcn_readfirstlane(end_all);
 
   // ---- one step of the chunk -> its stage of the ring: kLoadsPerStage loads per lane, all 256 lanes.
   //      Step j starts 32 j tokens past `begin`; tokens at or past `end` are clamped to the last one (their
@@ -320,47 +337,53 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
     __syncthreads();
     if (it + NSTG - 1 < n_steps) issue_step(it + NSTG - 1);
 
-    // -- online softmax (Alg. 1 lines 6-8, 10), the same in all four waves
+    // -- online softmax (Alg. 1 lines 6-8, 10), the same in all four waves.  A step that every row of the
+    //    tile sees in full needs no masks: all steps but the few that hold a row's first or last token.
     half8v pa[RT];
     float corr[RT];
     bool moved = false;
+    auto softmax = [&](auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      float sc[2][4];
-      bool ok[2][4];
-      float mx = kNegBig;
+      for (int rt = 0; rt < RT; ++rt) {
+        float sc[2][4];
+        bool ok[2][4];
+        float mx = kNegBig;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const float4v x = (s_part[buf][0][rt * 2 + t][lane] + s_part[buf][1][rt * 2 + t][lane]) +
-                          (s_part[buf][2][rt * 2 + t][lane] + s_part[buf][3][rt * 2 + t][lane]);
+        for (int t = 0; t < 2; ++t) {
+          const float4v x = (s_part[buf][0][rt * 2 + t][lane] + s_part[buf][1][rt * 2 + t][lane]) +
+                            (s_part[buf][2][rt * 2 + t][lane] + s_part[buf][3][rt * 2 + t][lane]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int tok = tok0 + 16 * t + 4 * kq + i;
-          ok[t][i] = tok >= lo_col[rt] && tok < end_col[rt];
-          sc[t][i] = x[i] * raw_to_log2;
-          mx = ok[t][i] ? fmaxf(mx, sc[t][i]) : mx;
+          for (int i = 0; i < 4; ++i) {
+            const int tok = tok0 + 16 * t + 4 * kq + i;
+            ok[t][i] = !MASKED || (tok >= lo_col[rt] && tok < end_col[rt]);
+            sc[t][i] = x[i] * raw_to_log2;
+            mx = ok[t][i] ? fmaxf(mx, sc[t][i]) : mx;
+          }
         }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[rt], mx);
+        moved = moved || m_new > m_run[rt];
+        corr[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+        m_run[rt] = m_new;
+        float sum = 0.0f;
+        float pr[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            pr[t][i] = ok[t][i] ? __builtin_amdgcn_exp2f(sc[t][i] - m_new) : 0.0f;
+            sum += pr[t][i];
+          }
+        l_run[rt] = fmaf(l_run[rt], corr[rt], sum);
+        // k-slots 2i, 2i+1: token slots i and 4+i
+        pa[rt] = half8v{(half_t)pr[0][0], (half_t)pr[1][0], (half_t)pr[0][1], (half_t)pr[1][1],
+                        (half_t)pr[0][2], (half_t)pr[1][2], (half_t)pr[0][3], (half_t)pr[1][3]};
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rt], mx);
-      moved = moved || m_new > m_run[rt];
-      corr[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-      m_run[rt] = m_new;
-      float sum = 0.0f;
-      float pr[2][4];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          pr[t][i] = ok[t][i] ? __builtin_amdgcn_exp2f(sc[t][i] - m_new) : 0.0f;
-          sum += pr[t][i];
-        }
-      l_run[rt] = fmaf(l_run[rt], corr[rt], sum);
-      // k-slots 2i, 2i+1: token slots i and 4+i
-      pa[rt] = half8v{(half_t)pr[0][0], (half_t)pr[1][0], (half_t)pr[0][1], (half_t)pr[1][1],
-                      (half_t)pr[0][2], (half_t)pr[1][2], (half_t)pr[0][3], (half_t)pr[1][3]};
-    }
+    };
+    if (tok0 >= lo_all && tok0 + 32 <= end_all) softmax(std::false_type{});
+    else softmax(std::true_type{});
     if (__builtin_amdgcn_ballot_w64(moved) != 0) {               // some row's maximum moved: rescale (Alg. 1 line 9)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
@@ -438,13 +461,10 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
 
 bool wide_supported(int head_dim) { return head_dim == D; }
 
-// Row tiles per KV head for `rows` query rows: tiles of 32 rows where that still leaves the chip enough
-// blocks (`units` = batch x KV heads, `tokens` = the longest sequence), else tiles of 16.
-int wide_row_tiles(int rows, int64_t units, int tokens) {
-  const int t16 = (rows + 15) / 16, t32 = (rows + 31) / 32;
-  const int64_t max_splits = std::max(1, std::min(kMaxSplits, tokens / 64));
-  return (rows > 16 && units * t32 * max_splits >= 512) ? t32 : t16;
-}
+// Row tiles per KV head for `rows` query rows: tiles of 16.  (The kernel also takes tiles of 32 rows, RT = 2,
+// which dequantise the stream once for twice the rows; but such a block has a compute unit to itself, and two
+// blocks of 16 rows that cover each other's waits are faster: 97 against 108 us for 8 sequences x 32 heads at 32K.)
+int wide_row_tiles(int rows, int64_t, int) { return (rows + 15) / 16; }
 
 hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim, hipStream_t s) {
   DecodeParams p = p_in;
@@ -461,8 +481,8 @@ hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim
                                      : dim3(p.n_splits, p.n_kv_heads * p.kv_share, batch);
   // more blocks than compute units: shallow rings, two blocks per unit (16-row tiles); else one block with a deep ring
   const bool crowded = (int64_t)grid.x * grid.y * grid.z > 256;
-  if (rt == 2) hipLaunchKernelGGL((decode_partial_wide_kernel<2, 5>), grid, dim3(256), 0, s, p);
-  else if (crowded) hipLaunchKernelGGL((decode_partial_wide_kernel<1, 3>), grid, dim3(256), 0, s, p);
+  if (rt == 2) return hipErrorInvalidValue;       // (not instantiated, see wide_row_tiles)
+  if (crowded) hipLaunchKernelGGL((decode_partial_wide_kernel<1, 3>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((decode_partial_wide_kernel<1, 6>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
