@@ -60,7 +60,7 @@ typedef struct tq_kv_cache {
   void* v_zero;
   int32_t batch;
   int32_t n_kv_heads;
-  int32_t head_dim;    /* 128, 256 or 512 (512: generic kernel only, one query token) */
+  int32_t head_dim;    /* 128, 256 or 512 */
   int32_t group_size;  /* 32 */
   int32_t capacity;    /* tokens allocated per (batch, kv head) */
   int32_t layout;      /* TQ_LAYOUT_CANONICAL */
@@ -69,7 +69,8 @@ typedef struct tq_kv_cache {
 /* Optional tuning knobs for the decode entry points; NULL or zeros = library defaults. */
 typedef struct tq_decode_opts {
   int32_t n_splits;  /* chunks the sequence is split into (Sec. 3.2); 0 = heuristic            */
-  int32_t variant;   /* 0 = default kernel, 1 = generic vector-ALU kernel, 2 = matrix-core kernel */
+  int32_t variant;   /* 0 = default kernel, 1 = generic vector-ALU kernel, 2 = matrix-core kernel
+                        (head_dim 512 has a matrix-core kernel of its own: 0 and 2 both take it)    */
   int32_t window;    /* sliding-window attention (the Gemma local layers of Appendix A): > 0 = every
                         sequence attends only its last `window` tokens, [len - window, len); 0 = all.
                         tq_dequant_then_attend does not offer it (UNSUPPORTED).                  */
@@ -84,8 +85,8 @@ typedef struct tq_decode_opts {
                         to tq_sdpa_int4_reduce; k_new / v_new of tq_sdpa_int4_append_decode are
                         [batch][n_kv_heads][n_queries][head_dim].  Every sequence length must be at least
                         n_queries.  With a window, query t attends the last `window` of its tokens.
-                        Matrix-core kernel only (variant 1, attn_scale <= 0, head_dim 512 and
-                        tq_dequant_then_attend answer UNSUPPORTED).                               */
+                        Matrix-core kernels only (variant 1, tq_dequant_then_attend and, at head_dim
+                        128 / 256, attn_scale <= 0 answer UNSUPPORTED).                            */
 } tq_decode_opts;
 
 /* Quantise and append (Sec. 2.1, Eq. 2-3; "quantize -> store" arm of Sec. 3.3).
