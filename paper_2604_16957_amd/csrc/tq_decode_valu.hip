@@ -181,8 +181,9 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 // in LDS; the weighted sum over chunks is split over 256/D thread groups with independent,
 // unrolled loads, so the kernel is a handful of memory round trips long.
 template <int D>
-__global__ __launch_bounds__(D > 256 ? D : 256) void reduce_kernel(DecodeParams p) {
-  constexpr int THREADS = D > 256 ? D : 256, WAVES = THREADS / 64;
+__global__ __launch_bounds__(D > 256 ? 2 * D : 256) void reduce_kernel(DecodeParams p) {
+  // (d = 512: two threads per output element, so that 128 chunks are four rounds of loads per thread, not eight)
+  constexpr int THREADS = D > 256 ? 2 * D : 256, WAVES = THREADS / 64;
   constexpr int PARTS = THREADS / D;
   // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
@@ -348,7 +349,7 @@ hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStre
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(256), 0, s, p);
   else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((reduce_kernel<512>), grid, dim3(512), 0, s, p);
+  else hipLaunchKernelGGL((reduce_kernel<512>), grid, dim3(1024), 0, s, p);
   return hipGetLastError();
 }
 
