@@ -164,6 +164,25 @@ Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_
   return {true, use_mfma, merge, single && merge, false};
 }
 
+// waves that share one (sequence, KV head) row where single-chunk rows are packed several to a block
+int waves_per_packed_row(int64_t total_rows, int target) {
+  return total_rows > 4 * target ? 1 : total_rows > 2 * target ? 2 : total_rows > target ? 4 : 8;
+}
+
+// Many short sequences with their own lengths: where the (sequence, KV head) rows fill at least two rounds of
+// blocks and the longest sequence is no more than about a thousand tokens per wave that will work on it, every
+// row is ONE chunk of its own length: the decode kernel writes the output itself, and neither the device-side
+// chunk plan nor the merge kernel (one block per sequence and query head) is needed.
+bool rows_as_chunks(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts,
+                    bool paged) {
+  if (paged || queries_of(opts) > 1 || (opts && opts->n_splits > 0)) return false;
+  const Route r = route_of(cache, n_q_heads, seq_len, attn_scale, opts);
+  if (!r.ok || !r.use_mfma) return false;
+  const int64_t total = (int64_t)cache->batch * cache->n_kv_heads *
+                        tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts));
+  return total >= 2 * kBlocksMfma && windowed(seq_len, opts) <= 1024 * waves_per_packed_row(total, kBlocksMfma);
+}
+
 // One launch of phase 1: what to attend, and what came of it.
 struct PartialRequest {
   const tq_kv_cache* cache;            // validated; for a paged pool: the view with batch = sequences
@@ -206,8 +225,10 @@ int run_partial(PartialRequest& rq) {
                                : 1;
   const int rows_per_batch =
       cache->n_kv_heads * (use_mfma ? tq::mfma_kv_share(cache->head_dim, rows_of(cache, n_q_heads, opts)) : row_tiles);
-  const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, opts ? opts->n_splits : 0, target,
-                                use_mfma ? 8 : r.wide ? 2 : 1);
+  const bool one_chunk_rows = seq_lens && rq.out != nullptr && !append_in_merge &&
+                              rows_as_chunks(cache, n_q_heads, seq_len, rq.attn_scale, opts, rq.paged != nullptr);
+  const Plan plan = plan_splits(cache->batch, rows_per_batch, attended, one_chunk_rows ? 1 : opts ? opts->n_splits : 0,
+                                target, use_mfma ? 8 : r.wide ? 2 : 1);
   DecodeParams p = make_params(cache, rq.q, n_q_heads, seq_len, rq.attn_scale, rq.out, rq.workspace, plan,
                                queries_of(opts));
   p.seq_lens = seq_lens;
@@ -227,7 +248,7 @@ int run_partial(PartialRequest& rq) {
     p.max_blocks = rq.paged->max_blocks;
     p.page_shift = rq.paged->page_shift;
   }
-  if (seq_lens && !(opts && opts->n_splits > 0)) {
+  if (seq_lens && !(opts && opts->n_splits > 0) && !one_chunk_rows) {
     // per-sequence lengths, no chunk count asked for: the kernels plan the chunks themselves from the lengths,
     // `target` chunks over all sequences of a KV head (a requested n_splits keeps the fixed chunking)
     // per KV head: r rounds of target / H_kv chunks, r the smallest count that leaves at least half of them
@@ -248,11 +269,10 @@ int run_partial(PartialRequest& rq) {
   }
   rq.n_splits = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(rq.stream);
-  rq.merged = rq.out != nullptr && r.merge && !seq_lens && !append_in_merge;
+  rq.merged = one_chunk_rows || (rq.out != nullptr && r.merge && !seq_lens && !append_in_merge);
   if (rq.merged && use_mfma && plan.n_splits == 1 && !rq.paged) {
     // more single-chunk rows than the chip holds blocks: pack 2, 4 or 8 of them into a block
-    const int64_t total = (int64_t)cache->batch * rows_per_batch;
-    p.waves_per_row = total > 4 * target ? 1 : total > 2 * target ? 2 : total > target ? 4 : 8;
+    p.waves_per_row = waves_per_packed_row((int64_t)cache->batch * rows_per_batch, target);
   }
   if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
   if (r.wide) {
@@ -490,7 +510,9 @@ namespace {
 // in where it can (one query token; a window, if any, of at least two tokens), else the append kernel runs first.
 int append_decode_with_lengths(PartialRequest& rq, const void* k_new, const void* v_new) {
   const tq_decode_opts* opts = rq.opts;
-  if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2) {
+  // (where every row is a single chunk there is no merge kernel to take the token in: the append kernel, then the decode)
+  const bool one_chunk_rows = rows_as_chunks(rq.cache, rq.n_q_heads, rq.seq_len, rq.attn_scale, opts, rq.paged != nullptr);
+  if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2 && !one_chunk_rows) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {

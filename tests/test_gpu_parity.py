@@ -1042,11 +1042,14 @@ def test_more_rows_than_blocks_are_packed_several_to_a_block(shape):
                 assert_close(out, _oracle_causal(q4, ocache, [S] * batch, w.attn_scale), f"{shape} batch={batch} S={S}, 2 queries")
 
 
-def test_eighty_sequences_with_their_own_lengths_and_a_step():
-    """Enough (sequence, head) rows that the chunk list's slots share blocks and the merge kernel takes four heads
-    per block: plain decode and the one-call step (append + attend) with per-sequence lengths, against the oracle."""
+@pytest.mark.parametrize("S", [1800, 2600])
+def test_eighty_sequences_with_their_own_lengths_and_a_step(S):
+    """640 (sequence, KV head) rows with their own lengths.  Up to 2048 tokens every row is one chunk of its own
+    length, packed four to a block, and the decode kernel writes the output itself (no chunk plan, no merge kernel;
+    the step appends with the append kernel); beyond that the device plans chunks whose slots share blocks and the
+    merge kernel takes the step's token in.  Plain decode, a window, and the one-call step, against the oracle."""
     rng = np.random.default_rng(80)
-    B, S = 80, 1800
+    B = 80
     lens = [int(x) for x in rng.integers(1, S + 1, B)]
     lens[0], lens[1] = S, 1
     w = wl.custom(batch=B, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=S, seed=1900, outlier_channels=4)
@@ -1058,6 +1061,9 @@ def test_eighty_sequences_with_their_own_lengths_and_a_step():
     out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale)
     torch.cuda.synchronize()
     assert_close(out, ref, "80 sequences, own lengths")
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, window=300)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_window(q, ocache, lens, 300, w.attn_scale), "80 sequences, own lengths, window 300")
     # the step: wipe every sequence's last token, hand it over as the new one
     kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
     vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
