@@ -180,10 +180,13 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 // One block per query head.  The chunk weights are computed once (one chunk per thread) and kept
 // in LDS; the weighted sum over chunks is split over 256/D thread groups with independent,
 // unrolled loads, so the kernel is a handful of memory round trips long.
-template <int D>
-__global__ __launch_bounds__(D > 256 ? 2 * D : 256) void reduce_kernel(DecodeParams p) {
-  // (d = 512: two threads per output element, so that 128 chunks are four rounds of loads per thread, not eight)
-  constexpr int THREADS = D > 256 ? 2 * D : 256, WAVES = THREADS / 64;
+// THREADS: 256 (d = 512: 1024, two threads per output element, so that 128 chunks are four rounds of loads per
+// thread, not eight); for launches of thousands of blocks with few chunks each, D threads: twice as many blocks
+// fit a compute unit, and such a launch is as long as its rounds of blocks.
+template <int D, int THREADS>
+__global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
+  constexpr int WAVES = THREADS / 64;
+  static_assert(THREADS % D == 0 && THREADS >= kMaxSplits && THREADS >= 8 * (D / kGroup), "one thread per chunk, per lane of the appender");
   constexpr int PARTS = THREADS / D;
   // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
@@ -290,7 +293,8 @@ __global__ __launch_bounds__(D > 256 ? 2 * D : 256) void reduce_kernel(DecodePar
   for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off);
   if ((tid & 63) == 0) red_l[tid >> 6] = lw;
   __syncthreads();
-  float den = (red_l[0] + red_l[1]) + (red_l[2] + red_l[3]);
+  float den = red_l[0] + red_l[1];
+  if constexpr (WAVES >= 4) den += red_l[2] + red_l[3];
 #pragma unroll
   for (int w = 4; w < WAVES; w += 4) den += (red_l[w] + red_l[w + 1]) + (red_l[w + 2] + red_l[w + 3]);
 
@@ -347,9 +351,11 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
-  if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128>), grid, dim3(256), 0, s, p);
-  else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((reduce_kernel<512>), grid, dim3(1024), 0, s, p);
+  const bool many = (int64_t)grid.x * grid.y >= 4096;      // several rounds of blocks: smaller blocks, more at once
+  if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
+  else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);
+  else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256, 256>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((reduce_kernel<512, 1024>), grid, dim3(1024), 0, s, p);
   return hipGetLastError();
 }
 
