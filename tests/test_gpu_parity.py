@@ -184,6 +184,36 @@ def test_sharp_softmax_large_scores(variant):
     assert max_abs <= 2e-3 * max(1.0, np.abs(ref).max())
 
 
+@pytest.mark.parametrize("route", ["packed_rows", "one_block", "planned_chunks"])
+def test_sharp_softmax_every_head_keeps_its_own_reference(route):
+    """Scores with a spread of tens of log2 units (attn_scale 1 on N(0,1) queries and keys): new maxima keep turning
+    up, for one head or another of the group, all along a wave's tokens.  A head's exp2 reference must move only
+    when its OWN maximum outgrows it: one that follows every move of a neighbour ends tens of units above the head's
+    scores and its weights p * s_v sink into fp16's subnormals (percent-level errors on single rows).  Routes: many
+    rows of their own length packed four to a block; one long chunk per block; the device-planned chunks."""
+    if route == "packed_rows":
+        B, Hkv, S, n_splits = 131, 4, 1025, 0
+    elif route == "one_block":
+        B, Hkv, S, n_splits = 3, 2, 6000, 1
+    else:
+        B, Hkv, S, n_splits = 9, 4, 6000, 0
+    rng = np.random.default_rng(4052)
+    lens = [int(x) for x in rng.integers(S // 2, S + 1, B)]
+    w = wl.custom(batch=B, n_q_heads=8 * Hkv, n_kv_heads=Hkv, head_dim=128, seq_len=S, seed=54052, attn_scale=1.0,
+                  v_std=0.5)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), S,
+                                        w.attn_scale, n_splits=n_splits)
+    torch.cuda.synchronize()
+    worst = np.abs(np16(out).astype(np.float64) - ref).max(axis=-1)      # per (sequence, head) row
+    assert worst.max() <= MAX_ABS * max(1.0, float(np.abs(ref).max())), \
+        f"{route}: {int((worst > MAX_ABS).sum())} rows off, worst {worst.max():.2e}"
+    assert_close(out, ref, route) if float(np.abs(ref).max()) <= 1.0 else None
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_bitwise_repeatable(variant):
     w = wl.custom(seq_len=3000, seed=45, **SHAPES["g8_d128_b2_kv3"])
@@ -314,7 +344,13 @@ def test_decode_with_per_sequence_lengths(shape, variant):
     same = torch.full((len(lens),), 1000, dtype=torch.int32, device="cuda")
     a = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant, n_splits=3)
     b = tq.tq_sdpa_int4_decode(cache, q.cuda(), 1000, w.attn_scale, variant=variant, n_splits=3)
-    assert torch.equal(a, b)                     # same chunking, same bits
+    # same chunking, same partials.  The generic kernel merges both with the merge kernel: same bits.  The plain call of
+    # the matrix-core kernel may merge in the kernel instead, in another fp32 summation order: an fp16 ulp apart at most
+    if variant == 1:
+        assert torch.equal(a, b)
+    else:
+        fa, fb = a.float(), b.float()
+        assert bool(((fa - fb).abs() <= 2.0 ** -10 * fb.abs() + 2.0 ** -24).all())
     c = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), same, 1000, w.attn_scale, variant=variant)
     assert_close(c, np16(b).astype(np.float64), "device-planned chunks vs fixed chunks")
 
