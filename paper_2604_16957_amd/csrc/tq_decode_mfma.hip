@@ -336,11 +336,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   if (whole && begin0 >= seq && p.merge_slot < 0) return;
   const int end = max(begin0, min(seq, begin0 + tokens_per_split));
   // Several query tokens under a sliding window: the rows start at different tokens (row t one token after
-  // row t - 1), all inside the sequence's first attended supertile; that supertile then takes the masked path
-  // too (wave 0, after its other work) and the fast path starts one supertile later.
-  // The same goes for a paged cache under a window, whose first supertile holds `lead` tokens before the window.
-  const bool head = ((NQ > 1 && p.row_window > 0) || lead > 0) && split == 0 && end > begin0;
-  const int begin = begin0 + (head ? 32 : 0);     // origin of the supertile indices below
+  // row t - 1); the supertile that holds those starts takes the masked path too (wave 0, after its other work)
+  // and the fast path starts behind it.  The same goes for a paged cache under a window, whose first supertile
+  // holds `lead` tokens before the window.  With both, the rows start at tokens lead .. lead + NQ - 1, which may
+  // straddle the sequence's first two supertiles: then the second is masked as well, in whichever chunk it lies.
+  const bool rows_windowed = NQ > 1 && p.row_window > 0;
+  const bool straddle = rows_windowed && lead + NQ - 1 >= 32;
+  const bool head = (rows_windowed || lead > 0) && end > begin0 && (begin0 == 0 || (begin0 == 32 && straddle));
+  const bool head2 = head && begin0 == 0 && straddle && end > 32;
+  const int begin = begin0 + (head2 ? 64 : head ? 32 : 0);   // origin of the supertile indices below
   // `seq` is what the last query token attends; query token t attends NQ - 1 - t tokens fewer.  Supertiles
   // that every row attends in full take the fast path; the sequence's last one or two (ragged, or holding
   // tokens some rows must not see) take the masked path.
@@ -475,10 +479,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
   };
   const int n_mine = count_of(n_full);
-  bool tail_mine[3];                              // [2]: the masked FIRST supertile (see `head`)
+  bool tail_mine[4];                              // [2], [3]: the masked FIRST supertile(s) (see `head`), the one just
+                                                  // before `begin` and the one before that
 #pragma unroll
   for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
   tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
+  tail_mine[3] = head2 && (whole ? wave == 0 : sub == 0);
 
   // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
@@ -829,9 +835,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   wait_loads<0>();                                           // phantom stages included: the rings are quiet
 #pragma unroll 1
-  for (int u = 0; u < 3; ++u) {                              // the masked supertiles: the sequence's last one or two,
-    if (!tail_mine[u]) continue;                             // and under a window its first
-    const int sidx = u < 2 ? n_full + u : -1;
+  for (int u = 0; u < 4; ++u) {                              // the masked supertiles: the sequence's last one or two,
+    if (!tail_mine[u]) continue;                             // and under a window its first (or first two)
+    const int sidx = u < 2 ? n_full + u : 1 - u;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     issue_tail(0, sidx);
     wait_loads<0>();
@@ -853,7 +859,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
   float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
   if constexpr (C::ALIAS) __syncthreads();                   // everybody is done reading the rings
-  const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1] || tail_mine[2];
+  const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1] || tail_mine[2] || tail_mine[3];
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
     // (a row whose tokens were all masked still has the initial reference: it counts as empty)

@@ -890,6 +890,42 @@ def test_paged_cache(shape, variant):
     assert_close(out, np.concatenate(rows, axis=0), f"{shape} paged append+attend variant={variant}")
 
 
+@pytest.mark.parametrize("shape", ["g8_d128_kv2", "g2_d256", "g6_d512"])
+def test_paged_window_whose_rows_start_in_two_supertiles(shape):
+    """Paged pool + sliding window + several query tokens: a paged sequence is read from the 32-token boundary before
+    its window, and the query rows start one token after another; with the window's first token in the last slots
+    of a supertile the later rows start in the NEXT one, which then has to be masked too, in whichever chunk it
+    lies.  (A window of 50 on 115 tokens with 4 query tokens: rows start at tokens 62 .. 65.)"""
+    shapes = dict(SHAPES, g8_d128_kv2=dict(n_q_heads=16, n_kv_heads=2, head_dim=128, outlier_channels=4))
+    PT, window = 64, 50
+    for nq in (4, 8):
+        # first attended token of the earliest row: len - window - (nq - 1); 29, 30, 31 and 0 modulo 32
+        lens = [29 + 32 + window + nq - 1, 30 + 64 + window + nq - 1, 31 + window + nq - 1, 64 + window + nq - 1, window - 7]
+        S = max(lens)
+        w = wl.custom(batch=len(lens), seq_len=S, seed=2100 + nq, **dict(shapes[shape], attn_scale=1.0))
+        _, k, v = make(w)
+        q4 = _queries_for(w, nq)
+        B, Hkv, d = w.batch, w.n_kv_heads, w.head_dim
+        max_blocks = (S + PT - 1) // PT
+        rng = np.random.default_rng(nq)
+        table = torch.from_numpy(rng.permutation(B * max_blocks + 2)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)).cuda()
+        pool = tq.KVCache(B * max_blocks + 2, Hkv, d, PT)
+        pad = max_blocks * PT - S
+        tq.tq_quantize_kv_paged(pool, table, torch.nn.functional.pad(k, (0, 0, 0, pad)).contiguous().cuda(),
+                                torch.nn.functional.pad(v, (0, 0, 0, pad)).contiguous().cuda(),
+                                torch.zeros(B, dtype=torch.int32, device="cuda"))
+        ocache = oracle_cache_from(k, v)
+        lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        ref = _oracle_causal(q4, ocache, lens, w.attn_scale, window)
+        for n_splits in (0, 1, 3, 4):
+            out = tq.tq_sdpa_int4_decode_paged(pool, table, q4.cuda(), lens_dev, S, w.attn_scale, window=window,
+                                               n_splits=n_splits)
+            torch.cuda.synchronize()
+            max_abs, rel = errors(out, ref)
+            assert max_abs <= MAX_ABS * max(1.0, float(np.abs(ref).max())) and rel <= REL_L2, \
+                f"{shape} nq={nq} n_splits={n_splits}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
+
+
 def test_many_sequences_with_their_own_lengths():
     """More sequences than one round of blocks has chunks for: the device-side plan spreads them over
     several rounds; contiguous rows and pages."""
