@@ -700,11 +700,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                            fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
     if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {   // wave-uniform, rare
-      // Only the heads that outgrew their reference move (to kSlack above their new maximum: the next move is
-      // 2*kSlack away).  The others keep theirs: a reference that crept up with every move of a neighbour would
-      // push the head's own weights p * s_v down into fp16's subnormals on a sharp softmax.
-      const float bmax = blocks_max(mx);
-      const float m_new = bmax > m_run + slack ? bmax + slack : m_run;
+      // Every head's reference becomes at least its own current maximum plus kSlack (for the heads that outgrew
+      // theirs the next move is then 2*kSlack away; the others get their headroom back while the rescale is being
+      // paid for anyway).  A reference is thus never more than kSlack above its head's running maximum: one that
+      // followed every move of a neighbour instead would creep up and push the head's own weights p * s_v down
+      // into fp16's subnormals on a sharp softmax.
+      const float m_new = fmaxf(m_run, blocks_max(mx) + slack);
       const float f = __builtin_amdgcn_exp2f((m_run - m_new) * kappa);
       m_run = m_new;
       l_run *= f;
