@@ -549,6 +549,85 @@ def test_random_configurations_with_several_query_tokens():
         assert max_abs <= MAX_ABS * scale and rel <= REL_L2, f"{what}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
 
 
+def test_random_configurations_of_the_decode_step():
+    """The same kind of sweep over the one-call step (append the sequences' last tokens, then attend): common and
+    per-sequence lengths, paged pools, 1 ... 4 query tokens, windows, chunk counts, every head dimension; enough
+    rows in some cases for the packed-rows routes.  Output against the oracle, and every stored bit of the cache."""
+    rng = np.random.default_rng(20260418)
+    names = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero")
+    shapes = [(128, 8), (128, 4), (128, 16), (128, 3), (256, 2), (256, 4), (256, 1), (512, 2), (512, 32), (512, 6)]
+    for case in range(48):
+        kind = str(rng.choice(["common", "own", "own_many", "paged"]))
+        d, G = shapes[rng.integers(len(shapes))]
+        Hkv, B = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        if kind == "own_many":
+            d, G = [(128, 8), (128, 4), (256, 2)][rng.integers(3)]
+            Hkv, B = int(rng.choice([4, 8])), int(rng.choice([64, 70, 130]))
+            B = max(B, 512 // Hkv + 2)
+        nq = int(rng.choice([1, 1, 1, 2, 4])) if kind != "own_many" else 1
+        S = max(nq + 1, int(rng.choice([2, 3, 31, 32, 33, 64, 65, 257, 700, 1000, 1025, 2049, 4000])))
+        if kind == "own_many":
+            S = min(S, 1500)
+        alpha = float(rng.choice([1.0 / np.sqrt(d), 1.0, 0.02]))
+        window = int(rng.choice([0, 0, 0, 1, 9, 50, 1500]))
+        n_splits = int(rng.choice([0, 0, 0, 1, 3, 128])) if kind != "own_many" else 0
+        w = wl.custom(batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=S, seed=7000 + case, attn_scale=alpha,
+                      qk_std=float(rng.choice([1.0, 0.1])), v_std=float(rng.choice([1.0, 0.5])),
+                      outlier_channels=int(rng.choice([0, 4])))
+        lens = [int(x) for x in rng.integers(nq, S + 1, B)] if kind != "common" else [S] * B
+        PT = int(rng.choice([32, 64, 256]))
+        what = f"case {case} [{kind}]: d={d} G={G} Hkv={Hkv} B={B} S={S} nq={nq} n_splits={n_splits} window={window} PT={PT}"
+        _, k, v = make(w)
+        q = _queries_for(w, nq) if nq > 1 else make(w)[0]
+        ocache = oracle_cache_from(k, v)
+        ref = _oracle_causal(q, ocache, lens, alpha, window) if nq > 1 else \
+            _oracle_window(q, ocache, lens, window if window > 0 else S, alpha)
+        lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        # the step's new tokens are each sequence's last nq; the cache holds everything else, 0xEE in their place
+        kn = torch.stack([k[b, :, lens[b] - nq:lens[b]] for b in range(B)]).contiguous().cuda()
+        vn = torch.stack([v[b, :, lens[b] - nq:lens[b]] for b in range(B)]).contiguous().cuda()
+        if kind == "paged":
+            max_blocks = (S + PT - 1) // PT
+            table = rng.permutation(B * max_blocks + 3)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+            table_dev = torch.from_numpy(table).cuda()
+            pool = tq.KVCache(B * max_blocks + 3, Hkv, d, PT)
+            pad = max_blocks * PT - S
+            tq.tq_quantize_kv_paged(pool, table_dev, torch.nn.functional.pad(k, (0, 0, 0, pad)).contiguous().cuda(),
+                                    torch.nn.functional.pad(v, (0, 0, 0, pad)).contiguous().cuda(),
+                                    torch.zeros(B, dtype=torch.int32, device="cuda"))
+            for t in pool.tensors():
+                for b in range(B):
+                    for pos in range(lens[b] - nq, lens[b]):
+                        t.view(torch.uint8)[int(table[b, pos // PT]), :, pos % PT] = 0xEE
+            out = tq.tq_sdpa_int4_append_decode_paged(pool, table_dev, kn, vn, q.cuda(), lens_dev, S, alpha,
+                                                      n_splits=n_splits, window=window)
+            torch.cuda.synchronize()
+            stored = [np.stack([np.concatenate([np16(t)[table[b, j]] for j in range(max_blocks)], axis=1)[:, :S]
+                                for b in range(B)]) for t in pool.tensors()]
+        else:
+            cache = gpu_cache_from(k, v, capacity=S + 5)
+            for t in cache.tensors():
+                for b in range(B):
+                    t.view(torch.uint8)[b, :, lens[b] - nq:lens[b]] = 0xEE
+            if kind == "common":
+                out = tq.tq_sdpa_int4_append_decode(cache, kn, vn, q.cuda(), S, alpha, n_splits=n_splits, window=window)
+            else:
+                out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn, vn, q.cuda(), lens_dev, S, alpha, n_splits=n_splits,
+                                                           window=window)
+            torch.cuda.synchronize()
+            stored = [np16(t)[:, :, :S] for t in cache.tensors()]
+            for t in cache.tensors():
+                assert bool((t.view(torch.uint8)[:, :, S:] == 0xEE).all()), f"{what}: wrote past the sequences"
+        max_abs, rel = errors(out, ref)
+        assert max_abs <= MAX_ABS * max(1.0, float(np.abs(ref).max())) and rel <= REL_L2, \
+            f"{what}: max-abs {max_abs:.2e} rel-L2 {rel:.2e}"
+        for name, g, o in zip(names, stored, ocache):     # (tokens past a sequence's own length: the bulk fill's, untouched)
+            o = o[:, :, :S]
+            if g.dtype == np.float16:
+                g, o = g.view(np.uint16), o.view(np.uint16)
+            assert np.array_equal(g, o), f"{what}: {name} differs from the oracle"
+
+
 # ---------------------------------------------------------------- one call per decode step
 
 @pytest.mark.parametrize("variant", [0, 1])
