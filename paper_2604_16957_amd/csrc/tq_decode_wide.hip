@@ -112,9 +112,13 @@ __device__ __forceinline__ void wait_loads() {    // until at most N vector-memo
 // RT: 16-row tiles per block.  NSTG: stages of the ring (3 with 16 rows: two blocks fit a compute unit's LDS and
 // registers and cover each other's waits; more where a compute unit gets one block anyway).
 template <int RT, int NSTG>
-__global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_kernel(DecodeParams p) {
   static_assert(NSTG >= 3 && NSTG <= 6, "ring depth");
-  __shared__ float4v s_part[2][4][RT * 2][64];    // [buffer][wave][row tile, token tile][lane]
+  // partial scores of the four waves, [buffer][wave][row tile, token tile][lane]: two buffers and one barrier per
+  // step with 16 rows; with 32 rows one buffer and a second barrier (before it is written again), which keeps
+  // the block at half a compute unit's LDS
+  constexpr int SB = RT == 1 ? 2 : 1;
+  __shared__ float4v s_part[SB][4][RT * 2][64];
   __shared__ __attribute__((aligned(16))) char ring[NSTG * kStageBytes];
 
   const int lane = threadIdx.x & 63;
@@ -320,7 +324,8 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
         }
       }
     }
-    const int buf = it & 1;
+    const int buf = SB == 2 ? (it & 1) : 0;
+    if (SB == 1) __syncthreads();                 // everybody has read the previous step's partial scores
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -461,10 +466,14 @@ __global__ __launch_bounds__(256) void decode_partial_wide_kernel(DecodeParams p
 
 bool wide_supported(int head_dim) { return head_dim == D; }
 
-// Row tiles per KV head for `rows` query rows: tiles of 16.  (The kernel also takes tiles of 32 rows, RT = 2,
-// which dequantise the stream once for twice the rows; but such a block has a compute unit to itself, and two
-// blocks of 16 rows that cover each other's waits are faster: 97 against 108 us for 8 sequences x 32 heads at 32K.)
-int wide_row_tiles(int rows, int64_t, int) { return (rows + 15) / 16; }
+// Row tiles per KV head for `rows` query rows: tiles of 32 rows (the stream is dequantised once for twice the
+// rows) where that still gives every compute unit two blocks (`units` = batch x KV heads, `tokens` = the longest
+// sequence), else tiles of 16.
+int wide_row_tiles(int rows, int64_t units, int tokens) {
+  const int t16 = (rows + 15) / 16, t32 = (rows + 31) / 32;
+  const int64_t max_splits = std::max(1, std::min(kMaxSplits, tokens / 64));
+  return (rows > 16 && units * t32 * max_splits >= 512) ? t32 : t16;
+}
 
 hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim, hipStream_t s) {
   DecodeParams p = p_in;
@@ -481,8 +490,8 @@ hipError_t launch_partial_wide(const DecodeParams& p_in, int batch, int head_dim
                                      : dim3(p.n_splits, p.n_kv_heads * p.kv_share, batch);
   // more blocks than compute units: shallow rings, two blocks per unit (16-row tiles); else one block with a deep ring
   const bool crowded = (int64_t)grid.x * grid.y * grid.z > 256;
-  if (rt == 2) return hipErrorInvalidValue;       // (not instantiated, see wide_row_tiles)
-  if (crowded) hipLaunchKernelGGL((decode_partial_wide_kernel<1, 3>), grid, dim3(256), 0, s, p);
+  if (rt == 2) hipLaunchKernelGGL((decode_partial_wide_kernel<2, 3>), grid, dim3(256), 0, s, p);
+  else if (crowded) hipLaunchKernelGGL((decode_partial_wide_kernel<1, 3>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((decode_partial_wide_kernel<1, 6>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
