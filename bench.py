@@ -39,7 +39,8 @@ def parse():
                     help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | global512_32k (d=512, GQA 32: "
                          "the head_dim 512 matrix-core kernel) | varlen8 (8 sequences of "
                          "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | paged8 (the same "
-                         "over a pool of 256-token pages in random order) | sweep80 "
+                         "over a pool of 256-token pages in random order) | varlen256 (256 sequences of 64 ... 1024 tokens of the llama "
+                         "shape: every (sequence, KV head) row is one chunk, no merge kernel) | sweep80 "
                          "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
@@ -212,9 +213,13 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     paged = args.workload == "paged8"             # varlen8 with the sequences scattered over a pool of 256-token pages
-    varlen = args.workload == "varlen8" or paged
+    many = args.workload == "varlen256"           # many short sequences: 256 of 64 ... 1024 tokens
+    varlen = args.workload == "varlen8" or paged or many
     PT = 256
-    if varlen:     # continuous batching: 8 sequences of the llama shape, lengths drawn in [4096, 32768]
+    if many:
+        w = wl.custom("varlen256", batch=256, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=1024, seed=1200,
+                      outlier_channels=4)
+    elif varlen:   # continuous batching: 8 sequences of the llama shape, lengths drawn in [4096, 32768]
         w = wl.custom("paged8" if paged else "varlen8", batch=8, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=32768, seed=1100,
                       outlier_channels=4)
     else:
@@ -223,7 +228,7 @@ def main():
     lens = None
     if varlen:
         g = torch.Generator().manual_seed(w.seed + 5)
-        lens = torch.randint(4096, S + 1, (B,), generator=g, dtype=torch.int32)
+        lens = torch.randint(64 if many else 4096, S + 1, (B,), generator=g, dtype=torch.int32)
         lens[0] = S                               # the bound is attained
         lens_dev, pos_dev = lens.to(dev), (lens - 1).to(dev)
 
@@ -473,7 +478,8 @@ def main():
         "vs_baseline": None, "dtype": "int4 codes + fp16 scale/zero in HBM; fp16 MFMA/VALU inputs, fp32 accumulate, fp16 out",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
-                   "seq_len": S, "seq_lens": None if lens is None else lens.tolist(), "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
+                   "seq_len": S, "seq_lens": None if lens is None else lens.tolist() if B <= 16 else
+                   {"count": B, "min": int(lens.min()), "max": int(lens.max()), "sum": int(lens.sum()), "seed": w.seed + 5}, "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "window": args.window, "n_queries": NQ,
                    "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
                                   "tq_sdpa_int4_append_decode_paged" if paged and not args.two_calls else
