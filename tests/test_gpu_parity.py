@@ -477,6 +477,67 @@ def test_graph_capture_and_replay():
             assert torch.equal(out1, want1) and torch.equal(out2, want2)
 
 
+@pytest.mark.parametrize("route", ["d512", "own_lengths_planned", "own_lengths_rows_as_chunks"])
+def test_graph_capture_and_replay_of_the_other_routes(route):
+    """The one-call step captured and replayed on the routes the test above does not take: the head_dim 512 kernel
+    (its ring is static LDS above 64 KB), per-sequence lengths with device-planned chunks (the plan and the merge
+    kernel's appender are redone by every replay), and many rows of their own length (append kernel + decode)."""
+    if route == "d512":
+        w = wl.custom(seq_len=1500, seed=93, **SHAPES["g32_d512"])
+        lens = None
+    elif route == "own_lengths_planned":
+        w = wl.custom(batch=6, n_q_heads=16, n_kv_heads=2, head_dim=128, seq_len=3000, seed=94)
+        lens = [3000, 1, 77, 2049, 1000, 2999]
+    else:
+        w = wl.custom(batch=70, n_q_heads=32, n_kv_heads=8, head_dim=128, seq_len=600, seed=95)
+        lens = [int(x) for x in np.random.default_rng(95).integers(2, 601, 70)]
+    S, B = w.seq_len, w.batch
+    q, k, v = make(w)
+    ocache = oracle_cache_from(k, v)
+    cache = gpu_cache_from(k, v, capacity=S)
+    own = lens if lens is not None else [S] * B
+    kn = torch.stack([k[b, :, own[b] - 1:own[b]] for b in range(B)]).contiguous().cuda()
+    vn = torch.stack([v[b, :, own[b] - 1:own[b]] for b in range(B)]).contiguous().cuda()
+    qd = q.cuda()
+    out = torch.empty_like(qd)
+    ws = torch.empty(tq.tq_workspace_bytes(B, w.n_q_heads, w.head_dim), dtype=torch.uint8, device="cuda")
+    lens_dev = None if lens is None else torch.tensor(lens, dtype=torch.int32, device="cuda")
+
+    def wipe():                                   # the step has to write every sequence's last token again
+        for t in cache.tensors():
+            for b in range(B):
+                t.view(torch.uint8)[b, :, own[b] - 1] = 0xEE
+
+    def step():
+        if lens is None:
+            tq.tq_sdpa_int4_append_decode(cache, kn, vn, qd, S, w.attn_scale, out=out, workspace=ws)
+        else:
+            tq.tq_sdpa_int4_append_decode_varlen(cache, kn, vn, qd, lens_dev, S, w.attn_scale, out=out, workspace=ws)
+
+    wipe()
+    step()
+    torch.cuda.synchronize()
+    want = out.clone()
+    ref = oracle_attend(q, ocache, S, w.attn_scale) if lens is None else _oracle_varlen(q, ocache, lens, w.attn_scale)
+    assert_close(want, ref, f"{route} eager step")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for _ in range(3):
+        out.zero_()
+        wipe()
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"{route}: a replay differs from the eager step"
+        for name, t, o in zip(("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"), cache.tensors(), ocache):
+            gt = np16(t)
+            if gt.dtype == np.float16:
+                gt, o = gt.view(np.uint16), o.view(np.uint16)
+            assert np.array_equal(gt[:, :, :S], o[:, :, :S]), f"{route}: {name} after a replay"
+
+
 # ---------------------------------------------------------------- many small random configurations
 
 def test_random_configurations_against_the_oracle():
