@@ -813,7 +813,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     }
     load_v(slot, vr);
     float sc[2][4];
+    // (d = 128: the wave asks for issue priority while it unpacks K, feeds the matrix cores and scales the
+    //  scores: the two waves of a SIMD then take turns phase by phase rather than instruction by instruction,
+    //  0 - 1 % faster at 128K from box to box; at d = 256 the same costs 3 %)
+    if constexpr (D == 128) __builtin_amdgcn_s_setprio(1);
     scores(kr, 0, std::false_type{}, sc);
+    if constexpr (D == 128) __builtin_amdgcn_s_setprio(0);
     if constexpr (C::PFK) {                                  // past the last supertile this fetches unused bytes
       wait_loads<(NS - 2) * LPS>();
       load_k(next, kr);
