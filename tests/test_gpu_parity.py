@@ -71,6 +71,50 @@ def test_quantize_random_bit_exact(name):
     assert_cache_bit_exact(cache, oracle_cache_from(k, v), w.seq_len)
 
 
+@pytest.mark.parametrize("mode", ["any_bits", "narrow_groups", "full_range", "subnormal", "mixed_exponents", "constant", "ties"])
+def test_quantize_adversarial_values_bit_exact(mode):
+    """Inputs chosen to sit on the quantiser's edges (Sec. 2.1, Eq. 2-3): arbitrary finite fp16 bit patterns, groups
+    of tiny range on a large offset (zero-points in the hundreds), the full fp16 range (scales in the thousands),
+    subnormals (the scale underflows to the constant-group rule), exponents mixed inside a group, constant groups with
+    single outliers, ramps whose codes land on .5 (round-half-even).  Both quantisers, the append kernel and the one
+    inside the merge kernel (the step's new token), against the oracle, bit for bit."""
+    modes = ["any_bits", "narrow_groups", "full_range", "subnormal", "mixed_exponents", "constant", "ties"]
+    rng = np.random.default_rng(2600 + modes.index(mode))
+    for d in (128, 256, 512):
+        B, H, S = 2, 2, 65
+        n = B * H * S * d
+        if mode == "any_bits":
+            x = rng.integers(0, 1 << 16, n, dtype=np.uint16)
+            x = np.where((x & 0x7C00) == 0x7C00, x & 0x83FF, x).astype(np.uint16).view(np.float16)     # no inf / nan
+        elif mode == "narrow_groups":
+            base = rng.normal(0, 1, (n // 32, 1)) * rng.choice([1, 100, 1000])
+            x = (base + rng.normal(0, 1, (n // 32, 32)) * rng.choice([1e-3, 1e-2, 1])).astype(np.float16).ravel()
+        elif mode == "full_range":
+            x = (rng.uniform(-1, 1, n) * 65504).astype(np.float16)
+        elif mode == "subnormal":
+            x = (rng.uniform(-1, 1, n) * rng.choice([1e-4, 6e-5, 1e-6, 6e-8])).astype(np.float16)
+        elif mode == "mixed_exponents":
+            x = (rng.normal(0, 1, n) * np.exp2(rng.integers(-20, 14, n))).astype(np.float16)
+        elif mode == "constant":
+            x = np.repeat(rng.normal(0, 10, n // 32).astype(np.float16), 32)
+            x[rng.integers(0, n, n // 200)] += np.float16(0.001)
+        else:
+            k2 = rng.integers(0, 31, n).astype(np.float64) * 0.5
+            off = rng.integers(-8, 8, (n // 32, 1)).repeat(32, 1).ravel()
+            x = ((k2 + off) * np.exp2(rng.integers(-6, 6, (n // 32, 1)).repeat(32, 1).ravel())).astype(np.float16)
+        x = np.where(np.isfinite(x), x, np.float16(0)).astype(np.float16).reshape(B, H, S, d)
+        kt, vt = torch.from_numpy(x.copy()), torch.from_numpy(np.ascontiguousarray(x[..., ::-1]))
+        ocache = oracle_cache_from(kt, vt)
+        cache = gpu_cache_from(kt, vt, capacity=S + 2)
+        torch.cuda.synchronize()
+        assert_cache_bit_exact(cache, ocache, S)
+        step = gpu_cache_from(kt[:, :, :S - 1].contiguous(), vt[:, :, :S - 1].contiguous(), capacity=S + 2)
+        tq.tq_sdpa_int4_append_decode(step, kt[:, :, S - 1:].contiguous().cuda(), vt[:, :, S - 1:].contiguous().cuda(),
+                                      torch.zeros(B, H, d, dtype=torch.float16, device="cuda"), S, 1.0)
+        torch.cuda.synchronize()
+        assert_cache_bit_exact(step, ocache, S)
+
+
 def test_append_writes_only_its_positions():
     w = wl.custom(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, seq_len=40, seed=23)
     q, k, v = make(w)
