@@ -189,7 +189,7 @@ struct PartialRequest {
   const void* q;
   int32_t n_q_heads, seq_len;          // seq_len: the common length, or the bound of seq_lens
   const int32_t* seq_lens = nullptr;   // device, per-sequence lengths
-  float attn_scale;
+  float attn_scale = 0.0f;
   void* out = nullptr;                 // non-null: the kernel may merge the chunks itself and write it
   void* workspace;
   const tq_decode_opts* opts = nullptr;
