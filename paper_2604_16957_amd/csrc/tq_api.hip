@@ -191,7 +191,7 @@ struct PartialRequest {
   const int32_t* seq_lens = nullptr;   // device, per-sequence lengths
   float attn_scale = 0.0f;
   void* out = nullptr;                 // non-null: the kernel may merge the chunks itself and write it
-  void* workspace;
+  void* workspace = nullptr;
   const tq_decode_opts* opts = nullptr;
   const void* k_new = nullptr;         // append-and-attend: the step's new token (then seq_len includes it),
   const void* v_new = nullptr;         // taken in by the merge kernel, which then has to run
