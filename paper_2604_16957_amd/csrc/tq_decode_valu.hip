@@ -329,6 +329,64 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   if (part == 0) p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
 }
 
+// Eq. 6 for launches of thousands of outputs with few chunks each (many sequences with their own lengths): one
+// block per (output row, KV head), a thread per output element and up to four of the group's query heads.  The
+// chunks are folded in four at a time, all their loads in flight together, with a running maximum (Alg. 1's
+// rescaling applied to chunks), so the usual handful of chunks is one memory round trip after the lengths, with
+// no LDS and no barrier, and the launch is one round of blocks where one block per query head takes several.
+template <int D>
+__global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
+  const int kv = blockIdx.x, b = blockIdx.y, j = threadIdx.x % D, part = threadIdx.x / D;
+  const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;
+  int n = p.n_splits;
+  if (p.seq_lens) {
+    const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
+    const int c = p.var_chunks > 0 ? *p.plan : p.tokens_per_split;
+    n = min(n, (var_len(p, sequence) + c - 1) / c);
+  }
+  n = max(n, 1);
+  for (int h0 = 0; h0 < p.gqa; h0 += 8) {
+    int64_t row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) row[i] = (int64_t)b * p.n_q_heads + kv * p.gqa + min(h0 + part * 4 + i, p.gqa - 1);
+    float m_run[4], num[4], den[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { m_run[i] = kNegBig; num[i] = 0.0f; den[i] = 0.0f; }
+    for (int c0 = 0; c0 < n; c0 += 4) {
+      float2 ml[4][4];
+      float o[4][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int64_t ph = row[i] * part_stride + min(c0 + u, n - 1);
+          ml[i][u] = *reinterpret_cast<const float2*>(p.part_ml + ph * 2);
+          o[i][u] = p.part_o[ph * D + j];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float mx = m_run[i];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) mx = c0 + u < n ? fmaxf(mx, ml[i][u].x) : mx;
+        const float keep = exp2f(m_run[i] - mx);
+        num[i] *= keep;
+        den[i] *= keep;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float e = c0 + u < n ? exp2f(ml[i][u].x - mx) : 0.0f;
+          num[i] = fmaf(o[i][u], e, num[i]);
+          den[i] = fmaf(ml[i][u].y, e, den[i]);
+        }
+        m_run[i] = mx;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (h0 + part * 4 + i < p.gqa) p.out[row[i] * D + j] = (half_t)(num[i] / den[i]);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s) {
@@ -349,10 +407,16 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
   return hipGetLastError();
 }
 
+bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa) {
+  return head_dim == 128 && out_rows * n_q_heads >= 4096 && gqa >= 4;
+}
+
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   const bool many = (int64_t)grid.x * grid.y >= 4096;      // several rounds of blocks: smaller blocks, more at once
-  if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
+  if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa) && !p.k_new)
+    hipLaunchKernelGGL((reduce_group_kernel<128>), dim3(p.n_kv_heads, grid.y), dim3(256), 0, s, p);
+  else if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
   else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);
   else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256, 256>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((reduce_kernel<512, 1024>), grid, dim3(1024), 0, s, p);

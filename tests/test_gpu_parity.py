@@ -1336,3 +1336,53 @@ def test_eighty_sequences_with_their_own_lengths_and_a_step(S):
             if gb.dtype == np.float16:
                 gb, ob = gb.view(np.uint16), ob.view(np.uint16)
             assert np.array_equal(gb, ob), f"{name} sequence {b}"
+
+
+@pytest.mark.parametrize("B,Hq,Hkv", [(128, 32, 8), (172, 24, 4), (86, 48, 4), (32, 128, 8)])
+def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
+    """At 4096 and more (sequence, query head) outputs of 128 elements, with four or more query heads to a KV head,
+    the chunk merge (Eq. 6) folds a whole group's heads in one block, four chunks at a time, and the step appends
+    with the append kernel first: groups of 4, 6, 12 and 16 heads, chunk counts from 1 to 7 per sequence, with the
+    chunk count asked for and with the device's plan, plain, windowed, two query tokens, and the one-call step."""
+    S = 700
+    rng = np.random.default_rng(B + Hq)
+    lens = [int(x) for x in rng.integers(1, S + 1, B)]
+    lens[0], lens[1], lens[2] = S, 1, 101
+    w = wl.custom(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=128, seq_len=S, seed=2700 + B, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    for n_splits in (7, 2):
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, n_splits=n_splits)
+        torch.cuda.synchronize()
+        assert_close(out, ref, f"own lengths, {n_splits} chunks")
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, n_splits=5, window=90)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_window(q, ocache, lens, 90, w.attn_scale), "own lengths, 5 chunks, window 90")
+    out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, n_splits=3)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_varlen(q, ocache, [S] * B, w.attn_scale), "common length, 3 chunks")
+    lens2 = [max(2, n) for n in lens]
+    q2 = _queries_for(w, 2)
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q2.cuda(), torch.tensor(lens2, dtype=torch.int32, device="cuda"), S,
+                                        w.attn_scale, n_splits=4)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_causal(q2, ocache, lens2, w.attn_scale), "own lengths, 4 chunks, 2 query tokens")
+    # the step: wipe every sequence's last token, hand it over as the new one
+    kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    for t in cache.tensors():
+        for b in range(B):
+            t.view(torch.uint8)[b, :, lens[b] - 1] = 0xEE
+    out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale, n_splits=6)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "own lengths, 6 chunks, append + decode")
+    for name, g, o in zip(("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"), cache.tensors(), ocache):
+        g = np16(g)
+        for b in range(B):
+            gb, ob = g[b, :, :lens[b]], o[b, :, :lens[b]]
+            if gb.dtype == np.float16:
+                gb, ob = gb.view(np.uint16), ob.view(np.uint16)
+            assert np.array_equal(gb, ob), f"{name} sequence {b}"
