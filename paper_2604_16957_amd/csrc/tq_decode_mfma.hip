@@ -113,7 +113,7 @@ struct Cfg {
   static constexpr int SZ = 32 * NG * 2;         // one fp16 scale (or zero-point) array of the supertile
   static constexpr int OFF_V = 2 * KT, OFF_KS = OFF_V + VB, OFF_KZ = OFF_KS + SZ, OFF_VS = OFF_KZ + SZ,
                        OFF_VZ = OFF_VS + SZ, STAGE = OFF_VZ + SZ;
-  static constexpr int NS = 2;                  // ring depth per wave  // ring depth per wave (LDS: 160 KB per CU)
+  static constexpr int NS = 2;                  // ring depth per wave (LDS: 160 KB per CU)
   static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
   static constexpr int RING = NW * NS * STAGE;
   static constexpr int MERGE = (NW * GP * D + NW * GP * NG + 2 * NW * GP) * 4;  // o, zero-point term, m, l
