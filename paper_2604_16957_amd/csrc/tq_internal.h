@@ -158,6 +158,22 @@ __device__ inline void var_lens_load(const DecodeParams& p, VarLens& L) {
 #pragma unroll
   for (int t = 0; t < kPlanTiles; ++t) L.len[t] = t * 64 < p.batch ? var_len_of_lane(p, t) : 0;
 }
+// ceil(len / c), the chunks of a sequence, without the integer division (some forty instructions, and the planner
+// below does dozens per wave before its first load): the quotient is estimated with the float reciprocal of c,
+// handed in as rc, and put right by one step either way.  Exact for 0 <= len, c < 2^23 with c >= 32: len + c - 1
+// is then exact as a float, the estimate is off by less than 2^-21 of a quotient below 2^19, i.e. by less than one.
+// Longer caches take the division.
+__device__ inline int var_chunks_of(int len, int c, float rc, bool exact_floats) {
+  const int x = len + c - 1;
+  if (!exact_floats) return x / c;
+  int q = (int)((float)x * rc);
+  const int r = x - q * c;
+  q += r >= c ? 1 : 0;
+  q -= r < 0 ? 1 : 0;
+  return q;
+}
+__device__ inline bool var_exact_floats(const DecodeParams& p) { return p.seq_len < (1 << 23); }
+
 // The chunk length: the smallest multiple of 32 tokens for which all sequences together need at most
 // p.var_chunks chunks (the grid), not below p.var_min_chunk and long enough that no sequence needs more than
 // kMaxSplits.  The count for a candidate length is a wave-wide sum, and the candidates are bisected between
@@ -174,15 +190,24 @@ __device__ inline int var_chunk_tokens(const DecodeParams& p, const VarLens& L) 
   const int floor_c = max(p.var_min_chunk, (p.seq_len + kMaxSplits - 1) / kMaxSplits);
   auto round_up = [](long long c) { return (int)((c + kTile - 1) / kTile * kTile); };
   const int budget = p.var_chunks - p.batch;      // >= var_chunks / 2 by the host's choice of var_chunks
-  int hi = round_up(max((long long)floor_c, (total + budget - 1) / budget));
-  int lo = round_up(max((long long)floor_c, (total + p.var_chunks - 1) / p.var_chunks));
+  // (the two bounds: 32-bit divisions where the total allows, which is nearly always; a 64-bit one is some
+  // hundred and fifty instructions)
+  const bool narrow = total < (1ll << 31) - (1 << 24) && p.var_chunks < (1 << 24);
+  const long long need_hi = narrow ? (long long)(((uint32_t)total + (uint32_t)budget - 1) / (uint32_t)budget)
+                                   : (total + budget - 1) / budget;
+  const long long need_lo = narrow ? (long long)(((uint32_t)total + (uint32_t)p.var_chunks - 1) / (uint32_t)p.var_chunks)
+                                   : (total + p.var_chunks - 1) / p.var_chunks;
+  int hi = round_up(max((long long)floor_c, need_hi));
+  int lo = round_up(max((long long)floor_c, need_lo));
+  const bool fl = var_exact_floats(p);
   while (lo < hi) {
     const int mid = (lo + (hi - lo) / 2) / kTile * kTile;        // lo <= mid < hi, a multiple of 32
+    const float rmid = 1.0f / (float)mid;
     int n = 0;
 #pragma unroll
     for (int t = 0; t < kPlanTiles; ++t)
-      if (t < tiles) n += (L.len[t] + mid - 1) / mid;
-    for (int t = kPlanTiles; t < tiles; ++t) n += (var_len_of_lane(p, t) + mid - 1) / mid;
+      if (t < tiles) n += var_chunks_of(L.len[t], mid, rmid, fl);
+    for (int t = kPlanTiles; t < tiles; ++t) n += var_chunks_of(var_len_of_lane(p, t), mid, rmid, fl);
     if (wave_sum(n) <= p.var_chunks) hi = mid;
     else lo = mid + kTile;
   }
@@ -200,8 +225,10 @@ __device__ inline bool var_plan(const DecodeParams& p, int slot, VarPlan& out) {
   const int tiles = (p.batch + 63) >> 6, lane = threadIdx.x & 63;
   int first = 0;
   bool found = false;
+  const float rc = 1.0f / (float)c;
+  const bool fl = var_exact_floats(p);
   auto visit = [&](int t, int len) {              // tile t: does it hold the slot?  (wave-uniform)
-    const int n = (len + c - 1) / c;              // this lane's sequence: its chunks
+    const int n = var_chunks_of(len, c, rc, fl);  // this lane's sequence: its chunks
     const int in_tile = wave_sum(n);
     if (slot < first + in_tile) {
       int incl = n;                               // inclusive prefix sum over the lanes
