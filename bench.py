@@ -40,7 +40,8 @@ def parse():
                          "the head_dim 512 matrix-core kernel) | varlen8 (8 sequences of "
                          "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | paged8 (the same "
                          "over a pool of 256-token pages in random order) | varlen256 (256 sequences of 64 ... 1024 tokens of the llama "
-                         "shape: every (sequence, KV head) row is one chunk, no merge kernel) | sweep80 "
+                         "shape: every (sequence, KV head) row is one chunk, no merge kernel) | varlen256_2k (the same with 64 ... 2048 tokens: "
+                         "chunks planned on the device, merge kernel of one block per sequence and KV head) | sweep80 "
                          "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
@@ -213,12 +214,12 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     paged = args.workload == "paged8"             # varlen8 with the sequences scattered over a pool of 256-token pages
-    many = args.workload == "varlen256"           # many short sequences: 256 of 64 ... 1024 tokens
+    many = args.workload in ("varlen256", "varlen256_2k")   # many short sequences: 256 of 64 ... 1024 (2048) tokens
     varlen = args.workload == "varlen8" or paged or many
     PT = 256
     if many:
-        w = wl.custom("varlen256", batch=256, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=1024, seed=1200,
-                      outlier_channels=4)
+        w = wl.custom(args.workload, batch=256, n_q_heads=64, n_kv_heads=8, head_dim=128,
+                      seq_len=2048 if args.workload == "varlen256_2k" else 1024, seed=1200, outlier_channels=4)
     elif varlen:   # continuous batching: 8 sequences of the llama shape, lengths drawn in [4096, 32768]
         w = wl.custom("paged8" if paged else "varlen8", batch=8, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=32768, seed=1100,
                       outlier_channels=4)
@@ -320,6 +321,8 @@ def main():
     #      launch (partials and chunk merge in the same kernel) that launch is timed; otherwise phase 1,
     #      the partial kernel, which tq_sdpa_int4_partial launches on its own.
     fused = (not paged) and tq.tq_decode_launches(caches[0], Hq, S, w.attn_scale, n_queries=NQ, **kw) == 1
+    if args.workload == "varlen256_2k":           # (the launch count above is that of a common length; these lengths
+        fused = False                             # take chunks planned on the device and the merge kernel)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     n_splits = 0 if paged else tq.tq_sdpa_int4_partial(caches[0], qs[0], S, w.attn_scale, ws, **kw)
     lo = max(0, S - args.window) if args.window > 0 else 0     # first attended token
