@@ -183,18 +183,24 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 // THREADS: 256 (d = 512: 1024, two threads per output element, so that 128 chunks are four rounds of loads per
 // thread, not eight); for launches of thousands of blocks with few chunks each, D threads: twice as many blocks
 // fit a compute unit, and such a launch is as long as its rounds of blocks.
-template <int D, int THREADS>
+// SLICES: blocks that share a query head, each with D / SLICES of its output elements (d = 512 with at most 64
+// outputs: four or eight blocks of 512 threads per head: with few heads the partials, 256 KB a head at 128 chunks,
+// are otherwise pulled in by as many compute units as there are heads).  Every slice works out the chunk weights and,
+// when appending, the new token's score for itself; slice 0 stores the token.
+template <int D, int THREADS, int SLICES = 1>
 __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   constexpr int WAVES = THREADS / 64;
-  static_assert(THREADS % D == 0 && THREADS >= kMaxSplits && THREADS >= 8 * (D / kGroup), "one thread per chunk, per lane of the appender");
-  constexpr int PARTS = THREADS / D;
+  constexpr int DS = D / SLICES;                  // output elements of this block
+  static_assert(D % SLICES == 0 && THREADS % DS == 0 && THREADS >= kMaxSplits && THREADS >= 8 * (D / kGroup),
+                "one thread per chunk, per lane of the appender");
+  constexpr int PARTS = THREADS / DS;
   // b: row of the [B * n_queries][H_q] outputs (one per query token of every sequence)
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int h = blockIdx.x / SLICES, slice = blockIdx.x % SLICES, b = blockIdx.y, tid = threadIdx.x;
   const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;   // chunk slots a row has in the workspace
   const int64_t ph0 = (int64_t)(b * p.n_q_heads + h) * part_stride;
   __shared__ float w_c[kMaxSplits];
   __shared__ float red_m[WAVES], red_l[WAVES];
-  __shared__ float acc_part[PARTS][D];
+  __shared__ float acc_part[PARTS][DS];
 
   // chunks that exist for this sequence: all of them, or those that start before its own end (with a plan made
   // on the device: its chunk length, which the decode kernel left in the workspace)
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   // else: they do not depend on the weights, so the kernel is about one memory round trip long (two with
   // per-sequence lengths, which have to arrive first).
   constexpr int FIRST = 16;
-  const int j = tid % D, part = tid / D;
+  const int jl = tid % DS, j = slice * DS + jl, part = tid / DS;
   const float* src = p.part_o + ph0 * D + j;
   float pre[FIRST];
 #pragma unroll
@@ -252,7 +258,7 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
       quantize_scale_zero(mn, mx, s16, z16);
       const float sf = (float)s16, zf = (float)z16;
       const uint32_t w = quantize_word(x, sf, zf);
-      if (h % p.gqa == 0) {
+      if (h % p.gqa == 0 && slice == 0) {
         int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + append_pos;
         if (p.block_table) {                       // paged cache: the page the block table names for that position
           const int page = p.block_table[(int64_t)b * p.max_blocks + (append_pos >> p.page_shift)];
@@ -268,7 +274,8 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
         hat[which][g * kGroup + part4 * 8 + jj] = ((float)((w >> (4 * jj)) & 0xFu) - zf) * sf;   // Eq. 3
     }
     __syncthreads();
-    float prod = tid < D ? (float)p.q[(int64_t)(b * p.n_q_heads + h) * D + tid] * hat[0][tid] : 0.0f;
+    float prod = 0.0f;
+    for (int e = tid; e < D; e += THREADS) prod = fmaf((float)p.q[(int64_t)(b * p.n_q_heads + h) * D + e], hat[0][e], prod);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) prod += __shfl_xor(prod, off);
     if ((tid & 63) == 0) red_a[tid >> 6] = prod;
@@ -319,11 +326,11 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   }
   for (; c < n; c += PARTS) num = fmaf(src[(int64_t)c * D], w_c[c], num);
   if constexpr (PARTS > 1) {
-    acc_part[part][j] = num;
+    acc_part[part][jl] = num;
     __syncthreads();
     if (part == 0) {
 #pragma unroll
-      for (int q = 1; q < PARTS; ++q) num += acc_part[q][j];
+      for (int q = 1; q < PARTS; ++q) num += acc_part[q][jl];
     }
   }
   if (part == 0) p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
@@ -419,6 +426,10 @@ hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStre
   else if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
   else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);
   else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256, 256>), grid, dim3(256), 0, s, p);
+  // d = 512: with few outputs, several blocks per query head (measured: 32 outputs 8 slices, 64 outputs 4; from
+  // 128 outputs on slicing no longer pays and one block of 1024 threads per head is the shortest)
+  else if ((int64_t)grid.x * grid.y <= 32) hipLaunchKernelGGL((reduce_kernel<512, 512, 8>), dim3(8 * grid.x, grid.y), dim3(512), 0, s, p);
+  else if ((int64_t)grid.x * grid.y <= 64) hipLaunchKernelGGL((reduce_kernel<512, 512, 4>), dim3(4 * grid.x, grid.y), dim3(512), 0, s, p);
   else hipLaunchKernelGGL((reduce_kernel<512, 1024>), grid, dim3(1024), 0, s, p);
   return hipGetLastError();
 }
