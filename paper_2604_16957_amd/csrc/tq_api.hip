@@ -511,10 +511,7 @@ namespace {
 int append_decode_with_lengths(PartialRequest& rq, const void* k_new, const void* v_new) {
   const tq_decode_opts* opts = rq.opts;
   // (where every row is a single chunk there is no merge kernel to take the token in: the append kernel, then the decode)
-  // (nor where the merge of thousands of outputs runs as one block per KV head: three shorter launches)
-  const bool one_chunk_rows = rows_as_chunks(rq.cache, rq.n_q_heads, rq.seq_len, rq.attn_scale, opts, rq.paged != nullptr) ||
-                              tq::reduce_is_grouped(rq.cache->head_dim, rq.cache->batch, rq.n_q_heads,
-                                                    rq.n_q_heads / rq.cache->n_kv_heads);
+  const bool one_chunk_rows = rows_as_chunks(rq.cache, rq.n_q_heads, rq.seq_len, rq.attn_scale, opts, rq.paged != nullptr);
   if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2 && !one_chunk_rows) {
     rq.k_new = k_new;
     rq.v_new = v_new;

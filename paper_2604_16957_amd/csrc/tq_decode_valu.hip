@@ -176,6 +176,49 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   }
 }
 
+// Append-and-attend in a merge kernel: the step's new token of (row b, KV head kv), quantised with the device
+// function the append kernel uses (same bits; Sec. 2.1) by the block's first 8 * D / 32 threads (four lanes per
+// group of 32 elements, eight elements each, K and V), stored at `append_pos` if `store`, and left dequantised
+// (Eq. 3) in hat[0] (K) and hat[1] (V).  The caller synchronises the block before reading hat.
+template <int D>
+__device__ inline void quantize_new_token(const DecodeParams& p, int b, int kv, int append_pos, int tid, bool store,
+                                          float (*hat)[D]) {
+  constexpr int NG = D / kGroup;
+  if (tid < 8 * NG) {
+    const int which = tid / (4 * NG), g = (tid >> 2) % NG, part4 = tid & 3;   // 0 = K, 1 = V
+    const half_t* src = (which ? p.v_new : p.k_new) + (int64_t)(b * p.n_kv_heads + kv) * D + g * kGroup + part4 * 8;
+    Pack16 u;
+    u.v = *reinterpret_cast<const uint4*>(src);
+    float x[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) x[jj] = (float)u.h[jj];
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int jj = 1; jj < 8; ++jj) { mn = fminf(mn, x[jj]); mx = fmaxf(mx, x[jj]); }
+    // the group's min and max: over the four lanes (exact in any order)
+    mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
+    mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
+    half_t s16, z16;
+    quantize_scale_zero(mn, mx, s16, z16);
+    const float sf = (float)s16, zf = (float)z16;
+    const uint32_t w = quantize_word(x, sf, zf);
+    if (store) {
+      int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + append_pos;
+      if (p.block_table) {                         // paged cache: the page the block table names for that position
+        const int page = p.block_table[(int64_t)b * p.max_blocks + (append_pos >> p.page_shift)];
+        row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (append_pos & ((1 << p.page_shift) - 1));
+      }
+      uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes) + row * (D / 2) + g * (kGroup / 2);
+      reinterpret_cast<uint32_t*>(codes)[part4] = w;
+      if (part4 == 0) const_cast<half_t*>(which ? p.v_scale : p.k_scale)[row * NG + g] = s16;
+      if (part4 == 1) const_cast<half_t*>(which ? p.v_zero : p.k_zero)[row * NG + g] = z16;
+    }
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj)
+      hat[which][g * kGroup + part4 * 8 + jj] = ((float)((w >> (4 * jj)) & 0xFu) - zf) * sf;   // Eq. 3
+  }
+}
+
 // Eq. 6 with un-normalised chunk outputs: o = sum_c e^{m_c-m_g} o_c / sum_c e^{m_c-m_g} l_c.
 // One block per query head.  The chunk weights are computed once (one chunk per thread) and kept
 // in LDS; the weighted sum over chunks is split over 256/D thread groups with independent,
@@ -233,46 +276,13 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   // the chunks.  Every block quantises it for its KV head with the device function the append kernel uses (same
   // bits; Sec. 2.1), the block of the group's first query head stores it, and its attention term enters Eq. 6
   // as one more chunk: m = its score, l = 1, o = its dequantised V.
-  constexpr int NG = D / kGroup;
   __shared__ float hat[2][D];
   __shared__ float red_a[WAVES];
   const bool appending = p.k_new != nullptr;
   float a_new = kNegBig;
   if (appending) {
     const int kv = h / p.gqa;
-    if (tid < 8 * NG) {                           // four lanes per group of 32 elements, eight elements each
-      const int which = tid / (4 * NG), g = (tid >> 2) % NG, part4 = tid & 3;   // 0 = K, 1 = V
-      const half_t* src = (which ? p.v_new : p.k_new) + (int64_t)(b * p.n_kv_heads + kv) * D + g * kGroup + part4 * 8;
-      Pack16 u;
-      u.v = *reinterpret_cast<const uint4*>(src);
-      float x[8];
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj) x[jj] = (float)u.h[jj];
-      float mn = x[0], mx = x[0];
-#pragma unroll
-      for (int jj = 1; jj < 8; ++jj) { mn = fminf(mn, x[jj]); mx = fmaxf(mx, x[jj]); }
-      // the group's min and max: over the four lanes (exact in any order)
-      mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1));
-      mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2));
-      half_t s16, z16;
-      quantize_scale_zero(mn, mx, s16, z16);
-      const float sf = (float)s16, zf = (float)z16;
-      const uint32_t w = quantize_word(x, sf, zf);
-      if (h % p.gqa == 0 && slice == 0) {
-        int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + append_pos;
-        if (p.block_table) {                       // paged cache: the page the block table names for that position
-          const int page = p.block_table[(int64_t)b * p.max_blocks + (append_pos >> p.page_shift)];
-          row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (append_pos & ((1 << p.page_shift) - 1));
-        }
-        uint8_t* codes = const_cast<uint8_t*>(which ? p.v_codes : p.k_codes) + row * (D / 2) + g * (kGroup / 2);
-        reinterpret_cast<uint32_t*>(codes)[part4] = w;
-        if (part4 == 0) const_cast<half_t*>(which ? p.v_scale : p.k_scale)[row * NG + g] = s16;
-        if (part4 == 1) const_cast<half_t*>(which ? p.v_zero : p.k_zero)[row * NG + g] = z16;
-      }
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj)
-        hat[which][g * kGroup + part4 * 8 + jj] = ((float)((w >> (4 * jj)) & 0xFu) - zf) * sf;   // Eq. 3
-    }
+    quantize_new_token<D>(p, b, kv, append_pos, tid, h % p.gqa == 0 && slice == 0, hat);
     __syncthreads();
     float prod = 0.0f;
     for (int e = tid; e < D; e += THREADS) prod = fmaf((float)p.q[(int64_t)(b * p.n_q_heads + h) * D + e], hat[0][e], prod);
@@ -341,17 +351,33 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
 // chunks are folded in four at a time, all their loads in flight together, with a running maximum (Alg. 1's
 // rescaling applied to chunks), so the usual handful of chunks is one memory round trip after the lengths, with
 // no LDS and no barrier, and the launch is one round of blocks where one block per query head takes several.
+// Append-and-attend (p.k_new set; one query token): the block quantises and stores its KV head's new token once
+// for the whole group, every head's score of it is a sum over the D threads that hold the head, and it enters
+// the fold as the last chunk (m = the score, l = 1, o = the dequantised V), as in reduce_kernel.
 template <int D>
 __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
-  const int kv = blockIdx.x, b = blockIdx.y, j = threadIdx.x % D, part = threadIdx.x / D;
+  static_assert(D % 64 == 0 && 2 * D >= 8 * (D / kGroup), "whole waves per head; one thread per lane of the appender");
+  const int kv = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, j = tid % D, part = tid / D;
   const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;
   int n = p.n_splits;
+  int append_pos = p.append_pos;
   if (p.seq_lens) {
     const int sequence = p.n_queries > 1 ? b / p.n_queries : b;
     const int c = p.var_chunks > 0 ? *p.plan : p.tokens_per_split;
     n = min(n, (var_len(p, sequence) + c - 1) / c);
+    // (append-and-attend: the length counts the new token, which goes to the last position; a sequence with no
+    // cached token has no chunk)
+    const int total = max(1, min(p.seq_lens[sequence], p.seq_len));
+    append_pos = total - 1;
+    if (total + p.len_bias < 1) n = 0;
   }
-  n = max(n, 1);
+  const bool appending = p.k_new != nullptr;
+  __shared__ float hat[2][D];
+  __shared__ float red_a[2 * D / 64][4];
+  if (appending) {
+    quantize_new_token<D>(p, b, kv, append_pos, tid, true, hat);
+    __syncthreads();
+  }
   for (int h0 = 0; h0 < p.gqa; h0 += 8) {
     int64_t row[4];
 #pragma unroll
@@ -388,6 +414,32 @@ __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
         m_run[i] = mx;
       }
     }
+    if (appending) {                              // (block-uniform)
+      float prod[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        prod[i] = (float)p.q[row[i] * D + j] * hat[0][j];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) prod[i] += __shfl_xor(prod[i], off);
+      }
+      __syncthreads();                            // (the previous pass has read red_a)
+      if ((tid & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red_a[tid >> 6][i] = prod[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float dot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < D / 64; ++w) dot += red_a[part * (D / 64) + w][i];
+        const float a_new = dot * p.scale_log2;
+        const float mx = fmaxf(m_run[i], a_new);
+        const float keep = exp2f(m_run[i] - mx), e = exp2f(a_new - mx);
+        num[i] = fmaf(hat[1][j], e, num[i] * keep);
+        den[i] = fmaf(den[i], keep, e);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (h0 + part * 4 + i < p.gqa) p.out[row[i] * D + j] = (half_t)(num[i] / den[i]);
@@ -421,7 +473,7 @@ bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa) {
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   const bool many = (int64_t)grid.x * grid.y >= 4096;      // several rounds of blocks: smaller blocks, more at once
-  if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa) && !p.k_new)
+  if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa))
     hipLaunchKernelGGL((reduce_group_kernel<128>), dim3(p.n_kv_heads, grid.y), dim3(256), 0, s, p);
   else if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
   else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);

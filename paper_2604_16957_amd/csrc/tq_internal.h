@@ -283,8 +283,7 @@ bool wide_supported(int head_dim);
 int wide_row_tiles(int rows, int64_t units, int tokens);
 hipError_t launch_partial_wide(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
-// Whether the merge of that many outputs runs as one block per (output row, KV head), which cannot take a new
-// token in: a step then appends with the append kernel first.
+// Whether the merge of that many outputs runs as one block per (output row, KV head).
 bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 

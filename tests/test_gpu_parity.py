@@ -1341,8 +1341,8 @@ def test_eighty_sequences_with_their_own_lengths_and_a_step(S):
 @pytest.mark.parametrize("B,Hq,Hkv", [(128, 32, 8), (172, 24, 4), (86, 48, 4), (32, 128, 8)])
 def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
     """At 4096 and more (sequence, query head) outputs of 128 elements, with four or more query heads to a KV head,
-    the chunk merge (Eq. 6) folds a whole group's heads in one block, four chunks at a time, and the step appends
-    with the append kernel first: groups of 4, 6, 12 and 16 heads, chunk counts from 1 to 7 per sequence, with the
+    the chunk merge (Eq. 6) folds a whole group's heads in one block, four chunks at a time, and in a step takes
+    the new token in as the last chunk: groups of 4, 6, 12 and 16 heads, chunk counts from 1 to 7 per sequence, with the
     chunk count asked for and with the device's plan, plain, windowed, two query tokens, and the one-call step."""
     S = 700
     rng = np.random.default_rng(B + Hq)
@@ -1386,3 +1386,11 @@ def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
             if gb.dtype == np.float16:
                 gb, ob = gb.view(np.uint16), ob.view(np.uint16)
             assert np.array_equal(gb, ob), f"{name} sequence {b}"
+    # ... and the step at a common length: the last token of every sequence again
+    for t in cache.tensors():
+        t.view(torch.uint8)[:, :, S - 1] = 0xEE
+    out = tq.tq_sdpa_int4_append_decode(cache, k[:, :, S - 1:S].contiguous().cuda(), v[:, :, S - 1:S].contiguous().cuda(),
+                                        q.cuda(), S, w.attn_scale, n_splits=3)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_varlen(q, ocache, [S] * B, w.attn_scale), "common length, 3 chunks, append + decode")
+    assert_cache_bit_exact(cache, ocache, S)
