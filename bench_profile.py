@@ -3,6 +3,7 @@
 
   kernel trace : python bench_profile.py trace  <dir with *_kernel_stats.csv>
   HBM traffic  : python bench_profile.py traffic <FETCH_SIZE run dir> <WRITE_SIZE run dir> [--json profiles/traffic.json]
+                 [--workload NAME]   (the key in the JSON file; default llama128k; a workload of 167 772 160 packed bytes)
 
 The traffic mode expects both runs to come from `bench.py --calibrate-copy`: the plain device copy of
 known size in that run gives the factor between the counter's reading and real bytes.
@@ -80,6 +81,7 @@ if __name__ == "__main__":
         trace(sys.argv[2])
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         jp = sys.argv[sys.argv.index("--json") + 1] if "--json" in sys.argv else None
-        traffic(sys.argv[2], sys.argv[3], jp)
+        wl = sys.argv[sys.argv.index("--workload") + 1] if "--workload" in sys.argv else "llama128k"
+        traffic(sys.argv[2], sys.argv[3], jp, workload=wl)
     else:
         sys.exit(__doc__)
