@@ -41,7 +41,7 @@ def parse():
                          "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | paged8 (the same "
                          "over a pool of 256-token pages in random order) | varlen256 (256 sequences of 64 ... 1024 tokens of the llama "
                          "shape: every (sequence, KV head) row is one chunk, no merge kernel) | varlen256_2k (the same with 64 ... 2048 tokens: "
-                         "chunks planned on the device, merge kernel of one block per sequence and KV head) | sweep80 "
+                         "chunks planned on the device, merge kernel of one block per sequence and four query heads) | sweep80 "
                          "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")

@@ -10,6 +10,7 @@
 // wave shuffles, waves through LDS, and the block writes ONE un-normalised partial
 // (o_c, m_c, l_c) per query head (Sec. 3.2).  Scores live in log2 units so exp is exp2.
 #include <algorithm>
+#include <type_traits>
 
 #include "tq_internal.h"
 
@@ -346,18 +347,21 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   if (part == 0) p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
 }
 
-// Eq. 6 for launches of thousands of outputs with few chunks each (many sequences with their own lengths): one
-// block per (output row, KV head), a thread per output element and up to four of the group's query heads.  The
-// chunks are folded in four at a time, all their loads in flight together, with a running maximum (Alg. 1's
-// rescaling applied to chunks), so the usual handful of chunks is one memory round trip after the lengths, with
-// no LDS and no barrier, and the launch is one round of blocks where one block per query head takes several.
-// Append-and-attend (p.k_new set; one query token): the block quantises and stores its KV head's new token once
-// for the whole group, every head's score of it is a sum over the D threads that hold the head, and it enters
+// Eq. 6 for launches of many hundreds of outputs and more (a dozen sequences and up): one block per (output row,
+// 2 * HPT query heads of a KV head's group), a thread per output element and HPT heads.  The chunks are folded in
+// four at a time (sequences of up to four chunks: one round of loads) or 32 / HPT at a time, all their loads in
+// flight together, with a running maximum (Alg. 1's rescaling applied to chunks): no LDS, no barrier, and a
+// launch of a quarter of the blocks that one block per query head needs.
+// Append-and-attend (p.k_new set; one query token): every block quantises its KV head's new token, the group's
+// first block stores it, every head's score of it is a sum over the D threads that hold the head, and it enters
 // the fold as the last chunk (m = the score, l = 1, o = the dequantised V), as in reduce_kernel.
-template <int D>
+template <int D, int HPT>
 __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
   static_assert(D % 64 == 0 && 2 * D >= 8 * (D / kGroup), "whole waves per head; one thread per lane of the appender");
-  const int kv = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, j = tid % D, part = tid / D;
+  // HPT heads per thread, 2 * HPT per block: a KV head's group takes `subs` blocks
+  const int subs = (p.gqa + 2 * HPT - 1) / (2 * HPT);
+  const int kv = blockIdx.x / subs, h0 = (blockIdx.x - kv * subs) * (2 * HPT);
+  const int b = blockIdx.y, tid = threadIdx.x, j = tid % D, part = tid / D;
   const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;
   int n = p.n_splits;
   int append_pos = p.append_pos;
@@ -373,40 +377,43 @@ __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
   }
   const bool appending = p.k_new != nullptr;
   __shared__ float hat[2][D];
-  __shared__ float red_a[2 * D / 64][4];
+  __shared__ float red_a[2 * D / 64][HPT];
   if (appending) {
-    quantize_new_token<D>(p, b, kv, append_pos, tid, true, hat);
+    quantize_new_token<D>(p, b, kv, append_pos, tid, h0 == 0, hat);
     __syncthreads();
   }
-  for (int h0 = 0; h0 < p.gqa; h0 += 8) {
-    int64_t row[4];
+  int64_t row[HPT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) row[i] = (int64_t)b * p.n_q_heads + kv * p.gqa + min(h0 + part * 4 + i, p.gqa - 1);
-    float m_run[4], num[4], den[4];
+  for (int i = 0; i < HPT; ++i) row[i] = (int64_t)b * p.n_q_heads + kv * p.gqa + min(h0 + part * HPT + i, p.gqa - 1);
+  float m_run[HPT], num[HPT], den[HPT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { m_run[i] = kNegBig; num[i] = 0.0f; den[i] = 0.0f; }
-    for (int c0 = 0; c0 < n; c0 += 4) {
-      float2 ml[4][4];
-      float o[4][4];
+  for (int i = 0; i < HPT; ++i) { m_run[i] = kNegBig; num[i] = 0.0f; den[i] = 0.0f; }
+  // (up to four chunks: one round of loads; more: 32 / HPT at a time, so that a sequence of many chunks among
+  // short ones, up to 128, stays a few rounds)
+  auto fold = [&](auto width) {
+    constexpr int CW = decltype(width)::value;
+    for (int c0 = 0; c0 < n; c0 += CW) {
+      float2 ml[HPT][CW];
+      float o[HPT][CW];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < HPT; ++i) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < CW; ++u) {
           const int64_t ph = row[i] * part_stride + min(c0 + u, n - 1);
           ml[i][u] = *reinterpret_cast<const float2*>(p.part_ml + ph * 2);
           o[i][u] = p.part_o[ph * D + j];
         }
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < HPT; ++i) {
         float mx = m_run[i];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) mx = c0 + u < n ? fmaxf(mx, ml[i][u].x) : mx;
+        for (int u = 0; u < CW; ++u) mx = c0 + u < n ? fmaxf(mx, ml[i][u].x) : mx;
         const float keep = exp2f(m_run[i] - mx);
         num[i] *= keep;
         den[i] *= keep;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < CW; ++u) {
           const float e = c0 + u < n ? exp2f(ml[i][u].x - mx) : 0.0f;
           num[i] = fmaf(o[i][u], e, num[i]);
           den[i] = fmaf(ml[i][u].y, e, den[i]);
@@ -414,36 +421,37 @@ __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
         m_run[i] = mx;
       }
     }
-    if (appending) {                              // (block-uniform)
-      float prod[4];
+  };
+  if (n <= 4) fold(std::integral_constant<int, 4>{});
+  else fold(std::integral_constant<int, 32 / HPT>{});
+  if (appending) {                                // (block-uniform)
+    float prod[HPT];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        prod[i] = (float)p.q[row[i] * D + j] * hat[0][j];
+    for (int i = 0; i < HPT; ++i) {
+      prod[i] = (float)p.q[row[i] * D + j] * hat[0][j];
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) prod[i] += __shfl_xor(prod[i], off);
-      }
-      __syncthreads();                            // (the previous pass has read red_a)
-      if ((tid & 63) == 0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) red_a[tid >> 6][i] = prod[i];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float dot = 0.0f;
-#pragma unroll
-        for (int w = 0; w < D / 64; ++w) dot += red_a[part * (D / 64) + w][i];
-        const float a_new = dot * p.scale_log2;
-        const float mx = fmaxf(m_run[i], a_new);
-        const float keep = exp2f(m_run[i] - mx), e = exp2f(a_new - mx);
-        num[i] = fmaf(hat[1][j], e, num[i] * keep);
-        den[i] = fmaf(den[i], keep, e);
-      }
+      for (int off = 32; off >= 1; off >>= 1) prod[i] += __shfl_xor(prod[i], off);
     }
+    if ((tid & 63) == 0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (h0 + part * 4 + i < p.gqa) p.out[row[i] * D + j] = (half_t)(num[i] / den[i]);
+      for (int i = 0; i < HPT; ++i) red_a[tid >> 6][i] = prod[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < HPT; ++i) {
+      float dot = 0.0f;
+#pragma unroll
+      for (int w = 0; w < D / 64; ++w) dot += red_a[part * (D / 64) + w][i];
+      const float a_new = dot * p.scale_log2;
+      const float mx = fmaxf(m_run[i], a_new);
+      const float keep = exp2f(m_run[i] - mx), e = exp2f(a_new - mx);
+      num[i] = fmaf(hat[1][j], e, num[i] * keep);
+      den[i] = fmaf(den[i], keep, e);
+    }
   }
+#pragma unroll
+  for (int i = 0; i < HPT; ++i)
+    if (h0 + part * HPT + i < p.gqa) p.out[row[i] * D + j] = (half_t)(num[i] / den[i]);
 }
 
 }  // namespace
@@ -466,15 +474,24 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
   return hipGetLastError();
 }
 
+// (measured on 64 query heads over 8 KV heads, sequences with their own lengths: no difference at 8 sequences,
+// 2 % per decode at 12, 8-10 % at 32 and 48, 6-8 % at 128 and 256)
+// Query heads per thread of reduce_group_kernel (a block: twice as many).  Measured against 4 and 1 on 64 query
+// heads over 8 KV heads: 4 is as good where every sequence has a few chunks but a block then pulls in eight heads'
+// partials, which for a sequence of 128 chunks among short ones is 512 KB through one compute unit (64 sequences,
+// one of 65536 tokens: 55 µs per decode against 40 with one block per head, 45 with 2); 1 is no faster than one block
+// per head.
+constexpr int kGroupHeads = 2;
 bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa) {
-  return head_dim == 128 && out_rows * n_q_heads >= 4096 && gqa >= 4;
+  return head_dim == 128 && out_rows * n_q_heads >= 768 && gqa >= 4;
 }
 
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   const bool many = (int64_t)grid.x * grid.y >= 4096;      // several rounds of blocks: smaller blocks, more at once
   if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa))
-    hipLaunchKernelGGL((reduce_group_kernel<128>), dim3(p.n_kv_heads, grid.y), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((reduce_group_kernel<128, kGroupHeads>), dim3(p.n_kv_heads * ((p.gqa + 2 * kGroupHeads - 1) / (2 * kGroupHeads)), grid.y),
+                       dim3(256), 0, s, p);
   else if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
   else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);
   else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256, 256>), grid, dim3(256), 0, s, p);

@@ -1340,9 +1340,9 @@ def test_eighty_sequences_with_their_own_lengths_and_a_step(S):
 
 @pytest.mark.parametrize("B,Hq,Hkv", [(128, 32, 8), (172, 24, 4), (86, 48, 4), (32, 128, 8)])
 def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
-    """At 4096 and more (sequence, query head) outputs of 128 elements, with four or more query heads to a KV head,
-    the chunk merge (Eq. 6) folds a whole group's heads in one block, four chunks at a time, and in a step takes
-    the new token in as the last chunk: groups of 4, 6, 12 and 16 heads, chunk counts from 1 to 7 per sequence, with the
+    """From 768 (sequence, query head) outputs of 128 elements on (here: thousands), with four or more query heads
+    to a KV head, the chunk merge (Eq. 6) folds four heads of a group in one block, 4 or 16 chunks at a time, and
+    in a step takes the new token in as the last chunk: groups of 4, 6, 12 and 16 heads, chunk counts from 1 to 7 per sequence, with the
     chunk count asked for and with the device's plan, plain, windowed, two query tokens, and the one-call step."""
     S = 700
     rng = np.random.default_rng(B + Hq)
