@@ -1394,3 +1394,31 @@ def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
     torch.cuda.synchronize()
     assert_close(out, _oracle_varlen(q, ocache, [S] * B, w.attn_scale), "common length, 3 chunks, append + decode")
     assert_cache_bit_exact(cache, ocache, S)
+
+
+def test_one_long_sequence_among_short_ones():
+    """24 sequences, one of 20000 tokens and the others of at most 300: the device's plan gives the long one some
+    thirty chunks and the others one each, and the grouped merge kernel (1536 outputs) folds the long one's 16 at
+    a time.  Decode and the one-call step, against the oracle."""
+    B, S = 24, 20000
+    rng = np.random.default_rng(24)
+    lens = [int(x) for x in rng.integers(1, 301, B)]
+    lens[5] = S
+    w = wl.custom(batch=B, n_q_heads=64, n_kv_heads=8, head_dim=128, seq_len=S, seed=2800, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "one long sequence among short ones")
+    kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    for t in cache.tensors():
+        for b in range(B):
+            t.view(torch.uint8)[b, :, lens[b] - 1] = 0xEE
+    out = tq.tq_sdpa_int4_append_decode_varlen(cache, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, ref, "one long sequence among short ones, append + decode")
+    assert_cache_bit_exact(cache, ocache, S)
