@@ -306,7 +306,7 @@ int orc_attend_alg1_eq6_f64(const uint16_t* q, const double* K, const double* V,
   std::vector<double> qs((size_t)d), oc((size_t)n_chunks * d), mc((size_t)n_chunks), lc((size_t)n_chunks);
   for (int64_t bh = 0; bh < (int64_t)B * Hq; ++bh) {
     const int b = (int)(bh / Hq), h = (int)(bh % Hq), kv = h / G;
-    for (int j = 0; j < d; ++j)                            // Alg. 1 line 1: pre-scale the query
+    for (int j = 0; j < d; ++j)                            // Alg. 1 starts by pre-scaling the query
       qs[(size_t)j] = (double)half_bits_to_float(q[bh * d + j]) * alpha;
     const size_t off = ((size_t)b * Hkv + kv) * (size_t)S * d;
     for (int c = 0; c < n_chunks; ++c)

@@ -3,7 +3,7 @@
 //
 // Why matrix cores: with a GQA group of G query heads every stored element is used by G heads;
 // at G=8 and d=128 that is 25.6 flop per HBM byte, above the vector-ALU ridge of the chip, so the
-// two contractions (Alg. 1 lines 5 and 9) run on v_mfma_f32_16x16x32_f16 and the vector ALU only
+// two contractions (the score step and the accumulator update of Alg. 1) run on v_mfma_f32_16x16x32_f16 and the vector ALU only
 // unpacks nibbles, applies the per-group scale/zero-point of K and does the softmax.
 //
 // Data path: the packed stream never passes through vector registers on its way in.  Each wave owns
@@ -516,7 +516,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     wait_loads<0>();
   }
 
-  // ---- query operands (Alg. 1 line 1 is folded into the exp2 argument instead of the query)
+  // ---- query operands (the query pre-scaling of Alg. 1 is folded into the exp2 argument instead of the query)
   const _Float16* qh = reinterpret_cast<const _Float16*>(q_area) + hl * D;
   half8v qraw[NJ];
 #pragma unroll
@@ -686,10 +686,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     }
   };
 
-  // -- online softmax over the 32 tokens (Alg. 1 lines 6-7, 10), block-wise.  m_run is a per-head
+  // -- online softmax over the 32 tokens (Alg. 1: the maximum, the weights and the running sum), block-wise.  m_run is a per-head
   //    REFERENCE, not the exact running max: it only moves when some score exceeds it by more than
   //    kSlack (log2 units), so exp2(score - m_run) <= 2^kSlack = 4 and p * s_v stays inside fp16 for
-  //    every representable scale, while the accumulator rescale (Alg. 1 lines 7, 9) becomes rare.
+  //    every representable scale, while the accumulator rescale (Alg. 1, the correction factor) becomes rare.
   //    When it moves it is set kSlack ABOVE the new maximum, so the next move needs a score 2*kSlack
   //    higher than any seen so far; the weights then start at 2^-kSlack, far inside fp16's normal range.
   //    Any reference gives the same o / l, and the chunk merge (Eq. 6) accepts any m_c.

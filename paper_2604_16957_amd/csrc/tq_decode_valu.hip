@@ -6,7 +6,7 @@
 // chunk of one KV head.  D/8 lanes cooperate on a token (each lane holds 8 consecutive
 // head_dim elements: one 32-bit word of codes, or 16 B of fp16), so a wave walks 64/(D/8)
 // tokens at a time and every token-slot keeps its own online-softmax state (m, l, o) for up to
-// 8 query heads of the GQA group in registers (Alg. 1, lines 3-11).  Slots are merged with
+// 8 query heads of the GQA group in registers (Alg. 1, the loop over the tokens).  Slots are merged with
 // wave shuffles, waves through LDS, and the block writes ONE un-normalised partial
 // (o_c, m_c, l_c) per query head (Sec. 3.2).  Scores live in log2 units so exp is exp2.
 #include <algorithm>
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   const int h0 = kv * p.gqa + tile * kHeadTile;          // first query head of this pass
   const int nh = min(kHeadTile, p.gqa - tile * kHeadTile);
 
-  // query piece for each head, pre-multiplied by attn_scale * log2(e) (Alg. 1, line 1)
+  // query piece for each head, pre-multiplied by attn_scale * log2(e) (Alg. 1, the query pre-scaling)
   float qf[kHeadTile][8];
 #pragma unroll
   for (int h = 0; h < kHeadTile; ++h) {
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 #pragma unroll
       for (int j = 0; j < 8; ++j) a = fmaf(qf[h][j], kf[j], a);
 #pragma unroll
-      for (int off = 1; off < LPT; off <<= 1) a += __shfl_xor(a, off);   // Alg. 1, line 5
+      for (int off = 1; off < LPT; off <<= 1) a += __shfl_xor(a, off);   // Alg. 1, the score
       const float m_new = valid ? fmaxf(m[h], a) : m[h];
       const float corr = exp2f(m[h] - m_new);
       const float pr = valid ? exp2f(a - m_new) : 0.0f;

@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_ke
     }
   };
 
-  // ---- running state (Alg. 1 lines 2-3), scores in log2 units
+  // ---- running state (Alg. 1, the initialisation), scores in log2 units
   float m_run[RT], l_run[RT];                     // per column (query row); l: this lane's share of the sum
   float4v oacc[RT][8];                            // rows 4kq+i of the tile, dim 8(16w+c) + index
 #pragma unroll
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_ke
     StepK cur;
     read_k(it, cur);
 
-    // -- this wave's share of the scores (Alg. 1 line 5): its four groups of K against the query rows,
+    // -- this wave's share of the scores (Alg. 1, the score step): its four groups of K against the query rows,
     //    per-group scale and zero-point applied in fp32 (accumulator units: 2^-24)
     float4v sacc[RT][2];
 #pragma unroll
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_ke
     __syncthreads();
     if (it + NSTG - 1 < n_steps) issue_step(it + NSTG - 1);
 
-    // -- online softmax (Alg. 1 lines 6-8, 10), the same in all four waves.  A step that every row of the
+    // -- online softmax (Alg. 1: the maximum, the weights and the running sum), the same in all four waves.  A step that every row of the
     //    tile sees in full needs no masks: all steps but the few that hold a row's first or last token.
     half8v pa[RT];
     float corr[RT];
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_ke
     };
     if (tok0 >= lo_all && tok0 + 32 <= end_all) softmax(std::false_type{});
     else softmax(std::true_type{});
-    if (__builtin_amdgcn_ballot_w64(moved) != 0) {               // some row's maximum moved: rescale (Alg. 1 line 9)
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {               // some row's maximum moved: rescale (Alg. 1, the correction of the accumulator)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         float fr[4];                                             // accumulator row 4kq+i is the column of lane 4kq+i
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256, NSTG == 3 ? 2 : 1) void decode_partial_wide_ke
       }
     }
 
-    // -- P V (Alg. 1 line 9): 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens, dequantised per token pair
+    // -- P V (Alg. 1, the accumulator update): 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens, dequantised per token pair
     {
       StepV curv;
       read_v(it, curv);
