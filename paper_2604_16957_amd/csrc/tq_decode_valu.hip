@@ -480,7 +480,7 @@ hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, b
 // heads over 8 KV heads: 4 is as good where every sequence has a few chunks but a block then pulls in eight heads'
 // partials, which for a sequence of 128 chunks among short ones is 512 KB through one compute unit (64 sequences,
 // one of 65536 tokens: 55 µs per decode against 40 with one block per head, 45 with 2); 1 is no faster than one block
-// per head.
+// per head.  (Where the host can rule such sequences out, launch_reduce takes 4.)
 constexpr int kGroupHeads = 2;
 bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa) {
   return head_dim == 128 && out_rows * n_q_heads >= 768 && gqa >= 4;
@@ -489,9 +489,17 @@ bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa) {
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s) {
   const dim3 grid(p.n_q_heads, batch * std::max(1, p.n_queries));
   const bool many = (int64_t)grid.x * grid.y >= 4096;      // several rounds of blocks: smaller blocks, more at once
-  if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa))
-    hipLaunchKernelGGL((reduce_group_kernel<128, kGroupHeads>), dim3(p.n_kv_heads * ((p.gqa + 2 * kGroupHeads - 1) / (2 * kGroupHeads)), grid.y),
-                       dim3(256), 0, s, p);
+  if (reduce_is_grouped(head_dim, grid.y, p.n_q_heads, p.gqa)) {
+    // Heads per thread: two; four (one block per KV head of eight query heads) where there are thousands of
+    // outputs and no sequence can have more than 16 chunks, which the host can tell from the longest length
+    // allowed and the planner's shortest chunk, or from the chunk count asked for.
+    const int most_chunks = p.var_chunks > 0 ? (p.seq_len + p.var_min_chunk - 1) / std::max(1, p.var_min_chunk) : p.n_splits;
+    if (many && most_chunks <= 16)
+      hipLaunchKernelGGL((reduce_group_kernel<128, 4>), dim3(p.n_kv_heads * ((p.gqa + 7) / 8), grid.y), dim3(256), 0, s, p);
+    else
+      hipLaunchKernelGGL((reduce_group_kernel<128, kGroupHeads>),
+                         dim3(p.n_kv_heads * ((p.gqa + 2 * kGroupHeads - 1) / (2 * kGroupHeads)), grid.y), dim3(256), 0, s, p);
+  }
   else if (head_dim == 128 && many) hipLaunchKernelGGL((reduce_kernel<128, 128>), grid, dim3(128), 0, s, p);
   else if (head_dim == 128) hipLaunchKernelGGL((reduce_kernel<128, 256>), grid, dim3(256), 0, s, p);
   else if (head_dim == 256) hipLaunchKernelGGL((reduce_kernel<256, 256>), grid, dim3(256), 0, s, p);

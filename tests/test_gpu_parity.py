@@ -1354,7 +1354,7 @@ def test_merge_of_thousands_of_outputs_runs_one_block_per_kv_head(B, Hq, Hkv):
     ocache = oracle_cache_from(k, v)
     lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
     ref = _oracle_varlen(q, ocache, lens, w.attn_scale)
-    for n_splits, variant in ((7, 0), (2, 0), (5, 1), (0, 1)):
+    for n_splits, variant in ((7, 0), (2, 0), (22, 0), (5, 1), (0, 1)):      # (22 chunks: two heads per thread, else four)
         out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale, n_splits=n_splits, variant=variant)
         torch.cuda.synchronize()
         assert_close(out, ref, f"own lengths, {n_splits} chunks, variant {variant}")
