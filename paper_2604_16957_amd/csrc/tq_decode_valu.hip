@@ -347,6 +347,43 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   if (part == 0) p.out[(int64_t)(b * p.n_q_heads + h) * D + j] = (half_t)(num / den);
 }
 
+// Folds the n chunks of HPT output rows into their running (maximum, numerator, denominator), CW chunks at a
+// time, all of a round's loads in flight together (Eq. 6 with Alg. 1's rescaling applied to chunks).
+template <int D, int HPT, int CW>
+__device__ __forceinline__ void fold_chunks(const float* __restrict__ part_ml, const float* __restrict__ part_o,
+                                            const int64_t (&row)[HPT], int part_stride, int n, int j,
+                                            float (&m_run)[HPT], float (&num)[HPT], float (&den)[HPT]) {
+  for (int c0 = 0; c0 < n; c0 += CW) {
+    float2 ml[HPT][CW];
+    float o[HPT][CW];
+#pragma unroll
+    for (int i = 0; i < HPT; ++i) {
+#pragma unroll
+      for (int u = 0; u < CW; ++u) {
+        const int64_t ph = row[i] * part_stride + min(c0 + u, n - 1);
+        ml[i][u] = *reinterpret_cast<const float2*>(part_ml + ph * 2);
+        o[i][u] = part_o[ph * D + j];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < HPT; ++i) {
+      float mx = m_run[i];
+#pragma unroll
+      for (int u = 0; u < CW; ++u) mx = c0 + u < n ? fmaxf(mx, ml[i][u].x) : mx;
+      const float keep = exp2f(m_run[i] - mx);
+      num[i] *= keep;
+      den[i] *= keep;
+#pragma unroll
+      for (int u = 0; u < CW; ++u) {
+        const float e = c0 + u < n ? exp2f(ml[i][u].x - mx) : 0.0f;
+        num[i] = fmaf(o[i][u], e, num[i]);
+        den[i] = fmaf(ml[i][u].y, e, den[i]);
+      }
+      m_run[i] = mx;
+    }
+  }
+}
+
 // Eq. 6 for launches of many hundreds of outputs and more (a dozen sequences and up): one block per (output row,
 // 2 * HPT query heads of a KV head's group), a thread per output element and HPT heads.  The chunks are folded in
 // four at a time (sequences of up to four chunks: one round of loads) or 32 / HPT at a time, all their loads in
@@ -356,12 +393,17 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
 // first block stores it, every head's score of it is a sum over the D threads that hold the head, and it enters
 // the fold as the last chunk (m = the score, l = 1, o = the dequantised V), as in reduce_kernel.
 template <int D, int HPT>
-__global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
+// (at least five waves per SIMD for the four-heads instance: at 97 registers the compiler left it at four, and the
+// launch of eight blocks per compute unit a third longer)
+__global__ __launch_bounds__(2 * D, HPT == 4 ? 5 : 4) void reduce_group_kernel(DecodeParams p) {
   static_assert(D % 64 == 0 && 2 * D >= 8 * (D / kGroup), "whole waves per head; one thread per lane of the appender");
   // HPT heads per thread, 2 * HPT per block: a KV head's group takes `subs` blocks
   const int subs = (p.gqa + 2 * HPT - 1) / (2 * HPT);
   const int kv = blockIdx.x / subs, h0 = (blockIdx.x - kv * subs) * (2 * HPT);
-  const int b = blockIdx.y, tid = threadIdx.x, j = tid % D, part = tid / D;
+  // (part: the same in all lanes of a wave, D being a multiple of 64: said so, the rows' addresses are scalar,
+  // which saves the four-chunk fold some 30 vector registers; the wide fold would need more scalar registers than
+  // there are and keeps its addresses in vector registers, part_v)
+  const int b = blockIdx.y, tid = threadIdx.x, j = tid % D, part_v = tid / D, part = __builtin_amdgcn_readfirstlane(part_v);
   const int part_stride = p.var_chunks > 0 ? kMaxSplits : p.n_splits;
   int n = p.n_splits;
   int append_pos = p.append_pos;
@@ -389,41 +431,16 @@ __global__ __launch_bounds__(2 * D) void reduce_group_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < HPT; ++i) { m_run[i] = kNegBig; num[i] = 0.0f; den[i] = 0.0f; }
   // (up to four chunks: one round of loads; more: 32 / HPT at a time, so that a sequence of many chunks among
-  // short ones, up to 128, stays a few rounds)
-  auto fold = [&](auto width) {
-    constexpr int CW = decltype(width)::value;
-    for (int c0 = 0; c0 < n; c0 += CW) {
-      float2 ml[HPT][CW];
-      float o[HPT][CW];
+  // short ones, up to 128, stays a few rounds.  HPT = 4 is launched only where a sequence has at most 16 chunks:
+  // four at a time, and 50 registers fewer)
+  if (HPT == 4 || n <= 4) {
+    fold_chunks<D, HPT, 4>(p.part_ml, p.part_o, row, part_stride, n, j, m_run, num, den);
+  } else {
+    int64_t row_v[HPT];
 #pragma unroll
-      for (int i = 0; i < HPT; ++i) {
-#pragma unroll
-        for (int u = 0; u < CW; ++u) {
-          const int64_t ph = row[i] * part_stride + min(c0 + u, n - 1);
-          ml[i][u] = *reinterpret_cast<const float2*>(p.part_ml + ph * 2);
-          o[i][u] = p.part_o[ph * D + j];
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < HPT; ++i) {
-        float mx = m_run[i];
-#pragma unroll
-        for (int u = 0; u < CW; ++u) mx = c0 + u < n ? fmaxf(mx, ml[i][u].x) : mx;
-        const float keep = exp2f(m_run[i] - mx);
-        num[i] *= keep;
-        den[i] *= keep;
-#pragma unroll
-        for (int u = 0; u < CW; ++u) {
-          const float e = c0 + u < n ? exp2f(ml[i][u].x - mx) : 0.0f;
-          num[i] = fmaf(o[i][u], e, num[i]);
-          den[i] = fmaf(ml[i][u].y, e, den[i]);
-        }
-        m_run[i] = mx;
-      }
-    }
-  };
-  if (n <= 4) fold(std::integral_constant<int, 4>{});
-  else fold(std::integral_constant<int, 32 / HPT>{});
+    for (int i = 0; i < HPT; ++i) row_v[i] = (int64_t)b * p.n_q_heads + kv * p.gqa + min(h0 + part_v * HPT + i, p.gqa - 1);
+    fold_chunks<D, HPT, 32 / HPT>(p.part_ml, p.part_o, row_v, part_stride, n, j, m_run, num, den);
+  }
   if (appending) {                                // (block-uniform)
     float prod[HPT];
 #pragma unroll
