@@ -124,6 +124,22 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
                         float attn_scale, void* out, void* workspace, size_t workspace_bytes,
                         const tq_decode_opts* opts, void* stream);
 
+/* tq_sdpa_int4_decode for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same call without the workspace arguments.  The
+ * per-chunk partial results go to an array of TQ_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * device code (one copy per GPU, held until the process ends); the call allocates and frees nothing, neither
+ * itself nor through the runtime.  Same kernels, same chunking, same result bits as tq_sdpa_int4_decode.
+ * A configuration whose tq_workspace_bytes(batch * n_queries, n_q_heads, head_dim) exceeds
+ * TQ_STATIC_SCRATCH_BYTES is rejected with TQ_ERR_WORKSPACE (the 70B shape at head_dim 128 fits up to batch 4).
+ * All calls on one GPU share that GPU's array: two of them in flight at the same time (different streams) race
+ * and give undefined output; calls on one stream are ordered and safe.  The array keeps the last call's
+ * contents; nothing in it has to be cleared between calls.  The first call on a device looks the array's address
+ * up (hipGetSymbolAddress), so make one call on each device before capturing a graph there.
+ * Errors: those of tq_sdpa_int4_decode; WORKSPACE as above; HIP if the address cannot be resolved. */
+#define TQ_STATIC_SCRATCH_BYTES ((size_t)20 << 20)
+int tq_sdpa_int4_decode_static(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                               float attn_scale, void* out, const tq_decode_opts* opts, void* stream);
+
 /* One decode step in one call: tq_quantize_kv(cache, k_new, v_new, seq_len - 1, 1) followed by
  * tq_sdpa_int4_decode(cache, q, ..., seq_len, ...), i.e. the new token of every sequence (k_new,
  * v_new: fp16 [batch][n_kv_heads][1][head_dim]) is quantised, written at position seq_len - 1 and

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     tq_sdpa_int4_append_decode_varlen,
     tq_sdpa_int4_decode,
     tq_sdpa_int4_decode_paged,
+    tq_sdpa_int4_decode_static,
     tq_sdpa_int4_decode_varlen,
     tq_sdpa_int4_partial,
     tq_sdpa_int4_reduce,

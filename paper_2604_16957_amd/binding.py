@@ -54,6 +54,8 @@ def raw():
         OP = ctypes.POINTER(TqDecodeOptsStruct)
         L.tq_quantize_kv.argtypes = [CP, P, P, I, I, P]
         L.tq_sdpa_int4_decode.argtypes = [CP, P, I, I, F, P, P, SZ, OP, P]
+        L.tq_sdpa_int4_decode_static.argtypes = [CP, P, I, I, F, P, OP, P]
+        L.tq_sdpa_int4_decode_static.restype = ctypes.c_int
         L.tq_quantize_kv_paged.argtypes = [CP, P, I, I, P, P, P, I, P]
         L.tq_sdpa_int4_decode_paged.argtypes = [CP, P, I, I, P, I, P, I, F, P, P, SZ, OP, P]
         L.tq_sdpa_int4_append_decode.argtypes = [CP, P, P, P, I, I, F, P, P, SZ, OP, P]
@@ -196,6 +198,23 @@ def tq_sdpa_int4_decode(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scal
                                    float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
                                    _opts(n_splits, variant, window, nq), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_decode")
+    return out
+
+
+TQ_STATIC_SCRATCH_BYTES = 20 << 20
+
+
+def tq_sdpa_int4_decode_static(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out: torch.Tensor,
+                               n_splits: int = 0, variant: int = 0, stream=None, window: int = 0) -> torch.Tensor:
+    """tq_sdpa_int4_decode without a workspace (the library's own static device array takes its place) and
+    without any allocation: `out` has to be passed in."""
+    _need(q, torch.float16, "q")
+    _need(out, torch.float16, "out")
+    nq, hq = _queries(q)
+    rc = raw().tq_sdpa_int4_decode_static(ctypes.byref(cache.struct), q.data_ptr(), hq, int(seq_len),
+                                          float(attn_scale), out.data_ptr(), _opts(n_splits, variant, window, nq),
+                                          _stream_ptr(stream))
+    _check(rc, "tq_sdpa_int4_decode_static")
     return out
 
 

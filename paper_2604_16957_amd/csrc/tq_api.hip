@@ -3,6 +3,7 @@
 // launches nothing (and the checks themselves can be exercised on a machine without a GPU).
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "tq_internal.h"
 
@@ -305,6 +306,30 @@ int paged_view(const tq_kv_cache* pool, const int32_t* block_table, int32_t max_
   return TQ_OK;
 }
 
+// ---- tq_sdpa_int4_decode_static: the workspace of callers that cannot allocate.
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// stand-in for the symbol: the memory's address on a device is what hipGetSymbolAddress returns with that
+// device current, and that pointer is what the kernels get.
+constexpr size_t kScratchBytes = TQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices];                   // per device: where that device's copy of `scratch` lives
+
+// The current device's copy of `scratch` (resolved once per device, on the first call with that device current).
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TQ_ERR_HIP;
+  std::lock_guard<std::mutex> guard(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TQ_ERR_HIP;
+    scratch_ptr[dev] = ptr;
+  }
+  *out = scratch_ptr[dev];
+  return TQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -433,6 +458,29 @@ int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_hea
   rq.attn_scale = attn_scale;
   rq.out = out;
   rq.workspace = workspace;
+  rq.opts = opts;
+  rq.stream = stream;
+  return finish_decode(rq, run_partial(rq));
+}
+
+int tq_sdpa_int4_decode_static(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
+                               float attn_scale, void* out, const tq_decode_opts* opts, void* stream) {
+  // everything that can be told without the workspace first (a fake, aligned address stands in for it), so that a
+  // rejected call touches neither the device nor the runtime
+  void* const fake = reinterpret_cast<void*>(uintptr_t{256});
+  int rc = check_decode(cache, q, n_q_heads, seq_len, out, fake, ~size_t{0}, opts, true);
+  if (rc != TQ_OK) return rc;
+  if (tq_workspace_bytes(cache->batch * queries_of(opts), n_q_heads, cache->head_dim) > kScratchBytes)
+    return TQ_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc != TQ_OK) return rc;
+  // Nothing in the array has to start at zero: every partial the merge reads has been written by the same call's
+  // first phase, and the arrival counters of the one-launch route live elsewhere and reset themselves.
+  PartialRequest rq{cache, q, n_q_heads, seq_len};
+  rq.attn_scale = attn_scale;
+  rq.out = out;
+  rq.workspace = ws;
   rq.opts = opts;
   rq.stream = stream;
   return finish_decode(rq, run_partial(rq));
