@@ -47,12 +47,13 @@
 //   the A-operand layout of P V when P V is computed as rows (h, r) x columns (dims): lane (h, r) of
 //   block kq already holds the probabilities of its 8 tokens, so they never move between lanes.
 //   For P V the contraction runs over tokens, so each lane needs 8 tokens of one dim in its k-slots:
-//   it reads the same packed word of 8 tokens and transposes 8x8 nibbles with two v_perm_b32 stages;
-//   the nibble-level stage is free because the unpack masks already separate even and odd nibbles.
+//   it reads the same packed word of 8 tokens and regroups it with one v_perm_b32 per (token pair, byte);
+//   a byte's two nibbles go through the matrix core mixed (n_even + 16 n_odd, still an exact subnormal)
+//   next to n_even alone, and the odd dim is recovered from the two sums at the end (see `pv`).
 //
 // Work split: grid (n_splits, H_kv * kv_share, B), 8 waves per block, one block per compute unit; the
-// waves of a block share the chunk's 32-token supertiles in a fixed pattern (9:7 between the older and
-// the younger wave of a SIMD, see the kernel), keep private online-softmax state, and are merged through
+// waves of a block share the chunk's 32-token supertiles in a fixed pattern (17:15 or 9:7 between the older
+// and the younger wave of a SIMD, see the kernel), keep private online-softmax state, and are merged through
 // LDS so that the block writes one partial (o_c, m_c, l_c) per query row.
 //
 // Query rows: the tile's GP columns take the G heads of the GQA group (Sec. 3.1), or, with several query
@@ -114,9 +115,13 @@ struct Cfg {
   static constexpr int OFF_V = 2 * KT, OFF_KS = OFF_V + VB, OFF_KZ = OFF_KS + SZ, OFF_VS = OFF_KZ + SZ,
                        OFF_VZ = OFF_VS + SZ, STAGE = OFF_VZ + SZ;
   static constexpr int NS = 2;                  // ring depth per wave (LDS: 160 KB per CU)
+  // The two waves of a SIMD split its supertiles (PER / 2 + 1) : (PER / 2 - 1), the older wave the larger share:
+  // 17 : 15 where the loop is leanest (measured: the older wave of the d = 128, 8-row kernel takes 1.32 us per
+  // supertile, the younger 1.45 us), 9 : 7 elsewhere
+  static constexpr int PER = (D == 128 && GP == 8) ? 32 : 16;
   static constexpr int LPS = 2 * (KT / 1024) + VB / 1024 + 4 * (SZ / 256);   // load instructions per stage
   static constexpr int RING = NW * NS * STAGE;
-  static constexpr int MERGE = (NW * GP * D + NW * GP * NG + 2 * NW * GP) * 4;  // o, zero-point term, m, l
+  static constexpr int MERGE = (NW * GP * D + 2 * NW * GP) * 4;  // o, m, l
   // the block-merge area sits behind the rings where both fit into the 160 KB of a compute unit, else on top of them
   static constexpr bool ALIAS = RING + MERGE > 160 * 1024;
   static constexpr int OFF_MERGE = ALIAS ? 0 : RING;
@@ -202,8 +207,8 @@ __device__ __forceinline__ float row_ror_add(float x) {      // x + (x rotated b
 // caches, and the loads stay plain.
 #define TQ_LDS_LOAD(NT_, TEXT_PLAIN, TEXT_NT, ...)                     \
   do {                                                                 \
-    if constexpr (NT_) asm volatile(TEXT_NT :: __VA_ARGS__ : "memory"); \
-    else asm volatile(TEXT_PLAIN :: __VA_ARGS__ : "memory");           \
+    if constexpr (NT_) asm volatile(TEXT_NT :: __VA_ARGS__ : "memory", "m0"); \
+    else asm volatile(TEXT_PLAIN :: __VA_ARGS__ : "memory", "m0");           \
   } while (0)
 template <bool NT>
 __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
@@ -213,11 +218,11 @@ __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t 
 }
 __device__ __forceinline__ void dma16_lane(const void* addr, uint32_t lds_base) {   // per-lane 64-bit address
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(addr), "s"(lds_base) : "memory");
+               :: "v"(addr), "s"(lds_base) : "memory", "m0");
 }
 __device__ __forceinline__ void dma4_lane(const void* addr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               :: "v"(addr), "s"(lds_base) : "memory");
+               :: "v"(addr), "s"(lds_base) : "memory", "m0");
 }
 // Several loads of one array behind a single M0: the instruction's immediate offset moves the global
 // and the LDS address alike, so pieces that are equally far apart on both sides share the base.
@@ -248,8 +253,9 @@ __device__ __forceinline__ void dma16_x4(const void* sbase, uint32_t voff, uint3
               "v"(voff), "s"(sbase), "s"(lds_base));
 }
 // device-scope (all compute dies) store and load of one float, without any cache-wide maintenance
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {      // two floats, 8-byte aligned
+  const uint64_t bits = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float ld_dev(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -259,7 +265,11 @@ __device__ __forceinline__ void wait_loads() {               // until at most N 
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int D, int GP, int NW, bool NT>
+// PLAIN = the launch has none of the per-sequence machinery: one common length, a contiguous cache, one query
+// token, one block per (chunk, KV head, sequence).  Everything below that serves the other shapes then folds
+// away at compile time; what is left is a short prologue (the first loads leave sooner) and a loop without the
+// scalar bookkeeping of pages and packed rows.
+template <int D, int GP, int NW, bool NT, bool PLAIN>
 __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_kernel(DecodeParams p) {
   using C = Cfg<D, GP, NW>;
   constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS, GR = C::GR;
@@ -276,10 +286,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // blockIdx.y counts groups of rows of the list [batch][KV head x part]; with per-sequence lengths a unit is a
   // slot of the chunk list, and blockIdx.x counts groups of slots.  A wave past the end of its list has no tokens
   // and only keeps the barriers company.
-  const int W = p.waves_per_row;                  // NW: the whole block on one unit
+  const int W = PLAIN ? NW : p.waves_per_row;     // NW: the whole block on one unit
   const bool whole = W == NW;
   bool row_valid = true;
-  if (!whole && p.var_chunks == 0) {
+  if (!PLAIN && !whole && p.var_chunks == 0) {
     const int rows_y = p.n_kv_heads * p.kv_share, total = p.batch * rows_y;
     const int row = blockIdx.y * (NW / W) + wave / W;
     row_valid = row < total;
@@ -287,8 +297,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     b = __builtin_amdgcn_readfirstlane(r / rows_y);
     kvv = __builtin_amdgcn_readfirstlane(r - (r / rows_y) * rows_y);
   }
-  const int kv = kvv / p.kv_share;                // the KV head whose rows are read
-  if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
+  const int kv_share = PLAIN ? 1 : p.kv_share;
+  const int kv = PLAIN ? kvv : kvv / kv_share;    // the KV head whose rows are read
+  if (!PLAIN && p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's
     VarPlan vp;
     vp.b = 0;
     vp.chunk = 0;
@@ -304,8 +315,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // Several query tokens per sequence (they are the sequence's last NQ tokens and causal among themselves):
   // a KV head then has NQ * GF query rows, row r = t * GF + g for query token t and head g of the group,
   // cut into kv_share parts of G rows; this block holds rows part * G .. part * G + G - 1.
-  const int NQ = p.n_queries, GF = p.gqa_full;
-  const int part = kvv - kv * p.kv_share;
+  const int NQ = PLAIN ? 1 : p.n_queries, GF = PLAIN ? G : p.gqa_full;
+  const int part = kvv - kv * kv_share;
   auto query_token = [&](int h) { return NQ > 1 ? min(part * G + h, NQ * GF - 1) / GF : 0; };
   auto query_row = [&](int h) -> int64_t {        // row of q / out / the partials that tile row h stands for
     const int r = part * G + h, t = query_token(h);
@@ -319,14 +330,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // ---- addressing: wave-uniform bases (scalar registers) + per-lane 32-bit byte offsets
   // tokens this sequence attends: the common length, or its own (a chunk past its end is empty); with a
   // sliding window the row simply starts `start` tokens later
-  const int seq = !row_valid ? 0 : p.seq_lens ? var_len(p, b) : p.seq_len;
-  const int start = p.seq_lens ? var_start(p, b) : p.start;
+  const bool var_lens = !PLAIN && p.seq_lens != nullptr;
+  const int seq = !row_valid ? 0 : var_lens ? var_len(p, b) : p.seq_len;
+  const int start = var_lens ? var_start(p, b) : p.start;
   // first row of the six arrays this block reads from: the sequence's own row (contiguous cache), or the
   // pool's row 0 (paged cache: the page's rows are added supertile by supertile)
-  const bool paged = p.block_table != nullptr;
+  const bool paged = !PLAIN && p.block_table != nullptr;
   // paged cache: token indices below count from `start` as well, but the rows are found page by page; the
   // window's first token may lie up to 31 tokens after `start` (see var_start)
-  const int lead = (paged && p.seq_lens) ? var_first(p, b) - start : 0;
+  const int lead = (paged && var_lens) ? var_first(p, b) - start : 0;
   const int pstart = paged ? start : 0;           // added to a token index where a page is looked up
   const int64_t row0 = paged ? 0 : (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
   const int begin0 = split * tokens_per_split;    // first token of the chunk
@@ -340,7 +352,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // and the fast path starts behind it.  The same goes for a paged cache under a window, whose first supertile
   // holds `lead` tokens before the window.  With both, the rows start at tokens lead .. lead + NQ - 1, which may
   // straddle the sequence's first two supertiles: then the second is masked as well, in whichever chunk it lies.
-  const bool rows_windowed = NQ > 1 && p.row_window > 0;
+  const bool rows_windowed = !PLAIN && NQ > 1 && p.row_window > 0;
   const bool straddle = rows_windowed && lead + NQ - 1 >= 32;
   const bool head = (rows_windowed || lead > 0) && end > begin0 && (begin0 == 0 || (begin0 == 32 && straddle));
   const bool head2 = head && begin0 == 0 && straddle && end > 32;
@@ -353,7 +365,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int last_tok = pstart + seq - 1;
   const int end_col = min(end, seq - (NQ - 1 - query_token(hl)));   // first token this lane's column must not see
   // ... and, under a window, the first one it sees: its own length less the window, relative to the row start
-  const int lo_col = !head ? 0 : (NQ > 1 && p.row_window > 0)
+  const int lo_col = !head ? 0 : rows_windowed
                                      ? max(0, start + seq - (NQ - 1 - query_token(hl)) - p.row_window) - start : lead;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
@@ -458,34 +470,29 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     issue_tok(ring_lds + slot * C::STAGE, pstart + begin0, paged ? page_of(pstart + begin0) : 0, 0u, 0u, zero_vs);
   };
   // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
-  //      issues from its older wave first, so wave w gets through a supertile in about 7/9 of the time
-  //      wave w+4 needs.  The chunk's supertiles are therefore dealt round-robin to the four SIMDs, and
-  //      of every 16 that a SIMD gets, its older wave takes 9 and the younger 7, in a fixed pattern.
+  //      issues from its older wave first, so wave w gets through a supertile in less time than wave w+4
+  //      (about 7/9 of it in the heavier instances, 10/11 in the leanest).  The chunk's supertiles are
+  //      therefore dealt round-robin to the four SIMDs, and of every PERIOD that a SIMD gets, its older wave
+  //      takes PERIOD/2 + 1 and the younger PERIOD/2 - 1, in a fixed pattern.
   //      The split is static: the summation order, and with it every output bit, is the same on every
   //      launch.  The ragged last supertile, if any, goes to the wave whose turn it would be and takes
   //      the clamped path.
   static_assert(NW == 8, "the work split assumes two waves per SIMD");
   const int simd = wave & 3, young = wave >> 2;
+  constexpr int PERIOD = C::PER, OLD = PERIOD / 2 + 1, YNG = PERIOD / 2 - 1;   // of every PER supertiles of a SIMD: older wave, younger wave
   const int sub = wave % W;                       // (several rows per block: the W waves of a row take its supertiles in turn)
   auto sidx_of = [&](int i) {                     // i-th supertile of this wave -> supertile of the chunk
     if (!whole) return W * i + sub;
-    const int blk = young ? i / 7 : i / 9, j = i - blk * (young ? 7 : 9);
-    const int k = 16 * blk + (young ? 2 * j + 1 : (j < 8 ? 2 * j : 15));
+    const int blk = young ? i / YNG : i / OLD, j = i - blk * (young ? YNG : OLD);
+    const int k = PERIOD * blk + (young ? 2 * j + 1 : (j < PERIOD / 2 ? 2 * j : PERIOD - 1));
     return 4 * k + simd;
   };
   auto count_of = [&](int n) {                    // how many of the chunk's first n supertiles are this wave's
     if (!whole) return n > sub ? (n - sub + W - 1) / W : 0;
-    const int K = n > simd ? (n - simd + 3) >> 2 : 0, r = K & 15;
-    return young ? 7 * (K >> 4) + (r >> 1) : 9 * (K >> 4) + ((r + 1) >> 1);
+    const int K = n > simd ? (n - simd + 3) >> 2 : 0, r = K % PERIOD;
+    return young ? YNG * (K / PERIOD) + (r >> 1) : OLD * (K / PERIOD) + ((r + 1) >> 1);
   };
   const int n_mine = count_of(n_full);
-  bool tail_mine[4];                              // [2], [3]: the masked FIRST supertile(s) (see `head`), the one just
-                                                  // before `begin` and the one before that
-#pragma unroll
-  for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
-  tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
-  tail_mine[3] = head2 && (whole ? wave == 0 : sub == 0);
-
   // ---- prologue: the query rows of this KV head's group come in by direct load as well (so that every
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
   //      Where the query block has to borrow the last ring slot, that slot is filled once the query
@@ -511,10 +518,17 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       if (s < n_mine) issue(s, sidx_of(s));
       else issue_phantom(s);
     }
-    wait_loads<NPRE * LPS>();
-  } else {
-    wait_loads<0>();
   }
+  // (the first loads are on their way: whatever they do not need is worked out behind them)
+  __builtin_amdgcn_sched_barrier(0);
+  bool tail_mine[4];                              // [2], [3]: the masked FIRST supertile(s) (see `head`), the one just
+                                                  // before `begin` and the one before that
+#pragma unroll
+  for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
+  tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
+  tail_mine[3] = head2 && (whole ? wave == 0 : sub == 0);
+  if (n_mine > 0) wait_loads<NPRE * LPS>();
+  else wait_loads<0>();
 
   // ---- query operands (the query pre-scaling of Alg. 1 is folded into the exp2 argument instead of the query)
   const _Float16* qh = reinterpret_cast<const _Float16*>(q_area) + hl * D;
@@ -558,7 +572,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   // supertile NS, the first one issued inside the loop, and how to step from one supertile to the next:
   // position j in the wave's pattern of 9 (or 7) out of 16
-  int nx_j = young ? NS % 7 : NS % 9;
+  int nx_j = young ? NS % YNG : NS % OLD;
   int nx_tok = tok_of(sidx_of(NS));
   // The page of the next supertile is looked up one supertile ahead of its use, by a scalar load the
   // compiler does not wait for: the wait is the lgkmcnt(0) that precedes every issue in the loop (the
@@ -575,7 +589,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
   float l_run = 0.0f;                             // this lane's share of sum(exp)
   float4v zacc[NA];                               // sum_t w z - 15 sum_t1 w (w = p s_v), rows (head, replica), col = group
-  float4v oacc[NCS][8][NA];                       // sum_t w c - 15 sum_t1 w, rows (head, replica), col = packed word
+  float4v oacc[NCS][8][NA];                       // rows (head, replica), col = packed word; [2j]: sum_t w c - 15 sum_t1 w for
+                                                  // dim 2j of the word, [2j+1]: the same for c(2j) + 16 c(2j+1), less 255 sum_t1 w
 #pragma unroll
   for (int a = 0; a < NA; ++a) zacc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
@@ -592,11 +607,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // groups (SWAP), words w and w+2 of groups 2(kq/2) and 2(kq/2)+1 of token row c instead
   const uint32_t k_rd = C::SWAP ? (32 * (kq >> 1) + c) * 16 + 4 * (kq & 1) : lane * 16;
   const uint32_t v_rd = kq * TB + c * 4 * NCS;                      // packed word(s) c of token kq (+4i)
-  // scales of this lane's groups / zero-point of group c%NG, tokens kq (+4i): eight consecutive dwords
-  // in the permuted layout, else one halfword per token at the array's own stride
+  // scales of this lane's groups / zero-point of the group this lane's P V column (packed word c) lies in,
+  // tokens kq (+4i): eight consecutive dwords in the permuted layout, else one halfword per token at the
+  // array's own stride
+  const int gz = (c * NCS) >> 2;
   const uint32_t sz_rd = C::PERM ? (kq * GR + rep) * 32 : (kq * NG + rep * NA) * 2;
-  const uint32_t zb_rd = C::PERM ? (kq * GR + ((c % NG) >> 1)) * 32 : (kq * NG + (c % NG)) * 2;
-  const uint32_t zb_sel = ((c % NG) & 1) ? 0x07060302u : 0x05040100u;   // which half of a zero-point dword
+  const uint32_t zb_rd = C::PERM ? (kq * GR + (gz >> 1)) * 32 : (kq * NG + gz) * 2;
+  const uint32_t zb_sel = (gz & 1) ? 0x07060302u : 0x05040100u;   // which half of a zero-point dword
 
   // Everything a supertile needs from LDS is fetched into registers well before it is used: the K part
   // while the previous supertile is still in its P V phase, the V part at the start of the K phase.
@@ -761,35 +778,35 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     for (int a = 0; a < NA; ++a) zacc[a] = mfma16(pa[a], pos15_odd, zacc[a]);
   };
 
-  // -- V codes: 8 tokens x 8 nibbles per lane -> 8 dims x 8 tokens (two byte-permute stages),
-  //    consumed two dims at a time so that few unpacked operands are live
+  // -- V codes: each lane holds the same packed word (8 dims) of 8 tokens and needs, per dim, the 8 tokens in
+  //    the k-slots of a B operand.  One byte-permute per (token pair, byte of the word) puts the pair's bytes
+  //    into the low byte of the two halves of a register: as fp16 subnormals that is n_even + 16 n_odd of the
+  //    byte's two nibbles, and one AND leaves n_even alone.  P V is linear in V, so the MIXED operand goes
+  //    through the matrix core as it is (its accumulator holds  sum w (n_even + 16 n_odd) ) and the odd dim is
+  //    recovered at the very end as (mixed - even) / 16: two vector instructions per pair of B registers instead
+  //    of the four that separating every nibble takes.  (The mixed sum is 17 times larger and is divided by 16
+  //    again: the odd dims carry about 1.5 times the accumulation noise of the even ones, a small part of the
+  //    error budget.)  The complement of the second tile (15 - n in every nibble, i.e. 255 - byte) keeps both
+  //    accumulators balanced around zero as before:  even: -15 sum_t1 w,  mixed: -255 sum_t1 w,  so that
+  //    (mixed - even) / 16 carries the same -15 sum_t1 w that the zero-point sum cancels.
   auto pv = [&](const VRegs& r, const half8v (&pa)[NA]) {
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
-      uint32_t x[8], y[8];
+      uint32_t v1[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t v1 = ~r.v[cs][i + 4];      // second tile: 15 - code in every nibble
-        x[i] = __builtin_amdgcn_perm(v1, r.v[cs][i], 0x05040100u);
-        x[i + 4] = __builtin_amdgcn_perm(v1, r.v[cs][i], 0x07060302u);
-      }
+      for (int i = 0; i < 4; ++i) v1[i] = ~r.v[cs][i + 4];   // second tile: 15 - code in every nibble
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if ((i & 2) == 0) {
-          y[i] = __builtin_amdgcn_perm(x[i + 2], x[i], 0x06020400u);
-          y[i + 2] = __builtin_amdgcn_perm(x[i + 2], x[i], 0x07030501u);
-        }
-      }
-      // y[2I+a], nibble 2M+cc = token slot (2M+a), dim (2I+cc) of the packed word
+      for (int j = 0; j < 4; ++j) {               // byte j of the word: dims 2j and 2j + 1
+        const uint32_t sel = 0x0C000C00u | ((4u + j) << 16) | (uint32_t)j;   // [tile 0 byte j, 0, tile 1 byte j, 0]
+        uint32_t mix[4];
 #pragma unroll
-      for (int I = 0; I < 4; ++I) {
-        const uint32_t r0 = y[2 * I], r1 = y[2 * I + 1], s0 = r0 >> 8, s1 = r1 >> 8;
-        const half8v v_even = as_half8(r0 & kMaskLo, r1 & kMaskLo, s0 & kMaskLo, s1 & kMaskLo);
-        const half8v v_odd = as_half8(r0 & kMaskHi, r1 & kMaskHi, s0 & kMaskHi, s1 & kMaskHi);
+        for (int i = 0; i < 4; ++i) mix[i] = __builtin_amdgcn_perm(v1[i], r.v[cs][i], sel);
+        const half8v v_mixed = as_half8(mix[0], mix[1], mix[2], mix[3]);
+        const half8v v_even = as_half8(mix[0] & kMaskLo, mix[1] & kMaskLo, mix[2] & kMaskLo, mix[3] & kMaskLo);
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
-          oacc[cs][2 * I][a] = mfma16(pa[a], v_even, oacc[cs][2 * I][a]);
-          oacc[cs][2 * I + 1][a] = mfma16(pa[a], v_odd, oacc[cs][2 * I + 1][a]);
+          oacc[cs][2 * j][a] = mfma16(pa[a], v_even, oacc[cs][2 * j][a]);
+          oacc[cs][2 * j + 1][a] = mfma16(pa[a], v_mixed, oacc[cs][2 * j + 1][a]);
         }
       }
     }
@@ -828,9 +845,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nx_page) :: "memory");   // every LDS read of this slot has returned
     if (i + NS < n_mine) {
       issue_tok(ring_lds + slot * C::STAGE, nx_tok, nx_page, koff, lane16, szoff);
-      // next supertile of the pattern: the older wave holds k = 0,2,..,14,15 of every 16, the younger 1,3,..,13
-      const int step = young ? (nx_j < 6 ? 2 : 4) : (nx_j < 7 ? 2 : 1);
-      nx_j = (nx_j == (young ? 6 : 8)) ? 0 : nx_j + 1;
+      // next supertile of the pattern: of every PERIOD the older wave holds k = 0, 2, .., PERIOD-2 and PERIOD-1,
+      // the younger k = 1, 3, .., PERIOD-3
+      const int step = young ? (nx_j < YNG - 1 ? 2 : 4) : (nx_j < PERIOD / 2 - 1 ? 2 : 1);
+      nx_j = (nx_j == (young ? YNG - 1 : OLD - 1)) ? 0 : nx_j + 1;
       nx_tok += whole ? step * (4 * 32) : W * 32;
       if (paged) nx_page = page_ahead(nx_tok);
     } else {
@@ -841,7 +859,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   wait_loads<0>();                                           // phantom stages included: the rings are quiet
 #pragma unroll 1
-  for (int u = 0; u < 4; ++u) {                              // the masked supertiles: the sequence's last one or two,
+  for (int u = 0; u < (PLAIN ? 1 : 4); ++u) {                // the masked supertiles: the sequence's last one or two,
     if (!tail_mine[u]) continue;                             // and under a window its first (or first two)
     const int sidx = u < 2 ? n_full + u : 1 - u;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -856,37 +874,38 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     pv(vr, pa);
   }
 
-  // ---- wave result -> LDS.  Raw accumulators go out (the 2^24 / 2^20 of the two nibble positions is
-  //      applied once per output element below); of a lane's NA accumulators per row only the one
-  //      whose group the lane's packed word belongs to is meaningful, so it is selected first and
-  //      the eight dims of the word leave as two 16-byte writes.
-  float* const lds_o = reinterpret_cast<float*>(smem + C::OFF_MERGE);  // [NW][GP][D]
-  float* const lds_zc = lds_o + NW * GP * D;                           // [NW][GP][NG]
-  float* const lds_m = lds_zc + NW * GP * NG;                          // [NW][GP]
-  float* const lds_l = lds_m + NW * GP;                                // [NW][GP]
+  // ---- wave result -> LDS.  Of a lane's NA accumulators per row only the one whose group the lane's packed
+  //      word belongs to is meaningful (and, the zero-point operand being laid out to match, the same one of its
+  //      NA zero-point sums): it is selected, brought to common units (the 2^24 / 2^20 of the two nibble
+  //      positions), the zero-point sum is taken off, and the eight dims of the word leave as two 16-byte writes.
+  float* const lds_o = reinterpret_cast<float*>(smem + C::OFF_MERGE);  // [NW][GP][D]   sum_t p_t v^_t
+  float* const lds_m = lds_o + NW * GP * D;                            // [GP][NW]
+  float* const lds_l = lds_m + NW * GP;                                // [GP][NW]
   if constexpr (C::ALIAS) __syncthreads();                   // everybody is done reading the rings
   const bool active = n_mine > 0 || tail_mine[0] || tail_mine[1] || tail_mine[2] || tail_mine[3];
   const float l_tot = blocks_sum(l_run);
   if (kq == 0 && rep == 0) {
     // (a row whose tokens were all masked still has the initial reference: it counts as empty)
-    lds_m[wave * GP + hl] = (active && m_run > kNegBig) ? m_run * kappa : kNegBig;
-    lds_l[wave * GP + hl] = active ? l_tot : 0.0f;
+    lds_m[hl * NW + wave] = (active && m_run > kNegBig) ? m_run * kappa : kNegBig;
+    lds_l[hl * NW + wave] = active ? l_tot : 0.0f;
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = 4 * kq + i, h = r % GP, rp = r / GP;       // accumulator row -> (head, replica)
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
-      if (c == rp * NA + a) lds_zc[(wave * GP + h) * NG + c] = zacc[a][i];
-#pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
       const int word = c * NCS + cs;              // packed word (8 dims) this lane's column stands for
       const int a_mine = (word >> 2) - rp * NA;
+      const bool second = NA == 2 && a_mine == 1;
+      const float zc = second ? zacc[NA - 1][i] : zacc[0][i];
       float4v lo, hi;
+      float acc[8];
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        lo[m] = (NA == 2 && a_mine == 1) ? oacc[cs][m][NA - 1][i] : oacc[cs][m][0][i];
-        hi[m] = (NA == 2 && a_mine == 1) ? oacc[cs][m + 4][NA - 1][i] : oacc[cs][m + 4][0][i];
+      for (int m = 0; m < 8; ++m) acc[m] = second ? oacc[cs][m][NA - 1][i] : oacc[cs][m][0][i];
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {               // dim m: the even sum, or (mixed - even) / 16, in units of 2^-24
+        lo[m] = fmaf((m & 1) ? acc[m] - acc[m - (m & 1)] : acc[m], (m & 1) ? 0x1p20f : 0x1p24f, -zc);
+        hi[m] = fmaf((m & 1) ? acc[m + 4] - acc[m + 4 - (m & 1)] : acc[m + 4], (m & 1) ? 0x1p20f : 0x1p24f, -zc);
       }
       if (a_mine >= 0 && a_mine < NA) {
         float4v* dst = reinterpret_cast<float4v*>(lds_o + (wave * GP + h) * D + word * 8);
@@ -898,56 +917,57 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   __syncthreads();
 
   // ---- merge the waves, write one partial per query head (Sec. 3.2); where the sequence is a single
-  //      chunk and the kernel is to produce the output, that partial, normalised, IS the output
+  //      chunk and the kernel is to produce the output, that partial, normalised, IS the output.
+  //      A thread takes two neighbouring dims of one head: the waves' maxima and sums of that head arrive as
+  //      16-byte reads (the same for the whole wave at d = 128, where wave h merges head h).
   const bool direct = p.merge_slot >= 0 && p.n_splits == 1;
-  if (!whole) {                                   // several units per block: the W waves of one merge among themselves
-    if (row_valid) {                              // (a single-chunk row: the output; a slot of the chunk list: its partial)
-      const int w0 = wave - sub;
-      for (int idx = sub * 64 + lane; idx < G * D; idx += W * 64) {
-        const int h = idx / D, j = idx % D;
-        const float unit = (j & 1) ? 0x1p20f : 0x1p24f;
-        float mg = lds_m[w0 * GP + h];
-        for (int w = 1; w < W; ++w) mg = fmaxf(mg, lds_m[(w0 + w) * GP + h]);
-        float num = 0.0f, den = 0.0f;
-        for (int w = w0; w < w0 + W; ++w) {
-          const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
-          num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
-          den = fmaf(lds_l[w * GP + h], e, den);
-        }
-        if (direct) {
-          p.out[query_row(h) * D + j] = (half_t)(num / den);
-        } else {
-          const int64_t ph = query_row(h) * part_stride + split;
-          st_dev(p.part_o + ph * D + j, num);
-          if (j == 0) { st_dev(p.part_ml + ph * 2, mg); st_dev(p.part_ml + ph * 2 + 1, den); }
-        }
+  // `first` .. `first + count - 1`: the waves to merge; `stride`, `lane0`: this thread's place among the threads that do it
+  auto merge_waves = [&](int first, int count, int lane0, int stride) {
+    for (int idx = lane0; idx < G * (D / 2); idx += stride) {
+      const int h = idx / (D / 2), j = (idx % (D / 2)) * 2;
+      float2 ow[NW];                              // (asked for first: their latency hides behind the weights' arithmetic)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) ow[w] = *reinterpret_cast<const float2*>(lds_o + (w * GP + h) * D + j);
+      float mw[NW], lw[NW];
+#pragma unroll
+      for (int w4 = 0; w4 < NW; w4 += 4) {
+        const float4v a = *reinterpret_cast<const float4v*>(lds_m + h * NW + w4);
+        const float4v bb = *reinterpret_cast<const float4v*>(lds_l + h * NW + w4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { mw[w4 + u] = a[u]; lw[w4 + u] = bb[u]; }
+      }
+      float mg = kNegBig;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) mg = (w >= first && w < first + count) ? fmaxf(mg, mw[w]) : mg;
+      float n0 = 0.0f, n1 = 0.0f, den = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        if (w < first || w >= first + count) continue;       // (wave-uniform)
+        const float e = __builtin_amdgcn_exp2f(mw[w] - mg);
+        n0 = fmaf(ow[w].x, e, n0);
+        n1 = fmaf(ow[w].y, e, n1);
+        den = fmaf(lw[w], e, den);
+      }
+      if (direct) {
+        half2v r;
+        r[0] = (_Float16)(n0 / den);
+        r[1] = (_Float16)(n1 / den);
+        *reinterpret_cast<half2v*>(p.out + query_row(h) * D + j) = r;
+      } else {
+        // device-scope stores: they go through to where every compute die sees them (the L2 caches of
+        // different dies are not coherent with each other), so no cache-wide write-back is needed later
+        const int64_t ph = query_row(h) * part_stride + split;
+        st_dev2(p.part_o + ph * D + j, n0, n1);
+        if (j == 0) st_dev2(p.part_ml + ph * 2, mg, den);
       }
     }
+  };
+  if (!whole) {                                   // several units per block: the W waves of one merge among themselves
+    // (a single-chunk row: the output; a slot of the chunk list: its partial)
+    if (row_valid) merge_waves(wave - sub, W, sub * 64 + lane, W * 64);
     return;
   }
-  for (int idx = threadIdx.x; idx < G * D; idx += NW * 64) {
-    const int h = idx / D, j = idx % D;
-    const float unit = (j & 1) ? 0x1p20f : 0x1p24f;          // odd dims were read from the high nibble position
-    float mg = lds_m[h];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) mg = fmaxf(mg, lds_m[w * GP + h]);
-    float num = 0.0f, den = 0.0f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      const float e = __builtin_amdgcn_exp2f(lds_m[w * GP + h] - mg);
-      num = fmaf(fmaf(lds_o[(w * GP + h) * D + j], unit, -lds_zc[(w * GP + h) * NG + (j >> 5)]), e, num);
-      den = fmaf(lds_l[w * GP + h], e, den);
-    }
-    if (direct) {
-      p.out[query_row(h) * D + j] = (half_t)(num / den);
-      continue;
-    }
-    const int64_t ph = query_row(h) * part_stride + split;
-    // device-scope stores: they go through to where every compute die sees them (the L2 caches of
-    // different dies are not coherent with each other), so no cache-wide write-back is needed later
-    st_dev(p.part_o + ph * D + j, num);
-    if (j == 0) { st_dev(p.part_ml + ph * 2, mg); st_dev(p.part_ml + ph * 2 + 1, den); }
-  }
+  merge_waves(0, NW, threadIdx.x, NW * 64);
   if (p.merge_slot < 0 || direct) return;
 
   // ---- chunk merge (Eq. 6) by whichever block of this (b, kv head) finishes last.  A block publishes
@@ -959,7 +979,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   wait_loads<0>();                                // vmcnt counts stores too: this wave's partial has landed
   __syncthreads();                                // every wave's has; and nobody reads the block-merge area any more
   if (threadIdx.x == 0) {
-    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * (p.n_kv_heads * p.kv_share) + kvv];
+    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * (p.n_kv_heads * kv_share) + kvv];
     *is_last = atomicInc(ctr, (unsigned int)(n - 1)) == (unsigned int)(n - 1);   // wraps to 0 on the last arrival
   }
   __syncthreads();
@@ -1039,7 +1059,7 @@ int kv_share_of(int head_dim, int gqa) {          // smallest split of the group
   return 0;
 }
 
-template <int D, int GP, bool NT>
+template <int D, int GP, bool NT, bool PLAIN>
 hipError_t launch_as(const DecodeParams& p, dim3 grid, hipStream_t s) {
   static_assert((64 + (2 * GP * kMaxSplits + GP) ) * 4 <= Cfg<D, GP, 8>::SMEM, "the chunk merge reuses the block's LDS");
   // one block of 8 waves per compute unit: 8 rings of 2 x 5 KB (d=128) or 2 x 10 KB (d=256, all 160 KB of LDS)
@@ -1048,18 +1068,21 @@ hipError_t launch_as(const DecodeParams& p, dim3 grid, hipStream_t s) {
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
   static bool configured = false;                 // dynamic LDS above 64 KB has to be opted into once
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW, NT>), grid, dim3(NW * 64), smem, s, p);
+  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>), grid, dim3(NW * 64), smem, s, p);
   return hipGetLastError();
 }
 // the stream is read once (non-temporal loads) unless several blocks share a KV head
 template <int D, int GP>
 hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
-  return p.kv_share == 1 ? launch_as<D, GP, true>(p, grid, s) : launch_as<D, GP, false>(p, grid, s);
+  const bool plain = p.kv_share == 1 && p.n_queries == 1 && p.waves_per_row == 8 && p.var_chunks == 0 &&
+                     p.seq_lens == nullptr && p.block_table == nullptr;
+  if (plain) return launch_as<D, GP, true, true>(p, grid, s);
+  return p.kv_share == 1 ? launch_as<D, GP, true, false>(p, grid, s) : launch_as<D, GP, false, false>(p, grid, s);
 }
 
 }  // namespace

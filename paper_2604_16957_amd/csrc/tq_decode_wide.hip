@@ -2,7 +2,7 @@
 // configuration table, Appendix A: 32 query heads on one KV head), phase 1 of Sec. 3.2.
 //
 // At d = 512 a KV head's query group is a tile of 16 or 32 rows, every fetched byte is used by all of them,
-// and the work is arithmetic, not traffic: both contractions of Alg. 1 (lines 5 and 9) run on
+// and the work is arithmetic, not traffic: both contractions of Alg. 1 (the score and the update of the output accumulator) run on
 // v_mfma_f32_16x16x32_f16 for all rows of the tile at once, and the vector ALU prepares each operand once
 // per block, whatever the number of rows.
 //
@@ -102,7 +102,7 @@ constexpr int kLoadsPerStage = 5;                 // per lane: 2 K, 2 V, 1 scale
 // direct global -> LDS load of 16 B per lane: lane l's bytes land at lds_base + 16 l (M0 carries the base)
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() {    // until at most N vector-memory loads of this wave are outstanding
