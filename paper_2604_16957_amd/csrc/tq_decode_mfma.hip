@@ -201,14 +201,18 @@ __device__ __forceinline__ float row_ror_add(float x) {      // x + (x rotated b
 // ---- direct global -> LDS loads.  Written as asm so that the compiler does not serialise them
 // against later LDS reads: each wave tracks its own ring with explicit vmcnt waits instead.
 // Lane l's bytes land at lds_base + l * (16 | 4).  M0 carries the LDS base of the instruction.
+// (M0 cannot be named as a clobber: the compiler reserves it and rejects that.  It keeps no value live in M0
+// across other instructions either: each of its own uses, such as an indexed register move, writes M0 right
+// before.  The kernels in this file and in tq_decode_wide.hip contain no such use at all: in their assembly M0
+// appears inside these blocks only.)
 // NT = the non-temporal cache policy: the packed stream is read once, and telling the caches so is worth
 // 6-9 % of the kernel's time (plain loads of the same 168 MB: 28 us per launch, non-temporal: 25 us).
 // Where several blocks stream the same KV head the later readers live on what the first left in the
 // caches, and the loads stay plain.
 #define TQ_LDS_LOAD(NT_, TEXT_PLAIN, TEXT_NT, ...)                     \
   do {                                                                 \
-    if constexpr (NT_) asm volatile(TEXT_NT :: __VA_ARGS__ : "memory", "m0"); \
-    else asm volatile(TEXT_PLAIN :: __VA_ARGS__ : "memory", "m0");           \
+    if constexpr (NT_) asm volatile(TEXT_NT :: __VA_ARGS__ : "memory"); \
+    else asm volatile(TEXT_PLAIN :: __VA_ARGS__ : "memory");           \
   } while (0)
 template <bool NT>
 __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
@@ -218,11 +222,11 @@ __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t 
 }
 __device__ __forceinline__ void dma16_lane(const void* addr, uint32_t lds_base) {   // per-lane 64-bit address
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(addr), "s"(lds_base) : "memory", "m0");
+               :: "v"(addr), "s"(lds_base) : "memory");
 }
 __device__ __forceinline__ void dma4_lane(const void* addr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               :: "v"(addr), "s"(lds_base) : "memory", "m0");
+               :: "v"(addr), "s"(lds_base) : "memory");
 }
 // Several loads of one array behind a single M0: the instruction's immediate offset moves the global
 // and the LDS address alike, so pieces that are equally far apart on both sides share the base.

@@ -102,7 +102,7 @@ constexpr int kLoadsPerStage = 5;                 // per lane: 2 K, 2 V, 1 scale
 // direct global -> LDS load of 16 B per lane: lane l's bytes land at lds_base + 16 l (M0 carries the base)
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+               :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() {    // until at most N vector-memory loads of this wave are outstanding
