@@ -28,6 +28,40 @@ if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+PROBE_SRC = ROOT / "bench_probe.hip"
+PROBE_LIB = ROOT / "libbench_probe.so"
+
+
+def build_probe():
+    """Compiles the benchmark's read-bandwidth probe (bench_probe.hip) for gfx950; returns the library's path."""
+    import subprocess
+    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+           str(PROBE_SRC), "-o", str(PROBE_LIB) + f".tmp{os.getpid()}"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on bench_probe.hip:\n" + res.stderr)
+    os.replace(cmd[-1], PROBE_LIB)
+    return PROBE_LIB
+
+
+def load_probe():
+    """bench_probe_read_stream(src, bytes, sink, stream) of the built probe library (built here if it is missing)."""
+    import ctypes
+    if not PROBE_LIB.exists():
+        build_probe()
+    f = ctypes.CDLL(str(PROBE_LIB)).bench_probe_read_stream
+    f.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    f.restype = ctypes.c_int
+    return f
+
+
+def dist(xs):
+    """median / p10 / p90 of a list of batch means (microseconds)."""
+    xs = sorted(xs)
+    pick = lambda f: xs[min(len(xs) - 1, max(0, round(f * (len(xs) - 1))))]
+    return {"median": round(statistics.median(xs), 3), "p10": round(pick(0.1), 3), "p90": round(pick(0.9), 3),
+            "batches": len(xs)}
 
 
 def parse():
@@ -57,6 +91,13 @@ def parse():
     ap.add_argument("--no-baseline", action="store_true", help="skip the unfused GPU comparator")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled oracle check")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the read-stream probe")
+    ap.add_argument("--batches", type=int, default=7,
+                    help="further batches of --steps steps (and of --steps kernel launches) timed after the first, for the "
+                         "median / p10 / p90 the line reports next to `value`")
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="untimed run of the step loop before the warm-up steps: the GPU's clocks take some tens of "
+                         "milliseconds of sustained load to settle (a cold start reads 36 us per launch, falling to "
+                         "29.5 us within about 40 ms)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of packed_bytes (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -78,7 +119,7 @@ def sweep(args):
     base = wl.WORKLOADS["llama128k"]
     S, Hq, Hkv, d = base.seq_len, base.n_q_heads, base.n_kv_heads, base.head_dim
     steps = args.steps if args.steps != 400 else 5
-    warmup = args.warmup if args.warmup != 40 else 1
+    warmup = args.warmup if args.warmup != 40 else 6      # (about 60 ms: the clocks settle)
     samples = {(0, 0), (L - 1, B - 1)}           # (layer, batch element) pairs checked against the oracle
     kept = {}
     caches, qs, news = [], [], []
@@ -302,20 +343,40 @@ def main():
             append(j)
             decode(j)
 
-    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def settle(fn):
+        """Runs fn(i) untimed for --settle-ms of GPU time: measurements start from settled clocks."""
+        i, spent = 0, 0.0
+        while spent < args.settle_ms:
+            e0.record()
+            for _ in range(200):
+                fn(i)
+                i += 1
+            e1.record()
+            torch.cuda.synchronize()
+            spent += e0.elapsed_time(e1)
+
+    def timed(fn, n):
+        """microseconds per call of n consecutive fn(i) between two events on the launch stream"""
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    # ---- timed region: (settling run,) W warm-up steps, then exactly K steps between synchronisations: `value`.
+    #      Further batches of K steps follow for the spread.
+    settle(step)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    e0.record()
-    for i in range(args.steps):
-        step(i)
-    e1.record()
-    torch.cuda.synchronize()
+    us_per_step = timed(step, args.steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-    us_per_step = ms_per_step * 1e3
+    ms_per_step = us_per_step * 1e-3
+    step_batches = [us_per_step] + [timed(step, args.steps) for _ in range(args.batches)]
 
     # ---- dominant kernel: stream events around each of its launches.  Where the decode call is ONE
     #      launch (partials and chunk merge in the same kernel) that launch is timed; otherwise phase 1,
@@ -348,12 +409,9 @@ def main():
     # figure the roofline uses; it agrees with rocprofv3's kernel trace of the step loop, whereas an
     # event pair around every single launch (kept as `kernel_us_bracketed_*`) adds the latency of the
     # two event packets, about 2 us, to each measurement.
-    e0.record()
-    for i in range(args.steps):
-        dominant(i % args.buffers)
-    e1.record()
-    torch.cuda.synchronize()
-    kernel_us = e0.elapsed_time(e1) * 1e3 / args.steps
+    settle(lambda i: dominant(i % args.buffers))
+    kernel_batches = [timed(lambda i: dominant(i % args.buffers), args.steps) for _ in range(1 + args.batches)]
+    kernel_us = statistics.fmean(kernel_batches)     # average launch duration over all timed launches
     achieved = packed_bytes / (kernel_us * 1e-6) / 1e9
 
     # ---- what the machine delivers for a read-once stream of this size: the library's read probe (non-temporal
@@ -364,17 +422,17 @@ def main():
     if probe_bytes > 0 and not args.no_ceiling:
         bufs = [torch.empty(probe_bytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(args.buffers)]
         sink = torch.zeros(1, dtype=torch.int32, device=dev)
-        for i in range(args.warmup):
-            tq.tq_probe_read_stream(bufs[i % args.buffers], sink)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            tq.tq_probe_read_stream(bufs[i % args.buffers], sink)
-        e1.record()
-        torch.cuda.synchronize()
-        probe_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        probe = load_probe()
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def read(i):
+            if probe(bufs[i % args.buffers].data_ptr(), probe_bytes, sink.data_ptr(), stream) != 0:
+                sys.exit("bench.py: the read probe rejected its arguments or failed to launch")
+
+        settle(read)
+        probe_us = statistics.fmean(timed(read, args.steps) for _ in range(1 + args.batches))
         probe_gbps = probe_bytes / (probe_us * 1e-6) / 1e9
-        ceiling = {"kernel": "tq_probe_read_stream (read-only, non-temporal loads)", "bytes_per_launch": probe_bytes,
+        ceiling = {"kernel": "bench_probe.hip: read-only stream, non-temporal loads, 256 blocks", "bytes_per_launch": probe_bytes,
                    "us_per_launch": round(probe_us, 3), "GBps": round(probe_gbps, 1),
                    "frac_of_peak": round(probe_gbps / HBM_PEAK_GBPS, 4),
                    "decode_kernel_vs_this": round(achieved / probe_gbps, 4)}
@@ -392,28 +450,31 @@ def main():
     baseline = None
     if not args.no_baseline and lens is None and NQ == 1:
         dense = torch.empty(tq.tq_dense_scratch_bytes(B, Hkv, S, d), dtype=torch.uint8, device=dev)
-        nb = max(3, min(20, args.steps // 10))
-        for i in range(2):
-            tq.tq_dequant_then_attend(caches[i % args.buffers], qs[i % args.buffers], S, w.attn_scale, out=out,
-                                      workspace=ws, dense_scratch=dense)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(nb):
+        nb = max(5, min(40, args.steps // 5))
+
+        def unfused(i):
             j = i % args.buffers
             tq.tq_dequant_then_attend(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, dense_scratch=dense)
-        e1.record()
-        torch.cuda.synchronize()
-        base_us = e0.elapsed_time(e1) * 1e3 / nb
-        e0.record()
-        for i in range(nb):                       # the fused call, timed the same way on the same inputs
+
+        def fused_call(i):                        # the fused call, timed the same way on the same inputs
             j = i % args.buffers
             tq.tq_sdpa_int4_decode(caches[j], qs[j], S, w.attn_scale, out=out, workspace=ws, **kw)
-        e1.record()
+
+        for i in range(3):
+            unfused(i)
         torch.cuda.synchronize()
-        fused_us = e0.elapsed_time(e1) * 1e3 / nb
+        base_us = statistics.median(timed(unfused, nb) for _ in range(3))
+        settle(fused_call)
+        fused_us = statistics.median(timed(fused_call, args.steps) for _ in range(3))
+        # what the unfused path moves: phase 1 reads the packed cache and writes dense fp16 K^ and V^, phase 2 reads them
+        dense_bytes = tq.tq_dense_scratch_bytes(B, Hkv, S, d)
+        moved = packed_bytes + 2 * dense_bytes
         baseline = {"name": "tq_dequant_then_attend (dense fp16)", "us_per_call": round(base_us, 2),
                     "fused_decode_us_per_call": round(fused_us, 2), "fused_speedup": round(base_us / fused_us, 2),
-                    "calls": nb}
+                    "calls": nb, "bytes_moved_per_call": moved,
+                    "GBps_on_bytes_moved": round(moved / (base_us * 1e-6) / 1e9, 1),
+                    "frac_of_hbm_peak_on_bytes_moved": round(moved / (base_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "byte_ratio_unfused_over_fused": round(moved / packed_bytes, 2)}
         del dense
 
     # ---- CPU oracle on the host cores (reported baseline, never the target) + sampled parity check
@@ -477,7 +538,7 @@ def main():
         "metric": "us_per_decode_step (int4 SDPA, one layer, append + fused attention)",
         "value": round(us_per_step, 3), "unit": "us/decode-step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 6), "higher_is_better": False, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 6), "step_us": dist(step_batches), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "int4 codes + fp16 scale/zero in HBM; fp16 MFMA/VALU inputs, fp32 accumulate, fp16 out",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
@@ -495,6 +556,7 @@ def main():
         "pct_of_hbm_peak": round(100 * packed_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
         "packed_bytes_per_step": packed_bytes,
         "host_wall_ms_timed_region": round(wall_ms, 2),
+        "settle_ms_before_warmup": args.settle_ms,
         "roofline": {"bound": "hbm",
                      "kernel": ("decode_partial_mfma_kernel: fused int4 attention over the chunks + in-kernel chunk merge "
                                 "(the whole tq_sdpa_int4_decode call)" if fused else
@@ -503,7 +565,8 @@ def main():
                                 "the whole tq_sdpa_int4_decode_varlen call (partial kernel + merge kernel)"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "kernel_us_mean": round(kernel_us, 3),
+                     "traffic": None, "traffic_source": None, "kernel_us_mean": round(kernel_us, 3),
+                     "kernel_us": dist(kernel_batches),
                      "kernel_us_bracketed_mean": round(kernel_us_bracketed, 3),
                      "kernel_us_bracketed_median": round(statistics.median(k_us), 3),
                      "algorithmic_bytes_per_launch": packed_bytes,
@@ -526,8 +589,10 @@ def main():
     if prof.exists():
         try:
             t = json.loads(prof.read_text()).get(w.name)
-            if t:          # measured with rocprofv3 --pmc, see profiles/*_hbm_traffic.txt
+            if t:          # measured with rocprofv3 --pmc, see profiles/*_hbm_traffic.txt: NOT measured in this run
                 line["roofline"]["traffic"] = t["total_bytes"]
+                line["roofline"]["traffic_source"] = ("profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                                      "bench, kept with their commands in profiles/*_hbm_traffic.txt; not measured in this run")
                 line["roofline"]["traffic_detail"] = t
         except Exception:
             pass

@@ -244,13 +244,6 @@ int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len);
 int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t seq_len,
                            float attn_scale, const tq_decode_opts* opts);
 
-/* Measurement aid: reads `bytes` (a multiple of 16384) of device memory at `src` (16-byte aligned) once,
- * with the same non-temporal policy the decode kernel streams the cache with, 256 blocks each reading one
- * contiguous slice, and does nothing else (a 4-byte result is stored to `sink` only if the XOR of all words
- * equals a magic value).  Timed next to the decode kernel it gives the read bandwidth this machine delivers
- * for a stream of that size, the ceiling the roofline fraction can be read against.  NULL, ALIGN, SHAPE. */
-int tq_probe_read_stream(const void* src, size_t bytes, void* sink, void* stream);
-
 /* Static, NUL-terminated description of a status code. */
 const char* tq_status_string(int status);
 

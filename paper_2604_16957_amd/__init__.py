@@ -12,7 +12,6 @@ from .binding import (  # noqa: F401
     tq_dequant_then_attend,
     tq_kv_bytes,
     tq_plan_splits,
-    tq_probe_read_stream,
     tq_quantize_kv,
     tq_quantize_kv_paged,
     tq_quantize_kv_varlen,

@@ -79,8 +79,6 @@ def raw():
         L.tq_plan_splits.restype = I
         L.tq_decode_launches.argtypes = [CP, I, I, F, OP]
         L.tq_decode_launches.restype = I
-        L.tq_probe_read_stream.argtypes = [P, SZ, P, P]
-        L.tq_probe_read_stream.restype = ctypes.c_int
         L.tq_status_string.argtypes = [ctypes.c_int]
         L.tq_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -376,12 +374,6 @@ def tq_sdpa_int4_reduce(batch: int, n_q_heads: int, head_dim: int, n_splits: int
                                    workspace.numel() * workspace.element_size(), out.data_ptr(), _stream_ptr(stream))
     _check(rc, "tq_sdpa_int4_reduce")
     return out
-
-
-def tq_probe_read_stream(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
-    """Measurement aid: reads all of `src` (bytes a multiple of 16 MiB) once with non-temporal loads."""
-    rc = raw().tq_probe_read_stream(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_ptr(stream))
-    _check(rc, "tq_probe_read_stream")
 
 
 def tq_dequant_then_attend(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,

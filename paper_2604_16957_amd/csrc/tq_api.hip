@@ -372,13 +372,6 @@ int32_t tq_decode_launches(const tq_kv_cache* cache, int32_t n_q_heads, int32_t 
   return r.merge ? 1 : 2;
 }
 
-int tq_probe_read_stream(const void* src, size_t bytes, void* sink, void* stream) {
-  if (!src || !sink) return TQ_ERR_NULL;
-  if (!aligned(src, 16) || !aligned(sink, 4)) return TQ_ERR_ALIGN;
-  if (bytes == 0 || bytes % (256 * 8 * 512 * 16) != 0) return TQ_ERR_SHAPE;   // whole unrolled rounds of every block
-  return hip_rc(tq::launch_read_probe(src, bytes, sink, static_cast<hipStream_t>(stream)));
-}
-
 const char* tq_status_string(int status) {
   switch (status) {
     case TQ_OK: return "ok";

@@ -285,6 +285,5 @@ hipError_t launch_partial_wide(const DecodeParams& p, int batch, int head_dim, h
 hipError_t launch_reduce(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 // Whether the merge of that many outputs runs as one block per (output row, KV head).
 bool reduce_is_grouped(int head_dim, int64_t out_rows, int n_q_heads, int gqa);
-hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 }  // namespace tq

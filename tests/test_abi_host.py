@@ -254,13 +254,11 @@ def test_append_decode_with_lengths_rejects_bad_arguments_without_a_gpu():
     assert callp(wsb=wsb4 - 1) == E.TQ_ERR_WORKSPACE and callp(v=FAKE + 4) == E.TQ_ERR_ALIGN
 
 
-def test_read_probe_rejects_bad_arguments_without_a_gpu():
-    f = B.raw().tq_probe_read_stream
-    assert f(None, 1 << 24, FAKE, None) == B.TQ_ERR_NULL
-    assert f(FAKE, 1 << 24, None, None) == B.TQ_ERR_NULL
-    assert f(FAKE + 8, 1 << 24, FAKE, None) == B.TQ_ERR_ALIGN
-    assert f(FAKE, 0, FAKE, None) == B.TQ_ERR_SHAPE
-    assert f(FAKE, (1 << 24) + 16, FAKE, None) == B.TQ_ERR_SHAPE
+def test_measurement_probe_is_not_part_of_the_product_abi():
+    """The read-bandwidth probe the benchmark times belongs to the bench (bench_probe.hip), not to the library."""
+    lib = ctypes.CDLL(str(tq.library_path()))
+    assert not hasattr(lib, "tq_probe_read_stream") and not hasattr(lib, "bench_probe_read_stream")
+    assert "probe" not in (ROOT / "include" / "tq.h").read_text()
 
 
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch, tmp_path):
