@@ -115,9 +115,12 @@ int tq_quantize_kv_varlen(const tq_kv_cache* cache, const void* k_new, const voi
  * order of the fp32 sums of the merge).  For short sequences, where launch overhead outweighs the
  * stream (see tq_decode_launches), the matrix-core kernel does both in ONE launch: the block that
  * finishes a (batch, KV head) last merges its chunks in place (a sequence that is a single chunk
- * needs no merge: its block writes out).  That path keeps its arrival counters in device memory
- * owned by the library (16 sets, taken in turn, left zero by every launch): at most 16 decode calls
- * may be in flight on one device at the same time.
+ * needs no merge: its block writes out).  That path counts the blocks in with arrival counters in device
+ * memory owned by the library, one set per WORKSPACE address (kept for the life of the process, left zero by
+ * every launch).  Calls that may run at the same time must not share a workspace (they would overwrite each
+ * other's partials), so they never share counters either, whether issued eagerly or replayed from a captured
+ * graph.  There are 64 sets; a call whose workspace is the 65th distinct address the library sees takes the
+ * merge kernel (two launches) instead, with the same result up to the summation order of the merge.
  * Errors: NULL, SHAPE, EMPTY (seq_len < 1), CAPACITY (seq_len > capacity), WORKSPACE,
  * UNSUPPORTED, HIP. */
 int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,

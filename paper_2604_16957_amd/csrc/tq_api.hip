@@ -271,11 +271,18 @@ int run_partial(PartialRequest& rq) {
   rq.n_splits = plan.n_splits;
   hipStream_t s = static_cast<hipStream_t>(rq.stream);
   rq.merged = one_chunk_rows || (rq.out != nullptr && r.merge && !seq_lens && !append_in_merge);
+  int merge_slot = -1;
+  if (rq.merged) {
+    // several chunks: the arrival counters of this workspace (none left: the merge kernel does it); rows that are
+    // single chunks count nothing
+    merge_slot = plan.n_splits > 1 ? tq::mfma_merge_slot_of(rq.workspace) : 0;
+    if (merge_slot < 0) rq.merged = false;
+  }
   if (rq.merged && use_mfma && plan.n_splits == 1 && !rq.paged) {
     // more single-chunk rows than the chip holds blocks: pack 2, 4 or 8 of them into a block
     p.waves_per_row = waves_per_packed_row((int64_t)cache->batch * rows_per_batch, target);
   }
-  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, rq.merged, s));
+  if (use_mfma) return hip_rc(tq::launch_partial_mfma(p, cache->batch, cache->head_dim, merge_slot, s));
   if (r.wide) {
     p.kv_share = row_tiles;
     return hip_rc(tq::launch_partial_wide(p, cache->batch, cache->head_dim, s));

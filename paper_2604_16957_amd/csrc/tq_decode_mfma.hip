@@ -61,8 +61,9 @@
 // rows (token, head) of one KV head; rows beyond one tile go to further blocks on the same KV head
 // (kv_share of them).  Per-row limits (causal end, window start) only exist in the masked path that the
 // ragged last supertile takes anyway.
-#include <atomic>
+#include <mutex>
 #include <type_traits>
+#include <unordered_map>
 
 #include "tq_internal.h"
 
@@ -75,12 +76,16 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 constexpr float kNegBig = -1.0e30f;
+constexpr int kMaxDevices = 64;
 
-// Arrival counters of the in-kernel chunk merge: one per (b, kv head), kCounterSlots independent sets so
-// that decode calls in flight at the same time (other streams) do not share one.  Zero when the module
-// is loaded; the block that arrives last wraps its counter back to zero, so every launch leaves them
-// zero again.
-constexpr int kCounterSlots = 16;
+// Arrival counters of the in-kernel chunk merge: one per (b, kv head), in kCounterSlots independent sets.  A set
+// belongs to ONE WORKSPACE (the host keeps the table, see merge_slot_of): calls that may be in flight at the same
+// time have different workspaces by the contract of the decode calls (they would overwrite each other's partials
+// otherwise), hence different sets, whether they are issued eagerly or replayed from a captured graph, which
+// keeps the set it was captured with.  Zero when the module is loaded; the block that arrives last wraps its
+// counter back to zero, so every launch leaves them zero again.  A workspace that finds all sets taken gets the
+// merge kernel instead (two launches: always correct).
+constexpr int kCounterSlots = 64;
 constexpr int kCountersPerSlot = 2048;
 __device__ unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
@@ -988,6 +993,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   }
   __syncthreads();
   if (*is_last == 0) return;
+  // What orders the partials before their readers is the machine's memory model for device-scope ATOMIC accesses,
+  // not a pair of fences: every partial is written with device-scope atomic stores (write-through: complete, as
+  // counted by vmcnt, once the data sits where every compute die reads it), the wave waits for vmcnt(0) and the
+  // block for its barrier before one thread counts the block in with a device-scope atomic, and the last block
+  // issues its device-scope atomic loads (which do not hit lines a die cached earlier) only after that atomic has
+  // returned.  A release fence before the count and an acquire fence after it (agent scope) were measured instead:
+  // each block then writes its die's whole L2 back, and a decode of 256 blocks goes from 13.4 to 16.7 us (one of
+  // 4 blocks from 10.3 to 11.2 us), more than the separate merge kernel costs (14.4 us), for no access that the
+  // atomics do not already cover.
   float* const c_m = reinterpret_cast<float*>(smem) + 64;     // [G][n] chunk maxima, then chunk weights
   float* const c_l = c_m + GP * kMaxSplits;                    // [G][n] chunk sums
   float* const h_den = c_l + GP * kMaxSplits;                  // [G]
@@ -1070,13 +1084,18 @@ hipError_t launch_as(const DecodeParams& p, dim3 grid, hipStream_t s) {
   constexpr int NW = 8;
   constexpr int smem = Cfg<D, GP, NW>::SMEM;
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
-  static bool configured = false;                 // dynamic LDS above 64 KB has to be opted into once
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // dynamic LDS above 64 KB has to be opted into, once per device and kernel instance (any thread may get here first)
+  static std::once_flag configured[kMaxDevices];
+  static hipError_t outcome[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::call_once(configured[dev], [&] {
+    outcome[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  });
+  if (outcome[dev] != hipSuccess) return outcome[dev];
   hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>), grid, dim3(NW * 64), smem, s, p);
   return hipGetLastError();
 }
@@ -1097,9 +1116,19 @@ bool mfma_supported(int head_dim, int gqa) { return kv_share_of(head_dim, gqa) >
 
 bool mfma_can_merge(int batch, int n_kv_heads) { return (int64_t)batch * n_kv_heads <= kCountersPerSlot; }
 
-hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim, bool merge_in_kernel,
-                               hipStream_t s) {
-  static std::atomic<unsigned int> next_slot{0};
+int mfma_merge_slot_of(const void* workspace) {
+  static std::mutex guard;
+  static std::unordered_map<const void*, int> slots;
+  std::lock_guard<std::mutex> lock(guard);
+  const auto it = slots.find(workspace);
+  if (it != slots.end()) return it->second;
+  if ((int)slots.size() >= kCounterSlots) return -1;
+  const int slot = (int)slots.size();
+  slots.emplace(workspace, slot);
+  return slot;
+}
+
+hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim, int merge_slot, hipStream_t s) {
   DecodeParams p = p_in;
   if (p.n_queries < 1) p.n_queries = 1;
   if (p.n_queries > kMaxQueries) return hipErrorNotSupported;
@@ -1109,9 +1138,10 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
   p.gqa = p.gqa * p.n_queries / p.kv_share;
   const int rows_y = p.n_kv_heads * p.kv_share;
   p.merge_slot = -1;
-  if (merge_in_kernel) {
-    if ((p.n_splits > 1 && !mfma_can_merge(batch, rows_y)) || p.out == nullptr) return hipErrorInvalidValue;
-    p.merge_slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kCounterSlots);
+  if (merge_slot >= 0) {
+    if ((p.n_splits > 1 && !mfma_can_merge(batch, rows_y)) || p.out == nullptr || merge_slot >= kCounterSlots)
+      return hipErrorInvalidValue;
+    p.merge_slot = merge_slot;
   }
   if (p.waves_per_row != 1 && p.waves_per_row != 2 && p.waves_per_row != 4) p.waves_per_row = 8;
   // several units per block: single-chunk rows whose output the kernel writes itself, or the slots of a chunk list

@@ -274,9 +274,13 @@ bool mfma_supported(int head_dim, int gqa);
 // How many blocks share the stream of one KV head for this GQA ratio (1 where the group fits one tile,
 // 0 = unsupported): the planner counts batch * n_kv_heads * share rows.
 int mfma_kv_share(int head_dim, int gqa);
-// With merge_in_kernel the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
+// With merge_slot >= 0 the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
+// The slot names the set of arrival counters the launch uses; mfma_merge_slot_of hands every workspace a set of
+// its own, for the life of the process, or -1 once all sets are taken (the caller then runs the merge kernel).
+// A launch whose rows are single chunks counts nothing and takes any slot >= 0.
 bool mfma_can_merge(int batch, int n_kv_heads);
-hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, bool merge_in_kernel, hipStream_t s);
+int mfma_merge_slot_of(const void* workspace);
+hipError_t launch_partial_mfma(const DecodeParams& p, int batch, int head_dim, int merge_slot, hipStream_t s);
 // head_dim 512: matrix-core kernel whose blocks take a tile of 16 or 32 query rows of one KV head
 // (p.kv_share = row tiles per KV head, from wide_row_tiles; p.gqa = H_q / H_kv; p.n_queries query tokens).
 bool wide_supported(int head_dim);

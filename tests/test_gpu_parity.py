@@ -527,6 +527,70 @@ def test_concurrent_calls_on_two_streams():
             assert np.array_equal(np16(t).view(np.uint16), first)
 
 
+def test_single_launch_decodes_on_24_streams_match_the_serial_result():
+    """24 decodes of the one-launch route (several chunks per KV head, merged by the block that arrives last) in
+    flight at once, each on its own stream with its own workspace: every workspace has its own set of arrival
+    counters, so all results equal, bit for bit, the result of the same call made alone."""
+    w = wl.custom(seq_len=8192, seed=93, **SHAPES["g8_d128_b2_kv3"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    qd = q.cuda()
+    assert tq.tq_decode_launches(cache, qd.shape[1], w.seq_len, w.attn_scale) == 1
+    assert tq.tq_plan_splits(w.batch, w.n_kv_heads, w.seq_len) > 1
+    nbytes = tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim)
+    alone = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(alone, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "alone")
+    want = np16(alone).view(np.uint16)
+    streams = [torch.cuda.Stream() for _ in range(24)]
+    ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in streams]
+    rounds = 12
+    outs = [[torch.zeros_like(qd) for _ in range(rounds)] for _ in streams]
+    torch.cuda.synchronize()
+    for i in range(rounds):
+        for s, wsp, o in zip(streams, ws, outs):
+            with torch.cuda.stream(s):
+                tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=o[i], workspace=wsp)
+    torch.cuda.synchronize()
+    for si, o in enumerate(outs):
+        for i, t in enumerate(o):
+            assert np.array_equal(np16(t).view(np.uint16), want), f"stream {si}, call {i} differs from the call made alone"
+
+
+def test_graph_replays_next_to_eager_calls_on_another_stream():
+    """A captured one-launch decode keeps the counter set of the workspace it was captured with: replays on one
+    stream while eager decodes (another workspace) run on a second stream share nothing, and every replay gives the
+    eager result bit for bit."""
+    w = wl.custom(seq_len=6000, seed=94, **SHAPES["g8_d128_b2_kv3"])
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    qd = q.cuda()
+    assert tq.tq_decode_launches(cache, qd.shape[1], w.seq_len, w.attn_scale) == 1
+    nbytes = tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim)
+    ws_graph, ws_eager = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2))
+    out_graph = torch.empty_like(qd)
+    want = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, workspace=ws_graph).clone()   # (eager first)
+    torch.cuda.synchronize()
+    assert_close(want, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=out_graph, workspace=ws_graph)
+    side = torch.cuda.Stream()
+    outs_eager = [torch.zeros_like(qd) for _ in range(40)]
+    for r in range(5):
+        out_graph.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):             # eager decodes in flight while the graph replays
+            for t in outs_eager[r * 8:(r + 1) * 8]:
+                tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=t, workspace=ws_eager)
+        g.replay()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_graph, want), f"replay round {r}"
+    for i, t in enumerate(outs_eager):
+        assert torch.equal(t, want), f"eager call {i}"
+
+
 def test_graph_capture_and_replay():
     """A captured decode step (append + attend, both decode routes) replays to the eager result, with
     eager work and synchronisations between the replays."""
