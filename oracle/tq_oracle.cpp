@@ -20,8 +20,10 @@
 //   STORED values; ties round half-to-even; a constant (or fp16-underflowing) group gets
 //   scale 1.0 and zero-point -min; zero-point saturates at +-65504 and -0 is stored as +0.
 //
+// Group size g: 32 (the paper's configuration), 64 or 128 (Sec. 2.1 states the scheme for any g).
+//
 // Pins (tests/test_oracle_*.py): closed-form groups, half-even ties, |x^-x| <= s/2, nibble
-// order, 5 bits/element and the memory table (Table 4 / Eq. 1), exhaustive fp16 conversion
+// order, 4 + 32/g bits/element and the memory table (Table 4 / Eq. 1), exhaustive fp16 conversion
 // against an independent converter, S=1, identical keys, score-shift invariance, argmax limit,
 // brute force on tiny inputs with exact rationals, Alg. 1 + Eq. 6 == definition, GQA mapping,
 // token-permutation invariance.  No function here is "parity unpinned".
@@ -36,7 +38,9 @@
 
 namespace {
 
-constexpr int kGroup = 32;
+constexpr int kMaxGroup = 128;                     // group sizes offered: 32 (the paper's), 64, 128
+
+inline bool group_ok(int d, int g) { return (g == 32 || g == 64 || g == 128) && d > 0 && d % g == 0; }
 
 // ---- fp16 <-> fp32, bit level (IEEE binary16, round-to-nearest-even) -------------------
 
@@ -97,11 +101,12 @@ uint16_t float_to_half_bits_rne(float f) {
 
 // ---- quantiser (Sec. 2.1, Eq. 2-3) ------------------------------------------------------
 
-void quantize_group(const uint16_t* x16, uint8_t* codes16, uint16_t* s_out, uint16_t* z_out) {
-  float x[kGroup];
-  for (int j = 0; j < kGroup; ++j) x[j] = half_bits_to_float(x16[j]);
+// One group of g consecutive elements: g/2 bytes of codes, one scale, one zero-point.
+void quantize_group(const uint16_t* x16, int g, uint8_t* codes_out, uint16_t* s_out, uint16_t* z_out) {
+  float x[kMaxGroup];
+  for (int j = 0; j < g; ++j) x[j] = half_bits_to_float(x16[j]);
   float mn = x[0], mx = x[0];
-  for (int j = 1; j < kGroup; ++j) { mn = std::min(mn, x[j]); mx = std::max(mx, x[j]); }
+  for (int j = 1; j < g; ++j) { mn = std::min(mn, x[j]); mx = std::max(mx, x[j]); }
   volatile float range = mx - mn;                  // volatile: keep each fp32 step separate
   volatile float s32 = range / 15.0f;              // Eq. 2, scale
   uint16_t s16 = float_to_half_bits_rne(s32);
@@ -113,15 +118,15 @@ void quantize_group(const uint16_t* x16, uint8_t* codes16, uint16_t* s_out, uint
   if ((z16 & 0x7FFFu) == 0x7C00u) z16 = (uint16_t)((z16 & 0x8000u) | 0x7BFFu);  // saturate
   if (z16 == 0x8000u) z16 = 0;
   const float zf = half_bits_to_float(z16);
-  uint8_t c[kGroup];
-  for (int j = 0; j < kGroup; ++j) {
+  uint8_t c[kMaxGroup];
+  for (int j = 0; j < g; ++j) {
     volatile float t = x[j] / sf;                  // Eq. 3: x/s ...
     volatile float u = t + zf;                     // ... + z, as a separate fp32 add
     float r = std::nearbyintf(u);                  // half-to-even in the default rounding mode
     r = std::min(15.0f, std::max(0.0f, r));
     c[j] = (uint8_t)r;
   }
-  for (int b = 0; b < kGroup / 2; ++b) codes16[b] = (uint8_t)(c[2 * b] | (c[2 * b + 1] << 4));
+  for (int b = 0; b < g / 2; ++b) codes_out[b] = (uint8_t)(c[2 * b] | (c[2 * b + 1] << 4));
   *s_out = s16;
   *z_out = z16;
 }
@@ -131,25 +136,25 @@ inline int code_at(const uint8_t* codes, int j) {  // element j of a packed vect
   return (j & 1) ? (byte >> 4) : (byte & 0xF);
 }
 
-inline double dequant_elem(const uint8_t* codes, const uint16_t* s, const uint16_t* z, int j) {
-  const double sf = (double)half_bits_to_float(s[j / kGroup]);
-  const double zf = (double)half_bits_to_float(z[j / kGroup]);
+inline double dequant_elem(const uint8_t* codes, const uint16_t* s, const uint16_t* z, int j, int g) {
+  const double sf = (double)half_bits_to_float(s[j / g]);
+  const double zf = (double)half_bits_to_float(z[j / g]);
   return ((double)code_at(codes, j) - zf) * sf;    // Eq. 3, x^ = (q - z) s, in fp64
 }
 
 struct CacheView {
   const uint8_t* codes; const uint16_t* scale; const uint16_t* zero;
-  int64_t capacity; int d;
+  int64_t capacity; int d; int g;
   const uint8_t* tok_codes(int64_t bh, int64_t t) const { return codes + (bh * capacity + t) * (d / 2); }
-  const uint16_t* tok_scale(int64_t bh, int64_t t) const { return scale + (bh * capacity + t) * (d / kGroup); }
-  const uint16_t* tok_zero(int64_t bh, int64_t t) const { return zero + (bh * capacity + t) * (d / kGroup); }
+  const uint16_t* tok_scale(int64_t bh, int64_t t) const { return scale + (bh * capacity + t) * (d / g); }
+  const uint16_t* tok_zero(int64_t bh, int64_t t) const { return zero + (bh * capacity + t) * (d / g); }
 };
 
 void dequant_head(const CacheView& c, int64_t bh, int64_t S, std::vector<double>& out) {
   out.resize((size_t)S * c.d);
   for (int64_t t = 0; t < S; ++t)
     for (int j = 0; j < c.d; ++j)
-      out[(size_t)t * c.d + j] = dequant_elem(c.tok_codes(bh, t), c.tok_scale(bh, t), c.tok_zero(bh, t), j);
+      out[(size_t)t * c.d + j] = dequant_elem(c.tok_codes(bh, t), c.tok_scale(bh, t), c.tok_zero(bh, t), j, c.g);
 }
 
 // softmax(alpha * q.K^ + bias) V^ for one query row, by definition (max-subtracted).
@@ -208,40 +213,39 @@ extern "C" {
 float orc_half_to_float(uint16_t h) { return half_bits_to_float(h); }
 uint16_t orc_float_to_half(float f) { return float_to_half_bits_rne(f); }
 
-// x: fp16 bits [n_vec][d]; codes [n_vec][d/2]; scale, zero: fp16 bits [n_vec][d/32].
-int orc_quantize(const uint16_t* x, int64_t n_vec, int d, uint8_t* codes, uint16_t* scale,
+// x: fp16 bits [n_vec][d]; codes [n_vec][d/2]; scale, zero: fp16 bits [n_vec][d/g], g = the group size.
+int orc_quantize(const uint16_t* x, int64_t n_vec, int d, int g, uint8_t* codes, uint16_t* scale,
                  uint16_t* zero, int nthreads) {
-  if (d <= 0 || d % kGroup != 0) return -1;
-  const int ng = d / kGroup;
+  if (!group_ok(d, g)) return -1;
+  const int ng = d / g;
   parallel_for(n_vec, nthreads, [=](int64_t v) {
-    for (int g = 0; g < ng; ++g)
-      quantize_group(x + v * d + g * kGroup, codes + v * (d / 2) + g * (kGroup / 2),
-                     scale + v * ng + g, zero + v * ng + g);
+    for (int i = 0; i < ng; ++i)
+      quantize_group(x + v * d + i * g, g, codes + v * (d / 2) + i * (g / 2), scale + v * ng + i, zero + v * ng + i);
   });
   return 0;
 }
 
 // fp64 value of every stored element: out [n_vec][d].
 int orc_dequantize_f64(const uint8_t* codes, const uint16_t* scale, const uint16_t* zero,
-                       int64_t n_vec, int d, double* out) {
-  if (d <= 0 || d % kGroup != 0) return -1;
-  const int ng = d / kGroup;
+                       int64_t n_vec, int d, int g, double* out) {
+  if (!group_ok(d, g)) return -1;
+  const int ng = d / g;
   for (int64_t v = 0; v < n_vec; ++v)
     for (int j = 0; j < d; ++j)
-      out[v * d + j] = dequant_elem(codes + v * (d / 2), scale + v * ng, zero + v * ng, j);
+      out[v * d + j] = dequant_elem(codes + v * (d / 2), scale + v * ng, zero + v * ng, j, g);
   return 0;
 }
 
 // What the unfused comparator's dense buffer must hold: fp16_rne of the fp64 value.
 int orc_dequantize_f16(const uint8_t* codes, const uint16_t* scale, const uint16_t* zero,
-                       int64_t n_vec, int d, uint16_t* out) {
-  if (d <= 0 || d % kGroup != 0) return -1;
-  const int ng = d / kGroup;
+                       int64_t n_vec, int d, int g, uint16_t* out) {
+  if (!group_ok(d, g)) return -1;
+  const int ng = d / g;
   for (int64_t v = 0; v < n_vec; ++v)
     for (int j = 0; j < d; ++j) {
       // (c - z) s has at most 4+11+11 significant bits: exact in fp64, and its fp32 rounding
       // followed by fp16 rounding could double-round, so round once from fp64 by hand.
-      const double x = dequant_elem(codes + v * (d / 2), scale + v * ng, zero + v * ng, j);
+      const double x = dequant_elem(codes + v * (d / 2), scale + v * ng, zero + v * ng, j, g);
       float f = (float)x;
       if ((double)f != x) {  // make the fp32 intermediate "sticky" so the fp16 rounding is single
         uint32_t u; std::memcpy(&u, &f, 4);
@@ -275,11 +279,11 @@ int orc_attend_dense_f64(const uint16_t* q, const double* K, const double* V, in
 int orc_attend_packed_f64(const uint16_t* q,
                           const uint8_t* k_codes, const uint16_t* k_scale, const uint16_t* k_zero,
                           const uint8_t* v_codes, const uint16_t* v_scale, const uint16_t* v_zero,
-                          int B, int Hq, int Hkv, int64_t capacity, int64_t S, int d, double alpha,
+                          int B, int Hq, int Hkv, int64_t capacity, int64_t S, int d, int g, double alpha,
                           double* out, int nthreads) {
-  if (Hkv <= 0 || Hq % Hkv != 0 || S < 1 || S > capacity || d % kGroup != 0) return -1;
+  if (Hkv <= 0 || Hq % Hkv != 0 || S < 1 || S > capacity || !group_ok(d, g)) return -1;
   const int G = Hq / Hkv;
-  const CacheView kc{k_codes, k_scale, k_zero, capacity, d}, vc{v_codes, v_scale, v_zero, capacity, d};
+  const CacheView kc{k_codes, k_scale, k_zero, capacity, d, g}, vc{v_codes, v_scale, v_zero, capacity, d, g};
   parallel_for((int64_t)B * Hkv, nthreads, [=](int64_t bkv) {
     std::vector<double> K, V, qd((size_t)d);
     dequant_head(kc, bkv, S, K);
@@ -326,10 +330,10 @@ int orc_attend_alg1_eq6_f64(const uint16_t* q, const double* K, const double* V,
   return 0;
 }
 
-// Bytes of a KV cache (K and V) for n_layers x n_kv_heads x seq_len tokens of dim d at int4 group 32
-// with fp16 scale + zero-point per group (Sec. 2.1), and the same at fp16 (Eq. 1).
-int64_t orc_kv_bytes_int4(int64_t n_layers, int64_t n_kv_heads, int64_t seq_len, int64_t d) {
-  return 2 * n_layers * n_kv_heads * seq_len * (d / 2 + 2 * 2 * (d / kGroup));
+// Bytes of a KV cache (K and V) for n_layers x n_kv_heads x seq_len tokens of dim d at int4 with one fp16 scale
+// and one fp16 zero-point per group of g elements (Sec. 2.1: 4 + 32/g bits per element), and the same at fp16 (Eq. 1).
+int64_t orc_kv_bytes_int4(int64_t n_layers, int64_t n_kv_heads, int64_t seq_len, int64_t d, int64_t g) {
+  return 2 * n_layers * n_kv_heads * seq_len * (d / 2 + 2 * 2 * (d / g));
 }
 int64_t orc_kv_bytes_fp16(int64_t n_layers, int64_t n_kv_heads, int64_t seq_len, int64_t d) {
   return 2 * n_layers * n_kv_heads * seq_len * d * 2;

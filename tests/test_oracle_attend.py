@@ -190,3 +190,30 @@ def test_quality_level_is_in_the_papers_ballpark():
     xf = x.astype(np.float64)
     cos = (xf * xh).sum() / math.sqrt((xf ** 2).sum() * (xh ** 2).sum())
     assert 0.994 < cos < 0.9995
+
+
+@pytest.mark.parametrize("g", [64, 128])
+def test_larger_groups_only_change_the_dequantised_values(g):
+    """At group size 64 / 128 the packed path reads the scale and zero-point of group j // g for element j and is
+    otherwise the same definition: it equals the dense path over numpy's own (code - z) * s with the metadata
+    repeated g times (an indexing slip in the packed path would break it), and one cached token returns that
+    token's dequantised value vector."""
+    rng = np.random.default_rng(40 + g)
+    q, k, v = _rand_case(rng, B=2, Hq=6, Hkv=3, S=29, d=256)
+    kc, ks, kz = oracle.quantize(k, group=g)
+    vc, vs, vz = oracle.quantize(v, group=g)
+    assert ks.shape[-1] == 256 // g
+
+    def dense(codes, sc, zp):
+        c = np.empty(codes.shape[:-1] + (256,), np.float64)
+        c[..., 0::2] = codes & 0xF
+        c[..., 1::2] = codes >> 4
+        return (c - np.repeat(zp.astype(np.float64), g, -1)) * np.repeat(sc.astype(np.float64), g, -1)
+
+    K, V = dense(kc, ks, kz), dense(vc, vs, vz)
+    assert np.array_equal(oracle.dequantize(kc, ks, kz), K) and np.array_equal(oracle.dequantize(vc, vs, vz), V)
+    out = oracle.attend_packed(q, kc, ks, kz, vc, vs, vz, seq_len=29, alpha=0.2)
+    assert np.allclose(out, oracle.attend_dense(q, K, V, 0.2), rtol=0, atol=1e-13)
+    one = oracle.attend_packed(q, kc, ks, kz, vc, vs, vz, seq_len=1, alpha=0.2)
+    for h in range(6):
+        assert np.array_equal(one[:, h], V[:, h // 2, 0])

@@ -36,32 +36,46 @@ def _unpack(codes):
 
 def test_closed_form_groups(golden_dir):
     cases = _parse_cases(golden_dir / "quant_closed_forms.txt")
-    assert len(cases) >= 6
+    assert len(cases) >= 8 and {int(c.get("g", [32])[0]) for c in cases} == {32, 64, 128}
     for c in cases:
+        g = int(c.get("g", [32])[0])
         x = np.array(c["x"], np.float16)
+        assert len(c["x"]) == g == len(c["q"]), c["name"]
         assert np.array_equal(x.astype(np.float64), np.array(c["x"])), c["name"]
-        codes, s, z = oracle.quantize(x[None, :])
+        codes, s, z = oracle.quantize(x[None, :], group=g)
+        assert s.shape == (1, 1) and codes.shape == (1, g // 2), c["name"]
         assert float(s[0, 0]) == c["s"][0], c["name"]
         assert float(z[0, 0]) == c["z"][0], c["name"]
         assert _unpack(codes)[0].tolist() == [int(v) for v in c["q"]], c["name"]
         # Eq. 3 with the hand-derived triple: x^ = (q - z) s
         xhat = (np.array(c["q"]) - c["z"][0]) * c["s"][0]
         assert np.array_equal(oracle.dequantize(codes, s, z)[0], xhat), c["name"]
-        if c["name"] != "ties":                               # on-grid inputs reconstruct exactly
+        if c["name"] not in ("ties", "halves_64", "quarters_128"):   # on-grid inputs reconstruct exactly
             assert np.array_equal(xhat, np.array(c["x"])), c["name"]
+        if g == 32:
+            # the same values repeated fill a group of 64 or 128 with the same min and max: same s and z, codes repeated
+            for big in (64, 128):
+                xb = np.tile(x, big // 32)[None, :]
+                cb, sb, zb = oracle.quantize(xb, group=big)
+                assert float(sb[0, 0]) == c["s"][0] and float(zb[0, 0]) == c["z"][0], (c["name"], big)
+                assert _unpack(cb)[0].tolist() == [int(v) for v in c["q"]] * (big // 32), (c["name"], big)
 
 
+GROUPS = [32, 64, 128]
+
+
+@pytest.mark.parametrize("g", GROUPS)
 @pytest.mark.parametrize("e", [-10, -3, 0, 2, 5])
 @pytest.mark.parametrize("m", [-1024, -37, -8, 0, 5, 600, 1009])
-def test_power_of_two_ramps(e, m):
+def test_power_of_two_ramps(e, m, g):
     # x = (m + k) 2^e with k covering 0..15  =>  s = 2^e, z = -m, q = k   (Eq. 2-3, exact arithmetic)
-    rng = np.random.default_rng(100 * (e + 20) + (m + 2000))
-    k = np.concatenate([np.arange(16), rng.integers(0, 16, 16)])
+    rng = np.random.default_rng(100 * (e + 20) + (m + 2000) + g)
+    k = np.concatenate([np.arange(16), rng.integers(0, 16, g - 16)])
     rng.shuffle(k)
     x64 = (m + k) * 2.0 ** e
     x = x64.astype(np.float16)
     assert np.array_equal(x.astype(np.float64), x64)
-    codes, s, z = oracle.quantize(x[None])
+    codes, s, z = oracle.quantize(x[None], group=g)
     assert float(s[0, 0]) == 2.0 ** e and float(z[0, 0]) == -m
     assert np.array_equal(_unpack(codes)[0], k)
 
@@ -102,35 +116,53 @@ def _roundtrip_inputs():
     return [a, b, c.astype(np.float16)]
 
 
-def test_roundtrip_error_at_most_half_a_step():
+@pytest.mark.parametrize("g", GROUPS)
+def test_roundtrip_error_at_most_half_a_step(g):
     # |x^ - x| <= s/2 per element (plus fp32 rounding of x/s+z) whenever nothing clamps, i.e. |z| <= 1024
     for x in _roundtrip_inputs():
-        codes, s, z = oracle.quantize(x)
+        codes, s, z = oracle.quantize(x, group=g)
         assert np.all(np.abs(z.astype(np.float64)) <= 1024)
         xh = oracle.dequantize(codes, s, z)
-        step = np.repeat(s.astype(np.float64), 32, axis=-1)
+        step = np.repeat(s.astype(np.float64), g, axis=-1)
         err = np.abs(xh - x.astype(np.float64))
         assert np.all(err <= step * (0.5 + 1e-3))
         # the step really is the group's range / 15 up to fp16 rounding
-        xg = x.astype(np.float64).reshape(x.shape[0], -1, 32)
+        xg = x.astype(np.float64).reshape(x.shape[0], -1, g)
         rng_ = xg.max(-1) - xg.min(-1)
         assert np.allclose(s.astype(np.float64), rng_ / 15, rtol=2 ** -11 * 1.01, atol=0)
 
 
-def test_min_maps_to_0_and_max_to_15():
+@pytest.mark.parametrize("g", GROUPS)
+def test_min_maps_to_0_and_max_to_15(g):
     for x in _roundtrip_inputs():
-        codes, s, z = oracle.quantize(x)
-        q = _unpack(codes).reshape(x.shape[0], -1, 32)
-        xg = x.reshape(x.shape[0], -1, 32)
+        codes, s, z = oracle.quantize(x, group=g)
+        q = _unpack(codes).reshape(x.shape[0], -1, g)
+        xg = x.reshape(x.shape[0], -1, g)
         assert np.all(np.take_along_axis(q, xg.argmin(-1)[..., None], -1) == 0)
         assert np.all(np.take_along_axis(q, xg.argmax(-1)[..., None], -1) == 15)
         assert set(np.unique(q)) == set(range(16))
 
 
-def test_codes_match_independent_numpy_evaluation():
+def test_a_larger_group_never_has_a_finer_step():
+    """A group of 64 (128) is the union of two (four) groups of 32: its range, hence its stored scale, is at least
+    the largest of theirs (fp16 rounding is monotone), and equal where one part already spans the whole range."""
+    for x in _roundtrip_inputs():
+        s32 = oracle.quantize(x, group=32)[1].astype(np.float64)
+        for g in (64, 128):
+            sg = oracle.quantize(x, group=g)[1].astype(np.float64)
+            parts = s32.reshape(x.shape[0], -1, g // 32)
+            assert np.all(sg >= parts.max(-1))
+            xg = x.astype(np.float64).reshape(x.shape[0], -1, g)
+            x32 = x.astype(np.float64).reshape(x.shape[0], -1, g // 32, 32)
+            spans_all = (x32.max(-1) - x32.min(-1)).max(-1) == xg.max(-1) - xg.min(-1)
+            assert np.all(sg[spans_all] == parts.max(-1)[spans_all])
+
+
+@pytest.mark.parametrize("g", GROUPS)
+def test_codes_match_independent_numpy_evaluation(g):
     """Eq. 2-3 evaluated with numpy float32 ops and numpy's own fp16 rounding."""
     for x in _roundtrip_inputs():
-        xf = x.astype(np.float32).reshape(x.shape[0], -1, 32)
+        xf = x.astype(np.float32).reshape(x.shape[0], -1, g)
         mn, mx = xf.min(-1), xf.max(-1)
         s16 = ((mx - mn) / np.float32(15)).astype(np.float16)
         sf = s16.astype(np.float32)
@@ -138,7 +170,7 @@ def test_codes_match_independent_numpy_evaluation():
         z16 = ((np.float32(0) - mn) / sf).astype(np.float16)
         v = xf / sf[..., None] + z16.astype(np.float32)[..., None]
         q = np.clip(np.rint(v), 0, 15).astype(np.uint8).reshape(x.shape)
-        codes, s, z = oracle.quantize(x)
+        codes, s, z = oracle.quantize(x, group=g)
         assert np.array_equal(s.view(np.uint16), s16.view(np.uint16))
         assert np.array_equal(z.view(np.uint16), z16.view(np.uint16))
         assert np.array_equal(_unpack(codes), q)
@@ -188,6 +220,12 @@ def test_format_size_and_paper_memory_table(golden_dir):
     assert oracle.kv_bytes_int4(1, 1, 1, 128) * 8 / (2 * 128) == 5.0
     codes, s, z = oracle.quantize(np.zeros((7, 256), np.float16))
     assert (codes.nbytes + s.nbytes + z.nbytes) * 8 / (7 * 256) == 5.0
+    # groups of g elements: 4 bits of code + 32 bits of fp16 scale and zero-point per g elements (Sec. 2.1)
+    for g, bits in ((32, 5.0), (64, 4.5), (128, 4.25)):
+        assert oracle.kv_bytes_int4(1, 1, 1, 128, group=g) * 8 / (2 * 128) == bits
+        codes, s, z = oracle.quantize(np.zeros((7, 256), np.float16), group=g)
+        assert (codes.nbytes + s.nbytes + z.nbytes) * 8 / (7 * 256) == bits
+        assert oracle.kv_bytes_int4(80, 8, 131072, 128, group=g) == 2 * 80 * 8 * 131072 * 128 * bits / 8   # Eq. 1's form
 
 
 def test_fp16_to_fp32_exhaustive_against_numpy():
