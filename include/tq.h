@@ -2,7 +2,8 @@
  *
  * The library computes single-query (decode) scaled-dot-product attention directly on a
  * KV cache stored as packed int4 codes with one fp16 scale and one fp16 zero-point per
- * group of 32 consecutive head_dim elements (Sec. 2.1, Eq. 2-3), dequantising in registers
+ * group of 32 consecutive head_dim elements (Sec. 2.1, Eq. 2-3; groups of 64 and 128 are offered
+ * too, see tq_kv_cache), dequantising in registers
  * and never writing a dequantised K or V matrix (Sec. 3.1, Alg. 1), with the sequence split
  * into chunks whose partial results are merged by an online-softmax correction
  * (Sec. 3.2, Eq. 6).
@@ -31,7 +32,7 @@ extern "C" {
 enum {
   TQ_OK = 0,
   TQ_ERR_NULL = -1,        /* a required pointer is NULL                                        */
-  TQ_ERR_SHAPE = -2,       /* head_dim not in {128,256,512}, group_size != 32, batch/heads < 1,
+  TQ_ERR_SHAPE = -2,       /* head_dim not in {128,256,512}, group_size not in {32,64,128}, batch/heads < 1,
                               n_q_heads not a multiple of n_kv_heads, unknown layout            */
   TQ_ERR_EMPTY = -3,       /* seq_len < 1 or n_new < 1                                          */
   TQ_ERR_CAPACITY = -4,    /* pos < 0, pos + n_new > capacity, or seq_len > capacity            */
@@ -49,8 +50,13 @@ enum { TQ_LAYOUT_CANONICAL = 0 };
  *                      in its high nibble (element j of a 16-bit word sits in bits 4j..4j+3,
  *                      the order the masks of Eq. 5 assume)
  *   k_scale, k_zero,
- *   v_scale, v_zero  : fp16  [batch][n_kv_heads][capacity][head_dim/32]
- * 5.0 bits per element in total.  Tokens [0, seq_len) are valid; the rest is never read. */
+ *   v_scale, v_zero  : fp16  [batch][n_kv_heads][capacity][head_dim/group_size]
+ * 4 + 32/group_size bits per element in total: 5.0 at the paper's group size of 32 (its 3.2x against fp16),
+ * 4.5 at 64, 4.25 at 128.  Tokens [0, seq_len) are valid; the rest is never read.
+ * group_size 32 is what the matrix-core kernels are built for (one matrix instruction per group).  Sec. 2.1
+ * states the scheme for groups of g consecutive elements: 64 and 128 are accepted by every call and take the
+ * generic vector-ALU kernels (same arithmetic per group, same bit-exact stores); options that only the
+ * matrix-core kernels offer (variant 2, n_queries > 1) answer UNSUPPORTED there. */
 typedef struct tq_kv_cache {
   void* k_codes;
   void* v_codes;
@@ -61,7 +67,7 @@ typedef struct tq_kv_cache {
   int32_t batch;
   int32_t n_kv_heads;
   int32_t head_dim;    /* 128, 256 or 512 */
-  int32_t group_size;  /* 32 */
+  int32_t group_size;  /* 32 (the paper's), 64 or 128 */
   int32_t capacity;    /* tokens allocated per (batch, kv head) */
   int32_t layout;      /* TQ_LAYOUT_CANONICAL */
 } tq_kv_cache;
@@ -237,6 +243,8 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
 size_t tq_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim);
 size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim);
 size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim);
+/* The same for a group size of 32, 64 or 128: 2 * batch * n_kv_heads * capacity * (head_dim/2 + 4*head_dim/group_size). */
+size_t tq_kv_bytes_grouped(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim, int32_t group_size);
 
 /* Chunk count the heuristic would pick (host only). */
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     tq_dense_scratch_bytes,
     tq_dequant_then_attend,
     tq_kv_bytes,
+    tq_kv_bytes_grouped,
     tq_plan_splits,
     tq_quantize_kv,
     tq_quantize_kv_paged,

@@ -75,6 +75,8 @@ def raw():
         L.tq_dense_scratch_bytes.restype = SZ
         L.tq_kv_bytes.argtypes = [I, I, I, I]
         L.tq_kv_bytes.restype = SZ
+        L.tq_kv_bytes_grouped.argtypes = [I, I, I, I, I]
+        L.tq_kv_bytes_grouped.restype = SZ
         L.tq_plan_splits.argtypes = [I, I, I]
         L.tq_plan_splits.restype = I
         L.tq_decode_launches.argtypes = [CP, I, I, F, OP]
@@ -101,6 +103,10 @@ def tq_kv_bytes(batch: int, n_kv_heads: int, capacity: int, head_dim: int) -> in
     return int(raw().tq_kv_bytes(batch, n_kv_heads, capacity, head_dim))
 
 
+def tq_kv_bytes_grouped(batch: int, n_kv_heads: int, capacity: int, head_dim: int, group_size: int) -> int:
+    return int(raw().tq_kv_bytes_grouped(batch, n_kv_heads, capacity, head_dim, group_size))
+
+
 def tq_plan_splits(batch: int, n_kv_heads: int, seq_len: int) -> int:
     return int(raw().tq_plan_splits(batch, n_kv_heads, seq_len))
 
@@ -115,8 +121,9 @@ def tq_decode_launches(cache: "KVCache", n_q_heads: int, seq_len: int, attn_scal
 class KVCache:
     """Caller-owned cache for one layer: six torch tensors in the canonical layout of tq.h."""
 
-    def __init__(self, batch: int, n_kv_heads: int, head_dim: int, capacity: int, device="cuda"):
-        ng = head_dim // 32
+    def __init__(self, batch: int, n_kv_heads: int, head_dim: int, capacity: int, device="cuda", group_size: int = 32):
+        ng = head_dim // group_size
+        self.group_size = group_size
         shape = (batch, n_kv_heads, capacity)
         self.k_codes = torch.empty(shape + (head_dim // 2,), dtype=torch.uint8, device=device)
         self.v_codes = torch.empty_like(self.k_codes)
@@ -127,7 +134,7 @@ class KVCache:
         self.batch, self.n_kv_heads, self.head_dim, self.capacity = batch, n_kv_heads, head_dim, capacity
         self.struct = TqKvCacheStruct(
             self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(), self.k_zero.data_ptr(),
-            self.v_scale.data_ptr(), self.v_zero.data_ptr(), batch, n_kv_heads, head_dim, 32, capacity, 0)
+            self.v_scale.data_ptr(), self.v_zero.data_ptr(), batch, n_kv_heads, head_dim, group_size, capacity, 0)
 
     def tensors(self):
         return (self.k_codes, self.k_scale, self.k_zero, self.v_codes, self.v_scale, self.v_zero)

@@ -21,7 +21,8 @@ int check_cache(const tq_kv_cache* c) {
   if (!c) return TQ_ERR_NULL;
   if (!c->k_codes || !c->v_codes || !c->k_scale || !c->k_zero || !c->v_scale || !c->v_zero) return TQ_ERR_NULL;
   if (!head_dim_ok(c->head_dim)) return TQ_ERR_SHAPE;
-  if (c->group_size != tq::kGroup) return TQ_ERR_SHAPE;
+  if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128) return TQ_ERR_SHAPE;
+  if (c->head_dim % c->group_size != 0) return TQ_ERR_SHAPE;
   if (c->batch < 1 || c->n_kv_heads < 1 || c->capacity < 1) return TQ_ERR_SHAPE;
   if (c->layout != TQ_LAYOUT_CANONICAL) return TQ_ERR_SHAPE;
   const void* ptrs[] = {c->k_codes, c->v_codes, c->k_scale, c->k_zero, c->v_scale, c->v_zero};
@@ -114,6 +115,7 @@ DecodeParams make_params(const tq_kv_cache* c, const void* q, int n_q_heads, int
   p.n_queries = n_queries;
   p.n_kv_heads = c->n_kv_heads;
   p.gqa = n_q_heads / c->n_kv_heads;
+  p.group = c->group_size;
   p.row_stride = c->capacity;
   p.seq_len = seq_len;
   p.n_splits = plan.n_splits;
@@ -141,6 +143,12 @@ int windowed(int seq_len, const tq_decode_opts* opts) {
 
 Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts) {
   const int variant = opts ? opts->variant : 0;
+  // groups of 64 or 128 elements: the generic vector-ALU kernel (the matrix-core kernels are built around groups
+  // of 32: one matrix instruction per group); one query token per sequence
+  if (cache->group_size != tq::kGroup) {
+    const bool ok = variant != 2 && queries_of(opts) == 1;
+    return {ok, false, false, false, false};
+  }
   // the matrix-core kernel folds attn_scale into its exp2 argument and needs it positive and finite
   const bool scale_ok = attn_scale > 0.0f && std::isfinite(attn_scale);
   if (variant == 2 && !scale_ok) return {false, false, false, false, false};
@@ -353,10 +361,15 @@ size_t tq_dense_scratch_bytes(int32_t batch, int32_t n_kv_heads, int32_t seq_len
   return (size_t)2 * batch * n_kv_heads * seq_len * head_dim * sizeof(half_t);
 }
 
-size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim) {
-  if (batch < 1 || n_kv_heads < 1 || capacity < 1 || head_dim < 32 || head_dim % tq::kGroup != 0) return 0;
-  const size_t per_token = (size_t)head_dim / 2 + 2 * sizeof(half_t) * (head_dim / tq::kGroup);
+size_t tq_kv_bytes_grouped(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim, int32_t group_size) {
+  if (group_size != 32 && group_size != 64 && group_size != 128) return 0;
+  if (batch < 1 || n_kv_heads < 1 || capacity < 1 || head_dim < group_size || head_dim % group_size != 0) return 0;
+  const size_t per_token = (size_t)head_dim / 2 + 2 * sizeof(half_t) * (head_dim / group_size);
   return (size_t)2 * batch * n_kv_heads * capacity * per_token;
+}
+
+size_t tq_kv_bytes(int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t head_dim) {
+  return tq_kv_bytes_grouped(batch, n_kv_heads, capacity, head_dim, tq::kGroup);
 }
 
 int32_t tq_plan_splits(int32_t batch, int32_t n_kv_heads, int32_t seq_len) {
@@ -504,7 +517,7 @@ int tq_sdpa_int4_append_decode(const tq_kv_cache* cache, const void* k_new, cons
   // The merge kernel takes the token in (one query token, at least one cached token to attend: no append launch,
   // nothing read back); else the append kernel runs first.  Where every sequence is a single chunk there is no
   // merge kernel to begin with (the decode kernel writes the output itself): the append kernel, then that.
-  if (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2 && !r.single) {
+  if (queries_of(opts) == 1 && windowed(seq_len, opts) >= 2 && !r.single && cache->group_size == tq::kGroup) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {                                        // the append kernel first, then the plain decode
@@ -560,7 +573,8 @@ int append_decode_with_lengths(PartialRequest& rq, const void* k_new, const void
   const tq_decode_opts* opts = rq.opts;
   // (where every row is a single chunk there is no merge kernel to take the token in: the append kernel, then the decode)
   const bool one_chunk_rows = rows_as_chunks(rq.cache, rq.n_q_heads, rq.seq_len, rq.attn_scale, opts, rq.paged != nullptr);
-  if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2 && !one_chunk_rows) {
+  if (queries_of(opts) == 1 && !(opts && opts->window == 1) && rq.seq_len >= 2 && !one_chunk_rows &&
+      rq.cache->group_size == tq::kGroup) {
     rq.k_new = k_new;
     rq.v_new = v_new;
   } else {

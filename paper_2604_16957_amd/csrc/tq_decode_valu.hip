@@ -28,14 +28,14 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   constexpr int LPT = D / 8;           // lanes per token
   constexpr int TPW = 64 / LPT;        // token slots per wave
   constexpr int SPB = 4 * TPW;         // token slots per block
-  constexpr int NG = D / kGroup;
   constexpr int kHeadTile = head_tile(D);
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int sub = lane % LPT;          // which 8-element piece of the head vector
   const int slot = wave * TPW + lane / LPT;
-  const int grp = sub / 4;             // quantisation group of that piece
+  const int NG = D / p.group;          // groups per token (the group size is a launch parameter: 32, 64 or 128)
+  const int grp = sub * 8 / p.group;   // quantisation group of that piece
 
   int split = blockIdx.x, b = blockIdx.z, tokens_per_split = p.tokens_per_split, part_stride = p.n_splits;
   if (p.var_chunks > 0) {                         // per-sequence lengths: which (sequence, chunk) is this block's

@@ -9,7 +9,9 @@
 
 namespace tq {
 
-constexpr int kGroup = 32;        // elements per quantisation group (Sec. 2.1)
+constexpr int kGroup = 32;        // elements per quantisation group (Sec. 2.1): the paper's configuration and the one the
+                                  // matrix-core kernels are built for; also the piece of a vector one thread of the
+                                  // quantiser handles.  Groups of 64 and 128 (DecodeParams::group) take the generic kernels.
 constexpr int kMaxSplits = 128;   // upper bound on sequence chunks (Sec. 3.2); sizes the workspace
 constexpr int kTile = 32;         // chunk boundaries are multiples of this many tokens
 constexpr int kMaxQueries = 8;    // query tokens per sequence in one call (the masked path covers two supertiles)
@@ -33,6 +35,7 @@ struct DecodeParams {
   half_t* out;              // [B][n_queries][H_q][D]
   int32_t* plan;            // one int behind part_ml: the chunk length of a device-planned launch, for the merge kernel
   int32_t n_q_heads, n_kv_heads, gqa;
+  int32_t group;            // elements per quantisation group: 32, 64 or 128 (scale / zero-point arrays: D / group per token)
   // Query tokens per sequence (>= 1): the sequence's last n_queries tokens, query t attending all tokens up
   // to its own (n_queries - 1 - t fewer than the sequence holds).  Matrix-core kernel only.
   int32_t n_queries;
@@ -105,17 +108,6 @@ __device__ inline uint32_t quantize_word(const float* x, float sf, float zf) {
   }
   return acc;
 }
-// One group of 32 values (fp16 inputs widened to fp32): the fp16 scale and zero-point and the 32 codes.
-__device__ inline void quantize_group32(const float (&x)[kGroup], uint32_t (&w)[4], half_t& s16, half_t& z16) {
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-  quantize_scale_zero(mn, mx, s16, z16);
-  const float sf = (float)s16, zf = (float)z16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) w[i] = quantize_word(x + 8 * i, sf, zf);
-}
-
 // Device-side chunk plan for per-sequence lengths.  One chunk length C for all sequences (var_chunk_tokens
 // below), so that the list "all chunks of sequence 0, then of sequence 1, ..." has at most p.var_chunks
 // entries: the grid.  Slot s of that list -> (b, chunk); returns false past the end of the list.

@@ -1,9 +1,11 @@
 // Quantise-and-append (Sec. 2.1, Eq. 2-3) and the comparator's dense dequantisation
 // (the materialising step of the dequantize-then-attend baseline, Sec. 3.1).
 //
-// One thread owns one group of 32 consecutive head_dim elements of one token: it reads 64 B of
-// fp16 (four 128-bit loads), finds min/max in registers, and writes 16 B of codes plus one fp16
-// scale and one fp16 zero-point.  No cross-lane traffic, no LDS.  The arithmetic must give the
+// One thread owns 32 consecutive head_dim elements of one token: it reads 64 B of fp16 (four 128-bit loads),
+// finds min/max in registers, and writes 16 B of codes; with groups of 32 that is a whole group, and the
+// thread also writes its fp16 scale and zero-point; a group of 64 or 128 elements is 2 or 4 neighbouring
+// lanes, which exchange their minima and maxima (exact in any order) before the scale is worked out, and the
+// first of them writes it.  No LDS.  The arithmetic must give the
 // same bits on every IEEE machine, so each fp32 step is a separately rounded operation:
 // contraction is off for this file and the correctly rounded divide is used.
 #include "tq_internal.h"
@@ -19,10 +21,11 @@ struct QuantParams {
   half_t* scale[2];       // [B*H_kv][capacity][D/32]
   half_t* zero[2];
   int32_t n_new, capacity, pos, head_dim, n_kv_heads;
+  int32_t group;              // elements per quantisation group: 32, 64 or 128
   const int32_t* pos_dev;     // per-sequence positions (device, [B]) or null
   const int32_t* block_table; // paged cache (see DecodeParams): [B][max_blocks] page numbers, or null
   int32_t max_blocks, page_shift;
-  int64_t groups_per_tensor;  // B*H_kv*n_new*(D/32)
+  int64_t groups_per_tensor;  // B*H_kv*n_new*(D/32): 32-element pieces, one per thread
 };
 
 union Pack16 { uint4 v; half_t h[8]; };
@@ -31,7 +34,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= p.groups_per_tensor) return;
   const int which = blockIdx.y;                       // 0 = K, 1 = V
-  const int ng = p.head_dim / kGroup;
+  const int ng = p.head_dim / kGroup;                 // 32-element pieces per token
   const int g = (int)(idx % ng);
   const int64_t vec = idx / ng;                       // (b*H_kv + h) * n_new + t
   const int64_t bh = vec / p.n_new;
@@ -52,9 +55,22 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) x[8 * i + j] = (float)u.h[j];
   }
-  uint32_t w[4];
+  // Eq. 2 over the whole group: this thread's 32 elements, and with larger groups its 1 or 3 neighbours'
+  // (pieces of a group are consecutive lanes of one wave, and they leave or stay together above)
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int j = 1; j < kGroup; ++j) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+  const int pieces = p.group / kGroup;                 // 1, 2 or 4
+  for (int off = 1; off < pieces; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off));
+    mx = fmaxf(mx, __shfl_xor(mx, off));
+  }
   half_t s16, z16;
-  quantize_group32(x, w, s16, z16);
+  quantize_scale_zero(mn, mx, s16, z16);
+  const float sf = (float)s16, zf = (float)z16;
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = quantize_word(x + 8 * i, sf, zf);   // Eq. 3
   int64_t row = bh * p.capacity + pos + t;
   if (p.block_table) {                                 // paged cache: capacity is the page length
     const int tok = pos + t;
@@ -63,8 +79,10 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantParams p) {
   }
   *reinterpret_cast<uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2)) =
       make_uint4(w[0], w[1], w[2], w[3]);
-  p.scale[which][row * ng + g] = s16;
-  p.zero[which][row * ng + g] = z16;
+  if (g % pieces == 0) {
+    p.scale[which][row * (ng / pieces) + g / pieces] = s16;
+    p.zero[which][row * (ng / pieces) + g / pieces] = z16;
+  }
 }
 
 struct DequantParams {
@@ -72,8 +90,8 @@ struct DequantParams {
   const half_t* scale[2];
   const half_t* zero[2];
   half_t* dense[2];           // [B*H_kv][seq_len][D]
-  int32_t seq_len, capacity, head_dim;
-  int64_t groups_per_tensor;  // B*H_kv*seq_len*(D/32)
+  int32_t seq_len, capacity, head_dim, group;
+  int64_t groups_per_tensor;  // B*H_kv*seq_len*(D/32): 32-element pieces, one per thread
 };
 
 // x^ = (q - z) * s (Eq. 3) rounded to fp16: what "dequantize, then attend" materialises.
@@ -88,8 +106,9 @@ __global__ __launch_bounds__(256) void dequant_dense_kernel(DequantParams p) {
   const int t = (int)(vec % p.seq_len);
   const int64_t row = bh * p.capacity + t;
   const uint4 c = *reinterpret_cast<const uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2));
-  const float sf = (float)p.scale[which][row * ng + g];
-  const float zf = (float)p.zero[which][row * ng + g];
+  const int pieces = p.group / kGroup;                // this piece's group: 32, 64 or 128 elements
+  const float sf = (float)p.scale[which][row * (ng / pieces) + g / pieces];
+  const float zf = (float)p.zero[which][row * (ng / pieces) + g / pieces];
   const uint32_t w[4] = {c.x, c.y, c.z, c.w};
   uint4* dst = reinterpret_cast<uint4*>(p.dense[which] + (vec * p.head_dim + g * kGroup));
 #pragma unroll
@@ -118,6 +137,7 @@ hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* 
   p.zero[0] = static_cast<half_t*>(c.k_zero);
   p.zero[1] = static_cast<half_t*>(c.v_zero);
   p.n_new = n_new;
+  p.group = c.group_size;
   p.capacity = c.capacity;
   p.pos = pos;
   p.pos_dev = pos_dev;
@@ -147,6 +167,7 @@ hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_den
   p.seq_len = seq_len;
   p.capacity = c.capacity;
   p.head_dim = c.head_dim;
+  p.group = c.group_size;
   p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * seq_len * (c.head_dim / kGroup);
   const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);
   hipLaunchKernelGGL(dequant_dense_kernel, dim3(blocks, 2), dim3(256), 0, s, p);

@@ -21,19 +21,19 @@ def np16(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().contiguous().numpy()
 
 
-def gpu_cache_from(k: torch.Tensor, v: torch.Tensor, capacity=None, pos=0, fill=0xEE):
+def gpu_cache_from(k: torch.Tensor, v: torch.Tensor, capacity=None, pos=0, fill=0xEE, group=32):
     """Quantise fp16 CPU tensors k, v [B,Hkv,S,d] into a fresh device cache with the HIP kernel."""
     B, Hkv, S, d = k.shape
-    cache = tq.KVCache(B, Hkv, d, capacity or (pos + S))
+    cache = tq.KVCache(B, Hkv, d, capacity or (pos + S), group_size=group)
     for t in cache.tensors():
         t.view(torch.uint8).fill_(fill)
     tq.tq_quantize_kv(cache, k.cuda(), v.cuda(), pos)
     return cache
 
 
-def oracle_cache_from(k: torch.Tensor, v: torch.Tensor):
-    kc, ks, kz = oracle.quantize(np16(k))
-    vc, vs, vz = oracle.quantize(np16(v))
+def oracle_cache_from(k: torch.Tensor, v: torch.Tensor, group=32):
+    kc, ks, kz = oracle.quantize(np16(k), group=group)
+    vc, vs, vz = oracle.quantize(np16(v), group=group)
     return kc, ks, kz, vc, vs, vz
 
 

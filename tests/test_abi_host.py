@@ -33,6 +33,11 @@ def test_size_queries_follow_the_papers_format():
     assert tq.tq_kv_bytes(1, 8, 131072, 128) == 167772160
     assert tq.tq_kv_bytes(1, 8, 131072, 128) * 80 == oracle.kv_bytes_int4(80, 8, 131072, 128)
     assert tq.tq_kv_bytes(1, 16, 32768, 256) == 167772160
+    # 4 + 32/g bits per element (Sec. 2.1): 5.0, 4.5, 4.25
+    for g, bits in ((32, 5.0), (64, 4.5), (128, 4.25)):
+        assert tq.tq_kv_bytes_grouped(1, 8, 131072, 128, g) * 8 == 2 * 8 * 131072 * 128 * bits
+        assert tq.tq_kv_bytes_grouped(1, 8, 131072, 128, g) * 80 == oracle.kv_bytes_int4(80, 8, 131072, 128, group=g)
+    assert tq.tq_kv_bytes_grouped(1, 8, 1024, 128, 48) == 0 and tq.tq_kv_bytes_grouped(1, 8, 1024, 128, 256) == 0
     assert tq.tq_dense_scratch_bytes(1, 8, 131072, 128) == 2 * 8 * 131072 * 128 * 2
     assert tq.tq_workspace_bytes(1, 64, 128) % 256 == 0 and tq.tq_workspace_bytes(1, 64, 128) > 0
     assert tq.tq_workspace_bytes(0, 64, 128) == 0 and tq.tq_kv_bytes(1, 8, 0, 128) == 0
@@ -76,7 +81,12 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(head_dim=512), wsb=tq.tq_workspace_bytes(1, 64, 512), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 1, 0, 2))) \
         == E.TQ_ERR_UNSUPPORTED                                          # several query tokens: matrix-core kernels only
     assert _decode(_cache(head_dim=1024)) == E.TQ_ERR_SHAPE
-    assert _decode(_cache(group_size=64)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(group_size=48)) == E.TQ_ERR_SHAPE and _decode(_cache(group_size=16)) == E.TQ_ERR_SHAPE
+    assert _decode(_cache(group_size=256)) == E.TQ_ERR_SHAPE
+    # groups of 64 / 128: the generic kernels only (no matrix-core variant, one query token)
+    assert _decode(_cache(group_size=64), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 2, 0, 0))) == E.TQ_ERR_UNSUPPORTED
+    assert _decode(_cache(group_size=128), wsb=tq.tq_workspace_bytes(2, 64, 128),
+                   opts=ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 2))) == E.TQ_ERR_UNSUPPORTED
     assert _decode(_cache(batch=0)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(layout=7)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(), hq=63) == E.TQ_ERR_SHAPE

@@ -132,6 +132,125 @@ def test_append_writes_only_its_positions():
     assert e.value.status == -4
 
 
+# ---------------------------------------------------------------- groups of 64 and 128 elements
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_larger_groups_quantise_bit_exact(group):
+    """Sec. 2.1 states the scheme for groups of g consecutive elements: with g = 64 / 128 two / four lanes of the
+    quantiser share a group (its min and max cross lanes before the scale is worked out).  Special values, edge
+    distributions and random data, bulk and token by token, bit for bit against the oracle at the same group size."""
+    rng = np.random.default_rng(6400 + group)
+    for d in (128, 256, 512):
+        x = _special_values(d)
+        k, v = x, torch.flip(x, dims=(2,)).contiguous()
+        assert_cache_bit_exact(gpu_cache_from(k, v, group=group), oracle_cache_from(k, v, group=group), k.shape[2])
+        B, H, S = 2, 3, 67
+        n = B * H * S * d
+        bits = rng.integers(0, 1 << 16, n, dtype=np.uint16)
+        any_bits = np.where((bits & 0x7C00) == 0x7C00, bits & 0x83FF, bits).astype(np.uint16).view(np.float16)
+        narrow = (rng.normal(0, 1, (n // group, 1)) * 100 + rng.normal(0, 1, (n // group, group)) * 1e-2).astype(np.float16).ravel()
+        ties = ((rng.integers(0, 31, n) * 0.5 + rng.integers(-8, 8, (n // group, 1)).repeat(group, 1).ravel())
+                * np.exp2(rng.integers(-6, 6, (n // group, 1)).repeat(group, 1).ravel())).astype(np.float16)
+        mixed = (rng.normal(0, 1, n) * np.exp2(rng.integers(-20, 14, n))).astype(np.float16)
+        for xs in (any_bits, narrow, ties, mixed):
+            xs = np.where(np.isfinite(xs), xs, np.float16(0)).astype(np.float16).reshape(B, H, S, d)
+            kt, vt = torch.from_numpy(xs.copy()), torch.from_numpy(np.ascontiguousarray(xs[..., ::-1]))
+            ocache = oracle_cache_from(kt, vt, group=group)
+            cache = gpu_cache_from(kt, vt, capacity=S + 3, group=group)
+            torch.cuda.synchronize()
+            assert_cache_bit_exact(cache, ocache, S)
+            for t in cache.tensors():
+                assert bool((t.view(torch.uint8)[:, :, S:] == 0xEE).all())
+            # the step's token through the one-call entry point (append kernel, then the decode)
+            step = gpu_cache_from(kt[:, :, :S - 1].contiguous(), vt[:, :, :S - 1].contiguous(), capacity=S + 3, group=group)
+            tq.tq_sdpa_int4_append_decode(step, kt[:, :, S - 1:].contiguous().cuda(), vt[:, :, S - 1:].contiguous().cuda(),
+                                          torch.zeros(B, 2 * H, d, dtype=torch.float16, device="cuda"), S, 1.0)
+            torch.cuda.synchronize()
+            assert_cache_bit_exact(step, ocache, S)
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256", "g4_d512"])
+def test_larger_groups_decode_matches_oracle(shape, group):
+    """Fused decode attention over a cache quantised in groups of 64 / 128 (generic vector-ALU kernel): lengths
+    around tile boundaries, chunk counts, per-sequence lengths, a sliding window, the one-call step, and the unfused
+    comparator, each against the oracle at the same group size."""
+    shapes = dict(SHAPES, g4_d512=dict(n_q_heads=8, n_kv_heads=2, head_dim=512, v_std=0.5))
+    for S in (1, 33, 1000, 4133):
+        w = wl.custom(seq_len=S, seed=640 + group + S, **shapes[shape])
+        q, k, v = make(w)
+        cache = gpu_cache_from(k, v, capacity=S + 7, group=group)
+        ocache = oracle_cache_from(k, v, group=group)
+        assert_cache_bit_exact(cache, ocache, S)
+        ref = oracle_attend(q, ocache, S, w.attn_scale)
+        for n_splits in (0, 1, 3, 128):
+            out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, n_splits=n_splits)
+            torch.cuda.synchronize()
+            assert_close(out, ref, f"{shape} g={group} S={S} n_splits={n_splits}")
+        assert_close(tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=1), ref, f"{shape} g={group} variant 1")
+        with pytest.raises(tq.TqError) as e:       # the matrix-core kernels are built around groups of 32
+            tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2)
+        assert e.value.status == -6
+        lens = [max(1, S - 19 * b) for b in range(w.batch)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_varlen(q, ocache, lens, w.attn_scale), f"{shape} g={group} per-sequence lengths S={S}")
+        win = max(1, S // 3)
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, window=win)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_window(q, ocache, [S] * w.batch, win, w.attn_scale), f"{shape} g={group} window S={S}")
+        base = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale)
+        torch.cuda.synchronize()
+        assert_comparator_close(base, q, ocache, S, w.attn_scale, f"{shape} g={group} comparator S={S}")
+        if S > 1:                                   # one decode step in one call
+            step = gpu_cache_from(k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(), capacity=S + 7, group=group)
+            out = tq.tq_sdpa_int4_append_decode(step, k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda(),
+                                                q.cuda(), S, w.attn_scale)
+            torch.cuda.synchronize()
+            assert_cache_bit_exact(step, ocache, S)
+            assert_close(out, ref, f"{shape} g={group} step S={S}")
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_larger_groups_over_a_paged_pool(group):
+    """Groups of 64 / 128 through the block table: fill, one step per sequence (append + attend in one call) and a
+    sliding window, against the oracle at the same group size."""
+    lens = [900, 77, 1300, 256]
+    PT, max_blocks, n_pages = 256, 6, 30
+    w = wl.custom(batch=len(lens), seq_len=max(lens), seed=660 + group, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                  outlier_channels=4)
+    q, k, v = make(w)
+    B, Hkv, d, S = w.batch, w.n_kv_heads, w.head_dim, w.seq_len
+    table = np.random.default_rng(6).permutation(n_pages)[:B * max_blocks].reshape(B, max_blocks).astype(np.int32)
+    table_dev = torch.from_numpy(table).cuda()
+    pool = tq.KVCache(n_pages, Hkv, d, PT, group_size=group)
+    for t in pool.tensors():
+        t.view(torch.uint8).fill_(0xEE)
+    # every sequence's tokens but its last go in by the bulk fill (positions 0), the last by the one-call step
+    kz, vz = k.clone(), v.clone()
+    tq.tq_quantize_kv_paged(pool, table_dev, kz.cuda(), vz.cuda(), torch.zeros(B, dtype=torch.int32, device="cuda"))
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    kn = torch.stack([k[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([v[b, :, lens[b] - 1:lens[b]] for b in range(B)]).contiguous()
+    for t in pool.tensors():                      # wipe each sequence's last token: the step has to write it again
+        for b in range(B):
+            t.view(torch.uint8)[table[b, (lens[b] - 1) // PT], :, (lens[b] - 1) % PT] = 0xEE
+    ocache = oracle_cache_from(k, v, group=group)
+    out = tq.tq_sdpa_int4_append_decode_paged(pool, table_dev, kn.cuda(), vn.cuda(), q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_varlen(q, ocache, lens, w.attn_scale), f"paged step g={group}")
+    for b in range(B):                            # the stored bits, read back through the table
+        for t, o in zip(pool.tensors(), ocache):
+            g = np.concatenate([np16(t)[table[b, j]] for j in range((lens[b] + PT - 1) // PT)], axis=1)[:, :lens[b]]
+            o = o[b, :, :lens[b]]
+            if g.dtype == np.float16:
+                g, o = g.view(np.uint16), o.view(np.uint16)
+            assert np.array_equal(g, o), f"sequence {b}"
+    out = tq.tq_sdpa_int4_decode_paged(pool, table_dev, q.cuda(), lens_dev, S, w.attn_scale, window=100)
+    torch.cuda.synchronize()
+    assert_close(out, _oracle_window(q, ocache, lens, 100, w.attn_scale), f"paged window g={group}")
+
+
 # ---------------------------------------------------------------- fused decode attention
 
 SHAPES = {
