@@ -85,22 +85,47 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
   const int lead = (p.block_table && p.seq_lens) ? var_first(p, b) - start : 0;
   const int64_t row0 = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + start;
 
-  for (int t0 = begin; t0 < end; t0 += SPB) {
-    const int t = t0 + slot;
-    const bool valid = t < end && t >= lead;
-    const int tc = t < end ? t : end - 1;                // clamped: always a written token
-    int64_t row = row0 + tc;
+  // row of the arrays that holds token t of this sequence (clamped to the chunk: always a written token)
+  auto row_of = [&](int t) -> int64_t {
+    const int tc = t < end ? t : end - 1;
     if (p.block_table) {                                 // paged cache: the page the block table names for this token
       const int ta = start + tc;
       const int page = p.block_table[(int64_t)b * p.max_blocks + (ta >> p.page_shift)];
-      row = ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & ((1 << p.page_shift) - 1));
+      return ((int64_t)page * p.n_kv_heads + kv) * p.row_stride + (ta & ((1 << p.page_shift) - 1));
     }
+    return row0 + tc;
+  };
+  // Dense fp16 rows (the comparator): 32 bytes per lane and token are all a pass asks of the memory system, far
+  // too little in flight to keep it busy, so the loads run kAhead passes ahead of the arithmetic in a small
+  // register ring (a pass past the end of the chunk re-reads its last row).
+  constexpr int kAhead = DENSE ? 3 : 0;
+  uint4 k_raw[kAhead + 1], v_raw[kAhead + 1];
+  if constexpr (DENSE) {
+#pragma unroll
+    for (int s = 0; s < kAhead; ++s) {
+      const int64_t row = row_of(begin + s * SPB + slot);
+      k_raw[s] = *reinterpret_cast<const uint4*>(p.k_dense + row * D + sub * 8);
+      v_raw[s] = *reinterpret_cast<const uint4*>(p.v_dense + row * D + sub * 8);
+    }
+  }
+
+  for (int t0 = begin; t0 < end; t0 += SPB) {
+    const int t = t0 + slot;
+    const bool valid = t < end && t >= lead;
+    const int64_t row = row_of(t);
 
     float kf[8], vf[8];
     if constexpr (DENSE) {
+      {
+        const int64_t ahead = row_of(t + kAhead * SPB);
+        k_raw[kAhead] = *reinterpret_cast<const uint4*>(p.k_dense + ahead * D + sub * 8);
+        v_raw[kAhead] = *reinterpret_cast<const uint4*>(p.v_dense + ahead * D + sub * 8);
+      }
       Pack16 ku, vu;
-      ku.v = *reinterpret_cast<const uint4*>(p.k_dense + row * D + sub * 8);
-      vu.v = *reinterpret_cast<const uint4*>(p.v_dense + row * D + sub * 8);
+      ku.v = k_raw[0];
+      vu.v = v_raw[0];
+#pragma unroll
+      for (int s = 0; s < kAhead; ++s) { k_raw[s] = k_raw[s + 1]; v_raw[s] = v_raw[s + 1]; }
 #pragma unroll
       for (int j = 0; j < 8; ++j) { kf[j] = (float)ku.h[j]; vf[j] = (float)vu.h[j]; }
     } else {
@@ -123,12 +148,19 @@ __global__ __launch_bounds__(256) void decode_partial_valu_kernel(DecodeParams p
 #pragma unroll
       for (int off = 1; off < LPT; off <<= 1) a += __shfl_xor(a, off);   // Alg. 1, the score
       const float m_new = valid ? fmaxf(m[h], a) : m[h];
-      const float corr = exp2f(m[h] - m_new);
-      const float pr = valid ? exp2f(a - m_new) : 0.0f;
-      l[h] = fmaf(l[h], corr, pr);
+      // Alg. 1's correction factor is 1 unless this token raises the running maximum of some slot of the wave,
+      // which soon becomes rare: the accumulator is only rescaled then
+      if (__builtin_amdgcn_ballot_w64(m_new > m[h]) != 0) {
+        const float corr = __builtin_amdgcn_exp2f(m[h] - m_new);
+        l[h] *= corr;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o[h][j] = fmaf(o[h][j], corr, pr * vf[j]);
-      m[h] = m_new;
+        for (int j = 0; j < 8; ++j) o[h][j] *= corr;
+        m[h] = m_new;
+      }
+      const float pr = valid ? __builtin_amdgcn_exp2f(a - m_new) : 0.0f;
+      l[h] += pr;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[h][j] = fmaf(pr, vf[j], o[h][j]);
     }
   }
 
