@@ -4,6 +4,8 @@
   kernel trace : python bench_profile.py trace  <dir with *_kernel_stats.csv>
   HBM traffic  : python bench_profile.py traffic <FETCH_SIZE run dir> <WRITE_SIZE run dir> [--json profiles/traffic.json]
                  [--workload NAME]   (the key in the JSON file; default llama128k; a workload of 167 772 160 packed bytes)
+  counters     : python bench_profile.py counters <--pmc run dir> [<--pmc run dir> ...]
+                 (per-dispatch means of every counter collected for the decode kernels, and what follows from them)
 
 The traffic mode expects both runs to come from `bench.py --calibrate-copy`: the plain device copy of
 known size in that run gives the factor between the counter's reading and real bytes.
@@ -76,9 +78,41 @@ def traffic(fetch_dir, write_dir, json_path=None, workload="llama128k", known_by
         print(f"wrote {json_path}")
 
 
+def counters(dirs):
+    """Per-dispatch means of the counters of the decode kernels (first quarter of the dispatches dropped: warm-up)."""
+    acc = {}
+    for d in dirs:
+        for r in _rows(d, "counter_collection.csv"):
+            k = r["Kernel_Name"]
+            if "decode_partial" not in k:
+                continue
+            name = "decode_partial" + k.split("decode_partial")[1].split("(")[0]
+            acc.setdefault(name, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    for name, cs in acc.items():
+        m = {c: statistics.fmean(v[len(v) // 4:]) for c, v in cs.items()}
+        print(f"kernel {name}  ({len(next(iter(cs.values())))} dispatches)")
+        for c in sorted(m):
+            print(f"  {c:30s} {m[c]:16.1f}")
+        w = m.get("SQ_WAVES")
+        if w:
+            simds = 1024.0                                 # 256 compute units x 4
+            print(f"  -- per wave: VALU instructions {m.get('SQ_INSTS_VALU', 0) / w:.0f} (of which matrix {m.get('SQ_INSTS_MFMA', 0) / w:.0f}), "
+                  f"scalar {m.get('SQ_INSTS_SALU', 0) / w:.0f}, LDS {m.get('SQ_INSTS_LDS', 0) / w:.0f}, vector memory {m.get('SQ_INSTS_VMEM_RD', 0) / w:.0f}")
+            if "SQ_WAVE_CYCLES" in m and "SQ_ACTIVE_INST_VALU" in m:
+                # SQ_WAVE_CYCLES and SQ_ACTIVE_INST_* count in units of 4 cycles, summed over waves / SIMDs
+                wave_q = m["SQ_WAVE_CYCLES"] / w
+                print(f"  -- a wave lives {4 * wave_q:.0f} cycles; its SIMD's vector ALU is busy {100 * (m['SQ_ACTIVE_INST_VALU'] / simds) / wave_q:.0f} % "
+                      f"of that; matrix cores busy {100 * (m.get('SQ_VALU_MFMA_BUSY_CYCLES', 0) / simds) / (4 * wave_q):.0f} %; "
+                      f"waves waiting on any counter {100 * m.get('SQ_WAIT_INST_ANY', 0) / m['SQ_WAVE_CYCLES']:.0f} % of their time")
+            if "SQ_LDS_BANK_CONFLICT" in m and m.get("SQ_LDS_IDX_ACTIVE"):
+                print(f"  -- LDS bank-conflict cycles / LDS active cycles: {100 * m['SQ_LDS_BANK_CONFLICT'] / m['SQ_LDS_IDX_ACTIVE']:.0f} %")
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "trace":
         trace(sys.argv[2])
+    elif len(sys.argv) >= 3 and sys.argv[1] == "counters":
+        counters(sys.argv[2:])
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         jp = sys.argv[sys.argv.index("--json") + 1] if "--json" in sys.argv else None
         wl = sys.argv[sys.argv.index("--workload") + 1] if "--workload" in sys.argv else "llama128k"
