@@ -108,6 +108,42 @@ __device__ inline uint32_t quantize_word(const float* x, float sf, float zf) {
   }
   return acc;
 }
+// The same codes, bit for bit, without a correctly rounded divide per element.  x / s + z is formed as one fused
+// multiply-add with a reciprocal of s refined once per group (the scale is shared), which lands within a few units
+// in the last place of what quantize_word rounds.  The two can pick different codes only where the value sits that
+// close to a rounding boundary k + 1/2: those elements push `far` (the largest distance of a value from its rounded
+// integer) up to 1/2 - tol, and the caller then redoes its words with quantize_word, so that the result never
+// depends on the shortcut.  On zero-mean data about one group in a thousand is redone.
+struct QuantFast { float zf, rcp, tol; };
+__device__ inline QuantFast quantize_fast_setup(float sf, float zf, float abs_max) {
+#pragma clang fp contract(off)
+  QuantFast f;
+  f.zf = zf;
+  const float r0 = __builtin_amdgcn_rcpf(sf);              // 1 ulp; one Newton step brings it to about half an ulp
+  f.rcp = __builtin_fmaf(__builtin_fmaf(-sf, r0, 1.0f), r0, r0);
+  // with Q = abs_max / s >= |x/s| and V = Q + |z| >= |x/s + z|: the reciprocal moves the quotient by at most
+  // 2^-23 Q, quantize_word's own two roundings by 2^-24 (Q + V), the fused one by 2^-24 V: below 2^-21 V together,
+  // doubled for margin
+  f.tol = (abs_max * f.rcp * 1.0001f + fabsf(zf)) * 0x1p-20f;
+  return f;
+}
+__device__ inline bool quantize_fast_in_doubt(float far, const QuantFast& f) { return !(far < 0.5f - f.tol); }
+__device__ inline uint32_t quantize_word_fast(const half_t* x, const QuantFast& f, float& far) {
+#pragma clang fp contract(off)
+  // Adding 1.5 * 2^23 rounds a value of [0, 15] to an integer, half to even, and leaves that integer in the low
+  // bits of the sum's encoding; eight encodings summed at 4-bit offsets carry the same known excess.
+  constexpr float kMagic = 12582912.0f;
+  constexpr uint32_t kExcess = 0x4B400000u * 0x11111111u;
+  uint32_t acc = 0;
+#pragma unroll
+  for (int j = 7; j >= 0; --j) {
+    const float v = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)x[j], f.rcp, f.zf), 0.0f, 15.0f);
+    const float t = v + kMagic;
+    far = fmaxf(far, fabsf(v - (t - kMagic)));
+    acc = (acc << 4) + __float_as_uint(t);
+  }
+  return acc - kExcess;
+}
 // Device-side chunk plan for per-sequence lengths.  One chunk length C for all sequences (var_chunk_tokens
 // below), so that the list "all chunks of sequence 0, then of sequence 1, ..." has at most p.var_chunks
 // entries: the grid.  Slot s of that list -> (b, chunk); returns false past the end of the list.
