@@ -101,16 +101,23 @@ struct Cfg {
   static constexpr int NJ = NG;                  // K MFMAs per 16-token tile (= packed words per lane)
   static constexpr int NCS = D / 128;            // V column sets (16 packed words each)
   static constexpr bool SWAP = (D == 128 && GP == 8);
-  static_assert(NG % GR == 0 && NA >= 1 && NA <= 2, "unsupported (head_dim, padded GQA) pair");
+  // WIDE: every column of the tile is a query row of its own (no group replicas), so each of the four groups of
+  // a token has its own score accumulator, and the P V columns are regrouped so that the 16 columns of one
+  // matrix instruction lie in ONE group (see `pv`): its A operand p * s_v is then right for all of them.
+  static constexpr bool WIDE = (GR == 1);
+  static constexpr int NDW = (NA + 1) / 2;       // dwords of fp16 scales (or zero-points) a lane needs per token
+  static_assert(NG % GR == 0 && NA >= 1 && (NA <= 2 || (WIDE && D == 128)), "unsupported (head_dim, padded GQA) pair");
   // K MFMA j takes, from lane block kq, packed word a_word(j,kq) of group a_group(j,kq) and adds
   // into accumulator acc(j); column replica r of that accumulator stands for group r*NA + acc(j).
   static __device__ constexpr int a_group(int j, int kq) {
-    return SWAP ? 2 * (kq >> 1) + (j & 1) : (D == 128 ? kq : 2 * kq + (j >> 2));
+    return WIDE ? j : SWAP ? 2 * (kq >> 1) + (j & 1) : (D == 128 ? kq : 2 * kq + (j >> 2));
   }
   static __device__ constexpr int a_word(int j, int kq) {
-    return SWAP ? 2 * (j >> 1) + (kq & 1) : (D == 128 ? j : (j & 3));
+    return WIDE ? kq : SWAP ? 2 * (j >> 1) + (kq & 1) : (D == 128 ? j : (j & 3));
   }
-  static __device__ constexpr int acc(int j) { return SWAP ? (j & 1) : (D == 128 ? 0 : (NA == 2 ? (j >> 2) : 0)); }
+  static __device__ constexpr int acc(int j) {
+    return WIDE ? j : SWAP ? (j & 1) : (D == 128 ? 0 : (NA == 2 ? (j >> 2) : 0));
+  }
 
   // LDS stage of one 32-token supertile, in the order the stream is laid out in HBM
   static constexpr int TB = D / 2;               // bytes of codes per token
@@ -133,21 +140,24 @@ struct Cfg {
   // Where the query block of a wave lands before it is turned into operands: in an area of its own if
   // there is room, so that the whole ring can be filled at once; else in the last ring slot.
   static constexpr int QBLK = GP * D * 2;
+  static_assert(QBLK <= STAGE, "the query block borrows one ring slot");
   static constexpr bool QSEP = !ALIAS && RING + MERGE + NW * QBLK <= 160 * 1024;
   static constexpr int OFF_QBLK = RING + MERGE;
   static constexpr int SMEM = ALIAS ? (RING > MERGE ? RING : MERGE) : RING + MERGE + (QSEP ? NW * QBLK : 0);
   // The fp16 scale and zero-point arrays are fetched dword by dword (two groups of one token), and the
   // direct loads may gather: with NA == 2 a lane needs exactly one dword per token, so the dwords are
-  // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads.
+  // laid out in LDS as [kq][replica][tile][i] and a lane reads its eight tokens with two 16-byte reads; with
+  // NA == 4 (WIDE) it needs both dwords of a token: [kq][dword][tile][i], four 16-byte reads.
   static constexpr bool PERM = (NA == 2);
   // Whether the K part of the next supertile is fetched into registers during the current one (it is
   // not where the accumulators alone take half of the register file).
   static constexpr bool PFK = !(D == 256 && NA == 2);
   static __device__ constexpr int sz_token(int P) {       // token (0..31) whose dword sits at stage dword P
-    return PERM ? 16 * ((P >> 2) & 1) + 4 * (P & 3) + (P >> 3) / GR : P / (NG / 2);
+    return WIDE ? 16 * ((P >> 2) & 1) + 4 * (P & 3) + (P >> 4)
+                : PERM ? 16 * ((P >> 2) & 1) + 4 * (P & 3) + (P >> 3) / GR : P / (NG / 2);
   }
   static __device__ constexpr int sz_column(int P) {      // which dword of that token's NG/2
-    return PERM ? (P >> 3) % GR : P % (NG / 2);
+    return WIDE ? (P >> 3) & 1 : PERM ? (P >> 3) % GR : P % (NG / 2);
   }
 };
 
@@ -507,11 +517,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //      Where the query block has to borrow the last ring slot, that slot is filled once the query
   //      operands sit in registers.
   constexpr int NPRE = C::QSEP ? NS : NS - 1;     // stages issued before the query operands are built
-  char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + C::OFF_V;
+  // (a borrowed slot: behind its K tiles where the block fits there, else from the slot's start)
+  constexpr int Q_IN_SLOT = C::QBLK <= C::STAGE - C::OFF_V ? C::OFF_V : 0;
+  char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + Q_IN_SLOT;
   {
     const uint32_t l = C::QSEP ? (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + C::OFF_QBLK +
                                      wave * C::QBLK
-                               : ring_lds + (NS - 1) * C::STAGE + C::OFF_V;
+                               : ring_lds + (NS - 1) * C::STAGE + Q_IN_SLOT;
 #pragma unroll
     for (int u = 0; u < GP * D * 2 / 1024; ++u) {
       const int chunk = u * 64 + lane;            // 16-byte chunk of the [GP][D] fp16 query block
@@ -598,8 +610,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   float m_run = kNegBig;                          // per-head reference for exp2 (raw units)
   float l_run = 0.0f;                             // this lane's share of sum(exp)
   float4v zacc[NA];                               // sum_t w z - 15 sum_t1 w (w = p s_v), rows (head, replica), col = group
-  float4v oacc[NCS][8][NA];                       // rows (head, replica), col = packed word; [2j]: sum_t w c - 15 sum_t1 w for
-                                                  // dim 2j of the word, [2j+1]: the same for c(2j) + 16 c(2j+1), less 255 sum_t1 w
+  // rows (head, replica), col = packed word; [2j]: sum_t w c - 15 sum_t1 w for dim 2j of the word, [2j+1]: the same
+  // for c(2j) + 16 c(2j+1), less 255 sum_t1 w.  WIDE: [2g], [2g+1] are the even and the mixed sum of group g, whose
+  // column c stands for byte c / 4 of the group's word c % 4; one accumulator each.
+  constexpr int NAO = C::WIDE ? 1 : NA;
+  float4v oacc[NCS][8][NAO];
 #pragma unroll
   for (int a = 0; a < NA; ++a) zacc[a] = float4v{0, 0, 0, 0};
 #pragma unroll
@@ -607,29 +622,34 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
     for (int m = 0; m < 8; ++m)
 #pragma unroll
-      for (int a = 0; a < NA; ++a) oacc[cs][m][a] = float4v{0, 0, 0, 0};
+      for (int a = 0; a < NAO; ++a) oacc[cs][m][a] = float4v{0, 0, 0, 0};
 
   const half8v pos15_odd = as_half8(kPos15Odd, kPos15Odd, kPos15Odd, kPos15Odd);
 
   // per-lane LDS byte offsets inside a stage
   // K codes: the 16 B this lane asked for; where the query operand is block-diagonal over pairs of
   // groups (SWAP), words w and w+2 of groups 2(kq/2) and 2(kq/2)+1 of token row c instead
-  const uint32_t k_rd = C::SWAP ? (32 * (kq >> 1) + c) * 16 + 4 * (kq & 1) : lane * 16;
-  const uint32_t v_rd = kq * TB + c * 4 * NCS;                      // packed word(s) c of token kq (+4i)
+  // (WIDE: word kq of every group of token row c, one dword each, 256 B apart)
+  const uint32_t k_rd = C::WIDE ? c * 16 + 4 * kq : C::SWAP ? (32 * (kq >> 1) + c) * 16 + 4 * (kq & 1) : lane * 16;
+  // packed word(s) c of token kq (+4i); WIDE: word c % 4 of every group, 16 B apart
+  const uint32_t v_rd = C::WIDE ? kq * TB + (c & 3) * 4 : kq * TB + c * 4 * NCS;
+  const uint32_t v_sel = 0x0C000C00u | ((4u + (c >> 2)) << 16) | (uint32_t)(c >> 2);   // WIDE: this column's byte of a word
   // scales of this lane's groups / zero-point of the group this lane's P V column (packed word c) lies in,
   // tokens kq (+4i): eight consecutive dwords in the permuted layout, else one halfword per token at the
   // array's own stride
-  const int gz = (c * NCS) >> 2;
-  const uint32_t sz_rd = C::PERM ? (kq * GR + rep) * 32 : (kq * NG + rep * NA) * 2;
-  const uint32_t zb_rd = C::PERM ? (kq * GR + (gz >> 1)) * 32 : (kq * NG + gz) * 2;
+  // (WIDE: the zero-point operand's column c stands for group c % 4)
+  const int gz = C::WIDE ? (c & 3) : (c * NCS) >> 2;
+  const uint32_t sz_rd = C::WIDE ? kq * 64 : C::PERM ? (kq * GR + rep) * 32 : (kq * NG + rep * NA) * 2;
+  const uint32_t zb_rd = C::WIDE ? kq * 64 + (gz >> 1) * 32 : C::PERM ? (kq * GR + (gz >> 1)) * 32 : (kq * NG + gz) * 2;
   const uint32_t zb_sel = (gz & 1) ? 0x07060302u : 0x05040100u;   // which half of a zero-point dword
 
   // Everything a supertile needs from LDS is fetched into registers well before it is used: the K part
   // while the previous supertile is still in its P V phase, the V part at the start of the K phase.
-  struct KRegs { uint32_t kw[2][NJ]; uint32_t ks[2][4], kz[2][4]; };   // kw[t][j]: A operand of K MFMA j, tile t
-  struct VRegs { uint32_t v[NCS][8]; uint32_t vs[2][4]; uint32_t zb[8]; };
-  auto load_sz = [&](const char* arr, uint32_t rd, uint32_t (&dst)[2][4]) {
-    if constexpr (C::PERM) {
+  constexpr int NDW = C::NDW, NVW = C::WIDE ? NG : NCS;
+  struct KRegs { uint32_t kw[2][NJ]; uint32_t ks[NDW][2][4], kz[NDW][2][4]; };   // kw[t][j]: A operand of K MFMA j, tile t
+  struct VRegs { uint32_t v[NVW][8]; uint32_t vs[NDW][2][4]; uint32_t zb[8]; };
+  auto load_sz1 = [&](const char* arr, uint32_t rd, uint32_t (&dst)[2][4]) {
+    if constexpr (C::PERM || C::WIDE) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const uint4v x = *reinterpret_cast<const uint4v*>(arr + rd + t * 16);
@@ -643,11 +663,18 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
           dst[t][i] = *reinterpret_cast<const uint16_t*>(arr + (t * 16 + i * 4) * NG * 2 + rd);
     }
   };
+  auto load_sz = [&](const char* arr, uint32_t rd, uint32_t (&dst)[NDW][2][4]) {
+#pragma unroll
+    for (int dw = 0; dw < NDW; ++dw) load_sz1(arr + dw * 32, rd, dst[dw]);
+  };
   auto load_k = [&](int slot, KRegs& r) {
     const char* st = ring + slot * C::STAGE;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      if constexpr (C::SWAP) {
+      if constexpr (C::WIDE) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) r.kw[t][j] = *reinterpret_cast<const uint32_t*>(st + t * C::KT + j * 256 + k_rd);
+      } else if constexpr (C::SWAP) {
         // the lane wants words w, w+2 of two neighbouring groups, 256 B apart in the tile: two 2-dword reads
         const uint32_t* g0 = reinterpret_cast<const uint32_t*>(st + t * C::KT + k_rd);
         r.kw[t][0] = g0[0]; r.kw[t][2] = g0[2]; r.kw[t][1] = g0[64]; r.kw[t][3] = g0[66];
@@ -666,13 +693,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   auto load_v = [&](int slot, VRegs& r) {
     const char* st = ring + slot * C::STAGE;
 #pragma unroll
-    for (int cs = 0; cs < NCS; ++cs)
+    for (int cs = 0; cs < NVW; ++cs)
 #pragma unroll
       for (int i = 0; i < 8; ++i)                 // token slot i: token 16*(i/4) + 4*(i%4) + kq
-        r.v[cs][i] = *reinterpret_cast<const uint32_t*>(st + C::OFF_V + (16 * (i >> 2) + 4 * (i & 3)) * TB + v_rd + cs * 4);
+        r.v[cs][i] = *reinterpret_cast<const uint32_t*>(st + C::OFF_V + (16 * (i >> 2) + 4 * (i & 3)) * TB + v_rd +
+                                                        cs * (C::WIDE ? 16 : 4));
     load_sz(st + C::OFF_VS, sz_rd, r.vs);
     uint32_t zr[2][4];
-    load_sz(st + C::OFF_VZ, zb_rd, zr);
+    load_sz1(st + C::OFF_VZ, zb_rd, zr);
 #pragma unroll
     for (int i = 0; i < 8; ++i) r.zb[i] = zr[i >> 2][i & 3];
     __builtin_amdgcn_sched_barrier(0);
@@ -695,11 +723,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       for (int j = 0; j < NJ; ++j) acc[C::acc(j)] = mfma16(unpack_word(r.kw[t][j]), qb[j], acc[C::acc(j)]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {               // token 16t + 4i + kq
-        float x = __builtin_fmaf((float)sz_half(r.ks[t][i], 0),
-                                 __builtin_fmaf(-(float)sz_half(r.kz[t][i], 0), qsum[0], acc[0][i]), 0.0f);
-        if constexpr (NA == 2)
-          x = __builtin_fmaf((float)sz_half(r.ks[t][i], 1),
-                             __builtin_fmaf(-(float)sz_half(r.kz[t][i], 1), qsum[NA - 1], acc[NA - 1][i]), x);
+        float x = 0.0f;
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+          x = __builtin_fmaf((float)sz_half(r.ks[a >> 1][t][i], a & 1),
+                             __builtin_fmaf(-(float)sz_half(r.kz[a >> 1][t][i], a & 1), qsum[a], acc[a][i]), x);
         if constexpr (GR >= 2) x = row_ror_add<8>(x);
         if constexpr (GR >= 4) x = row_ror_add<4>(x);
         if constexpr (GR >= 8) x = row_ror_add<2>(x);
@@ -747,7 +775,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
         for (int m = 0; m < 8; ++m)
 #pragma unroll
-          for (int a = 0; a < NA; ++a)
+          for (int a = 0; a < NAO; ++a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) oacc[cs][m][a][i] *= fr[i];
     }
@@ -765,11 +793,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     for (int i = 0; i < 4; ++i) {                 // k-slots 2i, 2i+1: tokens 4i + kq of tile 0 and of tile 1
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
-        pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)sz_half(r.vs[0][i], a), 0.0f);
-        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(-pr[1][i], (float)sz_half(r.vs[1][i], a), 0.0f);
+        pa[a][2 * i] = (_Float16)__builtin_fmaf(pr[0][i], (float)sz_half(r.vs[a >> 1][0][i], a & 1), 0.0f);
+        pa[a][2 * i + 1] = (_Float16)__builtin_fmaf(-pr[1][i], (float)sz_half(r.vs[a >> 1][1][i], a & 1), 0.0f);
       }
     }
-    if constexpr (C::PERM) {
+    if constexpr (C::PERM || C::WIDE) {
       uint32_t zw[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) zw[i] = __builtin_amdgcn_perm(r.zb[4 + i], r.zb[i], zb_sel) ^ 0x80000000u;
@@ -798,7 +826,22 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //    error budget.)  The complement of the second tile (15 - n in every nibble, i.e. 255 - byte) keeps both
   //    accumulators balanced around zero as before:  even: -15 sum_t1 w,  mixed: -255 sum_t1 w,  so that
   //    (mixed - even) / 16 carries the same -15 sum_t1 w that the zero-point sum cancels.
+  //    WIDE: the 16 columns of a matrix instruction are the 4 words x 4 bytes of ONE group (column c = byte c / 4
+  //    of word c % 4), so the lane holds that word of every group and picks its byte with a selector of its own.
   auto pv = [&](const VRegs& r, const half8v (&pa)[NA]) {
+    if constexpr (C::WIDE) {
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        uint32_t mix[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mix[i] = __builtin_amdgcn_perm(~r.v[g][i + 4], r.v[g][i], v_sel);
+        const half8v v_mixed = as_half8(mix[0], mix[1], mix[2], mix[3]);
+        const half8v v_even = as_half8(mix[0] & kMaskLo, mix[1] & kMaskLo, mix[2] & kMaskLo, mix[3] & kMaskLo);
+        oacc[0][2 * g][0] = mfma16(pa[g], v_even, oacc[0][2 * g][0]);
+        oacc[0][2 * g + 1][0] = mfma16(pa[g], v_mixed, oacc[0][2 * g + 1][0]);
+      }
+      return;
+    }
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
       uint32_t v1[4];
@@ -813,7 +856,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         const half8v v_mixed = as_half8(mix[0], mix[1], mix[2], mix[3]);
         const half8v v_even = as_half8(mix[0] & kMaskLo, mix[1] & kMaskLo, mix[2] & kMaskLo, mix[3] & kMaskLo);
 #pragma unroll
-        for (int a = 0; a < NA; ++a) {
+        for (int a = 0; a < NAO; ++a) {
           oacc[cs][2 * j][a] = mfma16(pa[a], v_even, oacc[cs][2 * j][a]);
           oacc[cs][2 * j + 1][a] = mfma16(pa[a], v_mixed, oacc[cs][2 * j + 1][a]);
         }
@@ -905,8 +948,23 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     lds_m[hl * NW + wave] = (active && m_run > kNegBig) ? m_run * kappa : kNegBig;
     lds_l[hl * NW + wave] = active ? l_tot : 0.0f;
   }
+  if constexpr (C::WIDE) {
+    // row 4 kq + i = head; group g's zero-point sum of that head sits in column g (any column c with c % 4 == g)
+    // of zacc[g]; this lane's column is byte c / 4 of word c % 4 of every group: two neighbouring dims per group
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const float zc = __shfl(zacc[g][i], (lane & 48) | g);
+        const float even = oacc[0][2 * g][0][i], mixed = oacc[0][2 * g + 1][0][i];
+        float2 o2;
+        o2.x = fmaf(even, 0x1p24f, -zc);
+        o2.y = fmaf(mixed - even, 0x1p20f, -zc);
+        *reinterpret_cast<float2*>(lds_o + (wave * GP + 4 * kq + i) * D + (4 * g + (c & 3)) * 8 + 2 * (c >> 2)) = o2;
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < (C::WIDE ? 0 : 4); ++i) {
     const int r = 4 * kq + i, h = r % GP, rp = r / GP;       // accumulator row -> (head, replica)
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
@@ -917,7 +975,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       float4v lo, hi;
       float acc[8];
 #pragma unroll
-      for (int m = 0; m < 8; ++m) acc[m] = second ? oacc[cs][m][NA - 1][i] : oacc[cs][m][0][i];
+      for (int m = 0; m < 8; ++m) acc[m] = second ? oacc[cs][m][NAO - 1][i] : oacc[cs][m][0][i];
 #pragma unroll
       for (int m = 0; m < 4; ++m) {               // dim m: the even sum, or (mixed - even) / 16, in units of 2^-24
         lo[m] = fmaf((m & 1) ? acc[m] - acc[m - (m & 1)] : acc[m], (m & 1) ? 0x1p20f : 0x1p24f, -zc);
@@ -1031,20 +1089,20 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     c_l[(idx / n) * kMaxSplits + idx % n] = ld_dev(ml + 1);
   }
   __syncthreads();
-  if (wave < G) {                                 // wave h: weights and denominator of head h
+  for (int h = wave; h < G; h += NW) {            // a wave per head: its chunk weights and its denominator
     float mx = kNegBig;
-    for (int cc = lane; cc < n; cc += 64) mx = fmaxf(mx, c_m[wave * kMaxSplits + cc]);
+    for (int cc = lane; cc < n; cc += 64) mx = fmaxf(mx, c_m[h * kMaxSplits + cc]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     float dsum = 0.0f;
     for (int cc = lane; cc < n; cc += 64) {
-      const float w = __builtin_amdgcn_exp2f(c_m[wave * kMaxSplits + cc] - mx);
-      c_m[wave * kMaxSplits + cc] = w;
-      dsum = fmaf(c_l[wave * kMaxSplits + cc], w, dsum);
+      const float w = __builtin_amdgcn_exp2f(c_m[h * kMaxSplits + cc] - mx);
+      c_m[h * kMaxSplits + cc] = w;
+      dsum = fmaf(c_l[h * kMaxSplits + cc], w, dsum);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) dsum += __shfl_xor(dsum, off);
-    if (lane == 0) h_den[wave] = dsum;
+    if (lane == 0) h_den[h] = dsum;
   }
   __syncthreads();
 #pragma unroll
@@ -1071,14 +1129,18 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 }
 
 int padded_gqa(int head_dim, int gqa) {           // columns a group of `gqa` heads takes in the tile; 0 = too many
-  if (head_dim == 128) return gqa <= 4 ? 4 : (gqa <= 8 ? 8 : 0);
+  if (head_dim == 128) return gqa <= 4 ? 4 : (gqa <= 8 ? 8 : (gqa <= 16 ? 16 : 0));
   return gqa <= 2 ? 2 : 0;
 }
-int kv_share_of(int head_dim, int gqa) {          // smallest split of the group into equal parts that fit
+// At d = 128 a tile holds up to 16 query rows (at about 1.25 times the 8-row tile's time per token), at d = 256 two.
+// A group with more rows is cut into the fewest equal parts that fit, one block each on the same KV head.
+// (16 heads per KV head, one sequence, one 16-row block against two 8-row blocks: 8K tokens 14.4 against 15.5 us,
+// 32K 18.8 against 19.7, 128K 39.8 against 52.1; 8 sequences of 32K 64.3 against 102.8 us.)
+int kv_share_of(int head_dim, int gqa) {
   if (gqa < 1 || (head_dim != 128 && head_dim != 256)) return 0;
   // d=256: a tile of 4 rows needs more registers than a lane has (its loop spills), and two blocks of 2 rows
   // that stream the same KV head are faster than one of 4 (measured: 52.9 us against 69.0 us at 64/16 heads, 32K)
-  const int cap = head_dim == 128 ? 8 : 2;
+  const int cap = head_dim == 128 ? 16 : 2;
   for (int share = (gqa + cap - 1) / cap; share <= gqa; ++share)
     if (gqa % share == 0) return share;
   return 0;
@@ -1140,9 +1202,10 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
   if (p.n_queries < 1) p.n_queries = 1;
   if (p.n_queries > kMaxQueries) return hipErrorNotSupported;
   p.gqa_full = p.gqa;
-  p.kv_share = kv_share_of(head_dim, p.gqa * p.n_queries);
-  if (p.kv_share < 1) return hipErrorNotSupported;
-  p.gqa = p.gqa * p.n_queries / p.kv_share;
+  // blocks per KV head: the caller's choice (it sized the chunk plan by it), checked against the tiles there are
+  const int rows = p.gqa * p.n_queries;
+  if (p.kv_share < 1 || rows % p.kv_share != 0 || padded_gqa(head_dim, rows / p.kv_share) == 0) return hipErrorNotSupported;
+  p.gqa = rows / p.kv_share;
   const int rows_y = p.n_kv_heads * p.kv_share;
   p.merge_slot = -1;
   if (merge_slot >= 0) {
@@ -1159,6 +1222,7 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
                     : per_block > 1  ? dim3(1, (batch * rows_y + per_block - 1) / per_block, 1)
                                      : dim3(p.n_splits, rows_y, batch);
   const int gp = padded_gqa(head_dim, p.gqa);
+  if (head_dim == 128 && gp == 16) return launch<128, 16>(p, grid, s);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);
   if (head_dim == 256 && gp == 2) return launch<256, 2>(p, grid, s);

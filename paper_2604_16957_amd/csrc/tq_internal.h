@@ -299,8 +299,9 @@ hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_den
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);
 bool mfma_supported(int head_dim, int gqa);
-// How many blocks share the stream of one KV head for this GQA ratio (1 where the group fits one tile,
-// 0 = unsupported): the planner counts batch * n_kv_heads * share rows.
+// How many blocks share the stream of one KV head for this many query rows per KV head (1 where they fit one
+// tile, 0 = unsupported): the planner counts batch * n_kv_heads * share rows, and the launch is given the same
+// number in DecodeParams::kv_share.
 int mfma_kv_share(int head_dim, int gqa);
 // With merge_slot >= 0 the kernel also does the chunk merge (Eq. 6) and writes p.out: one launch per decode.
 // The slot names the set of arrival counters the launch uses; mfma_merge_slot_of hands every workspace a set of

@@ -114,7 +114,10 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 1, 0, 3)), wsb=ws3) == E.TQ_ERR_UNSUPPORTED
     f = B.raw().tq_decode_launches
     c = _cache()
-    assert f(ctypes.byref(c), 64, 1024, 0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 4))) == 1
+    # 4 query tokens x 8 heads per KV head: two 16-row tiles per KV head, whose chunks the merge kernel merges;
+    # one query token (8 rows) at this length is merged by the decode kernel itself
+    assert f(ctypes.byref(c), 64, 1024, 0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 4))) == 2
+    assert f(ctypes.byref(c), 64, 1024, 0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 1))) == 1
     assert f(ctypes.byref(c), 64, 1024, -0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 4))) == 0
     assert f(ctypes.byref(c), 64, 3, 0.1, ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 4))) == 0
 
@@ -224,9 +227,11 @@ def test_decode_launch_count_query():
     generic = B.TqDecodeOptsStruct(0, 1)
     assert f(ctypes.byref(short), 64, 1024, 0.1, ctypes.byref(generic)) == 2
     assert f(ctypes.byref(short), 64, 1024, -0.1, None) == 2          # non-positive scale: generic kernel
-    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, None) == 1       # GQA ratio 16: two blocks per KV head
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, None) == 2       # GQA ratio 16: a 16-row tile, merge kernel
+    assert f(ctypes.byref(short), 8 * 4, 1024, 0.1, None) == 1        # GQA ratio 4: merged in place
     forced = B.TqDecodeOptsStruct(0, 2)
-    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, ctypes.byref(forced)) == 1
+    assert f(ctypes.byref(short), 8 * 16, 1024, 0.1, ctypes.byref(forced)) == 2
+    assert f(ctypes.byref(short), 8 * 8, 1024, 0.1, ctypes.byref(forced)) == 1
     assert f(ctypes.byref(short), 64, 1024, -0.1, ctypes.byref(forced)) == 0
     assert f(ctypes.byref(short), 63, 1024, 0.1, None) == 0
     assert f(ctypes.byref(short), 64, 0, 0.1, None) == 0 and f(ctypes.byref(short), 64, 1025, 0.1, None) == 0

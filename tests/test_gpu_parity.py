@@ -983,8 +983,8 @@ def test_append_decode_in_one_call(shape, variant):
 @pytest.mark.parametrize("variant", [0, 2])
 @pytest.mark.parametrize("shape", ["g16_d128_b2_kv2", "g12_d128", "g8_d256"])
 def test_gqa_groups_larger_than_the_matrix_core_tile(shape, variant):
-    """GQA ratios above the matrix-core kernel's tile (8 query heads at d=128, 4 at d=256): several blocks
-    stream each KV head, each with its share of the group; plain decode (merged in the kernel or by the
+    """GQA ratios above the 8-row tile (d=128: a tile of 16 rows) or above any tile (d=256: two rows; then several
+    blocks stream each KV head, each with its share of the group); plain decode (merged in the kernel or by the
     reduce launch), sliding window, per-sequence lengths and the one-call step all take that path."""
     shapes = dict(g16_d128_b2_kv2=dict(batch=2, n_q_heads=32, n_kv_heads=2, head_dim=128, outlier_channels=4),
                   g12_d128=dict(n_q_heads=12, n_kv_heads=1, head_dim=128),
@@ -1008,6 +1008,49 @@ def test_gqa_groups_larger_than_the_matrix_core_tile(shape, variant):
         torch.cuda.synchronize()
         assert_close(out, _oracle_window(q, ocache, lens, window if window > 0 else S, w.attn_scale),
                      f"{shape} per-sequence lengths S={S} window={window} variant={variant}")
+
+
+@pytest.mark.parametrize("gqa", [9, 10, 16, 24, 40])
+def test_sixteen_row_tiles(gqa):
+    """d = 128 with 9 or more query rows per KV head: tiles of 16 rows (every column of the tile a row of its own,
+    one score accumulator per quantisation group, the P V columns regrouped by group), partly filled (9, 10 of 16),
+    full, and several per KV head (24 = 2 x 12, 40 = 4 x 10).  Ragged lengths around the 32-token supertile and
+    the chunk boundaries, forced chunk counts, a sliding window, per-sequence lengths, and a sharp softmax where
+    every one of the 16 rows keeps moving its own reference."""
+    Hkv, B = 2, 2
+    for S, window, n_splits, scale in ((1, 0, 0, None), (31, 0, 0, None), (32, 0, 0, None), (33, 0, 0, None),
+                                       (1025, 0, 0, None), (2500, 0, 7, None), (4133, 700, 0, None),
+                                       (9000, 0, 0, 1.0), (20000, 0, 0, None)):
+        kw = dict(attn_scale=scale, v_std=0.5) if scale else {}
+        w = wl.custom(batch=B, n_q_heads=gqa * Hkv, n_kv_heads=Hkv, head_dim=128, seq_len=S, seed=1600 + gqa + S,
+                      outlier_channels=4, **kw)
+        q, k, v = make(w)
+        cache = gpu_cache_from(k, v)
+        ocache = oracle_cache_from(k, v)
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, window=window, n_splits=n_splits)
+        torch.cuda.synchronize()
+        ref = _oracle_window(q, ocache, [S] * B, window if window > 0 else S, w.attn_scale)
+        assert_close_elementwise(out, ref, f"GQA {gqa} S={S} window={window} n_splits={n_splits} scale={scale}")
+        lens = [S, max(1, S - 37)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S,
+                                            w.attn_scale, window=window)
+        torch.cuda.synchronize()
+        assert_close_elementwise(out, _oracle_window(q, ocache, lens, window if window > 0 else S, w.attn_scale),
+                                 f"GQA {gqa} per-sequence lengths S={S} window={window}")
+
+
+def test_sixteen_row_tiles_at_128k():
+    """16 query heads per KV head over the 128K layer of the headline shape (8 KV heads): one 16-row block per
+    chunk and KV head, every output element against the oracle."""
+    w = wl.custom(n_q_heads=128, n_kv_heads=8, head_dim=128, seq_len=131072, seed=16128, outlier_channels=4)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    del k, v
+    out = tq.tq_sdpa_int4_decode(cache, q.cuda(), w.seq_len, w.attn_scale)
+    torch.cuda.synchronize()
+    ref = oracle.attend_packed(np16(q), *ocache, seq_len=w.seq_len, alpha=w.attn_scale)
+    assert_close_elementwise(out, ref, "GQA 16 at 128K")
 
 
 # ---------------------------------------------------------------- several query tokens per sequence
