@@ -384,7 +384,9 @@ def tq_sdpa_int4_reduce(batch: int, n_q_heads: int, head_dim: int, n_splits: int
 
 
 def tq_dequant_then_attend(cache: KVCache, q: torch.Tensor, seq_len: int, attn_scale: float, out=None,
-                           workspace=None, dense_scratch=None, n_splits: int = 0, stream=None) -> torch.Tensor:
+                           workspace=None, dense_scratch=None, n_splits: int = 0, stream=None,
+                           variant: int = 0) -> torch.Tensor:
+    """The unfused comparator; variant 1 = its attention phase on the generic vector-ALU kernel."""
     _need(q, torch.float16, "q")
     if out is None:
         out = torch.empty_like(q)
@@ -395,6 +397,6 @@ def tq_dequant_then_attend(cache: KVCache, q: torch.Tensor, seq_len: int, attn_s
     rc = raw().tq_dequant_then_attend(ctypes.byref(cache.struct), q.data_ptr(), int(q.shape[1]), int(seq_len),
                                       float(attn_scale), out.data_ptr(), workspace.data_ptr(), wbytes,
                                       dense_scratch.data_ptr(), dense_scratch.numel() * dense_scratch.element_size(),
-                                      _opts(n_splits, 0), _stream_ptr(stream))
+                                      _opts(n_splits, variant), _stream_ptr(stream))
     _check(rc, "tq_dequant_then_attend")
     return out

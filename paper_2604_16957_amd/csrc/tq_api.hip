@@ -673,12 +673,20 @@ int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_
   half_t* v_dense = k_dense + need / sizeof(half_t) / 2;
   rc = hip_rc(tq::launch_dequant_dense(*cache, seq_len, k_dense, v_dense, s));
   if (rc != TQ_OK) return rc;
-  const Plan plan = plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0, kBlocksValu, 1);
+  // attention over the dense tensors: on the matrix cores where that kernel covers the shape (variant 1 asks for
+  // the generic vector-ALU kernel), one block per compute unit and at least a supertile per wave
+  const bool on_mfma = !(opts && opts->variant == 1) && attn_scale > 0.0f && std::isfinite(attn_scale) &&
+                       tq::dense_mfma_supported(cache->head_dim, n_q_heads / cache->n_kv_heads);
+  const Plan plan = on_mfma ? plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
+                                          kBlocksMfma, tq::dense_mfma_waves(cache->head_dim))
+                            : plan_splits(cache->batch, cache->n_kv_heads, seq_len, opts ? opts->n_splits : 0,
+                                          kBlocksValu, 1);
   DecodeParams p = make_params(cache, q, n_q_heads, seq_len, attn_scale, out, workspace, plan);
   p.k_dense = k_dense;
   p.v_dense = v_dense;
   p.row_stride = seq_len;                  // the dense buffers are packed to seq_len rows
-  rc = hip_rc(tq::launch_partial_valu(p, cache->batch, cache->head_dim, true, s));
+  rc = hip_rc(on_mfma ? tq::launch_partial_dense_mfma(p, cache->batch, cache->head_dim, s)
+                      : tq::launch_partial_valu(p, cache->batch, cache->head_dim, true, s));
   if (rc != TQ_OK) return rc;
   return hip_rc(tq::launch_reduce(p, cache->batch, cache->head_dim, s));
 }

@@ -298,6 +298,12 @@ hipError_t launch_quantize(const tq_kv_cache& c, const void* k_new, const void* 
 hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_dense, half_t* v_dense,
                                 hipStream_t s);
 hipError_t launch_partial_valu(const DecodeParams& p, int batch, int head_dim, bool dense, hipStream_t s);
+// Attention phase of the unfused comparator on the matrix cores (dense fp16 K^ / V^ in p.k_dense / p.v_dense,
+// p.row_stride rows apart per (sequence, KV head)): head_dim 128 or 256, up to 16 query heads per KV head, one
+// common length.  Chunks of whole 32-token tiles; writes the partials the merge kernel reads.
+bool dense_mfma_supported(int head_dim, int gqa);
+int dense_mfma_waves(int head_dim);
+hipError_t launch_partial_dense_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 bool mfma_supported(int head_dim, int gqa);
 // How many blocks share the stream of one KV head for this many query rows per KV head (1 where they fit one
 // tile, 0 = unsupported): the planner counts batch * n_kv_heads * share rows, and the launch is given the same

@@ -8,6 +8,8 @@
 // first of them writes it.  No LDS.  The arithmetic must give the
 // same bits on every IEEE machine, so each fp32 step is a separately rounded operation:
 // contraction is off for this file and the correctly rounded divide is used.
+#include <algorithm>
+
 #include "tq_internal.h"
 
 #pragma clang fp contract(off)
@@ -110,36 +112,34 @@ struct DequantParams {
   const half_t* scale[2];
   const half_t* zero[2];
   half_t* dense[2];           // [B*H_kv][seq_len][D]
-  int32_t seq_len, capacity, head_dim, group;
-  int64_t groups_per_tensor;  // B*H_kv*seq_len*(D/32): 32-element pieces, one per thread
+  int32_t seq_len, capacity, head_dim, group, rows;   // rows = B * H_kv
 };
 
 // x^ = (q - z) * s (Eq. 3) rounded to fp16: what "dequantize, then attend" materialises.
+// One thread per packed word (8 elements): a wave reads 256 contiguous bytes of codes and writes 1 KB of
+// contiguous fp16 with one 16-byte store per lane.  (One thread per 32 elements, four 16-byte stores at a 64-byte
+// stride across the wave, was measured at 176 us for a 128K layer against this kernel's time: the partial lines
+// of every store went to the L2 one by one.)  grid: (pieces of a row's seq_len * D / 8 words, row or rows, K | V).
 __global__ __launch_bounds__(256) void dequant_dense_kernel(DequantParams p) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= p.groups_per_tensor) return;
-  const int which = blockIdx.y;
-  const int ng = p.head_dim / kGroup;
-  const int g = (int)(idx % ng);
-  const int64_t vec = idx / ng;                       // bh * seq_len + t
-  const int64_t bh = vec / p.seq_len;
-  const int t = (int)(vec % p.seq_len);
-  const int64_t row = bh * p.capacity + t;
-  const uint4 c = *reinterpret_cast<const uint4*>(p.codes[which] + row * (p.head_dim / 2) + g * (kGroup / 2));
-  const int pieces = p.group / kGroup;                // this piece's group: 32, 64 or 128 elements
-  const float sf = (float)p.scale[which][row * (ng / pieces) + g / pieces];
-  const float zf = (float)p.zero[which][row * (ng / pieces) + g / pieces];
-  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
-  uint4* dst = reinterpret_cast<uint4*>(p.dense[which] + (vec * p.head_dim + g * kGroup));
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  const int which = blockIdx.z;
+  const int wpt = p.head_dim / 8;                     // packed words per token
+  const uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x;   // word of the (sequence, KV head) row's seq_len tokens
+  if (idx >= (uint32_t)p.seq_len * wpt) return;
+  const uint32_t t = idx / wpt, wd = idx - t * wpt;   // (head_dim is a power of two: shifts)
+  const int gpt = p.head_dim / p.group;               // groups per token
+  const int g = wd * 8 / p.group;
+  for (int bh = blockIdx.y; bh < p.rows; bh += gridDim.y) {
+    const int64_t row = (int64_t)bh * p.capacity + t;
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(p.codes[which] + row * (p.head_dim / 2) + wd * 4);
+    const float sf = (float)p.scale[which][row * gpt + g];
+    const float zf = (float)p.zero[which][row * gpt + g];
     Pack16 u;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float q = (float)((w[i] >> (4 * j)) & 0xFu);
+      const float q = (float)((w >> (4 * j)) & 0xFu);
       u.h[j] = (half_t)((q - zf) * sf);
     }
-    dst[i] = u.v;
+    *reinterpret_cast<uint4*>(p.dense[which] + ((int64_t)bh * p.seq_len + t) * p.head_dim + wd * 8) = u.v;
   }
 }
 
@@ -188,9 +188,10 @@ hipError_t launch_dequant_dense(const tq_kv_cache& c, int seq_len, half_t* k_den
   p.capacity = c.capacity;
   p.head_dim = c.head_dim;
   p.group = c.group_size;
-  p.groups_per_tensor = (int64_t)c.batch * c.n_kv_heads * seq_len * (c.head_dim / kGroup);
-  const unsigned blocks = (unsigned)((p.groups_per_tensor + 255) / 256);
-  hipLaunchKernelGGL(dequant_dense_kernel, dim3(blocks, 2), dim3(256), 0, s, p);
+  p.rows = c.batch * c.n_kv_heads;
+  if ((int64_t)seq_len * (c.head_dim / 8) >= (1ll << 32)) return hipErrorNotSupported;   // a row's words are counted in 32 bits
+  const unsigned blocks = (unsigned)(((int64_t)seq_len * (c.head_dim / 8) + 255) / 256);
+  hipLaunchKernelGGL(dequant_dense_kernel, dim3(blocks, (unsigned)std::min(p.rows, 65535), 2), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

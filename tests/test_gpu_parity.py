@@ -405,17 +405,26 @@ def test_in_kernel_merge_agrees_with_the_two_phase_path():
 
 # ---------------------------------------------------------------- unfused comparator
 
-def test_dequant_then_attend_matches_oracle():
-    for shape, S in (("g8_d128_b2_kv3", 1999), ("g2_d256", 1030)):
-        w = wl.custom(seq_len=S, seed=51, **SHAPES[shape])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_dequant_then_attend_matches_oracle(variant):
+    """Both attention kernels of the comparator (0: matrix cores where they cover the shape, i.e. d = 128 / 256 and
+    up to 16 heads per KV head; 1: the generic vector-ALU kernel) against the comparator's definition, over lengths
+    with and without a ragged last supertile, a single token, forced chunk counts, and a group of 20 heads that
+    only the generic kernel takes."""
+    shapes = dict(SHAPES, g20_d128=dict(n_q_heads=20, n_kv_heads=1, head_dim=128))
+    for shape, S, n_splits in (("g8_d128_b2_kv3", 1999, 0), ("g2_d256", 1030, 0), ("g8_d128_b2_kv3", 1, 0),
+                               ("g8_d128_b2_kv3", 31, 0), ("g8_d128_b2_kv3", 4096, 3), ("g16_d128", 9001, 0),
+                               ("g3_d128", 700, 2), ("g2_d256", 6000, 5), ("g20_d128", 333, 0)):
+        w = wl.custom(seq_len=S, seed=51, **shapes[shape])
         q, k, v = make(w)
         cache = gpu_cache_from(k, v, capacity=S + 5)
         ocache = oracle_cache_from(k, v)
         nbytes = tq.tq_dense_scratch_bytes(w.batch, w.n_kv_heads, S, w.head_dim)
         dense = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        out = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale, dense_scratch=dense)
+        out = tq.tq_dequant_then_attend(cache, q.cuda(), S, w.attn_scale, dense_scratch=dense, n_splits=n_splits,
+                                        variant=variant)
         torch.cuda.synchronize()
-        assert_comparator_close(out, q, ocache, S, w.attn_scale, f"baseline {shape}")
+        assert_comparator_close(out, q, ocache, S, w.attn_scale, f"baseline {shape} S={S} variant={variant}")
         # the dense buffers hold fp16((q - z) s) to within one fp16 ulp
         got = np16(dense.view(torch.float16).view(2, w.batch, w.n_kv_heads, S, w.head_dim))
         for i, part in enumerate((ocache[:3], ocache[3:])):
