@@ -230,7 +230,9 @@ int tq_sdpa_int4_reduce(int32_t batch, int32_t n_q_heads, int32_t head_dim, int3
  * phase 1 writes dense fp16 K^ and V^ [batch][n_kv_heads][seq_len][head_dim] (K^ first, then V^)
  * into dense_scratch, phase 2 runs fp16 decode attention over them with the same split/merge.
  * (The paper's baseline materialises FP32; fp16 is used here, which only favours the baseline.)
- * dense_scratch: at least tq_dense_scratch_bytes() bytes.  Other arguments and errors as for
+ * Phase 2 runs on the matrix cores for head_dim 128 / 256 with up to 16 query heads per KV head and a
+ * positive scale, else (and with opts->variant = 1) on the generic vector-ALU kernel; variant 2 means the same
+ * as 0 here.  dense_scratch: at least tq_dense_scratch_bytes() bytes.  Other arguments and errors as for
  * tq_sdpa_int4_decode. */
 int tq_dequant_then_attend(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,
                            float attn_scale, void* out, void* workspace, size_t workspace_bytes,
