@@ -125,8 +125,9 @@ int tq_quantize_kv_varlen(const tq_kv_cache* cache, const void* k_new, const voi
  * memory owned by the library, one set per WORKSPACE address (kept for the life of the process, left zero by
  * every launch).  Calls that may run at the same time must not share a workspace (they would overwrite each
  * other's partials), so they never share counters either, whether issued eagerly or replayed from a captured
- * graph.  There are 64 sets; a call whose workspace is the 65th distinct address the library sees takes the
- * merge kernel (two launches) instead, with the same result up to the summation order of the merge.
+ * graph.  There are 256 sets; a call whose workspace is the 257th distinct address the library sees takes the
+ * merge kernel (two launches) instead, with the same result up to the summation order of the merge: results are
+ * bit-for-bit repeatable per workspace, not across workspaces.
  * Errors: NULL, SHAPE, EMPTY (seq_len < 1), CAPACITY (seq_len > capacity), WORKSPACE,
  * UNSUPPORTED, HIP. */
 int tq_sdpa_int4_decode(const tq_kv_cache* cache, const void* q, int32_t n_q_heads, int32_t seq_len,

@@ -147,9 +147,11 @@ int mfma_share_of(const tq_kv_cache* cache, int n_q_heads, const tq_decode_opts*
 
 Route route_of(const tq_kv_cache* cache, int n_q_heads, int seq_len, float attn_scale, const tq_decode_opts* opts) {
   const int variant = opts ? opts->variant : 0;
-  // groups of 64 or 128 elements: the generic vector-ALU kernel (the matrix-core kernels are built around groups
-  // of 32: one matrix instruction per group); one query token per sequence
-  if (cache->group_size != tq::kGroup) {
+  // groups of 64 or 128 elements: the matrix-core kernel at head_dim 128 (see mfma_supports_group), else the
+  // generic vector-ALU kernel with one query token per sequence
+  // (groups of 128 under a sliding window: a window may start at an odd token, in the middle of a pair)
+  const bool pairs_split = cache->group_size == 4 * tq::kGroup && opts && opts->window > 0;
+  if (!tq::mfma_supports_group(cache->head_dim, cache->group_size, cache->capacity) || pairs_split) {
     const bool ok = variant != 2 && queries_of(opts) == 1;
     return {ok, false, false, false, false};
   }

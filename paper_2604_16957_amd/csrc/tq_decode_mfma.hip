@@ -85,7 +85,7 @@ constexpr int kMaxDevices = 64;
 // keeps the set it was captured with.  Zero when the module is loaded; the block that arrives last wraps its
 // counter back to zero, so every launch leaves them zero again.  A workspace that finds all sets taken gets the
 // merge kernel instead (two launches: always correct).
-constexpr int kCounterSlots = 64;
+constexpr int kCounterSlots = 256;
 constexpr int kCountersPerSlot = 2048;
 __device__ unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
@@ -288,9 +288,17 @@ __device__ __forceinline__ void wait_loads() {               // until at most N 
 // token, one block per (chunk, KV head, sequence).  Everything below that serves the other shapes then folds
 // away at compile time; what is left is a short prologue (the first loads leave sooner) and a loop without the
 // scalar bookkeeping of pages and packed rows.
-template <int D, int GP, int NW, bool NT, bool PLAIN>
+//
+// GS = log2(group size / 32).  Groups of 64 or 128 elements (Sec. 2.1) change what the stored scales and zero-points
+// MEAN, not what the kernel does with them: the direct loads fetch, for every 32-dim block of a token, the dword
+// that holds its group's value (one dword of two groups per token at 64, one dword of two TOKENS at 128), and the
+// lane copies the half it needs into both halves of the register, after which everything is as with groups of 32.
+// Instantiated for the layouts whose metadata is gathered dword by dword (d = 128 with 8 or 16 rows).
+template <int D, int GP, int NW, bool NT, bool PLAIN, int GS = 0>
 __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_kernel(DecodeParams p) {
   using C = Cfg<D, GP, NW>;
+  static_assert(GS == 0 || ((C::PERM || C::WIDE) && !PLAIN), "larger groups: the gathered metadata layouts only");
+  constexpr int SZB = (D / kGroup * 2) >> GS;     // bytes of one metadata array per token
   constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS, GR = C::GR;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -388,10 +396,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
                                      ? max(0, start + seq - (NQ - 1 - query_token(hl)) - p.row_window) - start : lead;
   const char* kc_row = reinterpret_cast<const char*>(p.k_codes) + row0 * TB;
   const char* vc_row = reinterpret_cast<const char*>(p.v_codes) + row0 * TB;
-  const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * (NG * 2),
-                           reinterpret_cast<const char*>(p.k_zero) + row0 * (NG * 2),
-                           reinterpret_cast<const char*>(p.v_scale) + row0 * (NG * 2),
-                           reinterpret_cast<const char*>(p.v_zero) + row0 * (NG * 2)};
+  const char* sz_row[4] = {reinterpret_cast<const char*>(p.k_scale) + row0 * SZB,
+                           reinterpret_cast<const char*>(p.k_zero) + row0 * SZB,
+                           reinterpret_cast<const char*>(p.v_scale) + row0 * SZB,
+                           reinterpret_cast<const char*>(p.v_zero) + row0 * SZB};
   // Where a supertile starts: in a contiguous cache, `tok0` tokens into the sequence's own row; in a paged
   // one, in the page the block table names, at the token's offset inside the page (supertiles never
   // straddle pages: a page is a multiple of 32 tokens and paged sequences start at token 0).
@@ -402,7 +410,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   auto page_of = [&](int tok0) { return tbl[min(tok0 >> p.page_shift, p.max_blocks - 1)]; };
   auto bases_of_page = [&](int page) -> Bases {   // row 0 of `page` for this KV head (a page is 2^page_shift rows)
     const int64_t r = (int64_t)(page * p.n_kv_heads + kv) << p.page_shift;
-    const int64_t rc = r * TB, rs = r * (NG * 2);
+    const int64_t rc = r * TB, rs = r * SZB;
     return {row_bases.k + rc, row_bases.v + rc, {row_bases.s[0] + rs, row_bases.s[1] + rs, row_bases.s[2] + rs,
                                                  row_bases.s[3] + rs}};
   };
@@ -422,10 +430,11 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const uint32_t lane16 = lane * 16;
   uint32_t szoff[C::SZ / 256];
 #pragma unroll
-  for (int u = 0; u < C::SZ / 256; ++u) szoff[u] = (sz_tok[u] * (NG / 2) + sz_col[u]) * 4;
+  for (int u = 0; u < C::SZ / 256; ++u)           // (larger groups: the token's only dword, or the dword it shares)
+    szoff[u] = GS == 0 ? (sz_tok[u] * (NG / 2) + sz_col[u]) * 4 : GS == 1 ? sz_tok[u] * 4 : (sz_tok[u] >> 1) * 4;
   auto issue_at = [&](uint32_t l, const Bases& B, uint32_t off_c, uint32_t vk, uint32_t vv,
                       const uint32_t (&vs)[C::SZ / 256]) {
-    const uint32_t off_s = off_c >> 3;            // (NG*2) / TB = 1/8: scale bytes per code byte
+    const uint32_t off_s = off_c >> (3 + GS);     // SZB / TB: metadata bytes per code byte
     // the supertile's offset goes into the (scalar) base, not into the per-lane offsets: scalar adds are free
     // next to a vector ALU that is the kernel's bottleneck
     const char* const bk = B.k + off_c;
@@ -456,8 +465,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     const int row_first = paged ? (base & ~page_mask) : 0;
     const char* const kc_row = B.k - (int64_t)row_first * TB;
     const char* const vc_row = B.v - (int64_t)row_first * TB;
-    const char* const sz_row[4] = {B.s[0] - (int64_t)row_first * (NG * 2), B.s[1] - (int64_t)row_first * (NG * 2),
-                                   B.s[2] - (int64_t)row_first * (NG * 2), B.s[3] - (int64_t)row_first * (NG * 2)};
+    const char* const sz_row[4] = {B.s[0] - (int64_t)row_first * SZB, B.s[1] - (int64_t)row_first * SZB,
+                                   B.s[2] - (int64_t)row_first * SZB, B.s[3] - (int64_t)row_first * SZB};
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int tok = min(base + 16 * t + tok_of_row(c), last_tok);
@@ -476,7 +485,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 #pragma unroll
       for (int u = 0; u < C::SZ / 256; ++u) {
         const int tok = min(base + (int)sz_tok[u], last_tok);
-        dma4_lane(sz_row[a] + (int64_t)tok * (NG * 2) + sz_col[u] * 4, l + C::OFF_KS + a * C::SZ + u * 256);
+        const int64_t src = GS == 0 ? (int64_t)tok * (NG * 2) + sz_col[u] * 4 : GS == 1 ? (int64_t)tok * 4 : (int64_t)(tok >> 1) * 4;
+        dma4_lane(sz_row[a] + src, l + C::OFF_KS + a * C::SZ + u * 256);
       }
   };
   const uint32_t zero_vs[C::SZ / 256] = {};
@@ -641,7 +651,15 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const int gz = C::WIDE ? (c & 3) : (c * NCS) >> 2;
   const uint32_t sz_rd = C::WIDE ? kq * 64 : C::PERM ? (kq * GR + rep) * 32 : (kq * NG + rep * NA) * 2;
   const uint32_t zb_rd = C::WIDE ? kq * 64 + (gz >> 1) * 32 : C::PERM ? (kq * GR + (gz >> 1)) * 32 : (kq * NG + gz) * 2;
-  const uint32_t zb_sel = (gz & 1) ? 0x07060302u : 0x05040100u;   // which half of a zero-point dword
+  // which half of a zero-point dword: the group's place in its pair; with larger groups the pair's place among the
+  // token's two groups, or the token's place in its pair of tokens (this lane's tokens are kq, kq + 4, ...)
+  const bool zb_hi = GS == 0 ? (gz & 1) : GS == 1 ? ((gz >> 1) & 1) : (kq & 1);
+  const uint32_t zb_sel = zb_hi ? 0x07060302u : 0x05040100u;
+  // larger groups: the half of a fetched scale / zero-point dword that this lane's 32-dim blocks share.  With 8 rows
+  // the lane's two blocks are 2 rep and 2 rep + 1 (group rep of the token's two); with 16 rows register dw holds
+  // blocks 2 dw and 2 dw + 1 (group dw); with groups of 128 it is the token's parity either way.
+  const uint32_t dup_lo = 0x01000100u, dup_hi = 0x03020302u;
+  const uint32_t dup_lane = (GS == 2 ? (kq & 1) : rep) ? dup_hi : dup_lo;
 
   // Everything a supertile needs from LDS is fetched into registers well before it is used: the K part
   // while the previous supertile is still in its P V phase, the V part at the start of the K phase.
@@ -665,7 +683,16 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   };
   auto load_sz = [&](const char* arr, uint32_t rd, uint32_t (&dst)[NDW][2][4]) {
 #pragma unroll
-    for (int dw = 0; dw < NDW; ++dw) load_sz1(arr + dw * 32, rd, dst[dw]);
+    for (int dw = 0; dw < NDW; ++dw) {
+      load_sz1(arr + dw * 32, rd, dst[dw]);
+      if constexpr (GS > 0) {
+        const uint32_t sel = (GS == 1 && C::WIDE) ? (dw ? dup_hi : dup_lo) : dup_lane;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dst[dw][t][i] = __builtin_amdgcn_perm(dst[dw][t][i], dst[dw][t][i], sel);
+      }
+    }
   };
   auto load_k = [&](int slot, KRegs& r) {
     const char* st = ring + slot * C::STAGE;
@@ -926,6 +953,19 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     wait_loads<0>();
     load_k(0, kr);
     load_v(0, vr);
+    if constexpr (GS == 2) {
+      // a token pair's dword may reach one token past the sequence's last: whatever lies there must not meet the
+      // (zero) weights of the masked tokens as an Inf or NaN (the scores of such tokens are replaced, not scaled)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (begin + sidx * 32 + 16 * t + 4 * i + kq >= seq) {
+#pragma unroll
+            for (int dw = 0; dw < NDW; ++dw) vr.vs[dw][t][i] = 0;
+            vr.zb[4 * t + i] = 0;
+          }
+    }
     float sc[2][4];
     scores(kr, sidx, std::true_type{}, sc);
     half8v pa[NA];
@@ -1146,7 +1186,7 @@ int kv_share_of(int head_dim, int gqa) {
   return 0;
 }
 
-template <int D, int GP, bool NT, bool PLAIN>
+template <int D, int GP, bool NT, bool PLAIN, int GS = 0>
 hipError_t launch_as(const DecodeParams& p, dim3 grid, hipStream_t s) {
   static_assert((64 + (2 * GP * kMaxSplits + GP) ) * 4 <= Cfg<D, GP, 8>::SMEM, "the chunk merge reuses the block's LDS");
   // one block of 8 waves per compute unit: 8 rings of 2 x 5 KB (d=128) or 2 x 10 KB (d=256, all 160 KB of LDS)
@@ -1161,16 +1201,23 @@ hipError_t launch_as(const DecodeParams& p, dim3 grid, hipStream_t s) {
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
   std::call_once(configured[dev], [&] {
-    outcome[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>),
+    outcome[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN, GS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   });
   if (outcome[dev] != hipSuccess) return outcome[dev];
-  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN>), grid, dim3(NW * 64), smem, s, p);
+  hipLaunchKernelGGL((decode_partial_mfma_kernel<D, GP, NW, NT, PLAIN, GS>), grid, dim3(NW * 64), smem, s, p);
   return hipGetLastError();
 }
 // the stream is read once (non-temporal loads) unless several blocks share a KV head
 template <int D, int GP>
 hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
+  if constexpr (D == 128 && GP >= 8) {            // groups of 64 / 128 elements
+    if (p.group == 2 * kGroup)
+      return p.kv_share == 1 ? launch_as<D, GP, true, false, 1>(p, grid, s) : launch_as<D, GP, false, false, 1>(p, grid, s);
+    if (p.group == 4 * kGroup)
+      return p.kv_share == 1 ? launch_as<D, GP, true, false, 2>(p, grid, s) : launch_as<D, GP, false, false, 2>(p, grid, s);
+  }
+  if (p.group != kGroup) return hipErrorNotSupported;
   const bool plain = p.kv_share == 1 && p.n_queries == 1 && p.waves_per_row == 8 && p.var_chunks == 0 &&
                      p.seq_lens == nullptr && p.block_table == nullptr;
   if (plain) return launch_as<D, GP, true, true>(p, grid, s);
@@ -1182,6 +1229,13 @@ hipError_t launch(const DecodeParams& p, dim3 grid, hipStream_t s) {
 int mfma_kv_share(int head_dim, int gqa) { return kv_share_of(head_dim, gqa); }
 
 bool mfma_supported(int head_dim, int gqa) { return kv_share_of(head_dim, gqa) > 0; }
+
+// Groups of 64 or 128 elements: head_dim 128 only; at 128 two tokens share a dword of every metadata array, which
+// has to be aligned and must not straddle two (sequence, KV head) rows: an even number of tokens per row.
+bool mfma_supports_group(int head_dim, int group, int capacity) {
+  if (group == kGroup) return true;
+  return head_dim == 128 && (group == 2 * kGroup || (group == 4 * kGroup && capacity % 2 == 0));
+}
 
 bool mfma_can_merge(int batch, int n_kv_heads) { return (int64_t)batch * n_kv_heads <= kCountersPerSlot; }
 
@@ -1221,7 +1275,8 @@ hipError_t launch_partial_mfma(const DecodeParams& p_in, int batch, int head_dim
   const dim3 grid = p.var_chunks > 0 ? dim3((p.var_chunks + per_block - 1) / per_block, rows_y, 1)
                     : per_block > 1  ? dim3(1, (batch * rows_y + per_block - 1) / per_block, 1)
                                      : dim3(p.n_splits, rows_y, batch);
-  const int gp = padded_gqa(head_dim, p.gqa);
+  int gp = padded_gqa(head_dim, p.gqa);
+  if (p.group != kGroup && gp == 4) gp = 8;       // (larger groups: the 8- and 16-row layouts only)
   if (head_dim == 128 && gp == 16) return launch<128, 16>(p, grid, s);
   if (head_dim == 128 && gp == 8) return launch<128, 8>(p, grid, s);
   if (head_dim == 128 && gp == 4) return launch<128, 4>(p, grid, s);

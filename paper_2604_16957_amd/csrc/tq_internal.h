@@ -305,6 +305,7 @@ bool dense_mfma_supported(int head_dim, int gqa);
 int dense_mfma_waves(int head_dim);
 hipError_t launch_partial_dense_mfma(const DecodeParams& p, int batch, int head_dim, hipStream_t s);
 bool mfma_supported(int head_dim, int gqa);
+bool mfma_supports_group(int head_dim, int group_size, int capacity);   // groups of 32 always; 64 / 128: see there
 // How many blocks share the stream of one KV head for this many query rows per KV head (1 where they fit one
 // tile, 0 = unsupported): the planner counts batch * n_kv_heads * share rows, and the launch is given the same
 // number in DecodeParams::kv_share.

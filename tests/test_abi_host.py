@@ -83,10 +83,16 @@ def test_decode_rejects_bad_arguments_without_a_gpu():
     assert _decode(_cache(head_dim=1024)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(group_size=48)) == E.TQ_ERR_SHAPE and _decode(_cache(group_size=16)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(group_size=256)) == E.TQ_ERR_SHAPE
-    # groups of 64 / 128: the generic kernels only (no matrix-core variant, one query token)
-    assert _decode(_cache(group_size=64), opts=ctypes.byref(B.TqDecodeOptsStruct(0, 2, 0, 0))) == E.TQ_ERR_UNSUPPORTED
-    assert _decode(_cache(group_size=128), wsb=tq.tq_workspace_bytes(2, 64, 128),
-                   opts=ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 2))) == E.TQ_ERR_UNSUPPORTED
+    # groups of 64 / 128: the matrix-core kernel covers them at head_dim 128 (groups of 128: an even capacity);
+    # elsewhere the generic kernel only (no matrix-core variant, one query token)
+    wsb256 = tq.tq_workspace_bytes(2, 64, 256)
+    for kw in (dict(group_size=64, head_dim=256), dict(group_size=128, head_dim=256), dict(group_size=128, capacity=1025)):
+        assert _decode(_cache(**kw), wsb=wsb256, opts=ctypes.byref(B.TqDecodeOptsStruct(0, 2, 0, 0))) == E.TQ_ERR_UNSUPPORTED
+        assert _decode(_cache(**kw), wsb=wsb256, opts=ctypes.byref(B.TqDecodeOptsStruct(0, 0, 0, 2))) == E.TQ_ERR_UNSUPPORTED
+    f = B.raw().tq_decode_launches
+    for g, hd, want in ((64, 128, 1), (128, 128, 1), (64, 256, 2), (128, 256, 2)):
+        c = _cache(group_size=g, head_dim=hd)
+        assert f(ctypes.byref(c), 64, 1024, 0.1, None) == want        # one launch = the matrix-core kernel merges in place
     assert _decode(_cache(batch=0)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(layout=7)) == E.TQ_ERR_SHAPE
     assert _decode(_cache(), hq=63) == E.TQ_ERR_SHAPE

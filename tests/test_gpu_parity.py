@@ -172,9 +172,10 @@ def test_larger_groups_quantise_bit_exact(group):
 @pytest.mark.parametrize("group", [64, 128])
 @pytest.mark.parametrize("shape", ["g8_d128_b2_kv3", "g2_d256", "g4_d512"])
 def test_larger_groups_decode_matches_oracle(shape, group):
-    """Fused decode attention over a cache quantised in groups of 64 / 128 (generic vector-ALU kernel): lengths
-    around tile boundaries, chunk counts, per-sequence lengths, a sliding window, the one-call step, and the unfused
-    comparator, each against the oracle at the same group size."""
+    """Fused decode attention over a cache quantised in groups of 64 / 128 (the matrix-core kernel at d = 128, where
+    with groups of 128 the capacity has to be even; the generic vector-ALU kernel elsewhere and as variant 1):
+    lengths around tile boundaries, chunk counts, per-sequence lengths, a sliding window, the one-call step, and
+    the unfused comparator, each against the oracle at the same group size."""
     shapes = dict(SHAPES, g4_d512=dict(n_q_heads=8, n_kv_heads=2, head_dim=512, v_std=0.5))
     for S in (1, 33, 1000, 4133):
         w = wl.custom(seq_len=S, seed=640 + group + S, **shapes[shape])
@@ -188,9 +189,14 @@ def test_larger_groups_decode_matches_oracle(shape, group):
             torch.cuda.synchronize()
             assert_close(out, ref, f"{shape} g={group} S={S} n_splits={n_splits}")
         assert_close(tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=1), ref, f"{shape} g={group} variant 1")
-        with pytest.raises(tq.TqError) as e:       # the matrix-core kernels are built around groups of 32
-            tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2)
-        assert e.value.status == -6
+        if w.head_dim == 128 and (group == 64 or (S + 7) % 2 == 0):   # the matrix-core kernel takes these (variant 0 too)
+            for n_splits in (0, 1, 3):
+                out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2, n_splits=n_splits)
+                assert_close(out, ref, f"{shape} g={group} variant 2 n_splits={n_splits}")
+        else:                                       # ... and no others: d = 256 / 512, pairs of tokens that straddle rows
+            with pytest.raises(tq.TqError) as e:
+                tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=2)
+            assert e.value.status == -6
         lens = [max(1, S - 19 * b) for b in range(w.batch)]
         out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale)
         torch.cuda.synchronize()
@@ -209,6 +215,67 @@ def test_larger_groups_decode_matches_oracle(shape, group):
             torch.cuda.synchronize()
             assert_cache_bit_exact(step, ocache, S)
             assert_close(out, ref, f"{shape} g={group} step S={S}")
+
+
+@pytest.mark.parametrize("group", [64, 128])
+@pytest.mark.parametrize("shape", ["g3_d128", "g8_d128_b2_kv3", "g16_d128", "g24_d128"])
+def test_larger_groups_on_the_matrix_cores(shape, group):
+    """Groups of 64 / 128 at d = 128 through the matrix-core kernel: the 8-row tile (3 and 8 heads per KV head), the
+    16-row tile (16 heads) and two of them per KV head (24 heads); lengths around the 32-token supertile and, at 128,
+    around the token pairs that share a metadata dword (odd and even lengths, odd per-sequence lengths); forced chunk
+    counts, a sharp softmax, several query tokens, a sliding window (groups of 64: the matrix-core kernel; of 128:
+    the generic one), the one-call step."""
+    shapes = dict(SHAPES, g24_d128=dict(n_q_heads=24, n_kv_heads=1, head_dim=128))
+    for S, n_splits, scale in ((2, 0, None), (31, 0, None), (32, 0, None), (33, 0, None), (34, 0, None), (700, 3, None),
+                               (4133, 0, None), (6000, 0, 1.0), (20001, 0, None)):
+        kw = dict(attn_scale=scale, v_std=0.5) if scale else {}
+        w = wl.custom(seq_len=S, seed=6400 + group + S, **dict(shapes[shape], **kw))
+        q, k, v = make(w)
+        cap = S + 2 + (S & 1)                       # even: pairs of tokens never straddle rows
+        cache = gpu_cache_from(k, v, capacity=cap, group=group)
+        ocache = oracle_cache_from(k, v, group=group)
+        assert tq.tq_decode_launches(cache, w.n_q_heads, S, w.attn_scale, variant=2) > 0
+        ref = oracle_attend(q, ocache, S, w.attn_scale)
+        for variant in (0, 2):
+            out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, variant=variant, n_splits=n_splits)
+            torch.cuda.synchronize()
+            assert_close_elementwise(out, ref, f"{shape} g={group} S={S} variant={variant} n_splits={n_splits}")
+        lens = [max(1, S - 17 * b) for b in range(w.batch)]
+        out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), torch.tensor(lens, dtype=torch.int32).cuda(), S, w.attn_scale,
+                                            variant=2)
+        torch.cuda.synchronize()
+        assert_close_elementwise(out, _oracle_varlen(q, ocache, lens, w.attn_scale), f"{shape} g={group} lengths S={S}")
+        if S >= 3:                                  # three query tokens, causal among themselves
+            q4 = _queries_for(w, 3)
+            out = tq.tq_sdpa_int4_decode(cache, q4.cuda(), S, w.attn_scale, n_splits=n_splits)
+            torch.cuda.synchronize()
+            assert_close(out, _oracle_causal(q4, ocache, [S] * w.batch, w.attn_scale), f"{shape} g={group} 3 queries S={S}")
+        win = max(1, S // 3)
+        out = tq.tq_sdpa_int4_decode(cache, q.cuda(), S, w.attn_scale, window=win)
+        torch.cuda.synchronize()
+        assert_close(out, _oracle_window(q, ocache, [S] * w.batch, win, w.attn_scale), f"{shape} g={group} window S={S}")
+        if S > 2:                                   # one decode step in one call
+            step = gpu_cache_from(k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(), capacity=cap, group=group)
+            out = tq.tq_sdpa_int4_append_decode(step, k[:, :, S - 1:].contiguous().cuda(), v[:, :, S - 1:].contiguous().cuda(),
+                                                q.cuda(), S, w.attn_scale)
+            torch.cuda.synchronize()
+            assert_cache_bit_exact(step, ocache, S)
+            assert_close_elementwise(out, ref, f"{shape} g={group} step S={S}")
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_larger_groups_full_size(group):
+    """The headline shape (64 / 8 heads, d = 128, 131072 tokens) quantised in groups of 64 / 128: cache bit-exact,
+    every output element against the oracle."""
+    w = wl.WORKLOADS["llama128k"]
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v, group=group)
+    ocache = oracle_cache_from(k, v, group=group)
+    del k, v
+    assert_cache_bit_exact(cache, ocache, w.seq_len)
+    out = tq.tq_sdpa_int4_decode(cache, q.cuda(), w.seq_len, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close_elementwise(out, oracle_attend(q, ocache, w.seq_len, w.attn_scale), f"llama128k g={group}")
 
 
 @pytest.mark.parametrize("group", [64, 128])
@@ -648,9 +715,9 @@ def test_concurrent_calls_on_two_streams():
             with torch.cuda.stream(s):
                 tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=o[i], workspace=wsp)
     torch.cuda.synchronize()
-    first = np16(outs[0][0]).view(np.uint16)
-    assert_close(outs[0][0], ref, "two streams")
-    for o in outs:
+    for si, o in enumerate(outs):                 # (bit for bit per workspace: see the test below)
+        assert_close(o[0], ref, f"two streams: stream {si}")
+        first = np16(o[0]).view(np.uint16)
         for t in o:
             assert np.array_equal(np16(t).view(np.uint16), first)
 
@@ -658,7 +725,9 @@ def test_concurrent_calls_on_two_streams():
 def test_single_launch_decodes_on_24_streams_match_the_serial_result():
     """24 decodes of the one-launch route (several chunks per KV head, merged by the block that arrives last) in
     flight at once, each on its own stream with its own workspace: every workspace has its own set of arrival
-    counters, so all results equal, bit for bit, the result of the same call made alone."""
+    counters, so every result equals, bit for bit, the result of the same call made alone WITH THE SAME WORKSPACE.
+    (A workspace keeps, for the life of the process, either a set of counters or, if it came when all were taken,
+    the merge kernel; the two merges sum in different orders, so results are compared per workspace.)"""
     w = wl.custom(seq_len=8192, seed=93, **SHAPES["g8_d128_b2_kv3"])
     q, k, v = make(w)
     cache = gpu_cache_from(k, v)
@@ -666,12 +735,15 @@ def test_single_launch_decodes_on_24_streams_match_the_serial_result():
     assert tq.tq_decode_launches(cache, qd.shape[1], w.seq_len, w.attn_scale) == 1
     assert tq.tq_plan_splits(w.batch, w.n_kv_heads, w.seq_len) > 1
     nbytes = tq.tq_workspace_bytes(w.batch, w.n_q_heads, w.head_dim)
-    alone = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale)
-    torch.cuda.synchronize()
-    assert_close(alone, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "alone")
-    want = np16(alone).view(np.uint16)
+    ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
     streams = [torch.cuda.Stream() for _ in range(24)]
     ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in streams]
+    want = []
+    for si, wsp in enumerate(ws):                 # each call alone, device idle before and after
+        alone = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, workspace=wsp)
+        torch.cuda.synchronize()
+        assert_close(alone, ref, f"alone, workspace {si}")
+        want.append(np16(alone).view(np.uint16))
     rounds = 12
     outs = [[torch.zeros_like(qd) for _ in range(rounds)] for _ in streams]
     torch.cuda.synchronize()
@@ -682,7 +754,7 @@ def test_single_launch_decodes_on_24_streams_match_the_serial_result():
     torch.cuda.synchronize()
     for si, o in enumerate(outs):
         for i, t in enumerate(o):
-            assert np.array_equal(np16(t).view(np.uint16), want), f"stream {si}, call {i} differs from the call made alone"
+            assert np.array_equal(np16(t).view(np.uint16), want[si]), f"stream {si}, call {i} differs from the call made alone"
 
 
 def test_graph_replays_next_to_eager_calls_on_another_stream():
@@ -698,8 +770,11 @@ def test_graph_replays_next_to_eager_calls_on_another_stream():
     ws_graph, ws_eager = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2))
     out_graph = torch.empty_like(qd)
     want = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, workspace=ws_graph).clone()   # (eager first)
+    want_eager = tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, workspace=ws_eager).clone()
     torch.cuda.synchronize()
-    assert_close(want, oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale), "eager")
+    ref = oracle_attend(q, oracle_cache_from(k, v), w.seq_len, w.attn_scale)
+    assert_close(want, ref, "eager, the graph's workspace")
+    assert_close(want_eager, ref, "eager, the other workspace")   # (bit for bit per workspace, see above)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         tq.tq_sdpa_int4_decode(cache, qd, w.seq_len, w.attn_scale, out=out_graph, workspace=ws_graph)
@@ -716,7 +791,7 @@ def test_graph_replays_next_to_eager_calls_on_another_stream():
         torch.cuda.synchronize()
         assert torch.equal(out_graph, want), f"replay round {r}"
     for i, t in enumerate(outs_eager):
-        assert torch.equal(t, want), f"eager call {i}"
+        assert torch.equal(t, want_eager), f"eager call {i}"
 
 
 def test_graph_capture_and_replay():

@@ -64,14 +64,15 @@ def test_more_workspaces_than_counter_sets_take_the_merge_kernel():
     """(Kept at the very end of the GPU suite: it uses up the library's sets of arrival counters for the rest of the
     process.)  The one-launch decode route gives every workspace a set of arrival counters of its own for the life
     of the process; a workspace that finds them all taken gets the merge kernel (two launches) instead, never a set
-    shared with another workspace.  100 distinct workspaces, all in flight together: all results right."""
+    shared with another workspace.  300 distinct workspaces (more than there are sets), in flight 8 at a time: all
+    results right."""
     torch.cuda.set_device(0)
     w, q, cache, ocache = _case(2, 24, 3, 128, 5000, 75)
     qg = q.cuda()
     assert tq.tq_decode_launches(cache, 24, 5000, w.attn_scale) == 1
     ref = oracle_attend(q, ocache, 5000, w.attn_scale)
     nbytes = tq.tq_workspace_bytes(2, 24, 128)
-    ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(100)]
+    ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(300)]
     streams = [torch.cuda.Stream() for _ in range(8)]
     outs = [torch.zeros_like(qg) for _ in ws]
     torch.cuda.synchronize()
