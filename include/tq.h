@@ -54,9 +54,12 @@ enum { TQ_LAYOUT_CANONICAL = 0 };
  * 4 + 32/group_size bits per element in total: 5.0 at the paper's group size of 32 (its 3.2x against fp16),
  * 4.5 at 64, 4.25 at 128.  Tokens [0, seq_len) are valid; the rest is never read.
  * group_size 32 is what the matrix-core kernels are built for (one matrix instruction per group).  Sec. 2.1
- * states the scheme for groups of g consecutive elements: 64 and 128 are accepted by every call and take the
- * generic vector-ALU kernels (same arithmetic per group, same bit-exact stores); options that only the
- * matrix-core kernels offer (variant 2, n_queries > 1) answer UNSUPPORTED there. */
+ * states the scheme for groups of g consecutive elements: 64 and 128 are accepted by every call (same
+ * arithmetic per group, same bit-exact stores).  At head_dim 128 they take the matrix-core kernel as well
+ * (group_size 128: with an even capacity and no sliding window); otherwise the generic vector-ALU kernels,
+ * where options that only the matrix-core kernels offer (variant 2, n_queries > 1) answer UNSUPPORTED.
+ * (With group_size 128 that kernel reads the scale / zero-point arrays two tokens at a time: up to one token
+ * past seq_len, inside the row.) */
 typedef struct tq_kv_cache {
   void* k_codes;
   void* v_codes;
