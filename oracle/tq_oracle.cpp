@@ -103,7 +103,7 @@ uint16_t float_to_half_bits_rne(float f) {
 
 // One group of g consecutive elements: g/2 bytes of codes, one scale, one zero-point.
 void quantize_group(const uint16_t* x16, int g, uint8_t* codes_out, uint16_t* s_out, uint16_t* z_out) {
-  float x[kMaxGroup];
+  float x[kMaxGroup] = {};                          // (callers pass g >= 32; zeroed only to say so to the compiler)
   for (int j = 0; j < g; ++j) x[j] = half_bits_to_float(x16[j]);
   float mn = x[0], mx = x[0];
   for (int j = 1; j < g; ++j) { mn = std::min(mn, x[j]); mx = std::max(mx, x[j]); }
