@@ -70,7 +70,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="llama128k",
-                    help="tiny | llama8k | llama128k (default, the headline shape) | gemma32k | global512_32k (d=512, GQA 32: "
+                    help="tiny | llama8k | llama128k (default, the headline shape) | gqa16_128k (the same with 128 query heads: "
+                         "the 16-row tile) | gemma32k | global512_32k (d=512, GQA 32: "
                          "the head_dim 512 matrix-core kernel) | varlen8 (8 sequences of "
                          "the llama shape with their own lengths in [4096, 32768], per-sequence append + decode) | paged8 (the same "
                          "over a pool of 256-token pages in random order) | varlen256 (256 sequences of 64 ... 1024 tokens of the llama "
@@ -80,6 +81,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
     ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--group-size", type=int, default=32,
+                    help="quantisation group: 32 (the paper's), 64 or 128 (fixed-length workloads in a contiguous cache)")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--window", type=int, default=0, help="sliding window: attend only the last N tokens (0 = all)")
     ap.add_argument("--n-queries", type=int, default=1,
@@ -274,6 +277,9 @@ def main():
         lens[0] = S                               # the bound is attained
         lens_dev, pos_dev = lens.to(dev), (lens - 1).to(dev)
 
+    GS = args.group_size
+    if GS != 32 and lens is not None:
+        sys.exit("bench.py: --group-size is offered for the fixed-length workloads")
     NQ = args.n_queries
     if NQ > 1 and (lens is not None or args.window > 0):
         sys.exit("bench.py: --n-queries is offered for the fixed-length workloads without a window")
@@ -291,7 +297,7 @@ def main():
             tq.tq_quantize_kv_paged(c, table, k[:, :, :S - 1].contiguous(), v[:, :, :S - 1].contiguous(),
                                     torch.zeros(B, dtype=torch.int32, device=dev))
         else:
-            c = tq.KVCache(B, Hkv, d, S)
+            c = tq.KVCache(B, Hkv, d, S, group_size=GS)
             tq.tq_quantize_kv(c, k[:, :, :S - NQ].contiguous(), v[:, :, :S - NQ].contiguous(), 0)
         news.append((k[:, :, S - NQ:].contiguous(), v[:, :, S - NQ:].contiguous()))
         caches.append(c)
@@ -300,7 +306,8 @@ def main():
     torch.cuda.synchronize()
     ws = torch.empty(tq.tq_workspace_bytes(B * NQ, Hq, d), dtype=torch.uint8, device=dev)
     out = torch.empty_like(qs[0])
-    packed_bytes = w.packed_bytes if lens is None else int(lens.sum()) * Hkv * (w.packed_bytes // (B * Hkv * S))
+    packed_bytes = tq.tq_kv_bytes_grouped(B, Hkv, S, d, GS) if lens is None else \
+        int(lens.sum()) * Hkv * (w.packed_bytes // (B * Hkv * S))
     kw = dict(n_splits=args.n_splits, variant=args.variant)
     if args.window > 0:                           # sliding window: only the attended tokens are streamed
         if lens is not None:
@@ -485,8 +492,8 @@ def main():
         q0, k0, v0 = wl.make_inputs(w, device="cpu")           # the named workload's own bits
         if NQ > 1:
             q0 = wl.make_queries(w, NQ, device="cpu")
-        kc, ks, kz = oracle.quantize(k0.numpy())
-        vc, vs, vz = oracle.quantize(v0.numpy())
+        kc, ks, kz = oracle.quantize(k0.numpy(), group=GS)
+        vc, vs, vz = oracle.quantize(v0.numpy(), group=GS)
         threads = oracle.default_threads()
         reps, times = 3, []
         ref = None
@@ -521,7 +528,7 @@ def main():
                 back = lambda t: t[table.long()].permute(0, 2, 1, 3, 4).reshape(B, Hkv, S, -1).cpu().numpy()
                 got_k, got_v = back(c.k_codes), back(c.v_codes)
             else:
-                c = tq.KVCache(B, Hkv, d, S)
+                c = tq.KVCache(B, Hkv, d, S, group_size=GS)
                 tq.tq_quantize_kv(c, k0.to(dev), v0.to(dev), 0)
                 if lens is None:
                     o = tq.tq_sdpa_int4_decode(c, q0.to(dev), S, w.attn_scale, workspace=ws, **kw)
@@ -543,7 +550,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d,
                    "seq_len": S, "seq_lens": None if lens is None else lens.tolist() if B <= 16 else
-                   {"count": B, "min": int(lens.min()), "max": int(lens.max()), "sum": int(lens.sum()), "seed": w.seed + 5}, "attn_scale": w.attn_scale, "group_size": 32, "kv_buffers_rotated": args.buffers,
+                   {"count": B, "min": int(lens.min()), "max": int(lens.max()), "sum": int(lens.sum()), "seed": w.seed + 5}, "attn_scale": w.attn_scale, "group_size": GS, "kv_buffers_rotated": args.buffers,
                    "n_splits": n_splits, "variant": args.variant, "window": args.window, "n_queries": NQ,
                    "step_calls": ("tq_sdpa_int4_append_decode" if one_call else
                                   "tq_sdpa_int4_append_decode_paged" if paged and not args.two_calls else

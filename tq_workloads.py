@@ -56,6 +56,8 @@ WORKLOADS = {
                         outlier_channels=4),
     "llama128k": Workload("llama128k", 1, 64, 8, 128, 131072, 1.0 / math.sqrt(128), 1003,
                           outlier_channels=4),
+    "gqa16_128k": Workload("gqa16_128k", 1, 128, 8, 128, 131072, 1.0 / math.sqrt(128), 1007,
+                           outlier_channels=4),
     "gemma32k": Workload("gemma32k", 1, 32, 16, 256, 32768, 1.0, 1004, qk_std=0.1),
     "global512_32k": Workload("global512_32k", 1, 32, 1, 512, 32768, 1.0, 1006, qk_std=0.1),
 }
