@@ -302,6 +302,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   constexpr int NG = C::NG, NA = C::NA, NJ = C::NJ, NCS = C::NCS, TB = C::TB, NS = C::NS, LPS = C::LPS, GR = C::GR;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
+  if constexpr (PLAIN) {
+    // every kernel argument the prologue needs, asked for at once: one round trip to the scalar cache before the
+    // first stream loads leave instead of two (the compiler otherwise fetches q and start behind a branch)
+    asm volatile("" :: "s"(p.q), "s"(p.start), "s"(p.k_codes), "s"(p.v_codes), "s"(p.k_scale), "s"(p.k_zero),
+                 "s"(p.v_scale), "s"(p.v_zero), "s"(p.seq_len), "s"(p.tokens_per_split), "s"(p.row_stride),
+                 "s"(p.n_kv_heads), "s"(p.n_q_heads), "s"(p.gqa));
+  }
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, kq = lane >> 4;
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // A chunk past the end of its sequence has nothing to emit: the merge kernel works out from the same
   // lengths which chunks exist.  (With the in-kernel merge the block still has to be counted in, so it
   // goes through and publishes an empty partial.)
-  if (whole && begin0 >= seq && p.merge_slot < 0) return;
+  if (!PLAIN && whole && begin0 >= seq && p.merge_slot < 0) return;
   const int end = max(begin0, min(seq, begin0 + tokens_per_split));
   // Several query tokens under a sliding window: the rows start at different tokens (row t one token after
   // row t - 1); the supertile that holds those starts takes the masked path too (wave 0, after its other work)
@@ -425,8 +432,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
 
   // Fills the ring slot at LDS address l with the supertile whose codes start off_c bytes into the row:
   // LPS load instructions, all 64 lanes each.  vk, vv, vs are the per-lane byte offsets inside the
-  // supertile (K tile, V block, scale array); passing zeros instead makes a PHANTOM stage, which reads
-  // one line per instruction and only keeps the count of outstanding loads uniform.
+  // supertile (K tile, V block, scale array).
   const uint32_t lane16 = lane * 16;
   uint32_t szoff[C::SZ / 256];
 #pragma unroll
@@ -489,14 +495,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         dma4_lane(sz_row[a] + src, l + C::OFF_KS + a * C::SZ + u * 256);
       }
   };
-  const uint32_t zero_vs[C::SZ / 256] = {};
   auto tok_of = [&](int sidx) { return pstart + begin + sidx * 32; };
   auto issue = [&](int slot, int sidx) {
     const int tok0 = tok_of(sidx);
     issue_tok(ring_lds + slot * C::STAGE, tok0, paged ? page_of(tok0) : 0, koff, lane16, szoff);
-  };
-  auto issue_phantom = [&](int slot) {
-    issue_tok(ring_lds + slot * C::STAGE, pstart + begin0, paged ? page_of(pstart + begin0) : 0, 0u, 0u, zero_vs);
   };
   // ---- work distribution.  The block's 8 waves sit two to a SIMD (waves w and w+4), and the SIMD
   //      issues from its older wave first, so wave w gets through a supertile in less time than wave w+4
@@ -541,13 +543,14 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       dma16_lane(p.q + query_row(h) * D + (chunk % (D / 8)) * 8, l + u * 1024);
     }
   }
-  // A wave with work always has exactly NS stages out before its loop and issues one per supertile,
-  // phantom ones standing in when its supertiles run out, so every wait in the loop is the same.
+  // A wave has up to NS stages out before its loop and issues one per supertile while it has supertiles left.
+  // (Stand-in loads that kept the count of outstanding loads the same to the end were taken out: the one issued in
+  // a wave's last iteration made it wait a whole memory round trip for bytes nobody reads, 0.3 us per launch at
+  // llama128k and 0.8 us at gemma32k; the waits below count what is really out instead.)
   if (n_mine > 0) {
 #pragma unroll
     for (int s = 0; s < NPRE; ++s) {
       if (s < n_mine) issue(s, sidx_of(s));
-      else issue_phantom(s);
     }
   }
   // (the first loads are on their way: whatever they do not need is worked out behind them)
@@ -558,7 +561,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
   tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
   tail_mine[3] = head2 && (whole ? wave == 0 : sub == 0);
-  if (n_mine > 0) wait_loads<NPRE * LPS>();
+  if (n_mine >= NPRE) wait_loads<NPRE * LPS>();          // (what was issued after the query block may still be out)
+  else if (n_mine == NPRE - 1 && NPRE == 2) wait_loads<LPS>();
   else wait_loads<0>();
 
   // ---- query operands (the query pre-scaling of Alg. 1 is folded into the exp2 argument instead of the query)
@@ -599,7 +603,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
   if (!C::QSEP && n_mine > 0) {
     if (NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
-    else issue_phantom(NS - 1);
   }
   // supertile NS, the first one issued inside the loop, and how to step from one supertile to the next:
   // position j in the wave's pattern of 9 (or 7) out of 16
@@ -896,22 +899,21 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //      refill the ring slot of supertile i with supertile i+NS, P V.
   KRegs kr;
   VRegs vr;
-  if (C::PFK && n_mine > 0) {
-    wait_loads<(NS - 1) * LPS>();
+  static_assert(C::PFK && NS == 2, "the waits below count one or two stages");
+  if (n_mine > 0) {
+    if (n_mine > 1) wait_loads<LPS>();                       // (loads land in order: stage 0 is in)
+    else wait_loads<0>();
     load_k(0, kr);
   }
   int slot = 0;
   for (int i = 0; i < n_mine; ++i) {
     const int next = (slot + 1 == NS) ? 0 : slot + 1;
-    if constexpr (!C::PFK) {
-      wait_loads<(NS - 1) * LPS>();
-      load_k(slot, kr);
-    }
     load_v(slot, vr);
     // The slot's bytes all sit in registers from here on; its refill with supertile i + NS is issued after the
     // softmax all the same.  (Measured at 128K / at the d = 256 instance: issued here, +0.4 / +0.6 us; issued after
     // the P V phase, +0.4 / +0.3 us; a ring of three stages, +1.0 us: the memory system is at its limit, and
-    // requests queued earlier than needed only delay the ones a wave is waiting for.)
+    // requests queued earlier than needed only delay the ones a wave is waiting for.  Issued here AND waited for
+    // stage by stage, so that two stages are in flight: the kernel alone unchanged, the decode call 1 us slower.)
     auto refill = [&] {
       asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(nx_page) :: "memory");   // every LDS read of this slot has returned
       if (i + NS < n_mine) {
@@ -922,8 +924,6 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
         nx_j = (nx_j == (young ? YNG - 1 : OLD - 1)) ? 0 : nx_j + 1;
         nx_tok += whole ? step * (4 * 32) : W * 32;
         if (paged) nx_page = page_ahead(nx_tok);
-      } else {
-        issue_phantom(slot);
       }
     };
     float sc[2][4];
@@ -933,8 +933,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     if constexpr (D == 128) __builtin_amdgcn_s_setprio(1);
     scores(kr, 0, std::false_type{}, sc);
     if constexpr (D == 128) __builtin_amdgcn_s_setprio(0);
-    if constexpr (C::PFK) {                                  // past the last supertile this fetches unused bytes
-      wait_loads<(NS - 2) * LPS>();
+    if (i + 1 < n_mine) {                                    // the only stage out is the next supertile's
+      wait_loads<0>();
       load_k(next, kr);
     }
     half8v pa[NA];
@@ -943,7 +943,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     pv(vr, pa);
     slot = next;
   }
-  wait_loads<0>();                                           // phantom stages included: the rings are quiet
+  wait_loads<0>();                                           // (nothing is out any more: the rings are quiet)
 #pragma unroll 1
   for (int u = 0; u < (PLAIN ? 1 : 4); ++u) {                // the masked supertiles: the sequence's last one or two,
     if (!tail_mine[u]) continue;                             // and under a window its first (or first two)
