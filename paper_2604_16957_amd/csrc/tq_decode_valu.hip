@@ -314,11 +314,13 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   const bool appending = p.k_new != nullptr;
   float a_new = kNegBig;
   if (appending) {
+    static_assert(THREADS >= D, "one query element per thread");
+    // (asked for with everything else above, not behind the block barrier below: one memory round trip less)
+    const float q_e = tid < D ? (float)p.q[(int64_t)(b * p.n_q_heads + h) * D + tid] : 0.0f;
     const int kv = h / p.gqa;
     quantize_new_token<D>(p, b, kv, append_pos, tid, h % p.gqa == 0 && slice == 0, hat);
     __syncthreads();
-    float prod = 0.0f;
-    for (int e = tid; e < D; e += THREADS) prod = fmaf((float)p.q[(int64_t)(b * p.n_q_heads + h) * D + e], hat[0][e], prod);
+    float prod = tid < D ? q_e * hat[0][tid] : 0.0f;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) prod += __shfl_xor(prod, off);
     if ((tid & 63) == 0) red_a[tid >> 6] = prod;
