@@ -87,7 +87,12 @@ constexpr int kMaxDevices = 64;
 // merge kernel instead (two launches: always correct).
 constexpr int kCounterSlots = 256;
 constexpr int kCountersPerSlot = 2048;
-__device__ unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
+// Within a set, the counters of neighbouring (b, KV head) rows lie 128 bytes apart (row r at (r % 64) * 32 + r / 64):
+// the blocks of a launch finish at about the same time, and their atomics on counters that share a cache line
+// queue up behind one another at that line's channel (8 KV heads x 32 chunks on one line: 1.4 us of a 13 us call).
+__device__ __attribute__((aligned(256))) unsigned int g_arrivals[kCounterSlots * kCountersPerSlot];
+static_assert(kCountersPerSlot == 64 * 32, "the spreading below");
+__device__ __forceinline__ int arrival_counter(int row) { return (row & 63) * 32 + (row >> 6); }
 constexpr float kSlack = 2.0f;              // log2 units: exp2(score - reference) <= 4
 constexpr uint32_t kMaskLo = 0x000F000Fu;   // nibbles 0 and 4 of a word -> fp16 subnormals c * 2^-24
 constexpr uint32_t kMaskHi = 0x00F000F0u;   // nibbles 1 and 5           -> c * 2^-20
@@ -528,7 +533,13 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   //      vector-memory operation of the kernel is one of the counted loads), then the ring is filled.
   //      Where the query block has to borrow the last ring slot, that slot is filled once the query
   //      operands sit in registers.
-  constexpr int NPRE = C::QSEP ? NS : NS - 1;     // stages issued before the query operands are built
+  // One stage is issued before the query operands are built.  The second follows once those operands sit in
+  // registers (d = 256) or, at d = 128, only when the first has landed and its K part has been read: with every
+  // wave's first stage requested alone, the first stages arrive within a short span of each other instead of
+  // queueing behind other waves' second stages, and the waves start (and end) closer together (0.1 - 0.3 us of
+  // the 128K launch; at d = 256 the later point costs 0.3 us).
+  constexpr int NPRE = NS - 1;
+  constexpr bool kSecondAfterFirstLanded = D == 128;
   // (a borrowed slot: behind its K tiles where the block fits there, else from the slot's start)
   constexpr int Q_IN_SLOT = C::QBLK <= C::STAGE - C::OFF_V ? C::OFF_V : 0;
   char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + Q_IN_SLOT;
@@ -561,8 +572,8 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   for (int u = 0; u < 2; ++u) tail_mine[u] = u < n_tail && count_of(n_full + u + 1) != count_of(n_full + u);
   tail_mine[2] = head && (whole ? wave == 0 : sub == 0);
   tail_mine[3] = head2 && (whole ? wave == 0 : sub == 0);
-  if (n_mine >= NPRE) wait_loads<NPRE * LPS>();          // (what was issued after the query block may still be out)
-  else if (n_mine == NPRE - 1 && NPRE == 2) wait_loads<LPS>();
+  static_assert(NPRE == 1, "one stage follows the query block");
+  if (n_mine > 0) wait_loads<LPS>();                         // (the stage issued after the query block may still be out)
   else wait_loads<0>();
 
   // ---- query operands (the query pre-scaling of Alg. 1 is folded into the exp2 argument instead of the query)
@@ -601,9 +612,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   const float kappa = p.scale_log2 * 0x1p24f;     // raw accumulator units -> log2 units
   const float slack = kSlack / kappa;             // the rescale slack in raw units
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the query block has been read: its slot may be refilled
-  if (!C::QSEP && n_mine > 0) {
-    if (NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
-  }
+  if (!kSecondAfterFirstLanded && NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
   // supertile NS, the first one issued inside the loop, and how to step from one supertile to the next:
   // position j in the wave's pattern of 9 (or 7) out of 16
   int nx_j = young ? NS % YNG : NS % OLD;
@@ -901,9 +910,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   VRegs vr;
   static_assert(C::PFK && NS == 2, "the waits below count one or two stages");
   if (n_mine > 0) {
-    if (n_mine > 1) wait_loads<LPS>();                       // (loads land in order: stage 0 is in)
+    if (!kSecondAfterFirstLanded && n_mine > 1) wait_loads<LPS>();   // (loads land in order: stage 0 is in)
     else wait_loads<0>();
     load_k(0, kr);
+    if (kSecondAfterFirstLanded && NS - 1 < n_mine) issue(NS - 1, sidx_of(NS - 1));
   }
   int slot = 0;
   for (int i = 0; i < n_mine; ++i) {
@@ -1093,7 +1103,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   wait_loads<0>();                                // vmcnt counts stores too: this wave's partial has landed
   __syncthreads();                                // every wave's has; and nobody reads the block-merge area any more
   if (threadIdx.x == 0) {
-    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + b * (p.n_kv_heads * kv_share) + kvv];
+    unsigned int* ctr = &g_arrivals[p.merge_slot * kCountersPerSlot + arrival_counter(b * (p.n_kv_heads * kv_share) + kvv)];
     *is_last = atomicInc(ctr, (unsigned int)(n - 1)) == (unsigned int)(n - 1);   // wraps to 0 on the last arrival
   }
   __syncthreads();
