@@ -417,7 +417,10 @@ def main():
     # event pair around every single launch (kept as `kernel_us_bracketed_*`) adds the latency of the
     # two event packets, about 2 us, to each measurement.
     settle(lambda i: dominant(i % args.buffers))
-    kernel_batches = [timed(lambda i: dominant(i % args.buffers), args.steps) for _ in range(1 + args.batches)]
+    # (Batches of at least 200 launches, whatever K is: the kernel's average duration does not depend on K, and in a
+    #  batch of 20 the two event records and the first launch's start-up weigh 0.3 - 1 us per launch on it.)
+    kernel_launches = max(args.steps, 200)
+    kernel_batches = [timed(lambda i: dominant(i % args.buffers), kernel_launches) for _ in range(1 + args.batches)]
     kernel_us = statistics.fmean(kernel_batches)     # average launch duration over all timed launches
     achieved = packed_bytes / (kernel_us * 1e-6) / 1e9
 
@@ -573,7 +576,7 @@ def main():
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None, "traffic_source": None, "kernel_us_mean": round(kernel_us, 3),
-                     "kernel_us": dist(kernel_batches),
+                     "kernel_us": dist(kernel_batches), "kernel_launches_per_batch": kernel_launches,
                      "kernel_us_bracketed_mean": round(kernel_us_bracketed, 3),
                      "kernel_us_bracketed_median": round(statistics.median(k_us), 3),
                      "algorithmic_bytes_per_launch": packed_bytes,

@@ -943,7 +943,10 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
     if constexpr (D == 128) __builtin_amdgcn_s_setprio(1);
     scores(kr, 0, std::false_type{}, sc);
     if constexpr (D == 128) __builtin_amdgcn_s_setprio(0);
-    if (i + 1 < n_mine) {                                    // the only stage out is the next supertile's
+    // The only stage out is the next supertile's.  Past the last supertile there is nothing to wait for and the
+    // fetch reads unused bytes; skipping it there takes a branch in the loop, which the d = 128 instances pay for in
+    // registers and schedule (16-row tile 33.3 -> 35.4 us, 8-row 28.7 -> 28.95) and the d = 256 instance gains by.
+    if (D == 128 || i + 1 < n_mine) {
       wait_loads<0>();
       load_k(next, kr);
     }
