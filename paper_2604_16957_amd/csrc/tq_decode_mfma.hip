@@ -539,7 +539,7 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // queueing behind other waves' second stages, and the waves start (and end) closer together (0.1 - 0.3 us of
   // the 128K launch; at d = 256 the later point costs 0.3 us).
   constexpr int NPRE = NS - 1;
-  constexpr bool kSecondAfterFirstLanded = D == 128;
+  const bool kSecondAfterFirstLanded = D == 128 && whole;   // (rows packed several to a block: 256 x 512 tokens 39.2 -> 40.0 us with it)
   // (a borrowed slot: behind its K tiles where the block fits there, else from the slot's start)
   constexpr int Q_IN_SLOT = C::QBLK <= C::STAGE - C::OFF_V ? C::OFF_V : 0;
   char* const q_area = C::QSEP ? smem + C::OFF_QBLK + wave * C::QBLK : ring + (NS - 1) * C::STAGE + Q_IN_SLOT;
