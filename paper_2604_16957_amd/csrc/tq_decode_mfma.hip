@@ -1117,9 +1117,9 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   // block for its barrier before one thread counts the block in with a device-scope atomic, and the last block
   // issues its device-scope atomic loads (which do not hit lines a die cached earlier) only after that atomic has
   // returned.  A release fence before the count and an acquire fence after it (agent scope) were measured instead:
-  // each block then writes its die's whole L2 back, and a decode of 256 blocks goes from 13.4 to 16.7 us (one of
-  // 4 blocks from 10.3 to 11.2 us), more than the separate merge kernel costs (14.4 us), for no access that the
-  // atomics do not already cover.
+  // each block then writes its die's whole L2 back and invalidates it, and a decode of 256 blocks over 8K tokens
+  // goes from 11.0 to 13.5 us (release alone +1.2 us, acquire alone +0.9 us), more than the separate merge kernel
+  // costs (13.1 us), for no access that the atomics do not already cover.
   float* const c_m = reinterpret_cast<float*>(smem) + 64;     // [G][n] chunk maxima, then chunk weights
   float* const c_l = c_m + GP * kMaxSplits;                    // [G][n] chunk sums
   float* const h_den = c_l + GP * kMaxSplits;                  // [G]
