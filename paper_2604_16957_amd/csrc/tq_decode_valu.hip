@@ -234,7 +234,12 @@ __device__ inline void quantize_new_token(const DecodeParams& p, int b, int kv, 
     half_t s16, z16;
     quantize_scale_zero(mn, mx, s16, z16);
     const float sf = (float)s16, zf = (float)z16;
-    const uint32_t w = quantize_word(x, sf, zf);
+    // Eq. 3 by the shortcut of the append kernel, redone with correctly rounded divides where it could matter
+    // (same bits either way; the divides are most of this function's time, which the merge kernel waits for)
+    const QuantFast fast = quantize_fast_setup(sf, zf, fmaxf(fabsf(mn), fabsf(mx)));
+    float far = 0.0f;
+    uint32_t w = quantize_word_fast(u.h, fast, far);
+    if (quantize_fast_in_doubt(far, fast)) w = quantize_word(x, sf, zf);
     if (store) {
       int64_t row = (int64_t)(b * p.n_kv_heads + kv) * p.row_stride + append_pos;
       if (p.block_table) {                         // paged cache: the page the block table names for that position
@@ -313,6 +318,12 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
   __shared__ float red_a[WAVES];
   const bool appending = p.k_new != nullptr;
   float a_new = kNegBig;
+  // (the chunk maxima of each wave go to LDS ahead of the barriers below, which then serve them as well)
+  float mw = m;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+  if ((tid & 63) == 0) red_m[tid >> 6] = mw;
+  if (!appending) __syncthreads();
   if (appending) {
     static_assert(THREADS >= D, "one query element per thread");
     // (asked for with everything else above, not behind the block barrier below: one memory round trip less)
@@ -330,11 +341,6 @@ __global__ __launch_bounds__(THREADS) void reduce_kernel(DecodeParams p) {
     for (int w = 0; w < WAVES; ++w) dot += red_a[w];
     a_new = dot * p.scale_log2;
   }
-  float mw = m;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
-  if ((tid & 63) == 0) red_m[tid >> 6] = mw;
-  __syncthreads();
   float mg = fmaxf(red_m[0], a_new);
 #pragma unroll
   for (int w = 1; w < WAVES; ++w) mg = fmaxf(mg, red_m[w]);
