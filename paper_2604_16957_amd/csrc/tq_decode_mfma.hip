@@ -330,11 +330,65 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
   bool row_valid = true;
   if (!PLAIN && !whole && p.var_chunks == 0) {
     const int rows_y = p.n_kv_heads * p.kv_share, total = p.batch * rows_y;
-    const int row = blockIdx.y * (NW / W) + wave / W;
-    row_valid = row < total;
-    const int r = min(row, total - 1);
-    b = __builtin_amdgcn_readfirstlane(r / rows_y);
-    kvv = __builtin_amdgcn_readfirstlane(r - (r / rows_y) * rows_y);
+    // One wave per row and per-sequence lengths: in list order a block's eight waves would all get rows of ONE
+    // sequence, and the launch would last as long as the longest sequence.  The two waves of a SIMD share its
+    // vector ALU, so what has to be even is the sum of their two rows: every block orders the sequences by length
+    // (a stable counting sort on the supertile count, in the idle block-merge area of LDS: the same order in every
+    // block) and pairs the i-th shortest with the i-th longest, the older wave of the SIMD taking the longer.
+    bool paired = false;
+    if constexpr (!C::ALIAS) {
+      constexpr int kPairMaxBatch = NW * 64;                 // one sequence per thread
+      static_assert(C::MERGE >= (NW * 64 + 128 + kPairMaxBatch) * 4, "the ordering uses the block-merge area");
+      paired = W == 1 && p.seq_lens != nullptr && (p.batch & 1) == 0 && p.batch <= kPairMaxBatch;
+      if (paired) {
+        int* const cnt = reinterpret_cast<int*>(smem + C::OFF_MERGE);      // [wave][64]: sequences of the wave per supertile count
+        int* const tot = cnt + NW * 64;                                     // [64]: sequences per count, then where each count starts
+        int* const order = tot + 128;                                       // [batch]: sequences, shortest first
+        const int t = threadIdx.x;                                          // this thread's sequence
+        const bool have = t < p.batch;
+        const int bk = have ? min(63, (var_len(p, t) + 31) >> 5) : 64;
+        cnt[t] = 0;
+        __syncthreads();
+        // place among the wave's sequences of the same count, by index
+        int ahead = 0;
+        for (uint64_t todo = __builtin_amdgcn_ballot_w64(have); todo != 0;) {
+          const int lead = __builtin_ctzll(todo);
+          const int bv = __shfl(bk, lead);
+          const uint64_t same = __builtin_amdgcn_ballot_w64(bk == bv);
+          if (bk == bv) ahead = __builtin_popcountll(same & ((1ull << lane) - 1));
+          if (lane == lead) cnt[wave * 64 + bv] = __builtin_popcountll(same);
+          todo &= ~same;
+        }
+        __syncthreads();
+        if (t < 64) {                                        // count t: where each wave's share starts inside it
+          int acc = 0;
+          for (int wv = 0; wv < NW; ++wv) { const int n_w = cnt[wv * 64 + t]; cnt[wv * 64 + t] = acc; acc += n_w; }
+          tot[t] = acc;
+        }
+        __syncthreads();
+        if (t == 0) {
+          int acc = 0;
+          for (int k = 0; k < 64; ++k) { const int n_k = tot[k]; tot[k] = acc; acc += n_k; }
+        }
+        __syncthreads();
+        if (have) order[tot[bk] + cnt[wave * 64 + bk] + ahead] = t;
+        __syncthreads();
+        const int half = p.batch >> 1;
+        const int pair = blockIdx.y * 4 + (wave & 3);        // waves w and w + 4 sit on one SIMD
+        row_valid = pair < half * rows_y;
+        const int pc = min(pair, half * rows_y - 1);
+        const int i = pc % half;
+        kvv = __builtin_amdgcn_readfirstlane(pc / half);
+        b = __builtin_amdgcn_readfirstlane(min(max(order[(wave >> 2) ? i : p.batch - 1 - i], 0), p.batch - 1));
+      }
+    }
+    if (!paired) {
+      const int row = blockIdx.y * (NW / W) + wave / W;
+      row_valid = row < total;
+      const int r = min(row, total - 1);
+      b = __builtin_amdgcn_readfirstlane(r / rows_y);
+      kvv = __builtin_amdgcn_readfirstlane(r - (r / rows_y) * rows_y);
+    }
   }
   const int kv_share = PLAIN ? 1 : p.kv_share;
   const int kv = PLAIN ? kvv : kvv / kv_share;    // the KV head whose rows are read

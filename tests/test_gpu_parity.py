@@ -412,6 +412,31 @@ def test_sharp_softmax_large_scores(variant):
     assert_close_elementwise(out, ref, f"sharp softmax variant={variant}")
 
 
+@pytest.mark.parametrize("B", [130, 256, 512])
+def test_rows_of_their_own_length_are_paired_long_with_short(B):
+    """More than a thousand (sequence, KV head) rows of their own lengths, each a single chunk taken by one wave:
+    every block orders the sequences by length and gives the two waves of a SIMD the i-th shortest and the i-th
+    longest.  Every block has to arrive at the SAME order (equal lengths included), or rows would be computed twice
+    and others not at all: every row against the oracle, many equal lengths, and two calls bit for bit alike."""
+    Hkv, S = 8, 300
+    rng = np.random.default_rng(7000 + B)
+    lens = rng.integers(1, S + 1, B).astype(np.int32)
+    lens[: B // 4] = rng.choice([33, 64, 65, 200], B // 4)          # many ties
+    lens[0] = S
+    w = wl.custom(batch=B, n_q_heads=2 * Hkv, n_kv_heads=Hkv, head_dim=128, seq_len=S, seed=7100 + B)
+    q, k, v = make(w)
+    cache = gpu_cache_from(k, v)
+    ocache = oracle_cache_from(k, v)
+    assert tq.tq_decode_launches(cache, w.n_q_heads, S, w.attn_scale) == 1
+    lens_dev = torch.from_numpy(lens).cuda()
+    out = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert_close_elementwise(out, _oracle_varlen(q, ocache, [int(x) for x in lens], w.attn_scale), f"{B} sequences")
+    again = tq.tq_sdpa_int4_decode_varlen(cache, q.cuda(), lens_dev, S, w.attn_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+
+
 @pytest.mark.parametrize("route", ["packed_rows", "one_block", "planned_chunks"])
 def test_sharp_softmax_every_head_keeps_its_own_reference(route):
     """Scores with a spread of tens of log2 units (attn_scale 1 on N(0,1) queries and keys): new maxima keep turning
