@@ -77,7 +77,8 @@ def parse():
                          "over a pool of 256-token pages in random order) | varlen256 (256 sequences of 64 ... 1024 tokens of the llama "
                          "shape: every (sequence, KV head) row is one chunk, no merge kernel) | varlen256_2k (the same with 64 ... 2048 tokens: "
                          "chunks planned on the device, merge kernel of one block per sequence and four query heads) | sweep80 "
-                         "(80 layers x batch 4 of the llama128k shape, append + attend per layer)")
+                         "(80 layers x batch 4 of the llama128k shape, append + attend per layer) | prefill128k (the prefill arm: "
+                         "one bulk tq_quantize_kv of a 128K layer)")
     ap.add_argument("--layers", type=int, default=80, help="sweep80 only: number of layers")
     ap.add_argument("--buffers", type=int, default=8, help="distinct KV caches the steps rotate over")
     ap.add_argument("--variant", type=int, default=0)
@@ -238,10 +239,74 @@ def sweep(args):
     print(json.dumps(line), flush=True)
 
 
+def prefill(args):
+    """The prefill arm of Sec. 3.3 (quantize -> store): one bulk tq_quantize_kv of a whole 128K layer of the
+    llama128k shape (537 MB of fp16 K and V in, 168 MB of codes, scales and zero-points out), over rotating
+    destination caches; codes checked bit for bit against the oracle on a slice."""
+    import numpy as np
+    import torch
+
+    import paper_2604_16957_amd as tq
+    import tq_workloads as wl
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS["llama128k"]
+    S, B, Hkv, d = w.seq_len, w.batch, w.n_kv_heads, w.head_dim
+    GS = args.group_size
+    _, k, v = wl.make_inputs(w, device=dev)
+    caches = [tq.KVCache(B, Hkv, d, S, group_size=GS) for _ in range(4)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(n):
+        e0.record()
+        for i in range(n):
+            tq.tq_quantize_kv(caches[i % 4], k, v, 0)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    steps = args.steps if args.steps != 400 else 100
+    spent = 0.0
+    while spent < args.settle_ms * 1e3:
+        spent += timed(50) * 50
+    for _ in range(args.warmup):
+        tq.tq_quantize_kv(caches[0], k, v, 0)
+    us = timed(steps)
+    batches = [us] + [timed(steps) for _ in range(args.batches)]
+    moved = 2 * B * Hkv * S * d * 2 + tq.tq_kv_bytes_grouped(B, Hkv, S, d, GS)
+    check = None
+    if not args.no_check:
+        import oracle
+        n = 4096                                   # the first tokens of every KV head
+        kc, ks, kz = oracle.quantize(k[:, :, :n].cpu().numpy(), group=GS)
+        c = caches[(steps - 1) % 4]
+        check = {"tokens": n, "codes_bit_exact": bool(np.array_equal(c.k_codes[:, :, :n].cpu().numpy(), kc) and
+                                                       np.array_equal(c.k_scale[:, :, :n].cpu().numpy().view(np.uint16), ks.view(np.uint16)) and
+                                                       np.array_equal(c.k_zero[:, :, :n].cpu().numpy().view(np.uint16), kz.view(np.uint16)))}
+        check["ok"] = check["codes_bit_exact"]
+    achieved = moved / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "us_per_bulk_quantise (one 128K layer, K and V)", "value": round(us, 2), "unit": "us/fill",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 6), "step_us": dist(batches),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp16 in; fp32 arithmetic of Eq. 2-3; int4 codes + fp16 scale/zero out", "data": "synthetic",
+        "config": {"workload": "prefill128k", "batch": B, "n_kv_heads": Hkv, "head_dim": d, "seq_len": S, "group_size": GS},
+        "roofline": {"bound": "hbm", "kernel": "quantize_append_kernel (the whole tq_quantize_kv call)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": moved},
+        "cpu_baseline": None, "oracle_check": check}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists).")
+    if args.workload == "prefill128k":
+        import torch
+        if not torch.cuda.is_available():
+            sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+        return prefill(args)
     if args.workload == "sweep80":
         import torch
         if not torch.cuda.is_available():
