@@ -991,12 +991,12 @@ __global__ __launch_bounds__(NW * 64, (NW + 3) / 4) void decode_partial_mfma_ker
       }
     };
     float sc[2][4];
-    // (d = 128: the wave asks for issue priority while it unpacks K, feeds the matrix cores and scales the
-    //  scores: the two waves of a SIMD then take turns phase by phase rather than instruction by instruction,
-    //  0 - 1 % faster at 128K from box to box; at d = 256 the same costs 3 %)
-    if constexpr (D == 128) __builtin_amdgcn_s_setprio(1);
+    // (the wave asks for issue priority while it unpacks K, feeds the matrix cores and scales the scores: the two
+    //  waves of a SIMD then take turns phase by phase rather than instruction by instruction, 0 - 1 % faster at
+    //  128K from box to box, 0.4 % at the d = 256 instance)
+    __builtin_amdgcn_s_setprio(1);
     scores(kr, 0, std::false_type{}, sc);
-    if constexpr (D == 128) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(0);
     // The only stage out is the next supertile's.  Past the last supertile there is nothing to wait for and the
     // fetch reads unused bytes; skipping it there takes a branch in the loop, which the d = 128 instances pay for in
     // registers and schedule (16-row tile 33.3 -> 35.4 us, 8-row 28.7 -> 28.95) and the d = 256 instance gains by.
